@@ -1,0 +1,174 @@
+/*
+ * mla_gfx950.h -- C ABI of the absorbed multi-head latent attention (MLA)
+ * decode library for AMD MI355X (gfx950).
+ *
+ * The three compute calls are the three lines of the paper's absorbed
+ * ("MQA paradigm") attention equation in Sec. 3.3:
+ *
+ *   q_hat_i = [ (W^{UK}_i)^T q^C_i ; q^R_i ]                    mla_absorb_q
+ *   o_hat_i = sum_j softmax_j( q_hat_i . k_hat_j * scale ) c_j  mla_decode_paged
+ *             with k_hat_j = [ c_j^{KV} ; k_j^R ]
+ *   o_i     = W^{UV}_i o_hat_i                                  mla_out_proj
+ *
+ * Notation: H query heads (paper: h), d_head (d), latent rank d_c (r_kv),
+ * decoupled-RoPE width d_rope (d^R).  The final W^O projection and every
+ * projection that produces q^C, q^R, c^{KV}, k^R are outside this library.
+ * q_rope and the k_rope part of the cache are passed ALREADY rotated by RoPE;
+ * no call here applies RoPE.
+ *
+ * General conventions
+ *  - Every pointer is a DEVICE pointer unless the comment says "host".
+ *    The caller owns every buffer, including the workspace; the library
+ *    allocates no device memory and keeps no state between calls.
+ *  - Tensors are dense, row-major, innermost index last, and 16-byte aligned.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    All work is enqueued on it and the call returns without waiting.
+ *  - Return value: MLA_OK (0) or a negative mla_status.  Arguments are
+ *    validated on the host before the first HIP call; on error nothing is
+ *    launched and no output is written.  Nothing throws across this ABI.
+ *  - "io dtype" is the type of q / weights / outputs (MLA_F32 or MLA_BF16);
+ *    all accumulation is fp32.
+ */
+#ifndef MLA_GFX950_H
+#define MLA_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MLA_F32      = 0,  /* IEEE binary32                                        */
+    MLA_BF16     = 1,  /* bfloat16 (upper half of binary32)                    */
+    MLA_FP8_E4M3 = 2   /* OCP E4M3 (max 448, no inf); cache storage only       */
+} mla_dtype;
+
+typedef enum {
+    MLA_OK              =  0,
+    MLA_ERR_NULL        = -1,  /* a required pointer is NULL                   */
+    MLA_ERR_SHAPE       = -2,  /* a size is <= 0 or inconsistent               */
+    MLA_ERR_UNSUPPORTED = -3,  /* shape / dtype combination not implemented    */
+    MLA_ERR_WORKSPACE   = -4,  /* workspace missing or too small               */
+    MLA_ERR_HIP         = -6   /* a HIP runtime call (launch) failed           */
+} mla_status;
+
+/* Flags for mla_decode_paged. */
+enum {
+    MLA_FLAG_DEFAULT        = 0,
+    MLA_FLAG_PORTABLE_KERNEL = 1  /* force the scalar-FMA kernel even where the
+                                     matrix-core kernel applies (cross-check)  */
+};
+
+/* Human-readable name of a status code.  Static storage; never free it. */
+const char* mla_status_string(int status);
+
+/* Library version as a static string. */
+const char* mla_version(void);
+
+/*
+ * Absorb (first line of the absorbed equation; App. A.2.2 folds the same
+ * product into W'^Q):   q_abs[b,h,:] = q_nope[b,h,:] . W_UK[h]
+ *
+ *   q_nope [B, H, d_head]    io dtype
+ *   W_UK   [H, d_head, d_c]  io dtype; W_UK[h] is W^{UK}_h (rows = head dims)
+ *   q_abs  [B, H, d_c]       io dtype (output)
+ * Any B, H, d_head, d_c >= 1.
+ */
+int mla_absorb_q(const void* q_nope, const void* W_UK, void* q_abs,
+                 int B, int H, int d_head, int d_c,
+                 mla_dtype io_dtype, void* hip_stream);
+
+/*
+ * Output up-projection (last line of the absorbed equation, inside the
+ * brackets):            out[b,h,:] = o_lat[b,h,:] . W_UV[h]
+ *
+ *   o_lat [B, H, d_c]        io dtype
+ *   W_UV  [H, d_c, d_head]   io dtype; W_UV[h] is (W^{UV}_h)^T
+ *   out   [B, H, d_head]     io dtype (output)
+ */
+int mla_out_proj(const void* o_lat, const void* W_UV, void* out,
+                 int B, int H, int d_c, int d_head,
+                 mla_dtype io_dtype, void* hip_stream);
+
+/*
+ * Bytes of device workspace mla_decode_paged needs for these sizes (split-KV
+ * partial results: fp32 [B, num_splits, H, d_c] + fp32 [B, num_splits, H]).
+ * Pure host function; returns 0 if an argument is <= 0.
+ */
+size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
+
+/*
+ * Paged absorbed decode (second line of the absorbed equation).  For every
+ * sequence b and head h, over the cached tokens j = 0 .. seq_lens[b]-1 (the
+ * current token's row is already in the cache; no other mask):
+ *
+ *   s_j   = softmax_scale * ( q_abs[b,h,:] . c_kv[j] + q_rope[b,h,:] . k_rope[j] )
+ *   p     = softmax_j(s)
+ *   o_lat[b,h,:] = sum_j p_j c_kv[j]          lse[b,h] = log sum_j exp(s_j)
+ *
+ *   q_abs      [B, H, d_c]     io dtype
+ *   q_rope     [B, H, d_rope]  io dtype, already rotated (position seq_len-1)
+ *   kv_cache   [num_pages, page_size, d_c + d_rope]  cache dtype; one pool,
+ *              row = [ c_kv | k_rope ], k_rope already rotated at its position
+ *   kv_scale   [num_pages, page_size] fp32: required iff cache dtype is
+ *              MLA_FP8_E4M3 (stored value = decode(code) * scale of that
+ *              token); must be NULL otherwise
+ *   page_table [B, max_pages_per_seq] int32: logical token j of sequence b
+ *              is row (j % page_size) of page page_table[b][j / page_size].
+ *              Entries at or beyond ceil(seq_len/page_size) are never read
+ *              (they may be -1).  An entry outside [0, num_pages) that WOULD
+ *              be read is not an error code (the table is device memory):
+ *              the tokens of that page are skipped.
+ *   seq_lens   [B] int32, each in [0, max_pages_per_seq * page_size].
+ *              Slots of the last page past seq_len, and pages not in the
+ *              table, are never used (they may hold NaN).
+ *   o_lat      [B, H, d_c] io dtype (output);  seq_len 0 gives zeros
+ *   lse        [B, H] fp32 natural-log-sum-exp of the scaled scores (output,
+ *              may be NULL);  seq_len 0 gives -inf
+ *   workspace  at least mla_decode_workspace_bytes(B, H, d_c, num_splits)
+ *              bytes, 256-byte aligned; contents are scratch
+ *   num_splits >= 1: each sequence's page list is cut into num_splits
+ *              contiguous chunks of ceil(max_pages_per_seq / num_splits)
+ *              pages (trailing chunks of short sequences are empty); every
+ *              chunk is reduced with its own running softmax and the chunks
+ *              are merged by log-sum-exp.  The result does not depend on
+ *              num_splits beyond fp32 rounding.
+ *   softmax_scale  the paper uses 1/sqrt(d_head + d_rope) for MLA
+ *
+ * Supported: io/cache dtype pairs (F32,F32), (BF16,BF16), (BF16,FP8_E4M3),
+ * (F32,BF16), (F32,FP8_E4M3); 1 <= H <= 64; d_c a multiple of 8 up to 512;
+ * d_rope a multiple of 8 in [0, 64]; any page_size >= 1.
+ * The matrix-core (MFMA) kernel is used for BF16 io with a BF16 cache,
+ * page_size 64, d_rope 64, d_c in {256, 512} and H <= 32; everything else
+ * runs on the portable scalar-FMA kernel.
+ */
+int mla_decode_paged(const void* q_abs, const void* q_rope,
+                     const void* kv_cache, const float* kv_scale,
+                     const int32_t* page_table, const int32_t* seq_lens,
+                     void* o_lat, float* lse,
+                     void* workspace, size_t workspace_bytes,
+                     int B, int H, int d_c, int d_rope, int page_size,
+                     int num_pages, int max_pages_per_seq, int num_splits,
+                     float softmax_scale, mla_dtype io_dtype,
+                     mla_dtype cache_dtype, unsigned flags, void* hip_stream);
+
+/*
+ * Test hook: the logical (un-paged) view of the cache, byte for byte, using
+ * the same page arithmetic as mla_decode_paged.
+ *
+ *   dense [B, max_len, row_bytes] bytes (output): row j of sequence b is the
+ *         row_bytes bytes of its cache row for j < seq_lens[b], else zeros.
+ * row_bytes must be a multiple of 4.  Page ids outside [0, num_pages) give
+ * zero rows.
+ */
+int mla_gather_paged(const void* kv_cache, const int32_t* page_table,
+                     const int32_t* seq_lens, void* dense,
+                     int B, int max_len, int row_bytes, int page_size,
+                     int num_pages, int max_pages_per_seq, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLA_GFX950_H */

@@ -1,0 +1,133 @@
+// C-ABI entry points: host-side argument validation, then kernel launches.
+// Validation never touches the HIP runtime, so every error path can be
+// exercised on a machine without a GPU.
+#include "mla_internal.h"
+
+using namespace mla;
+
+namespace {
+
+bool io_ok(mla_dtype t) { return t == MLA_F32 || t == MLA_BF16; }
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* mla_status_string(int status)
+{
+    switch (status) {
+        case MLA_OK:              return "MLA_OK";
+        case MLA_ERR_NULL:        return "MLA_ERR_NULL: a required pointer is NULL";
+        case MLA_ERR_SHAPE:       return "MLA_ERR_SHAPE: a size is non-positive or inconsistent";
+        case MLA_ERR_UNSUPPORTED: return "MLA_ERR_UNSUPPORTED: shape or dtype combination not implemented";
+        case MLA_ERR_WORKSPACE:   return "MLA_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case MLA_ERR_HIP:         return "MLA_ERR_HIP: a HIP runtime call failed";
+        default:                  return "unknown mla status";
+    }
+}
+
+const char* mla_version(void) { return "mla-gfx950 0.1"; }
+
+int mla_absorb_q(const void* q_nope, const void* W_UK, void* q_abs, int B, int H, int d_head,
+                 int d_c, mla_dtype io_dtype, void* hip_stream)
+{
+    if (!q_nope || !W_UK || !q_abs) return MLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || d_head <= 0 || d_c <= 0) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || (B + 15) / 16 > 65535) return MLA_ERR_UNSUPPORTED;
+    hipError_t e = launch_head_gemm(q_nope, W_UK, q_abs, B, H, d_head, d_c, io_dtype,
+                                    static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+int mla_out_proj(const void* o_lat, const void* W_UV, void* out, int B, int H, int d_c,
+                 int d_head, mla_dtype io_dtype, void* hip_stream)
+{
+    if (!o_lat || !W_UV || !out) return MLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || d_head <= 0 || d_c <= 0) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || (B + 15) / 16 > 65535) return MLA_ERR_UNSUPPORTED;
+    hipError_t e = launch_head_gemm(o_lat, W_UV, out, B, H, d_c, d_head, io_dtype,
+                                    static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits)
+{
+    if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return 0;
+    size_t o = (size_t)B * num_splits * H * d_c * sizeof(float);
+    size_t l = (size_t)B * num_splits * H * sizeof(float);
+    return align_up(o, 256) + align_up(l, 256);
+}
+
+int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache,
+                     const float* kv_scale, const int32_t* page_table, const int32_t* seq_lens,
+                     void* o_lat, float* lse, void* workspace, size_t workspace_bytes, int B, int H,
+                     int d_c, int d_rope, int page_size, int num_pages, int max_pages_per_seq,
+                     int num_splits, float softmax_scale, mla_dtype io_dtype, mla_dtype cache_dtype,
+                     unsigned flags, void* hip_stream)
+{
+    if (!q_abs || !kv_cache || !page_table || !seq_lens || !o_lat) return MLA_ERR_NULL;
+    if (d_rope > 0 && !q_rope) return MLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
+        max_pages_per_seq <= 0 || num_splits <= 0)
+        return MLA_ERR_SHAPE;
+    if ((long long)max_pages_per_seq * page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
+    if (!(softmax_scale == softmax_scale)) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (cache_dtype != MLA_F32 && cache_dtype != MLA_BF16 && cache_dtype != MLA_FP8_E4M3)
+        return MLA_ERR_UNSUPPORTED;
+    if (cache_dtype == MLA_F32 && io_dtype != MLA_F32) return MLA_ERR_UNSUPPORTED;
+    if (cache_dtype == MLA_FP8_E4M3 && !kv_scale) return MLA_ERR_NULL;
+    if (cache_dtype != MLA_FP8_E4M3 && kv_scale) return MLA_ERR_SHAPE;
+    if (H > 64 || d_c > 512 || d_c % 8 || d_rope > 64 || d_rope % 8) return MLA_ERR_UNSUPPORTED;
+    if (B > 65535 || num_splits > 65535) return MLA_ERR_UNSUPPORTED;
+    const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return MLA_ERR_WORKSPACE;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    DecodeParams p;
+    p.q_abs = q_abs; p.q_rope = q_rope; p.kv = kv_cache; p.kv_scale = kv_scale;
+    p.page_table = page_table; p.seq_lens = seq_lens;
+    p.o_part = static_cast<float*>(workspace);
+    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                          align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
+    p.B = B; p.H = H; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
+    p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = num_splits;
+    p.chunk_pages = (max_pages_per_seq + num_splits - 1) / num_splits;
+    p.scale = softmax_scale;
+
+    hipError_t e;
+    if (!(flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, io_dtype, cache_dtype))
+        e = launch_decode_mfma(p, stream);
+    else
+        e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
+    if (e != hipSuccess) return MLA_ERR_HIP;
+
+    MergeParams m;
+    m.o_part = p.o_part; m.lse_part = p.lse_part; m.o_lat = o_lat; m.lse = lse;
+    m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+    e = launch_merge(m, io_dtype, stream);
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+int mla_gather_paged(const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens,
+                     void* dense, int B, int max_len, int row_bytes, int page_size, int num_pages,
+                     int max_pages_per_seq, void* hip_stream)
+{
+    if (!kv_cache || !page_table || !seq_lens || !dense) return MLA_ERR_NULL;
+    if (B <= 0 || max_len <= 0 || row_bytes <= 0 || page_size <= 0 || num_pages <= 0 ||
+        max_pages_per_seq <= 0)
+        return MLA_ERR_SHAPE;
+    if ((long long)max_pages_per_seq * page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
+    if (row_bytes % 4 || B > 65535) return MLA_ERR_UNSUPPORTED;
+    hipError_t e = launch_gather(kv_cache, page_table, seq_lens, dense, B, max_len, row_bytes,
+                                 page_size, num_pages, max_pages_per_seq,
+                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+}  // extern "C"

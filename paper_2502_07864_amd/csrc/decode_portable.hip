@@ -1,0 +1,304 @@
+// Portable (scalar-FMA, fp32) kernels: paged decode for every supported dtype
+// pair and shape, the split-KV merge, and the page gather test hook.
+//
+// The decode kernel is the library's reference GPU path: it is the only path
+// for fp32 and fp8 caches and for shapes the matrix-core kernel does not
+// cover.  One workgroup handles (chunk, sequence, group of 8 heads): a tile of
+// 16 cached rows is widened to fp32 in LDS, scored against the 8 query rows,
+// folded into a running softmax (second line of the absorbed attention
+// equation, Sec. 3.3 of the paper) and accumulated into the latent output.
+#include "mla_internal.h"
+
+namespace mla {
+namespace {
+
+constexpr int PT_THREADS = 256;
+constexpr int PT_HG = 8;        // heads per workgroup
+constexpr int PT_TOK = 16;      // cached rows per tile
+constexpr int PT_MAX_ROW = 576; // max d_c + d_rope
+constexpr int PT_PAD = 1;       // LDS row padding (floats): rows start in different banks
+constexpr int PT_MAX_COLS = 2;  // d_c <= 512 = 2 * 256 threads
+
+template <typename T> struct Load8;
+
+template <> struct Load8<float> {
+    static __device__ __forceinline__ void run(const void* base, size_t elem, const float*, size_t, float* out)
+    {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+        float4 a = p[0], b = p[1];
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    }
+};
+
+struct bf16_tag {};
+template <> struct Load8<bf16_tag> {
+    static __device__ __forceinline__ void run(const void* base, size_t elem, const float*, size_t, float* out)
+    {
+        uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i]     = bf16_bits_to_f32(w[i] & 0xFFFFu);
+            out[2 * i + 1] = bf16_bits_to_f32(w[i] >> 16);
+        }
+    }
+};
+
+struct fp8_tag {};
+template <> struct Load8<fp8_tag> {
+    static __device__ __forceinline__ void run(const void* base, size_t elem, const float* scale, size_t row, float* out)
+    {
+        uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint8_t*>(base) + elem);
+        float s = scale[row];
+        uint32_t w[2] = {v.x, v.y};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = e4m3_to_f32((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * s;
+    }
+};
+
+template <typename QT> __device__ __forceinline__ float load_q(const void* p, size_t i);
+template <> __device__ __forceinline__ float load_q<float>(const void* p, size_t i)
+{
+    return static_cast<const float*>(p)[i];
+}
+template <> __device__ __forceinline__ float load_q<bf16_tag>(const void* p, size_t i)
+{
+    return bf16_bits_to_f32(static_cast<const uint16_t*>(p)[i]);
+}
+
+template <typename QT, typename CT>
+__global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParams p)
+{
+    __shared__ float q_s[PT_HG][PT_MAX_ROW + PT_PAD];
+    __shared__ float k_s[PT_TOK][PT_MAX_ROW + PT_PAD];
+    __shared__ float s_s[PT_HG][PT_TOK];
+    __shared__ float p_s[PT_HG][PT_TOK];
+    __shared__ float alpha_s[PT_HG], m_s[PT_HG], l_s[PT_HG];
+    __shared__ int valid_s[PT_TOK];
+
+    const int tid = threadIdx.x;
+    const int split = blockIdx.x, b = blockIdx.y, h0 = blockIdx.z * PT_HG;
+    const int row = p.d_c + p.d_rope;
+    const int nh = min(PT_HG, p.H - h0);
+
+    int L = p.seq_lens[b];
+    L = max(0, min(L, p.max_pages * p.page_size));
+    const long chunk_tok = (long)p.chunk_pages * p.page_size;
+    const long j0l = min((long)L, (long)split * chunk_tok);
+    const long j1l = min((long)L, j0l + chunk_tok);
+    const int j0 = (int)j0l, j1 = (int)j1l;
+    const size_t part = ((size_t)b * p.num_splits + split) * p.H;
+
+    if (j0 >= j1) {  // empty chunk: weight zero in the merge, partial output never read
+        if (tid < nh) p.lse_part[part + h0 + tid] = -INFINITY;
+        return;
+    }
+
+    // query rows [q_abs | q_rope] of this head group -> LDS (fp32)
+    for (int idx = tid; idx < PT_HG * row; idx += PT_THREADS) {
+        int h = idx / row, k = idx % row;
+        float v = 0.f;
+        if (h < nh) {
+            size_t bh = (size_t)b * p.H + h0 + h;
+            v = k < p.d_c ? load_q<QT>(p.q_abs, bh * p.d_c + k)
+                          : load_q<QT>(p.q_rope, bh * p.d_rope + (k - p.d_c));
+        }
+        q_s[h][k] = v;
+    }
+    if (tid < PT_HG) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; }
+
+    float acc[PT_MAX_COLS][PT_HG];
+#pragma unroll
+    for (int i = 0; i < PT_MAX_COLS; ++i)
+#pragma unroll
+        for (int h = 0; h < PT_HG; ++h) acc[i][h] = 0.f;
+
+    const int chunks_per_row = row / 8;
+    for (int t0 = j0; t0 < j1; t0 += PT_TOK) {
+        __syncthreads();  // previous tile fully consumed (and q_s / m_s written)
+        // ---- stage the tile: widen to fp32; rows outside the chunk or on a bad page are zero
+        for (int idx = tid; idx < PT_TOK * chunks_per_row; idx += PT_THREADS) {
+            int t = idx / chunks_per_row, c8 = (idx % chunks_per_row) * 8;
+            int j = t0 + t;
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            bool ok = j < j1;
+            if (ok) {
+                int page = p.page_table[(size_t)b * p.max_pages + j / p.page_size];
+                ok = page >= 0 && page < p.num_pages;
+                if (ok) {
+                    size_t r = (size_t)page * p.page_size + (j % p.page_size);
+                    Load8<CT>::run(p.kv, r * row + c8, p.kv_scale, r, v);
+                }
+            }
+            if (c8 == 0) valid_s[t] = ok ? 1 : 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) k_s[t][c8 + i] = v[i];
+        }
+        __syncthreads();
+        // ---- scores: (head, token) pair per two threads, each half of the row
+        if (tid < PT_HG * PT_TOK * 2) {
+            int pair = tid >> 1, half = tid & 1;
+            int h = pair / PT_TOK, t = pair % PT_TOK;
+            int kb = half * (row / 2), ke = kb + row / 2;
+            float dot = 0.f;
+            for (int k = kb; k < ke; ++k) dot = fmaf(q_s[h][k], k_s[t][k], dot);
+            dot += __shfl_xor(dot, 1);
+            if (half == 0) s_s[h][t] = valid_s[t] ? dot * p.scale : -INFINITY;
+        }
+        __syncthreads();
+        // ---- running softmax, one thread per head
+        if (tid < PT_HG) {
+            int h = tid;
+            float m_old = m_s[h], tmax = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < PT_TOK; ++t) tmax = fmaxf(tmax, s_s[h][t]);
+            float m_new = fmaxf(m_old, tmax);
+            float a = 1.f, sum = 0.f;
+            if (m_new == -INFINITY) {
+#pragma unroll
+                for (int t = 0; t < PT_TOK; ++t) p_s[h][t] = 0.f;
+            } else {
+                a = expf(m_old - m_new);  // exp(-inf) = 0 on the first tile
+#pragma unroll
+                for (int t = 0; t < PT_TOK; ++t) {
+                    float e = expf(s_s[h][t] - m_new);
+                    p_s[h][t] = e;
+                    sum += e;
+                }
+            }
+            alpha_s[h] = a;
+            l_s[h] = l_s[h] * a + sum;
+            m_s[h] = m_new;
+        }
+        __syncthreads();
+        // ---- latent values: thread owns columns tid, tid+256
+#pragma unroll
+        for (int i = 0; i < PT_MAX_COLS; ++i) {
+            int c = tid + i * PT_THREADS;
+            if (c < p.d_c) {
+#pragma unroll
+                for (int h = 0; h < PT_HG; ++h) acc[i][h] *= alpha_s[h];
+                for (int t = 0; t < PT_TOK; ++t) {
+                    float v = k_s[t][c];
+#pragma unroll
+                    for (int h = 0; h < PT_HG; ++h) acc[i][h] = fmaf(p_s[h][t], v, acc[i][h]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PT_MAX_COLS; ++i) {
+        int c = tid + i * PT_THREADS;
+        if (c < p.d_c) {
+            for (int h = 0; h < nh; ++h) {
+                float l = l_s[h];
+                p.o_part[(part + h0 + h) * p.d_c + c] = l > 0.f ? acc[i][h] / l : 0.f;
+            }
+        }
+    }
+    if (tid < nh) {
+        float l = l_s[tid];
+        p.lse_part[part + h0 + tid] = l > 0.f ? m_s[tid] + logf(l) : -INFINITY;
+    }
+}
+
+// ---- split-KV merge: lse = log sum_s e^{lse_s}, o = sum_s e^{lse_s - lse} o_s ----
+template <bool OUT_BF16>
+__global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
+{
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int S = p.num_splits;
+    const float* lp = p.lse_part + (size_t)b * S * p.H + h;  // stride H over s
+    float m = -INFINITY;
+    for (int s = 0; s < S; ++s) m = fmaxf(m, lp[(size_t)s * p.H]);
+    float z = 0.f;
+    if (m != -INFINITY)
+        for (int s = 0; s < S; ++s) z += expf(lp[(size_t)s * p.H] - m);  // exp(-inf) = 0
+    const float inv = z > 0.f ? 1.f / z : 0.f;
+    const size_t out_base = ((size_t)b * p.H + h) * p.d_c;
+    for (int c = tid * 4; c < p.d_c; c += 128 * 4) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < S; ++s) {
+            float ls = lp[(size_t)s * p.H];
+            if (ls == -INFINITY) continue;  // empty chunk: its partial output was never written
+            float w = expf(ls - m) * inv;
+            const float4 v = *reinterpret_cast<const float4*>(
+                p.o_part + (((size_t)b * S + s) * p.H + h) * p.d_c + c);
+            acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
+            acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
+        }
+        if (OUT_BF16) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
+            o.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.o_lat) + out_base + c) = o;
+        } else {
+            *reinterpret_cast<float4*>(static_cast<float*>(p.o_lat) + out_base + c) = acc;
+        }
+    }
+    if (p.lse && tid == 0) p.lse[(size_t)b * p.H + h] = z > 0.f ? m + logf(z) : -INFINITY;
+}
+
+// ---- page gather (byte exact) ---------------------------------------------
+__global__ __launch_bounds__(256) void gather_kernel(const uint32_t* kv, const int32_t* page_table,
+                                                     const int32_t* seq_lens, uint32_t* dense,
+                                                     int max_len, int row_words, int page_size,
+                                                     int num_pages, int max_pages)
+{
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= max_len) return;
+    int L = min(seq_lens[b], max_pages * page_size);
+    const uint32_t* src = nullptr;
+    if (j < L) {
+        int page = page_table[(size_t)b * max_pages + j / page_size];
+        if (page >= 0 && page < num_pages)
+            src = kv + ((size_t)page * page_size + (j % page_size)) * row_words;
+    }
+    uint32_t* dst = dense + ((size_t)b * max_len + j) * row_words;
+    for (int w = lane; w < row_words; w += 64) dst[w] = src ? src[w] : 0u;
+}
+
+}  // namespace
+
+hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s)
+{
+    dim3 grid(p.num_splits, p.B, (p.H + PT_HG - 1) / PT_HG), block(PT_THREADS);
+    if (io == MLA_F32 && cache == MLA_F32)
+        decode_portable_kernel<float, float><<<grid, block, 0, s>>>(p);
+    else if (io == MLA_F32 && cache == MLA_BF16)
+        decode_portable_kernel<float, bf16_tag><<<grid, block, 0, s>>>(p);
+    else if (io == MLA_F32 && cache == MLA_FP8_E4M3)
+        decode_portable_kernel<float, fp8_tag><<<grid, block, 0, s>>>(p);
+    else if (io == MLA_BF16 && cache == MLA_BF16)
+        decode_portable_kernel<bf16_tag, bf16_tag><<<grid, block, 0, s>>>(p);
+    else if (io == MLA_BF16 && cache == MLA_FP8_E4M3)
+        decode_portable_kernel<bf16_tag, fp8_tag><<<grid, block, 0, s>>>(p);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s)
+{
+    dim3 grid(p.H, p.B), block(128);
+    if (io == MLA_BF16) merge_kernel<true><<<grid, block, 0, s>>>(p);
+    else                merge_kernel<false><<<grid, block, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
+                         void* dense, int B, int max_len, int row_bytes, int page_size,
+                         int num_pages, int max_pages, hipStream_t s)
+{
+    dim3 grid((max_len + 3) / 4, B), block(256);
+    gather_kernel<<<grid, block, 0, s>>>(static_cast<const uint32_t*>(kv), page_table, seq_lens,
+                                         static_cast<uint32_t*>(dense), max_len, row_bytes / 4,
+                                         page_size, num_pages, max_pages);
+    return hipGetLastError();
+}
+
+}  // namespace mla

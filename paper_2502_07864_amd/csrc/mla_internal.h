@@ -1,0 +1,74 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "mla_gfx950.h"
+
+namespace mla {
+
+// Everything a decode kernel needs; passed by value as the kernel argument.
+struct DecodeParams {
+    const void* q_abs;          // [B,H,d_c]      io dtype
+    const void* q_rope;         // [B,H,d_rope]   io dtype
+    const void* kv;             // [num_pages, page_size, d_c+d_rope] cache dtype
+    const float* kv_scale;      // [num_pages, page_size] (fp8 cache) or nullptr
+    const int32_t* page_table;  // [B, max_pages]
+    const int32_t* seq_lens;    // [B]
+    float* o_part;              // [B, S, H, d_c]  chunk-normalised partial outputs
+    float* lse_part;            // [B, S, H]       natural-log LSE per chunk (-inf = empty)
+    int B, H, d_c, d_rope, page_size, num_pages, max_pages, num_splits, chunk_pages;
+    float scale;
+};
+
+struct MergeParams {
+    const float* o_part;
+    const float* lse_part;
+    void* o_lat;   // [B,H,d_c] io dtype
+    float* lse;    // [B,H] or nullptr
+    int B, H, d_c, num_splits;
+};
+
+// ---- small device helpers ------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16)
+{
+    return __uint_as_float(bits16 << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even, NaN kept quiet.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// OCP e4m3 code -> fp32 (bias 7, subnormals m*2^-9, S.1111.111 = NaN).
+__device__ __forceinline__ float e4m3_to_f32(uint32_t code)
+{
+    uint32_t sign = (code & 0x80u) << 24;
+    uint32_t em = code & 0x7Fu;
+    float mag;
+    if (em == 0x7Fu)      mag = __uint_as_float(0x7FC00000u);
+    else if (em < 8u)     mag = (float)em * 0.001953125f;                 // m * 2^-9
+    else                  mag = __uint_as_float((em << 20) + (120u << 23)); // rebias 7 -> 127
+    return __uint_as_float(__float_as_uint(mag) | sign);
+}
+
+// ---- launchers (each returns hipGetLastError() of its launch) --------------
+
+hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
+bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
+hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t s);
+hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s);
+hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
+                         void* dense, int B, int max_len, int row_bytes, int page_size,
+                         int num_pages, int max_pages, hipStream_t s);
+// Y[b,h,n] = sum_k X[b,h,k] * W[h,k,n]
+hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H, int K, int N,
+                            mla_dtype io, hipStream_t s);
+
+}  // namespace mla

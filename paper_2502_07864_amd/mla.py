@@ -1,0 +1,185 @@
+"""Python binding of the gfx950 MLA decode library (``include/mla_gfx950.h``).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, passes their device pointers and the current HIP stream to
+the C entry point of the same name, and returns the output tensor.  torch is
+used for device memory and streams; no arithmetic happens here and there is
+no fallback path: a missing library or a failing call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libmla_gfx950.so"
+_lib = None
+
+F32, BF16, FP8_E4M3 = 0, 1, 2
+FLAG_DEFAULT, FLAG_PORTABLE_KERNEL = 0, 1
+
+EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
+           "mla_decode_workspace_bytes", "mla_decode_paged", "mla_gather_paged")
+
+
+class MlaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmla_gfx950.so (built in-tree by ``python -m paper_2502_07864_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2502_07864_amd.build`")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        vp, i, u, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_float
+        L.mla_status_string.restype = ctypes.c_char_p
+        L.mla_status_string.argtypes = [i]
+        L.mla_version.restype = ctypes.c_char_p
+        L.mla_version.argtypes = []
+        L.mla_absorb_q.restype = i
+        L.mla_absorb_q.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.mla_out_proj.restype = i
+        L.mla_out_proj.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.mla_decode_workspace_bytes.restype = ctypes.c_size_t
+        L.mla_decode_workspace_bytes.argtypes = [i, i, i, i]
+        L.mla_decode_paged.restype = i
+        L.mla_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
+                                       i, i, i, i, i, i, i, i, f, i, i, u, vp]
+        L.mla_gather_paged.restype = i
+        L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mla_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return lib().mla_version().decode()
+
+
+def _io_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"io dtype must be float32 or bfloat16, got {t.dtype}")
+
+
+def _cache_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype in (torch.uint8, torch.float8_e4m3fn):
+        return FP8_E4M3
+    raise TypeError(f"cache dtype must be float32, bfloat16, uint8 or float8_e4m3fn, got {t.dtype}")
+
+
+def _dev(t: Optional[torch.Tensor], name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(t: torch.Tensor):
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MlaError(status, where)
+
+
+def absorb_q(q_nope: torch.Tensor, W_UK: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q_abs[b,h,:] = q_nope[b,h,:] . W_UK[h];  q_nope [B,H,d_head], W_UK [H,d_head,d_c]."""
+    B, H, d_head = q_nope.shape
+    H2, d_head2, d_c = W_UK.shape
+    if (H2, d_head2) != (H, d_head) or W_UK.dtype != q_nope.dtype:
+        raise ValueError("W_UK must be [H, d_head, d_c] of q_nope's dtype")
+    if out is None:
+        out = torch.empty((B, H, d_c), dtype=q_nope.dtype, device=q_nope.device)
+    _check(lib().mla_absorb_q(_dev(q_nope, "q_nope"), _dev(W_UK, "W_UK"), _dev(out, "out"),
+                              B, H, d_head, d_c, _io_code(q_nope), _stream(q_nope)), "mla_absorb_q")
+    return out
+
+
+def out_proj(o_lat: torch.Tensor, W_UV: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[b,h,:] = o_lat[b,h,:] . W_UV[h];  o_lat [B,H,d_c], W_UV [H,d_c,d_head]."""
+    B, H, d_c = o_lat.shape
+    H2, d_c2, d_head = W_UV.shape
+    if (H2, d_c2) != (H, d_c) or W_UV.dtype != o_lat.dtype:
+        raise ValueError("W_UV must be [H, d_c, d_head] of o_lat's dtype")
+    if out is None:
+        out = torch.empty((B, H, d_head), dtype=o_lat.dtype, device=o_lat.device)
+    _check(lib().mla_out_proj(_dev(o_lat, "o_lat"), _dev(W_UV, "W_UV"), _dev(out, "out"),
+                              B, H, d_c, d_head, _io_code(o_lat), _stream(o_lat)), "mla_out_proj")
+    return out
+
+
+def decode_workspace_bytes(B: int, H: int, d_c: int, num_splits: int) -> int:
+    return int(lib().mla_decode_workspace_bytes(B, H, d_c, num_splits))
+
+
+def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: torch.Tensor,
+                 page_table: torch.Tensor, seq_lens: torch.Tensor, softmax_scale: float,
+                 num_splits: int = 1, kv_scale: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                 lse: Optional[torch.Tensor] = None, return_lse: bool = False, flags: int = 0):
+    """Paged absorbed decode.  kv_cache [num_pages, page_size, d_c+d_rope];
+    page_table int32 [B, max_pages_per_seq]; seq_lens int32 [B].
+    Returns o_lat [B,H,d_c] (and lse [B,H] fp32 if return_lse or lse given)."""
+    B, H, d_c = q_abs.shape
+    num_pages, page_size, row = kv_cache.shape
+    d_rope = row - d_c
+    if d_rope < 0:
+        raise ValueError("cache rows are shorter than d_c")
+    if d_rope and (q_rope is None or tuple(q_rope.shape) != (B, H, d_rope) or q_rope.dtype != q_abs.dtype):
+        raise ValueError("q_rope must be [B, H, d_rope] of q_abs's dtype")
+    if page_table.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise TypeError("page_table and seq_lens must be int32")
+    if page_table.dim() != 2 or page_table.shape[0] != B or seq_lens.shape != (B,):
+        raise ValueError("page_table must be [B, max_pages_per_seq], seq_lens [B]")
+    if kv_scale is not None and (kv_scale.dtype != torch.float32 or tuple(kv_scale.shape) != (num_pages, page_size)):
+        raise ValueError("kv_scale must be float32 [num_pages, page_size]")
+    need = decode_workspace_bytes(B, H, d_c, num_splits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_abs.device)
+    if out is None:
+        out = torch.empty((B, H, d_c), dtype=q_abs.dtype, device=q_abs.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, H), dtype=torch.float32, device=q_abs.device)
+    _check(lib().mla_decode_paged(
+        _dev(q_abs, "q_abs"), _dev(q_rope, "q_rope"), _dev(kv_cache, "kv_cache"),
+        _dev(kv_scale, "kv_scale"), _dev(page_table, "page_table"), _dev(seq_lens, "seq_lens"),
+        _dev(out, "out"), _dev(lse, "lse"), _dev(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), B, H, d_c, d_rope, page_size, num_pages,
+        page_table.shape[1], num_splits, float(softmax_scale), _io_code(q_abs),
+        _cache_code(kv_cache), int(flags), _stream(q_abs)), "mla_decode_paged")
+    return (out, lse) if lse is not None else out
+
+
+def gather_paged(kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: torch.Tensor,
+                 max_len: int) -> torch.Tensor:
+    """Logical view of the cache: uint8 [B, max_len, row_bytes], rows past seq_len zeroed."""
+    num_pages, page_size, row = kv_cache.shape
+    row_bytes = row * kv_cache.element_size()
+    B = seq_lens.shape[0]
+    dense = torch.empty((B, max_len, row_bytes), dtype=torch.uint8, device=kv_cache.device)
+    _check(lib().mla_gather_paged(_dev(kv_cache, "kv_cache"), _dev(page_table, "page_table"),
+                                  _dev(seq_lens, "seq_lens"), _dev(dense, "dense"), B, max_len,
+                                  row_bytes, page_size, num_pages, page_table.shape[1],
+                                  _stream(kv_cache)), "mla_gather_paged")
+    return dense

@@ -1,0 +1,137 @@
+"""Host-side checks of the C-ABI that need no GPU: the library loads, exports
+every function the public header declares, and rejects bad arguments before
+touching the HIP runtime (so no launch can happen here)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parents[1]
+HEADER = ROOT / "include" / "mla_gfx950.h"
+LIBPATH = ROOT / "paper_2502_07864_amd" / "libmla_gfx950.so"
+
+OK, E_NULL, E_SHAPE, E_UNSUP, E_WS, E_HIP = 0, -1, -2, -3, -4, -6
+F32, BF16, FP8 = 0, 1, 2
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not LIBPATH.exists():
+        from paper_2502_07864_amd.build import build_library
+        build_library()
+    L = ctypes.CDLL(str(LIBPATH))
+    vp, i, u, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_float
+    L.mla_status_string.restype = ctypes.c_char_p
+    L.mla_version.restype = ctypes.c_char_p
+    L.mla_absorb_q.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+    L.mla_out_proj.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+    L.mla_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.mla_decode_workspace_bytes.argtypes = [i, i, i, i]
+    L.mla_decode_paged.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 8 + [f, i, i, u, vp]
+    L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    return L
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(mla_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    names = declared_functions()
+    assert {"mla_absorb_q", "mla_decode_paged", "mla_out_proj", "mla_decode_workspace_bytes",
+            "mla_gather_paged", "mla_status_string", "mla_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_binding_lists_the_same_entry_points():
+    src = (ROOT / "paper_2502_07864_amd" / "mla.py").read_text()
+    for n in declared_functions():
+        assert n in src, f"{n} has no Python binding"
+
+
+def test_status_strings(lib):
+    assert lib.mla_status_string(OK) == b"MLA_OK"
+    for code, key in [(E_NULL, b"NULL"), (E_SHAPE, b"SHAPE"), (E_UNSUP, b"UNSUPPORTED"),
+                      (E_WS, b"WORKSPACE"), (E_HIP, b"HIP")]:
+        assert key in lib.mla_status_string(code)
+    assert b"unknown" in lib.mla_status_string(-99)
+    assert lib.mla_version().startswith(b"mla-gfx950")
+
+
+def test_workspace_bytes(lib):
+    n = lib.mla_decode_workspace_bytes(16, 32, 512, 16)
+    assert n >= 16 * 16 * 32 * 513 * 4 and n % 256 == 0
+    assert lib.mla_decode_workspace_bytes(0, 32, 512, 16) == 0
+    assert lib.mla_decode_workspace_bytes(16, 32, 512, 0) == 0
+    assert lib.mla_decode_workspace_bytes(1, 1, 8, 1) >= 36
+
+
+P = 0x1000  # a non-null, 256-aligned fake pointer: validation must fail before it is ever used
+
+
+def test_projection_validation(lib):
+    for fn in (lib.mla_absorb_q, lib.mla_out_proj):
+        assert fn(None, P, P, 1, 1, 8, 8, F32, None) == E_NULL
+        assert fn(P, None, P, 1, 1, 8, 8, F32, None) == E_NULL
+        assert fn(P, P, None, 1, 1, 8, 8, F32, None) == E_NULL
+        assert fn(P, P, P, 0, 1, 8, 8, F32, None) == E_SHAPE
+        assert fn(P, P, P, 1, -1, 8, 8, F32, None) == E_SHAPE
+        assert fn(P, P, P, 1, 1, 0, 8, F32, None) == E_SHAPE
+        assert fn(P, P, P, 1, 1, 8, 8, FP8, None) == E_UNSUP
+        assert fn(P, P, P, 1, 1, 8, 8, 7, None) == E_UNSUP
+
+
+def decode_args(**kw):
+    a = dict(q_abs=P, q_rope=P, kv=P, kv_scale=None, table=P, lens=P, o=P, lse=None, ws=P,
+             ws_bytes=1 << 30, B=2, H=32, d_c=512, d_rope=64, page=64, num_pages=8, max_pages=4,
+             splits=2, scale=0.07, io=BF16, cache=BF16, flags=0, stream=None)
+    a.update(kw)
+    return [a[k] for k in ("q_abs", "q_rope", "kv", "kv_scale", "table", "lens", "o", "lse", "ws",
+                           "ws_bytes", "B", "H", "d_c", "d_rope", "page", "num_pages", "max_pages",
+                           "splits", "scale", "io", "cache", "flags", "stream")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q_abs=None), E_NULL), (dict(q_rope=None), E_NULL), (dict(kv=None), E_NULL),
+    (dict(table=None), E_NULL), (dict(lens=None), E_NULL), (dict(o=None), E_NULL),
+    (dict(cache=FP8), E_NULL),                       # fp8 cache without scales
+    (dict(kv_scale=P), E_SHAPE),                     # scales with a non-fp8 cache
+    (dict(B=0), E_SHAPE), (dict(H=0), E_SHAPE), (dict(d_c=0), E_SHAPE), (dict(d_rope=-8), E_SHAPE),
+    (dict(page=0), E_SHAPE), (dict(num_pages=0), E_SHAPE), (dict(max_pages=0), E_SHAPE),
+    (dict(splits=0), E_SHAPE), (dict(scale=float("nan")), E_SHAPE),
+    (dict(max_pages=1 << 30, page=64), E_SHAPE),
+    (dict(io=FP8), E_UNSUP), (dict(cache=5), E_UNSUP), (dict(io=BF16, cache=F32), E_UNSUP),
+    (dict(H=65), E_UNSUP), (dict(d_c=520), E_UNSUP), (dict(d_c=12), E_UNSUP),
+    (dict(d_rope=72), E_UNSUP), (dict(d_rope=4), E_UNSUP), (dict(B=70000), E_UNSUP),
+    (dict(ws=None), E_WS), (dict(ws_bytes=1024), E_WS), (dict(ws=P + 8), E_WS),
+])
+def test_decode_validation(lib, kw, want):
+    assert lib.mla_decode_paged(*decode_args(**kw)) == want
+
+
+def test_gather_validation(lib):
+    g = lib.mla_gather_paged
+    assert g(None, P, P, P, 1, 4, 64, 4, 2, 1, None) == E_NULL
+    assert g(P, P, P, None, 1, 4, 64, 4, 2, 1, None) == E_NULL
+    assert g(P, P, P, P, 0, 4, 64, 4, 2, 1, None) == E_SHAPE
+    assert g(P, P, P, P, 1, 0, 64, 4, 2, 1, None) == E_SHAPE
+    assert g(P, P, P, P, 1, 4, 0, 4, 2, 1, None) == E_SHAPE
+    assert g(P, P, P, P, 1, 4, 6, 4, 2, 1, None) == E_UNSUP
+
+
+def test_product_path_does_not_use_the_oracle():
+    """The library, its binding and its build script never reference the test oracle."""
+    pkg = ROOT / "paper_2502_07864_amd"
+    for f in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        if f.name == "synth.py" or not f.is_file():
+            continue
+        text = f.read_text()
+        assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    assert "import oracle" not in (pkg / "synth.py").read_text()
+    for f in (ROOT / "oracle").glob("*"):
+        if f.suffix in (".py", ".c"):
+            t = f.read_text()
+            assert "paper_2502_07864_amd" not in t and "mla_gfx950" not in t

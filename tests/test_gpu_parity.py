@@ -1,0 +1,363 @@
+"""GPU parity: every call goes through the C-ABI (via the thin binding) and is
+compared element by element with the CPU oracle on the same seeded inputs.
+
+Bars: fp32 path 1e-5, bf16 / fp8-cache path 2e-2, both as
+max|gpu - oracle| / max|oracle| over the tensor; page gather bit-exact.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, DeviceWorkload, lse_err, max_abs_rel, storage_bits, to_torch, widen_gpu
+from paper_2502_07864_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mla():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2502_07864_amd import mla as m
+    m.lib()  # fails loudly if the HIP library is not built
+    return m
+
+
+def oracle_decode(w, q_abs_np, b_sel=None):
+    """Oracle o_lat / lse for (a subset of) the sequences, given q_abs in its stored dtype."""
+    sel = slice(None) if b_sel is None else np.asarray(b_sel)
+    return oracle.decode_absorbed(q_abs_np[sel], w.q_rope[sel], w.pool, w.kv_scale,
+                                  w.page_table[sel], w.seq_lens[sel], w.softmax_scale)
+
+
+def gpu_q_abs(mla, d):
+    return mla.absorb_q(d.q_nope, d.W_UK)
+
+
+def q_abs_storage(t):
+    """GPU q_abs tensor -> numpy storage array the oracle wrapper understands."""
+    bits = storage_bits(t)
+    return bits if bits.dtype == np.uint16 else bits.view(np.float32)
+
+
+def run_decode(mla, d, q_abs, num_splits, flags=0):
+    w = d.w
+    o, lse = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                              num_splits=num_splits, kv_scale=d.kv_scale, return_lse=True, flags=flags)
+    return o, lse
+
+
+def check_decode(mla, w, num_splits, flags=0, b_sel=None, tol=None):
+    import torch
+    d = DeviceWorkload(w)
+    q_abs = gpu_q_abs(mla, d)
+    o, lse = run_decode(mla, d, q_abs, num_splits, flags)
+    torch.cuda.synchronize()
+    ref_o, ref_lse = oracle_decode(w, q_abs_storage(q_abs), b_sel)
+    sel = slice(None) if b_sel is None else np.asarray(b_sel)
+    got_o, got_lse = widen_gpu(o)[sel], widen_gpu(lse)[sel]
+    assert np.isfinite(got_o).all()
+    tol = tol or TOL[w.io_dtype]
+    err = max_abs_rel(got_o, ref_o)
+    assert err <= tol, f"{w.name} splits={num_splits} flags={flags}: o_lat err {err:.3e} > {tol}"
+    le = lse_err(got_lse, ref_lse)
+    assert le <= (1e-4 if w.io_dtype == "f32" else 2e-2), f"lse err {le:.3e}"
+    return err
+
+
+# ------------------------------------------------------------------ gather
+
+@pytest.mark.parametrize("name,shrink", [("C3", 16), ("C5", 64), ("C2", 4), ("C1", 1)])
+def test_gather_bit_exact(mla, name, shrink):
+    import torch
+    w = synth.config(name, shrink=shrink)
+    d = DeviceWorkload(w)
+    max_len = int(w.seq_lens.max())
+    dense = mla.gather_paged(d.pool, d.page_table, d.seq_lens, max_len)
+    torch.cuda.synchronize()
+    want = oracle.gather_paged(w.pool, w.page_table, w.seq_lens, max_len)
+    assert dense.cpu().numpy().tobytes() == want.tobytes()
+
+
+# ------------------------------------------------------- the two projections
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,d_head,d_c", [(1, 32, 128, 512), (16, 32, 128, 512), (37, 28, 128, 256),
+                                            (3, 5, 24, 40), (130, 4, 128, 512)])
+def test_absorb_and_out_proj(mla, io, B, H, d_head, d_c):
+    import torch
+    r = synth.stream(7, B * 1000 + H)
+    q = synth.store(synth.normal(r, (B, H, d_head)), io)
+    Wk = synth.store(synth.normal(r, (H, d_head, d_c), 1 / math.sqrt(d_c)), io)
+    o = synth.store(synth.normal(r, (B, H, d_c)), io)
+    Wv = synth.store(synth.normal(r, (H, d_c, d_head), 1 / math.sqrt(d_c)), io)
+    got_a = mla.absorb_q(to_torch(q, io), to_torch(Wk, io))
+    got_o = mla.out_proj(to_torch(o, io), to_torch(Wv, io))
+    torch.cuda.synchronize()
+    assert max_abs_rel(widen_gpu(got_a), oracle.absorb_q(q, Wk)) <= TOL[io]
+    assert max_abs_rel(widen_gpu(got_o), oracle.out_proj(o, Wv)) <= TOL[io]
+
+
+# ------------------------------------------------------------ decode, fp32
+
+@pytest.mark.parametrize("num_splits", [1, 4, 16])
+def test_decode_C1_fp32_full(mla, num_splits):
+    """Config 1 at full size: fp32 cache and io, 1024 tokens, identity page table."""
+    w = synth.config("C1")
+    err = check_decode(mla, w, num_splits)
+    assert err <= 1e-5
+
+
+def test_step_C1_fp32_three_calls(mla):
+    import torch
+    w = synth.config("C1")
+    d = DeviceWorkload(w)
+    q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+    o_lat = run_decode(mla, d, q_abs, 4)[0]
+    out = mla.out_proj(o_lat, d.W_UV)
+    torch.cuda.synchronize()
+    ref = oracle.mla_step(w.q_nope, w.q_rope, w.W_UK, w.W_UV, w.pool, None, w.page_table,
+                          w.seq_lens, w.softmax_scale)
+    assert max_abs_rel(widen_gpu(q_abs), ref["q_abs"]) <= 1e-5
+    assert max_abs_rel(widen_gpu(o_lat), ref["o_lat"]) <= 1e-5
+    assert max_abs_rel(widen_gpu(out), ref["out"]) <= 1e-5
+
+
+# ------------------------------------- decode, bf16: matrix-core + portable
+
+RAGGED = [1, 63, 64, 65, 127, 128, 129, 700, 1, 2048, 33, 1000]
+
+
+def ragged_workload(d_c=512, H=32, lens=RAGGED, seed=3, cache="bf16", io="bf16", **kw):
+    return synth.make_workload("ragged", B=len(lens), H=H, d_head=128, d_c=d_c, d_rope=64,
+                               seq_lens=lens, io_dtype=io, cache_dtype=cache, placement="random",
+                               free_frac=0.2, seed=seed, **kw)
+
+
+@pytest.mark.parametrize("num_splits", [1, 2, 7, 32])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_decode_bf16_ragged(mla, num_splits, flags):
+    """Lengths around the page size, several pages, ragged tails, NaN-poisoned
+    free pages and tail slots; both kernels."""
+    check_decode(mla, ragged_workload(), num_splits, flags)
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+def test_decode_bf16_C4_shape(mla, flags):
+    """28 heads (padded to the 32-row tile), d_c = 256."""
+    w = ragged_workload(d_c=256, H=28, lens=[4096 // 4, 100, 640, 64, 1], seed=4)
+    check_decode(mla, w, 2, flags)
+    check_decode(mla, w, 5, flags)
+
+
+def test_decode_bf16_C3_shrunk(mla):
+    """Variable lengths, 10 % of the pool free, k_rope x4."""
+    w = synth.config("C3", shrink=8)
+    check_decode(mla, w, w.num_splits)
+    check_decode(mla, w, 1, flags=1)
+
+
+def test_decode_fp8_cache(mla):
+    """fp8 e4m3 cache with one fp32 scale per token, bf16 and fp32 io."""
+    w = synth.config("C5", shrink=32)
+    check_decode(mla, w, w.num_splits)
+    check_decode(mla, w, 3)
+    w2 = ragged_workload(cache="fp8_e4m3", io="f32", lens=[1, 65, 300, 64], seed=9)
+    check_decode(mla, w2, 2, tol=1e-5)
+
+
+def test_decode_f32_io_bf16_cache(mla):
+    w = ragged_workload(cache="bf16", io="f32", lens=[130, 64, 7], seed=10)
+    check_decode(mla, w, 2, tol=1e-5)
+
+
+def test_mfma_matches_portable_kernel(mla):
+    """Two independent GPU implementations of the same call agree far inside the bar."""
+    import torch
+    w = ragged_workload(seed=11)
+    d = DeviceWorkload(w)
+    q_abs = gpu_q_abs(mla, d)
+    a = widen_gpu(run_decode(mla, d, q_abs, 4, 0)[0])
+    b = widen_gpu(run_decode(mla, d, q_abs, 4, 1)[0])
+    torch.cuda.synchronize()
+    assert max_abs_rel(a, b) <= 1e-2
+
+
+# ------------------------------------------------------------- edge cases
+
+def test_empty_and_single_token_sequences(mla):
+    import torch
+    w = ragged_workload(lens=[0, 1, 0, 64, 5], seed=12)
+    for flags in (0, 1):
+        d = DeviceWorkload(w)
+        q_abs = gpu_q_abs(mla, d)
+        o, lse = run_decode(mla, d, q_abs, 3, flags)
+        torch.cuda.synchronize()
+        o, lse = widen_gpu(o), widen_gpu(lse)
+        assert (o[0] == 0).all() and (o[2] == 0).all()
+        assert np.isneginf(lse[0]).all() and np.isneginf(lse[2]).all()
+        ref_o, ref_lse = oracle_decode(w, q_abs_storage(q_abs))
+        assert max_abs_rel(o, ref_o) <= 2e-2
+        # one cached token: the output is that token's latent row (softmax over one element)
+        row = oracle.widen(w.pool.reshape(-1, 576)[int(w.page_table[1, 0]) * 64])[:512]
+        assert np.abs(o[1] - row[None, :]).max() <= 2 ** -8 * np.abs(row).max()
+        assert lse_err(lse, ref_lse) <= 2e-2
+
+
+def test_out_of_pool_page_ids_are_skipped_not_dereferenced(mla):
+    """A page id outside [0, num_pages) inside the live range: its tokens are skipped."""
+    import torch
+    w = ragged_workload(lens=[256, 200], seed=13)
+    bad = w.page_table.copy()
+    bad[0, 1] = -1
+    bad[1, 2] = w.num_pages + 7
+    # oracle view: the same sequences with those pages removed
+    keep0 = [0, 2, 3]
+    keep1 = [0, 1, 3]
+    w_ref = ragged_workload(lens=[256, 200], seed=13)
+    pt = np.full_like(w.page_table, -1)
+    pt[0, :3] = w.page_table[0, keep0]
+    pt[1, :3] = w.page_table[1, keep1]
+    # sequence 1: pages 0,1 full, page 3 has 200-192 = 8 rows -> 136 tokens
+    lens_ref = np.array([192, 136], dtype=np.int32)
+    for flags in (0, 1):
+        d = DeviceWorkload(w)
+        d.page_table = to_torch(bad, "i32")
+        q_abs = gpu_q_abs(mla, d)
+        o, _ = run_decode(mla, d, q_abs, 2, flags)
+        torch.cuda.synchronize()
+        ref_o, _ = oracle.decode_absorbed(q_abs_storage(q_abs), w.q_rope, w_ref.pool, None, pt,
+                                          lens_ref, w.softmax_scale)
+        assert max_abs_rel(widen_gpu(o), ref_o) <= 2e-2
+
+
+def test_placement_invariance_and_determinism_bitwise(mla):
+    """Same logical rows at different physical pages -> identical output bits; and
+    the same call twice -> identical bits (fixed reduction order)."""
+    import torch
+    lens = [500, 64, 129]
+    a = ragged_workload(lens=lens, seed=14)
+    d = DeviceWorkload(a)
+    q_abs = gpu_q_abs(mla, d)
+    # rebuild the same rows under another placement: permute pages of the pool
+    perm = synth.stream(99, 1).permutation(a.num_pages).astype(np.int32)   # new index of page p
+    pool2 = np.empty_like(a.pool)
+    pool2[perm] = a.pool
+    pt2 = np.where(a.page_table >= 0, perm[np.maximum(a.page_table, 0)], -1).astype(np.int32)
+    for flags in (0, 1):
+        o1, l1 = run_decode(mla, d, q_abs, 3, flags)
+        o1b, _ = run_decode(mla, d, q_abs, 3, flags)
+        d2 = DeviceWorkload(a)
+        d2.pool = to_torch(pool2, "bf16")
+        d2.page_table = to_torch(pt2, "i32")
+        o2, l2 = run_decode(mla, d2, q_abs, 3, flags)
+        torch.cuda.synchronize()
+        assert storage_bits(o1).tobytes() == storage_bits(o1b).tobytes()
+        assert storage_bits(o1).tobytes() == storage_bits(o2).tobytes()
+        assert storage_bits(l1).tobytes() == storage_bits(l2).tobytes()
+
+
+def test_dominant_score_and_uniform_weights(mla):
+    """Closed forms on the GPU: a zero query averages the rows; one score far above
+    the rest selects its row (no overflow in the running softmax)."""
+    import torch
+    w = ragged_workload(lens=[300, 300], seed=15)
+    d = DeviceWorkload(w)
+    rows = oracle.widen(oracle.gather_paged(w.pool, w.page_table, w.seq_lens, 300).view(np.uint16))
+    for flags in (0, 1):
+        q0 = torch.zeros((2, 32, 512), dtype=torch.bfloat16, device="cuda")
+        r0 = torch.zeros((2, 32, 64), dtype=torch.bfloat16, device="cuda")
+        o, lse = mla.decode_paged(q0, r0, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                  num_splits=2, return_lse=True, flags=flags)
+        torch.cuda.synchronize()
+        mean = rows[:, :, :512].mean(axis=1)
+        assert np.abs(widen_gpu(o) - mean[:, None, :]).max() <= 2e-2 * np.abs(mean).max() + 1e-3
+        assert np.abs(widen_gpu(lse) - math.log(300)).max() <= 1e-3
+        # query = 40 x (row 217's latent): its score dominates all others by a wide margin
+        target = rows[:, 217, :512]
+        q1 = to_torch(synth.to_bf16_bits((40.0 * target[:, None, :].repeat(32, 1)).astype(np.float32)), "bf16")
+        o, lse = mla.decode_paged(q1, r0, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                  num_splits=2, return_lse=True, flags=flags)
+        torch.cuda.synchronize()
+        assert np.isfinite(widen_gpu(o)).all() and np.isfinite(widen_gpu(lse)).all()
+        assert np.abs(widen_gpu(o) - target[:, None, :]).max() <= 2e-2 * np.abs(target).max()
+
+
+def test_GQA_reduction_on_gpu(mla):
+    """Sec. 4.1 at GPU size: H = 32 heads in g = 2 groups, d_head = 128, latent
+    = [k_1 k_2 v_1 v_2] (d_c = 512), selector-identity W_UK / W_UV: the three
+    calls reproduce textbook grouped-query attention."""
+    import torch
+    H, g, dh, d_c = 32, 2, 128, 512
+    w = ragged_workload(lens=[200, 77], seed=16, softmax_scale=1 / math.sqrt(dh))
+    Wk = np.zeros((H, dh, d_c), dtype=np.float32)
+    Wv = np.zeros((H, d_c, dh), dtype=np.float32)
+    for i in range(1, H + 1):
+        kk = math.ceil(i / (H / g))
+        Wk[i - 1, :, (kk - 1) * dh:kk * dh] = np.eye(dh)
+        Wv[i - 1, (g + kk - 1) * dh:(g + kk) * dh, :] = np.eye(dh)
+    d = DeviceWorkload(w)
+    d.W_UK, d.W_UV = to_torch(synth.to_bf16_bits(Wk), "bf16"), to_torch(synth.to_bf16_bits(Wv), "bf16")
+    zero_rope = torch.zeros_like(d.q_rope)
+    q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+    o_lat = mla.decode_paged(q_abs, zero_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale, num_splits=2)
+    out = widen_gpu(mla.out_proj(o_lat, d.W_UV))
+    torch.cuda.synchronize()
+    q = oracle.widen(w.q_nope)
+    want = np.zeros((2, H, dh))
+    dense = oracle.widen(oracle.gather_paged(w.pool, w.page_table, w.seq_lens, 200).view(np.uint16))
+    for b, L in enumerate([200, 77]):
+        rows = dense[b, :L]
+        for i in range(H):
+            kk = i // (H // g)
+            K, V = rows[:, kk * dh:(kk + 1) * dh], rows[:, (g + kk) * dh:(g + kk + 1) * dh]
+            s = (K @ q[b, i]) * w.softmax_scale
+            p = np.exp(s - s.max())
+            want[b, i] = (p / p.sum()) @ V
+    assert max_abs_rel(out, want) <= 2e-2
+
+
+# ---------------------------------- full-size configurations (sampled rows)
+
+def test_step_C2_full_three_calls(mla):
+    """Headline configuration at full size, launch configuration of the benchmark:
+    batch 16, context 8192, bf16, random page placement, 16 chunks.  The oracle
+    checks every sequence and head."""
+    import torch
+    w = synth.config("C2")
+    d = DeviceWorkload(w)
+    q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+    o_lat, lse = run_decode(mla, d, q_abs, w.num_splits)
+    out = mla.out_proj(o_lat, d.W_UV)
+    torch.cuda.synchronize()
+    ref_q = oracle.absorb_q(w.q_nope, w.W_UK)
+    assert max_abs_rel(widen_gpu(q_abs), ref_q) <= 2e-2
+    ref_o, ref_lse = oracle_decode(w, q_abs_storage(q_abs))
+    assert max_abs_rel(widen_gpu(o_lat), ref_o) <= 2e-2
+    assert lse_err(widen_gpu(lse), ref_lse) <= 2e-2
+    ref_out = oracle.out_proj(storage_bits(o_lat), w.W_UV)
+    assert max_abs_rel(widen_gpu(out), ref_out) <= 2e-2
+    # and the whole chain against the un-rounded fp64 chain
+    chain = oracle.mla_step(w.q_nope, w.q_rope, w.W_UK, w.W_UV, w.pool, None, w.page_table,
+                            w.seq_lens, w.softmax_scale)
+    assert max_abs_rel(widen_gpu(out), chain["out"]) <= 2e-2
+
+
+def test_decode_C4_full_sampled(mla):
+    w = synth.config("C4")
+    check_decode(mla, w, w.num_splits, b_sel=[0, 1, 63, 64, 127])
+
+
+def test_decode_C3_full_sampled(mla):
+    w = synth.config("C3")
+    order = np.argsort(w.seq_lens)
+    b_sel = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, w.B - 1})
+    check_decode(mla, w, w.num_splits, b_sel=b_sel)
+
+
+def test_decode_C5_full_sampled(mla):
+    """fp8 cache, 131072-token context, 32 chunks; one of the four sequences checked."""
+    w = synth.config("C5")
+    check_decode(mla, w, w.num_splits, b_sel=[2])
