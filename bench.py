@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the absorbed MLA decode step on one MI355X.
+
+A step = mla_absorb_q -> mla_decode_paged (split-KV kernel + merge) ->
+mla_out_proj on one stream, for one batch of synthetic input already resident
+in HBM.  Workload: LLaMA-2-7B-shaped converted layer, batch 16, every
+sequence at context 8192, bf16 storage / fp32 accumulate, 64-token pages in a
+random physical order (H=32, d_head=128, d_c=512, d_rope=64).
+
+The timed loop cycles over several distinct copies of the cache so every step
+streams its 151 MB from HBM rather than from the 256 MB last-level cache.
+
+Prints ONE JSON line: us/step for the whole step, plus
+  roofline     - the split-KV decode kernel against the 8 TB/s HBM peak,
+                 its launches timed with events on the launch stream;
+  cpu_baseline - the fp64 CPU oracle timed on a bounded sample (reported
+                 baseline only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+sys.path.insert(0, str(ROOT / "tests"))
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--copies", type=int, default=6, help="distinct cache copies cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch the page-gather kernel (a plain copy of the whole cache, "
+                         "known size) so hardware byte counters can be scaled against it")
+    ap.add_argument("--traffic-json", default=str(ROOT / "profiles" / "decode_mfma_C2_traffic.json"),
+                    help="HBM traffic per launch from rocprofv3 counters, if recorded")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (collectives and sharding are not part "
+              "of it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from helpers import DeviceWorkload
+    from paper_2502_07864_amd import mla, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    mla.lib()
+
+    w = synth.config("C2")
+    d = DeviceWorkload(w, "cuda:0")
+    B, H, d_c, S = w.B, w.H, w.d_c, w.num_splits
+    # distinct HBM copies of cache + page table (copy i: pages rotated by i within the pool)
+    pools, tables = [], []
+    for i in range(max(1, args.copies)):
+        if i == 0:
+            pools.append(d.pool)
+            tables.append(d.page_table)
+        else:
+            shift = (i * 977) % w.num_pages
+            pools.append(torch.roll(d.pool, shifts=shift, dims=0).contiguous())
+            tables.append(((d.page_table + shift) % w.num_pages).to(torch.int32).contiguous())
+    ws = torch.empty(mla.decode_workspace_bytes(B, H, d_c, S), dtype=torch.uint8, device="cuda:0")
+    q_abs = torch.empty((B, H, d_c), dtype=torch.bfloat16, device="cuda:0")
+    o_lat = torch.empty((B, H, d_c), dtype=torch.bfloat16, device="cuda:0")
+    out = torch.empty((B, H, w.d_head), dtype=torch.bfloat16, device="cuda:0")
+
+    def step(i, events=None):
+        k = i % len(pools)
+        mla.absorb_q(d.q_nope, d.W_UK, out=q_abs)
+        if events is not None:
+            events[0].record()
+        mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
+                         num_splits=S, workspace=ws, flags=mla.FLAG_SKIP_MERGE)
+        if events is not None:
+            events[1].record()
+        mla.merge_partials(ws, B, H, d_c, S, torch.bfloat16, out=o_lat)
+        if events is not None:
+            events[2].record()
+        mla.out_proj(o_lat, d.W_UV, out=out)
+
+    if args.calib_copy:
+        for _ in range(3):
+            mla.gather_paged(d.pool, d.page_table, d.seq_lens, int(w.seq_lens.max()))
+        torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert torch.isfinite(out.float()).all()
+
+    # second pass over the same steps with events around the decode kernel and the merge
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    dec_us = np.array([e[0].elapsed_time(e[1]) * 1e3 for e in evs])
+    mrg_us = np.array([e[1].elapsed_time(e[2]) * 1e3 for e in evs])
+
+    cache_bytes = w.cache_bytes_per_step                      # 1152 B x 131072 tokens
+    dec_avg_us = float(dec_us.mean())
+    achieved = cache_bytes / (dec_avg_us * 1e-6) / 1e9
+    traffic = None
+    tp = Path(args.traffic_json)
+    if tp.exists():
+        try:
+            traffic = json.loads(tp.read_text()).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    rec = {
+        "metric": "MLA decode us/step (absorb + paged split-KV decode + out-proj), bs16 ctx8K bf16, 1 GPU",
+        "value": round(ms_per_step * 1e3, 3),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "C2: LLaMA-2-7B-shaped converted layer, batch 16 x context 8192, "
+                               "H=32 d_head=128 d_c=512 d_rope=64, bf16 cache in 64-token pages "
+                               "(random placement), 16 KV chunks per sequence",
+                   "batch": B, "context": int(w.seq_lens[0]), "num_splits": S,
+                   "cache_copies_cycled": len(pools)},
+        "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "step_hbm_GBps": round(cache_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_hbm_frac": round(cache_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "kernels_us": {"decode_split_kv": {"avg": round(dec_avg_us, 2),
+                                           "p10": round(float(np.percentile(dec_us, 10)), 2),
+                                           "p50": round(float(np.percentile(dec_us, 50)), 2),
+                                           "p90": round(float(np.percentile(dec_us, 90)), 2)},
+                       "merge": {"avg": round(float(mrg_us.mean()), 2)}},
+        "roofline": {"bound": "hbm", "kernel": "decode_mfma_bf16_kernel<512>",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": cache_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        n = max(1, min(args.cpu_seqs, B))
+        sel = np.arange(n)
+        times = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.mla_step(w.q_nope[sel], w.q_rope[sel], w.W_UK, w.W_UV, w.pool, None,
+                            w.page_table[sel], w.seq_lens[sel], w.softmax_scale)
+            times.append(time.perf_counter() - t0)
+        t_cpu = sorted(times)[1]
+        rec["cpu_baseline"] = {
+            "value": round(t_cpu * (B / n) * 1e6, 1), "unit": "us/step",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n} of {B} sequences (all 32 heads, 8192 tokens each), fp64 absorbed oracle "
+                      f"(absorb + decode + out-proj), median of 3 runs = {t_cpu:.2f} s, scaled by {B}/{n}"}
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

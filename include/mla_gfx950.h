@@ -57,8 +57,12 @@ typedef enum {
 /* Flags for mla_decode_paged. */
 enum {
     MLA_FLAG_DEFAULT        = 0,
-    MLA_FLAG_PORTABLE_KERNEL = 1  /* force the scalar-FMA kernel even where the
+    MLA_FLAG_PORTABLE_KERNEL = 1, /* force the scalar-FMA kernel even where the
                                      matrix-core kernel applies (cross-check)  */
+    MLA_FLAG_SKIP_MERGE      = 2  /* leave the per-chunk partial results in the
+                                     workspace and do not write o_lat / lse: the
+                                     caller merges them with mla_merge_partials
+                                     (o_lat may then be NULL)                  */
 };
 
 /* Human-readable name of a status code.  Static storage; never free it. */
@@ -153,6 +157,21 @@ int mla_decode_paged(const void* q_abs, const void* q_rope,
                      int num_pages, int max_pages_per_seq, int num_splits,
                      float softmax_scale, mla_dtype io_dtype,
                      mla_dtype cache_dtype, unsigned flags, void* hip_stream);
+
+/*
+ * Split-KV reduction on its own: merges the per-chunk partial results a
+ * mla_decode_paged call (same B, H, d_c, num_splits, same workspace) left
+ * behind, exactly as that call does when MLA_FLAG_SKIP_MERGE is not set:
+ *   lse = log sum_s exp(lse_s),   o_lat = sum_s exp(lse_s - lse) o_s
+ * (chunks with lse_s = -inf are skipped; all empty gives zeros and -inf).
+ * This is the softmax identity behind chunked evaluation; it lets a caller
+ * time or overlap the two phases, or merge chunks computed elsewhere.
+ *   workspace  [in]  as written by mla_decode_paged
+ *   o_lat      [B, H, d_c] io dtype (output);  lse [B, H] fp32 (output, may be NULL)
+ */
+int mla_merge_partials(const void* workspace, size_t workspace_bytes,
+                       void* o_lat, float* lse, int B, int H, int d_c,
+                       int num_splits, mla_dtype io_dtype, void* hip_stream);
 
 /*
  * Test hook: the logical (un-paged) view of the cache, byte for byte, using

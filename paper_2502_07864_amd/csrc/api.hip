@@ -69,7 +69,8 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
                      int num_splits, float softmax_scale, mla_dtype io_dtype, mla_dtype cache_dtype,
                      unsigned flags, void* hip_stream)
 {
-    if (!q_abs || !kv_cache || !page_table || !seq_lens || !o_lat) return MLA_ERR_NULL;
+    const bool skip_merge = (flags & MLA_FLAG_SKIP_MERGE) != 0;
+    if (!q_abs || !kv_cache || !page_table || !seq_lens || (!o_lat && !skip_merge)) return MLA_ERR_NULL;
     if (d_rope > 0 && !q_rope) return MLA_ERR_NULL;
     if (B <= 0 || H <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
         max_pages_per_seq <= 0 || num_splits <= 0)
@@ -106,11 +107,31 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
     else
         e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
     if (e != hipSuccess) return MLA_ERR_HIP;
+    if (skip_merge) return MLA_OK;
 
     MergeParams m;
     m.o_part = p.o_part; m.lse_part = p.lse_part; m.o_lat = o_lat; m.lse = lse;
     m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
     e = launch_merge(m, io_dtype, stream);
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_lat, float* lse,
+                       int B, int H, int d_c, int num_splits, mla_dtype io_dtype, void* hip_stream)
+{
+    if (!o_lat) return MLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || B > 65535 || d_c % 4) return MLA_ERR_UNSUPPORTED;
+    const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return MLA_ERR_WORKSPACE;
+    MergeParams m;
+    m.o_part = static_cast<const float*>(workspace);
+    m.lse_part = reinterpret_cast<const float*>(
+        static_cast<const char*>(workspace) + align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
+    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+    hipError_t e = launch_merge(m, io_dtype, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 

@@ -2,73 +2,96 @@
 //
 // Second line of the absorbed attention equation (Sec. 3.3 of the paper): all
 // H heads score against the ONE shared row k_hat_j = [c_j ; k^R_j] and weight
-// the same latent rows c_j, so per 64-token page both contractions are dense:
-//     S^T [64 tok x 32 heads] = K [64 x (d_c+64)] . Q^T [(d_c+64) x 32]
-//     O^T [d_c x 32 heads]   += V^T [d_c x 64 tok] . P^T [64 x 32]
+// the same latent rows c_j, so per tile of cached rows both contractions are
+// dense:
+//     S^T [tok x heads]   = K [tok x (d_c+64)] . Q^T [(d_c+64) x heads]
+//     O^T [d_c x heads]  += V^T [d_c x tok] . P^T [tok x heads]
 // with V = the first d_c columns of the very same LDS tile as K.
 //
-// Work decomposition (one workgroup = 4 wavefronts per (chunk, sequence)):
-//   wave = (hg, tg): head group hg (16 heads) x token half tg (32 of the 64
-//   rows of each page).  Each wave runs a complete, private online softmax for
-//   its 16 heads over its own rows, so the only workgroup barrier per page is
-//   the one that hands over the LDS tile; the two token halves are merged once
-//   at the end.  The page goes HBM -> LDS once (direct-to-LDS 128-bit loads,
-//   double buffered) and is read from LDS by both head groups.
+// Data movement.  The kernel is bound by streaming the cache from HBM, so the
+// design goal is to keep as many bytes in flight per CU as LDS allows.  A tile
+// is half a page (32 rows); a ring of four tiles fills LDS (4 x 36 KB at
+// d_c = 512).  One tile is being consumed while up to three are in flight as
+// direct-to-LDS 128-bit loads; a tile is requested the moment its ring slot is
+// released.  Every row is fetched from HBM exactly once per workgroup and
+// serves all heads.
 //
-// Operand layouts (v_mfma_f32_16x16x32_bf16, lane = 16*g + n):
-//   A holds row n, k = 8g..8g+7; B holds column n, k = 8g..8g+7;
-//   D holds rows 4g..4g+3 of column n.
-// Transposed formulation: S^T puts heads on the D columns, so every lane owns
-// ONE head: row max / sum need two cross-lane steps, the rescale factor is a
-// per-lane scalar, and the exponentiated scores are already the B operand of
-// the second contraction if its k-slots are ordered (4g+i, 16+4g+i).  The A
-// operand V^T (token-contiguous per lane) comes from ds_read_b64_tr_b16, which
+// Work decomposition (workgroup = 4 wavefronts per (chunk, sequence)):
+//   wave = (hg, tg): head group hg (16 heads) x row half tg (16 of the 32 rows).
+//   Each wave runs a complete private online softmax for its 16 heads over its
+//   own rows, so the only workgroup barrier per tile is the one that publishes
+//   the tile; the two row halves are merged once at the end.
+//
+// Operand layouts (lane = 16*g + n):
+//   v_mfma_f32_16x16x32_bf16: A = row n, k = 8g..8g+7; B = column n, k = 8g..8g+7
+//   v_mfma_f32_16x16x16_bf16: A = row n, k = 4g..4g+3; B = column n, k = 4g..4g+3
+//   both:                     D = rows 4g..4g+3 of column n.
+// Transposed formulation: S^T puts heads on the D columns, so every lane owns ONE
+// head: the row maximum needs two cross-lane steps, the rescale factor is a
+// per-lane scalar, and the exponentiated scores (rows 4g..4g+3) are, as they
+// stand, the B operand of the second contraction.  Its A operand V^T (four
+// consecutive rows of one column per lane) comes from ds_read_b64_tr_b16, which
 // transposes 4x16 blocks of 16-bit elements while reading LDS.
 //
-// LDS layout: row r of the tile occupies bytes [r*ROWB, (r+1)*ROWB); inside a
-// row, 16-byte chunk c is stored at chunk position c ^ ((r >> 1) & 7).  With
-// ROWB = 1152 or 640 bytes (= 32 banks mod 64) this makes both the row-wise
-// 128-bit reads of 16 consecutive rows and the transposing reads conflict free.
+// LDS layout: row r of a tile occupies bytes [r*ROWB, (r+1)*ROWB); inside a row,
+// 16-byte chunk c is stored at chunk position c ^ ((r >> 1) & 7), which spreads
+// both the row-wise 128-bit reads of 16 consecutive rows and the transposing
+// reads over the banks.
 #include "mla_internal.h"
 
 namespace mla {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 #define LDS_AS __attribute__((address_space(3)))
 #define CONST_AS __attribute__((address_space(4)))
 
 constexpr int MF_THREADS = 256;
+constexpr int TILE_ROWS = 32;     // cached rows per tile (half a page)
+constexpr int NBUF = 4;           // tiles in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float RESCALE_GAP = 32.f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// two fp32 -> packed bf16x2, round to nearest even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 template <int D_C>
-__global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_bf16_kernel(DecodeParams p)
+__global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_bf16_kernel(DecodeParams p)
 {
     constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
-    constexpr int TILE_B = 64 * ROWB;           // bytes per page
-    constexpr int NLOAD = TILE_B / (MF_THREADS * 16);  // 16-byte loads per thread per page
-    constexpr int NKS = ROW / 32;               // k-steps of the score contraction
-    constexpr int NCT = D_C / 16;               // column tiles of the value contraction
-    static_assert(TILE_B % (MF_THREADS * 16) == 0, "page must split evenly over the loads");
+    constexpr int PAGE_B = 64 * ROWB;           // bytes per page
+    constexpr int TILE_B = TILE_ROWS * ROWB;    // bytes per tile
+    constexpr int NLOAD = TILE_B / (MF_THREADS * 16);  // 16-byte loads per thread per tile (9 / 5)
+    constexpr int NKS = ROW / 32;               // k-steps of the score contraction (18 / 10)
+    constexpr int NCT = D_C / 16;               // column tiles of the value contraction (32 / 16)
+    constexpr int SG = NKS % 3 == 0 ? 3 : 2;    // k-steps per read-ahead group (score)
+    constexpr int VG = 8;                       // column tiles per read-ahead group (value)
+    static_assert(TILE_B % (MF_THREADS * 16) == 0, "tile must split evenly over the loads");
     static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
+    static_assert(NLOAD * (NBUF - 1) < 64, "vmcnt is a 6-bit counter");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * TILE_B];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
     const int tid = threadIdx.x;
@@ -79,19 +102,20 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_bf16_kernel(DecodeP
     const int split = blockIdx.x, b = blockIdx.y;
 
     // Read-only tables go through the scalar cache: scalar loads do not count against the
-    // vector-memory counter, so looking up a page id never waits on an in-flight page prefetch.
+    // vector-memory counter, so looking up a page id never waits on an in-flight prefetch.
     const CONST_AS int32_t* seq_lens_c = (const CONST_AS int32_t*)p.seq_lens;
     const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
     int L = seq_lens_c[b];
     L = max(0, min(L, p.max_pages * 64));
-    const int n_pages = (L + 63) >> 6;
-    const int pg0 = split * p.chunk_pages;
-    const int pg1 = min(pg0 + p.chunk_pages, n_pages);
+    const int row0 = split * p.chunk_pages * 64;                    // first cached row of this chunk
+    const int row1 = min(row0 + p.chunk_pages * 64, L);             // one past its last row
     const size_t part = ((size_t)b * p.num_splits + split) * p.H;
-    if (pg0 >= pg1) {  // empty chunk: weight zero in the merge, partial output never read
+    if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
         if (tid < p.H) p.lse_part[part + tid] = -INFINITY;
         return;
     }
+    const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
+    const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
 
     // ---- this wave's 16 query rows as B operands, resident for the whole chunk
     const int head = hg * 16 + n;
@@ -110,156 +134,208 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_bf16_kernel(DecodeP
         }
     }
 
-    // ---- page staging: HBM -> registers (128-bit loads, issued one page ahead) -> LDS.
-    // Load k of wave w covers LDS chunks [(4k+w)*64, +64) (contiguous per wave: conflict-free
-    // 128-bit LDS stores); LDS chunk P = row r, position pc holds the row's chunk pc ^ ((r>>1)&7),
-    // so a wave still reads whole 128-byte lines from HBM.
-    uint32_t goff[NLOAD];   // byte offset of this thread's chunk inside a page
-    uint32_t grow[NLOAD];   // its row, for the ragged last page
+    // ---- tile staging: HBM -> LDS with direct-to-LDS 128-bit loads.
+    // Load k of wave w fills LDS chunks [(4k+w)*64, +64) of the tile (the hardware writes lane
+    // i at base + 16 i); LDS chunk P = row r, position pc holds the row's chunk
+    // pc ^ ((r>>1)&7), so a wave still reads whole 128-byte lines from HBM.  The loads are
+    // written as inline assembly on purpose: the compiler then keeps no record of pending LDS
+    // writes and does not make LDS reads of the other ring slots wait for them.  Completion is
+    // awaited explicitly (vmcnt) before the barrier that publishes a tile.
+    uint32_t goff[NLOAD];   // byte offset of this thread's chunk inside a tile's rows
 #pragma unroll
     for (int k = 0; k < NLOAD; ++k) {
         int P = (k * 4 + wave) * 64 + lane;
         int r = P / CPR, pc = P % CPR;
         goff[k] = (uint32_t)(r * ROWB + ((pc ^ ((r >> 1) & 7)) << 4));
-        grow[k] = (uint32_t)r;
     }
-    const uint32_t st_off = (uint32_t)(wave * 1024 + lane * 16);  // + k*4096: where load k lands in a tile
-
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     const unsigned char* kv = static_cast<const unsigned char*>(p.kv);
-    u32x4 stg[NLOAD];
 
-    // rows of page pg that belong to the sequence (0 if its page id is outside the pool)
-    auto rows_valid = [&](int pg) {
-        int page = ptab[pg];
-        return (page >= 0 && page < p.num_pages) ? min(64, L - pg * 64) : 0;
+    // rows of tile t that belong to this chunk (0 if its page id is outside the pool)
+    auto rows_valid = [&](int t) {
+        int page = ptab[t >> 1];
+        return (page >= 0 && page < p.num_pages) ? min(TILE_ROWS, row1 - t * TILE_ROWS) : 0;
     };
-    // Rows past the end of the sequence are never fetched: they become zeros in LDS, so
-    // whatever those slots hold (NaN included) cannot reach the accumulators.
-    auto fetch_tile = [&](int pg) {
-        const int nv = rows_valid(pg);
-        const unsigned char* src = kv + (size_t)(nv > 0 ? ptab[pg] : 0) * TILE_B;
-        if (nv == 64) {  // whole page (the common case): no per-lane predicate
+    // returns the number of loads this thread issued (0 or NLOAD; uniform)
+    auto fetch_tile = [&](int t) -> int {
+        if (rows_valid(t) <= 0) return 0;   // a page outside the pool is never dereferenced
+        const unsigned char* src = kv + (size_t)ptab[t >> 1] * PAGE_B + (size_t)(t & 1) * TILE_B;
+        const uint32_t dst = lds_base + (uint32_t)(((t - t0) % NBUF) * TILE_B + wave * 1024);
 #pragma unroll
-            for (int k = 0; k < NLOAD; ++k) stg[k] = *reinterpret_cast<const u32x4*>(src + goff[k]);
-        } else {
-#pragma unroll
-            for (int k = 0; k < NLOAD; ++k) {
-                u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-                if ((int)grow[k] < nv) v = *reinterpret_cast<const u32x4*>(src + goff[k]);
-                stg[k] = v;
-            }
+        for (int k = 0; k < NLOAD; ++k) {
+            const unsigned char* gp = src + goff[k];
+            const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(m0v), "v"(gp) : "memory");
         }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int k = 0; k < NLOAD; ++k)
-            *(LDS_AS u32x4*)(lds + buf * TILE_B + k * 4096 + st_off) = stg[k];
+        return NLOAD;
     };
 
     // ---- running softmax state: this lane's head = column n of the D tiles
-    float m_run = -INFINITY;   // running max of scaled scores, in log2 units
-    float l_run = 0.f;         // this lane's share of the running sum (its 8 rows per page)
+    float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
+    float l_run = 0.f;         // this lane's share of the running sum (its 4 rows per tile)
     f32x4 oacc[NCT];
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct) oacc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const float sc = p.scale * LOG2E;
-    // LDS byte offsets that do not depend on the page.  A swizzled chunk index splits into a
+    // LDS byte offsets that do not depend on the tile.  A swizzled chunk index splits into a
     // per-lane part (low 3 bits, xor-ed with the row key) and a compile-time part (high bits).
-    // score A operand: row 32tg + n (+16), chunk 4ks + g
-    const uint32_t a_row = (uint32_t)((tg * 32 + n) * ROWB);
+    // score A operand: row 16tg + n, chunk 4ks + g
+    const uint32_t a_row = (uint32_t)((tg * 16 + n) * ROWB);
     const uint32_t a_key = (uint32_t)(n >> 1);
     uint32_t a_base[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e) a_base[e] = a_row + ((((uint32_t)(4 * e + g)) ^ a_key) << 4);
-    // value A operand (transposing read): the lane supplies row 32tg + 4g + (n>>2) (+16),
+    // value A operand (transposing read): the lane supplies row 16tg + 4g + (n>>2),
     // 8 bytes at element column 16ct + 4(n&3), i.e. chunk 2ct + ((n&3)>>1), half (n&1)
-    const uint32_t v_row = (uint32_t)((tg * 32 + g * 4 + (n >> 2)) * ROWB);
+    const uint32_t v_row = (uint32_t)((tg * 16 + g * 4 + (n >> 2)) * ROWB);
     const uint32_t v_key = (uint32_t)((2 * g + (n >> 3)) & 7);
     uint32_t v_base[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8);
 
-    fetch_tile(pg0);
-    store_tile(0);
-    if (pg0 + 1 < pg1) fetch_tile(pg0 + 1);
-
-    for (int pg = pg0; pg < pg1; ++pg) {
-        const int buf = (pg - pg0) & 1;
-        // the tile of this page is complete in LDS, and every wave has finished reading the
-        // other buffer (which receives the next page at the end of this iteration)
-        __syncthreads();
-        const int n_valid = rows_valid(pg);
-        LDS_AS unsigned char* tile = lds + buf * TILE_B;
-
-        // ---- S^T = K . Q^T for this wave's 32 rows x 16 heads
-        f32x4 sacc[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+    // The query loads were issued first and overlap the page-table lookups.  Pin their
+    // completion here, before any tile load exists: a wait placed later would also have to
+    // wait for the (younger, in-order) tile loads.
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            LDS_AS unsigned char* ap = tile + a_base[ks & 1] + (ks >> 1) * 128;
-            bf16x8 a0 = *(LDS_AS bf16x8*)(ap);
-            bf16x8 a1 = *(LDS_AS bf16x8*)(ap + 16 * ROWB);
-            sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[ks], sacc[0], 0, 0, 0);
-            sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[ks], sacc[1], 0, 0, 0);
-        }
+    for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
 
-        // ---- online softmax for head n over rows {32tg + 16mt + 4g + i}
-        float x[8];
-        float tmax = -INFINITY;
+    // loads issued for the tiles after the one being consumed, oldest first
+    int ahead[NBUF - 1];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+    for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
+    fetch_tile(t0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int tok = tg * 32 + mt * 16 + g * 4 + i;
-                float v = tok < n_valid ? sacc[mt][i] * sc : -INFINITY;
-                x[mt * 4 + i] = v;
-                tmax = fmaxf(tmax, v);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        uint32_t pw[4];
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            uint32_t w = pack_bf16x2(fast_exp2(x[2 * i] - m_use), fast_exp2(x[2 * i + 1] - m_use));
-            pw[i] = w;
-            psum += bf16_bits_to_f32(w & 0xFFFFu) + bf16_bits_to_f32(w >> 16);  // sum what is multiplied
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){pw[0], pw[1], pw[2], pw[3]});
+    for (int i = 0; i < NBUF - 2; ++i)
+        if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
 
+    // The tile loop is a hot inner loop that only ever touches the output accumulators with
+    // MFMA, nested in an outer loop whose body (rarely run) rescales them.  Exponentials are
+    // taken against a per-head reference m_run.  A head adopts its first finite tile maximum as
+    // reference (nothing is accumulated yet, so nothing needs rescaling); after that the
+    // reference only moves when a tile's maximum exceeds it by more than RESCALE_GAP (log2
+    // units), so p <= 2^RESCALE_GAP.  When that happens the inner loop is left before the tile
+    // is accumulated, the accumulators are rescaled, and the tile is scored again.
+    int t = t0;
+    bool staged = false;       // tile t has already been through its wait / barrier / prefetch step
+    float alpha = 1.f;         // pending rescale factor of this lane's head
+    while (true) {
         if (__any(alpha != 1.f)) {
+            l_run *= alpha;
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) oacc[ct] *= alpha;
+            alpha = 1.f;
         }
-
-        // ---- O^T += V^T . P^T
+        bool rescale = false;
+        for (; t < t1; ++t) {
+            LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+            const int n_valid = rows_valid(t);
+            if (!staged) {
+                // wait until my loads of tile t have landed (younger tiles may stay in flight);
+                // after the barrier everybody's have, and every wave is done with tile t-1,
+                // whose ring slot now receives tile t + NBUF - 1
+                const int younger = ahead[0] + ahead[1];
+                if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
+                else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
+                else                       wait_vmcnt<0>();
+                __syncthreads();
+                const int tn = t + NBUF - 1;
+                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+                if (n_valid < TILE_ROWS) {
+                    // ragged last tile (or a page id outside the pool): rows that are not part
+                    // of the sequence become zeros so that whatever they hold stays out
+                    for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
+                        *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+                    __syncthreads();
+                }
+                // tile t+1 becomes the oldest one in flight
 #pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            LDS_AS unsigned char* vp = tile + v_base[ct & 3] + (ct >> 2) * 128;
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vp));
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vp + 16 * ROWB));
-            s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, oacc[ct], 0, 0, 0);
-        }
+                for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
+                ahead[NBUF - 2] = 0;
+            }
+            staged = false;
 
-        // ---- hand the prefetched page to the other buffer, start fetching the one after it
-        if (pg + 1 < pg1) {
-            store_tile(buf ^ 1);
-            if (pg + 2 < pg1) fetch_tile(pg + 2);
+            // ---- S^T = K . Q^T for this wave's 16 rows x 16 heads.  Operand reads run one
+            // group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler
+            // from sinking the reads back next to their uses.
+            f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            bf16x8 a0[NKS];
+#pragma unroll
+            for (int ks = 0; ks < SG; ++ks)
+                a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s0 = 0; s0 < NKS; s0 += SG) {
+#pragma unroll
+                for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks)
+                    a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
+                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+
+            // ---- softmax numerators for head n over rows 16tg + 4g + i
+            float x[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
+            if (n_valid < TILE_ROWS) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (tg * 16 + g * 4 + i >= n_valid) x[i] = -INFINITY;
+            }
+            float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            if (m_run == -INFINITY) m_run = tmax;     // first finite maximum: nothing to rescale yet
+            if (__builtin_expect(__any(tmax > m_run + RESCALE_GAP), 0)) {
+                const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
+                alpha = fast_exp2(m_run - m_new);     // 1 for the lanes that keep their reference
+                m_run = m_new;
+                staged = true;
+                rescale = true;
+                break;
+            }
+            const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
+            const uint32_t p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
+            const uint32_t p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
+            // the normaliser sums exactly the rounded weights that get multiplied
+            l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                     (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
+            const s16x4 pb = __builtin_bit_cast(s16x4, (u32x2){p01, p23});
+
+            // ---- O^T += V^T . P^T, transposing reads one group of VG column tiles ahead
+            s16x4 va[NCT];
+#pragma unroll
+            for (int ct = 0; ct < VG; ++ct)
+                va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c0 = 0; c0 < NCT; c0 += VG) {
+#pragma unroll
+                for (int ct = c0 + VG; ct < c0 + 2 * VG && ct < NCT; ++ct)
+                    va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ct = c0; ct < c0 + VG && ct < NCT; ++ct)
+                    oacc[ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[ct], pb, oacc[ct], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+        if (!rescale) break;
     }
 
-    // ---- merge the two token halves of each head group, normalise, write the partial
+    // ---- merge the two row halves of each head group, normalise, write the partial
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
-    __syncthreads();  // tiles no longer needed: reuse LDS as exchange space
+    __syncthreads();  // tiles no longer needed (nothing is in flight): reuse LDS as exchange space
     constexpr int XCH = NCT * 1024 + 512;  // per head group: O tiles + m + l
+    static_assert(2 * XCH <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* xch = lds + hg * XCH;
     if (tg == 1) {
 #pragma unroll

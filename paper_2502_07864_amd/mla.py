@@ -18,10 +18,11 @@ _LIB_PATH = Path(__file__).resolve().parent / "libmla_gfx950.so"
 _lib = None
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
-FLAG_DEFAULT, FLAG_PORTABLE_KERNEL = 0, 1
+FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE = 0, 1, 2
 
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
-           "mla_decode_workspace_bytes", "mla_decode_paged", "mla_gather_paged")
+           "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
+           "mla_gather_paged")
 
 
 class MlaError(RuntimeError):
@@ -52,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.mla_decode_paged.restype = i
         L.mla_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        i, i, i, i, i, i, i, i, f, i, i, u, vp]
+        L.mla_merge_partials.restype = i
+        L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, vp]
         L.mla_gather_paged.restype = i
         L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
         _lib = L
@@ -157,7 +160,8 @@ def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: 
     need = decode_workspace_bytes(B, H, d_c, num_splits)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_abs.device)
-    if out is None:
+    skip_merge = bool(flags & FLAG_SKIP_MERGE)
+    if out is None and not skip_merge:
         out = torch.empty((B, H, d_c), dtype=q_abs.dtype, device=q_abs.device)
     if lse is None and return_lse:
         lse = torch.empty((B, H), dtype=torch.float32, device=q_abs.device)
@@ -168,6 +172,23 @@ def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: 
         workspace.numel() * workspace.element_size(), B, H, d_c, d_rope, page_size, num_pages,
         page_table.shape[1], num_splits, float(softmax_scale), _io_code(q_abs),
         _cache_code(kv_cache), int(flags), _stream(q_abs)), "mla_decode_paged")
+    if skip_merge:
+        return workspace
+    return (out, lse) if lse is not None else out
+
+
+def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits: int,
+                   dtype: torch.dtype, out: Optional[torch.Tensor] = None,
+                   lse: Optional[torch.Tensor] = None, return_lse: bool = False):
+    """Merge the per-chunk partials left in `workspace` by decode_paged(flags=FLAG_SKIP_MERGE)."""
+    if out is None:
+        out = torch.empty((B, H, d_c), dtype=dtype, device=workspace.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, H), dtype=torch.float32, device=workspace.device)
+    _check(lib().mla_merge_partials(_dev(workspace, "workspace"),
+                                    workspace.numel() * workspace.element_size(),
+                                    _dev(out, "out"), _dev(lse, "lse"), B, H, d_c, num_splits,
+                                    _io_code(out), _stream(workspace)), "mla_merge_partials")
     return (out, lse) if lse is not None else out
 
 
