@@ -105,6 +105,10 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     // vector-memory counter, so looking up a page id never waits on an in-flight prefetch.
     const CONST_AS int32_t* seq_lens_c = (const CONST_AS int32_t*)p.seq_lens;
     const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
+    // touch this chunk's first page-table line now, in parallel with the sequence length
+    // (both are scalar loads): the later look-ups then hit the scalar cache
+    const int warm = ptab[min(split * p.chunk_pages, p.max_pages - 1)];
+    asm volatile("" :: "s"(warm));
     int L = seq_lens_c[b];
     L = max(0, min(L, p.max_pages * 64));
     const int row0 = split * p.chunk_pages * 64;                    // first cached row of this chunk
@@ -196,12 +200,6 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     for (int e = 0; e < 4; ++e)
         v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8);
 
-    // The query loads were issued first and overlap the page-table lookups.  Pin their
-    // completion here, before any tile load exists: a wait placed later would also have to
-    // wait for the (younger, in-order) tile loads.
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
-
     // loads issued for the tiles after the one being consumed, oldest first
     int ahead[NBUF - 1];
 #pragma unroll
@@ -210,6 +208,14 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
 #pragma unroll
     for (int i = 0; i < NBUF - 2; ++i)
         if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+
+    // Pin the completion of the query loads here, outside the tile loop.  Left to itself the
+    // compiler would wait for them at their first use inside the loop, on every iteration, with
+    // a count that ignores the tile loads it does not know about - i.e. it would drain the
+    // prefetch ring each time.  (Vector loads return in order, so this one-time wait also
+    // covers the tiles requested just above.)
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
 
     // The tile loop is a hot inner loop that only ever touches the output accumulators with
     // MFMA, nested in an outer loop whose body (rarely run) rescales them.  Exponentials are
@@ -352,16 +358,30 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
         const float w0 = fast_exp2(m_run - m_use), w1 = fast_exp2(m1 - m_use);
         const float lt = l_w * w0 + l1 * w1;
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        if (head < p.H) {
-            float* dst = p.o_part + (part + head) * D_C + g * 4;
+        // The lane holds 4 consecutive columns of head n per column tile: writing that
+        // straight out would give 64-byte runs.  Transpose through a private LDS area (row
+        // stride padded by 16 bytes: conflict-free both ways) and store whole 1 KB runs.
+        constexpr int RSO = D_C * 4 + 16;
+        static_assert(2 * XCH + 2 * 16 * RSO <= NBUF * TILE_B, "transpose area must fit in the tile ring");
+        LDS_AS unsigned char* tr = lds + 2 * XCH + hg * 16 * RSO;
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                f32x4 o1 = *(LDS_AS f32x4*)(xch + (ct * 64 + lane) * 16);
-                f32x4 o = (oacc[ct] * w0 + o1 * w1) * inv;
-                *reinterpret_cast<f32x4*>(dst + ct * 16) = o;
-            }
-            if (g == 0) p.lse_part[part + head] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+        for (int ct = 0; ct < NCT; ++ct) {
+            f32x4 o1 = *(LDS_AS f32x4*)(xch + (ct * 64 + lane) * 16);
+            f32x4 o = (oacc[ct] * w0 + o1 * w1) * inv;
+            *(LDS_AS f32x4*)(tr + n * RSO + (ct * 16 + g * 4) * 4) = o;
         }
+        // same wavefront wrote and reads this area; LDS executes a wave's accesses in order
+        const int nrow = min(16, p.H - hg * 16);
+        for (int r = 0; r < nrow; ++r) {
+            float* dst = p.o_part + (part + hg * 16 + r) * D_C;
+#pragma unroll
+            for (int c = 0; c < D_C / 256; ++c) {
+                f32x4 v = *(LDS_AS f32x4*)(tr + r * RSO + (c * 64 + lane) * 16);
+                *reinterpret_cast<f32x4*>(dst + (c * 64 + lane) * 4) = v;
+            }
+        }
+        if (head < p.H && g == 0)
+            p.lse_part[part + head] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
     }
 }
 

@@ -241,6 +241,73 @@ __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
     if (p.lse && tid == 0) p.lse[(size_t)b * p.H + h] = z > 0.f ? m + logf(z) : -INFINITY;
 }
 
+// Streaming variant for d_c a multiple of 256 and at most 64 chunks: one wavefront per
+// (sequence, head, block of 256 columns).  Lane s owns the log-sum-exp of chunk s, so the
+// weights come from two wave reductions; every lane streams one float4 per chunk with the
+// loads of up to 16 chunks in flight.
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int blocks_per_row = p.d_c / 256;
+    const int total = p.B * p.H * blocks_per_row;
+    const int wid = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= total) return;
+    const int cb = wid % blocks_per_row;
+    const int bh = wid / blocks_per_row;
+    const int b = bh / p.H, h = bh % p.H;
+    const int S = p.num_splits;
+
+    // Start streaming the first chunks' partial rows before their weights are known (the
+    // weights need a load and two wave reductions).  Rows of empty chunks were never written:
+    // whatever is read there is discarded by a select, not multiplied by zero.
+    constexpr int BATCH = 16;
+    const size_t stride = (size_t)p.H * p.d_c;
+    const float* base = p.o_part + ((size_t)b * S * p.H + h) * p.d_c + cb * 256 + lane * 4;
+    float4 v[BATCH];
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i)
+        if (i < S) v[i] = *reinterpret_cast<const float4*>(base + (size_t)i * stride);
+
+    const float ls = lane < S ? p.lse_part[((size_t)b * S + lane) * p.H + h] : -INFINITY;
+    float m = ls;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    const float e = m == -INFINITY ? 0.f : expf(ls - m);   // exp(-inf) = 0 for empty chunks
+    float z = e;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
+    const float w = z > 0.f ? e / z : 0.f;
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < S; s0 += BATCH) {
+        if (s0 > 0) {
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i)
+                if (s0 + i < S) v[i] = *reinterpret_cast<const float4*>(base + (size_t)(s0 + i) * stride);
+        }
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            if (s0 + i < S) {
+                const float ws = __shfl(w, s0 + i);
+                const bool live = ws != 0.f;
+                acc.x = fmaf(ws, live ? v[i].x : 0.f, acc.x); acc.y = fmaf(ws, live ? v[i].y : 0.f, acc.y);
+                acc.z = fmaf(ws, live ? v[i].z : 0.f, acc.z); acc.w = fmaf(ws, live ? v[i].w : 0.f, acc.w);
+            }
+        }
+    }
+    const size_t o = (size_t)bh * p.d_c + cb * 256 + lane * 4;
+    if (OUT_BF16) {
+        uint2 r;
+        r.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
+        r.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.o_lat) + o) = r;
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(p.o_lat) + o) = acc;
+    }
+    if (p.lse && cb == 0 && lane == 0) p.lse[bh] = z > 0.f ? m + logf(z) : -INFINITY;
+}
+
 // ---- page gather (byte exact) ---------------------------------------------
 __global__ __launch_bounds__(256) void gather_kernel(const uint32_t* kv, const int32_t* page_table,
                                                      const int32_t* seq_lens, uint32_t* dense,
@@ -284,6 +351,13 @@ hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype
 
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s)
 {
+    if (p.d_c % 256 == 0 && p.num_splits <= 64) {
+        const int waves = p.B * p.H * (p.d_c / 256);
+        dim3 grid((waves + 3) / 4), block(256);
+        if (io == MLA_BF16) merge_wave_kernel<true><<<grid, block, 0, s>>>(p);
+        else                merge_wave_kernel<false><<<grid, block, 0, s>>>(p);
+        return hipGetLastError();
+    }
     dim3 grid(p.H, p.B), block(128);
     if (io == MLA_BF16) merge_kernel<true><<<grid, block, 0, s>>>(p);
     else                merge_kernel<false><<<grid, block, 0, s>>>(p);

@@ -73,11 +73,118 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
     }
 }
 
+// ---- matrix-core variant (bf16) ---------------------------------------------------------
+// One workgroup = one head x NT output columns x up to 64 batch rows (one 16-row tile per
+// wavefront).  The whole [K x NT] slab of W[h] is staged in LDS once with coalesced 128-bit
+// loads and shared by the four wavefronts.  v_mfma_f32_16x16x32_bf16 wants, per lane, eight
+// consecutive k of one column: W is stored k-major, so the B operand is read with the
+// transposing LDS load (two 4-row reads per k-step); the A operand (8 consecutive k of one
+// batch row) comes straight from global memory, X being tiny.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+#define LDS_AS __attribute__((address_space(3)))
+
+constexpr int HM_LDS_BYTES = 40 * 1024;
+
+template <int NT>
+__global__ __launch_bounds__(256) void head_gemm_mfma_kernel(const uint16_t* X, const uint16_t* W, uint16_t* Y,
+                                                             int B, int H, int K, int N)
+{
+    constexpr int RS = NT * 2 + 16;          // LDS row stride in bytes (padded: rows shift banks)
+    constexpr int CPR = NT / 8;              // 16-byte chunks per slab row
+    __shared__ __attribute__((aligned(16))) unsigned char smem[HM_LDS_BYTES];
+    LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    // consecutive workgroup ids go to different XCDs: keep the column tiles of one head on
+    // one XCD (ids that differ by a multiple of H) so they share its L2 lines of W[h]
+    const int h = blockIdx.x % H;
+    const int n0 = (blockIdx.x / H) * NT;
+    const int brow = (blockIdx.y * 4 + wave) * 16 + n;    // batch row of this lane's A operand
+
+    // A operands of every k-step (K <= 512), requested before the slab so both are in flight
+    const bool active = (blockIdx.y * 4 + wave) * 16 < B;
+    const bool live = brow < B;
+    const uint16_t* xrow = X + ((size_t)min(brow, B - 1) * H + h) * K + g * 8;
+    const int nks = K / 32;
+    u32x4 areg[16];
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        areg[ks] = (u32x4){0u, 0u, 0u, 0u};
+        if (active && live && ks < nks) areg[ks] = *reinterpret_cast<const u32x4*>(xrow + ks * 32);
+    }
+
+    // stage W[h][0:K][n0:n0+NT]
+    const uint16_t* Wh = W + ((size_t)h * K) * N + n0;
+    for (int c = tid; c < K * CPR; c += 256) {
+        int r = c / CPR, cc = c % CPR;
+        u32x4 v = *reinterpret_cast<const u32x4*>(Wh + (size_t)r * N + cc * 8);
+        *(LDS_AS u32x4*)(lds + r * RS + cc * 16) = v;
+    }
+    __syncthreads();
+    if (!active) return;
+
+    f32x4 acc[NT / 16];
+#pragma unroll
+    for (int j = 0; j < NT / 16; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // transposing read: the lane supplies row 8g + (n>>2) (+4), 8 bytes at column 4(n&3)
+    const uint32_t tr_off = (uint32_t)((g * 8 + (n >> 2)) * RS + (n & 3) * 8);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        if (ks < nks) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, areg[ks]);
+#pragma unroll
+            for (int j = 0; j < NT / 16; ++j) {
+                LDS_AS unsigned char* bp = lds + ks * 32 * RS + tr_off + j * 32;
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(bp));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(bp + 4 * RS));
+                s16x8 bb = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bb), acc[j], 0, 0, 0);
+            }
+        }
+    }
+    // D: lane holds rows 4g..4g+3 (batch) of column n
+#pragma unroll
+    for (int j = 0; j < NT / 16; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int bb = (blockIdx.y * 4 + wave) * 16 + g * 4 + i;
+            if (bb < B) Y[((size_t)bb * H + h) * N + n0 + j * 16 + n] = (uint16_t)f32_to_bf16_bits(acc[j][i]);
+        }
+}
+
+template <int NT>
+bool try_launch_mfma(const void* X, const void* W, void* Y, int B, int H, int K, int N, hipStream_t s,
+                     hipError_t* err)
+{
+    if (N % NT || K % 32 || K > 512 || (size_t)K * (NT * 2 + 16) > (size_t)HM_LDS_BYTES) return false;
+    dim3 grid(H * (N / NT), (B + 63) / 64), block(256);
+    head_gemm_mfma_kernel<NT><<<grid, block, 0, s>>>(static_cast<const uint16_t*>(X),
+                                                     static_cast<const uint16_t*>(W),
+                                                     static_cast<uint16_t*>(Y), B, H, K, N);
+    *err = hipGetLastError();
+    return true;
+}
+
 }  // namespace
 
 hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H, int K, int N,
                             mla_dtype io, hipStream_t s)
 {
+    if (io == MLA_BF16 && (size_t)H * (N / 16 + 1) < 60000) {
+        // widest column tile that still gives the chip a workgroup per CU
+        const long by = (B + 63) / 64;
+        hipError_t err = hipSuccess;
+        if (N % 64 == 0 && (long)H * (N / 64) * by >= 256 && try_launch_mfma<64>(X, W, Y, B, H, K, N, s, &err)) return err;
+        if (N % 32 == 0 && (long)H * (N / 32) * by >= 256 && try_launch_mfma<32>(X, W, Y, B, H, K, N, s, &err)) return err;
+        if (try_launch_mfma<16>(X, W, Y, B, H, K, N, s, &err)) return err;
+        if (try_launch_mfma<32>(X, W, Y, B, H, K, N, s, &err)) return err;
+        if (try_launch_mfma<64>(X, W, Y, B, H, K, N, s, &err)) return err;
+    }
     dim3 grid((N + HG_NT - 1) / HG_NT, H, (B + HG_BT - 1) / HG_BT), block(HG_THREADS);
     if (io == MLA_BF16) head_gemm_kernel<true><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
     else                head_gemm_kernel<false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
