@@ -122,11 +122,17 @@ def main():
     cache_bytes = w.cache_bytes_per_step                      # 1152 B x 131072 tokens
     dec_avg_us = float(dec_us.mean())
     achieved = cache_bytes / (dec_avg_us * 1e-6) / 1e9
+    # HBM bytes per launch from the committed rocprofv3 counter summary; only valid while the
+    # kernel source is the one the counters were taken on
     traffic = None
     tp = Path(args.traffic_json)
     if tp.exists():
         try:
-            traffic = json.loads(tp.read_text()).get("hbm_bytes_per_launch")
+            import hashlib
+            tj = json.loads(tp.read_text())
+            src = ROOT / "paper_2502_07864_amd" / "csrc" / "decode_mfma.hip"
+            if hashlib.sha256(src.read_bytes()).hexdigest()[:16] == tj.get("kernel_source_sha256_16"):
+                traffic = tj.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
 

@@ -34,9 +34,11 @@
 // transposes 4x16 blocks of 16-bit elements while reading LDS.
 //
 // LDS layout: row r of a tile occupies bytes [r*ROWB, (r+1)*ROWB); inside a row,
-// 16-byte chunk c is stored at chunk position c ^ ((r >> 1) & 7), which spreads
-// both the row-wise 128-bit reads of 16 consecutive rows and the transposing
-// reads over the banks.
+// 16-byte chunk c is stored at chunk position c ^ key(r), key(r) = a 3-bit
+// permutation of row bits 1..3 (see swz_key).  ROWB is 32 banks mod 64, so row
+// parity picks the bank half and the key spreads the rest: the row-wise 128-bit
+// reads of 16 consecutive rows hit 16 different bank groups, and each half-wave
+// of a transposing read (8 rows x 32 bytes) covers all 64 banks once.
 #include "mla_internal.h"
 
 namespace mla {
@@ -58,7 +60,8 @@ constexpr int TILE_ROWS = 32;     // cached rows per tile (half a page)
 constexpr int NBUF = 4;           // tiles in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-constexpr float RESCALE_GAP = 32.f;
+constexpr float RESCALE_GAP = 32.f;   // careful pass: move the reference when exceeded by this
+constexpr float FAST_GAP = 64.f;      // fast pass: largest excess over the fixed reference it tolerates
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -66,6 +69,13 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
+
+// chunk swizzle key of tile row r: bits (r2, r1, r3).  Rows r and r+2 differ in bit 1 of the
+// key (different 32-byte block), rows r and r+4 in bit 2, rows r and r+8 in bit 0.
+__device__ __forceinline__ constexpr int swz_key(int r)
+{
+    return (((r >> 2) & 1) << 2) | (((r >> 1) & 1) << 1) | ((r >> 3) & 1);
 }
 
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
@@ -141,7 +151,7 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     // ---- tile staging: HBM -> LDS with direct-to-LDS 128-bit loads.
     // Load k of wave w fills LDS chunks [(4k+w)*64, +64) of the tile (the hardware writes lane
     // i at base + 16 i); LDS chunk P = row r, position pc holds the row's chunk
-    // pc ^ ((r>>1)&7), so a wave still reads whole 128-byte lines from HBM.  The loads are
+    // pc ^ key(r), so a wave still reads whole 128-byte lines from HBM.  The loads are
     // written as inline assembly on purpose: the compiler then keeps no record of pending LDS
     // writes and does not make LDS reads of the other ring slots wait for them.  Completion is
     // awaited explicitly (vmcnt) before the barrier that publishes a tile.
@@ -150,7 +160,7 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     for (int k = 0; k < NLOAD; ++k) {
         int P = (k * 4 + wave) * 64 + lane;
         int r = P / CPR, pc = P % CPR;
-        goff[k] = (uint32_t)(r * ROWB + ((pc ^ ((r >> 1) & 7)) << 4));
+        goff[k] = (uint32_t)(r * ROWB + ((pc ^ swz_key(r)) << 4));
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     const unsigned char* kv = static_cast<const unsigned char*>(p.kv);
@@ -187,28 +197,130 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     // per-lane part (low 3 bits, xor-ed with the row key) and a compile-time part (high bits).
     // score A operand: row 16tg + n, chunk 4ks + g
     const uint32_t a_row = (uint32_t)((tg * 16 + n) * ROWB);
-    const uint32_t a_key = (uint32_t)(n >> 1);
+    const uint32_t a_key = (uint32_t)swz_key(n);
     uint32_t a_base[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e) a_base[e] = a_row + ((((uint32_t)(4 * e + g)) ^ a_key) << 4);
     // value A operand (transposing read): the lane supplies row 16tg + 4g + (n>>2),
     // 8 bytes at element column 16ct + 4(n&3), i.e. chunk 2ct + ((n&3)>>1), half (n&1)
     const uint32_t v_row = (uint32_t)((tg * 16 + g * 4 + (n >> 2)) * ROWB);
-    const uint32_t v_key = (uint32_t)((2 * g + (n >> 3)) & 7);
+    const uint32_t v_key = (uint32_t)swz_key(g * 4 + (n >> 2));
     uint32_t v_base[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8);
 
-    // loads issued for the tiles after the one being consumed, oldest first
+    // ---- one tile: publish it, score it, fold it into the running softmax, accumulate.
+    // `ahead` holds the loads issued for the tiles after the one being consumed, oldest first.
     int ahead[NBUF - 1];
-#pragma unroll
-    for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
-    fetch_tile(t0);
-#pragma unroll
-    for (int i = 0; i < NBUF - 2; ++i)
-        if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
 
+    auto start_ring = [&]() {
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
+        fetch_tile(t0);   // every chunk that gets here has at least one tile
+#pragma unroll
+        for (int i = 0; i < NBUF - 2; ++i)
+            if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+    };
+
+    // wait / barrier / refill step for tile t; returns its number of valid rows
+    auto stage_tile = [&](int t, LDS_AS unsigned char* tile) -> int {
+        const int n_valid = rows_valid(t);
+        // wait until my loads of tile t have landed (younger tiles may stay in flight); after
+        // the barrier everybody's have, and every wave is done with tile t-1, whose ring slot
+        // now receives tile t + NBUF - 1
+        const int younger = ahead[0] + ahead[1];
+        if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
+        else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
+        else                       wait_vmcnt<0>();
+        __syncthreads();
+        const int tn = t + NBUF - 1;
+        ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+        if (n_valid < TILE_ROWS) {
+            // ragged last tile (or a page id outside the pool): rows that are not part of the
+            // sequence become zeros so that whatever they hold stays out
+            for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
+                *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+            __syncthreads();
+        }
+        // tile t+1 becomes the oldest one in flight
+#pragma unroll
+        for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
+        ahead[NBUF - 2] = 0;
+        return n_valid;
+    };
+
+    // S^T = K . Q^T for this wave's 16 rows x 16 heads, scaled to log2 units, invalid rows at
+    // -inf; returns the maximum over the wave's rows of this lane's head.  Operand reads run
+    // one group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler from
+    // sinking the reads back next to their uses.
+    auto score_tile = [&](LDS_AS unsigned char* tile, int n_valid, float (&x)[4]) -> float {
+        f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        bf16x8 a0[NKS];
+#pragma unroll
+        for (int ks = 0; ks < SG; ++ks)
+            a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s0 = 0; s0 < NKS; s0 += SG) {
+#pragma unroll
+            for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks)
+                a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
+        if (n_valid < TILE_ROWS) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (tg * 16 + g * 4 + i >= n_valid) x[i] = -INFINITY;
+        }
+        float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        return tmax;
+    };
+
+    // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded
+    // weights), then O^T += V^T . P^T with transposing reads one group of VG tiles ahead
+    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x)[4]) {
+        const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
+        const uint32_t p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
+        const uint32_t p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
+        l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                 (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
+        const s16x4 pb = __builtin_bit_cast(s16x4, (u32x2){p01, p23});
+        s16x4 va[NCT];
+#pragma unroll
+        for (int ct = 0; ct < VG; ++ct)
+            va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c0 = 0; c0 < NCT; c0 += VG) {
+#pragma unroll
+            for (int ct = c0 + VG; ct < c0 + 2 * VG && ct < NCT; ++ct)
+                va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ct = c0; ct < c0 + VG && ct < NCT; ++ct)
+                oacc[ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[ct], pb, oacc[ct], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- fast pass.  A head takes the maximum of its first tile with a valid row as the
+    // reference m_run of all its exponentials and never moves it, so the output accumulators
+    // are only ever touched by MFMA (no rescaling, no register shuffling).  That is exact as
+    // long as no later score exceeds the reference by more than FAST_GAP (log2 units): then
+    // p <= 2^FAST_GAP and neither p, the normaliser nor the accumulators can overflow.  A
+    // larger jump is only recorded here; the chunk is then recomputed by the careful pass.
+    start_ring();
     // Pin the completion of the query loads here, outside the tile loop.  Left to itself the
     // compiler would wait for them at their first use inside the loop, on every iteration, with
     // a count that ignores the tile loads it does not know about - i.e. it would drain the
@@ -217,123 +329,58 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
 
-    // The tile loop is a hot inner loop that only ever touches the output accumulators with
-    // MFMA, nested in an outer loop whose body (rarely run) rescales them.  Exponentials are
-    // taken against a per-head reference m_run.  A head adopts its first finite tile maximum as
-    // reference (nothing is accumulated yet, so nothing needs rescaling); after that the
-    // reference only moves when a tile's maximum exceeds it by more than RESCALE_GAP (log2
-    // units), so p <= 2^RESCALE_GAP.  When that happens the inner loop is left before the tile
-    // is accumulated, the accumulators are rescaled, and the tile is scored again.
-    int t = t0;
-    bool staged = false;       // tile t has already been through its wait / barrier / prefetch step
-    float alpha = 1.f;         // pending rescale factor of this lane's head
-    while (true) {
-        if (__any(alpha != 1.f)) {
-            l_run *= alpha;
+    bool jumped = false;
+    for (int t = t0; t < t1; ++t) {
+        LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+        const int n_valid = stage_tile(t, tile);
+        float x[4];
+        const float tmax = score_tile(tile, n_valid, x);
+        if (m_run == -INFINITY) m_run = tmax;
+        jumped |= tmax > m_run + FAST_GAP;
+        accumulate_tile(tile, x);
+    }
+
+    if (__builtin_expect(__syncthreads_or(jumped), 0)) {
+        // ---- careful pass (rare): the same chunk again with a moving reference.  The tile
+        // loop is nested in an outer loop whose body rescales the accumulators; the inner loop
+        // is left, before the offending tile is accumulated, whenever a tile maximum exceeds
+        // the reference by more than RESCALE_GAP, and that tile is then scored again.
+        m_run = -INFINITY;
+        l_run = 0.f;
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) oacc[ct] *= alpha;
-            alpha = 1.f;
-        }
-        bool rescale = false;
-        for (; t < t1; ++t) {
-            LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
-            const int n_valid = rows_valid(t);
-            if (!staged) {
-                // wait until my loads of tile t have landed (younger tiles may stay in flight);
-                // after the barrier everybody's have, and every wave is done with tile t-1,
-                // whose ring slot now receives tile t + NBUF - 1
-                const int younger = ahead[0] + ahead[1];
-                if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
-                else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
-                else                       wait_vmcnt<0>();
-                __syncthreads();
-                const int tn = t + NBUF - 1;
-                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
-                if (n_valid < TILE_ROWS) {
-                    // ragged last tile (or a page id outside the pool): rows that are not part
-                    // of the sequence become zeros so that whatever they hold stays out
-                    for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
-                        *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
-                    __syncthreads();
+        for (int ct = 0; ct < NCT; ++ct) oacc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        start_ring();
+        int t = t0;
+        bool staged = false;       // tile t has already been through its stage step
+        int n_valid = 0;
+        float alpha = 1.f;         // pending rescale factor of this lane's head
+        while (true) {
+            if (__any(alpha != 1.f)) {
+                l_run *= alpha;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) oacc[ct] *= alpha;
+                alpha = 1.f;
+            }
+            bool rescale = false;
+            for (; t < t1; ++t) {
+                LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+                if (!staged) n_valid = stage_tile(t, tile);
+                staged = false;
+                float x[4];
+                const float tmax = score_tile(tile, n_valid, x);
+                if (m_run == -INFINITY) m_run = tmax;     // nothing accumulated yet: nothing to rescale
+                if (__any(tmax > m_run + RESCALE_GAP)) {
+                    const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
+                    alpha = fast_exp2(m_run - m_new);     // 1 for the lanes that keep their reference
+                    m_run = m_new;
+                    staged = true;
+                    rescale = true;
+                    break;
                 }
-                // tile t+1 becomes the oldest one in flight
-#pragma unroll
-                for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
-                ahead[NBUF - 2] = 0;
+                accumulate_tile(tile, x);
             }
-            staged = false;
-
-            // ---- S^T = K . Q^T for this wave's 16 rows x 16 heads.  Operand reads run one
-            // group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler
-            // from sinking the reads back next to their uses.
-            f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-            bf16x8 a0[NKS];
-#pragma unroll
-            for (int ks = 0; ks < SG; ++ks)
-                a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int s0 = 0; s0 < NKS; s0 += SG) {
-#pragma unroll
-                for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks)
-                    a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
-                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-
-            // ---- softmax numerators for head n over rows 16tg + 4g + i
-            float x[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
-            if (n_valid < TILE_ROWS) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (tg * 16 + g * 4 + i >= n_valid) x[i] = -INFINITY;
-            }
-            float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            if (m_run == -INFINITY) m_run = tmax;     // first finite maximum: nothing to rescale yet
-            if (__builtin_expect(__any(tmax > m_run + RESCALE_GAP), 0)) {
-                const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
-                alpha = fast_exp2(m_run - m_new);     // 1 for the lanes that keep their reference
-                m_run = m_new;
-                staged = true;
-                rescale = true;
-                break;
-            }
-            const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
-            const uint32_t p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
-            const uint32_t p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
-            // the normaliser sums exactly the rounded weights that get multiplied
-            l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
-                     (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
-            const s16x4 pb = __builtin_bit_cast(s16x4, (u32x2){p01, p23});
-
-            // ---- O^T += V^T . P^T, transposing reads one group of VG column tiles ahead
-            s16x4 va[NCT];
-#pragma unroll
-            for (int ct = 0; ct < VG; ++ct)
-                va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int c0 = 0; c0 < NCT; c0 += VG) {
-#pragma unroll
-                for (int ct = c0 + VG; ct < c0 + 2 * VG && ct < NCT; ++ct)
-                    va[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ct = c0; ct < c0 + VG && ct < NCT; ++ct)
-                    oacc[ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[ct], pb, oacc[ct], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            if (!rescale) break;
         }
-        if (!rescale) break;
     }
 
     // ---- merge the two row halves of each head group, normalise, write the partial
