@@ -30,13 +30,32 @@ sys.path.insert(0, str(ROOT / "tests"))
 
 HBM_PEAK_GBPS = 8000.0
 
+METRICS = {
+    "C2": "MLA decode us/step (absorb + paged split-KV decode + out-proj), bs16 ctx8K bf16, 1 GPU",
+    "C1": "MLA decode us/step, bs1 ctx1K fp32, 1 GPU",
+    "C3": "MLA decode us/step, bs64 ctx U[1K,32K] bf16, 1 GPU",
+    "C4": "MLA decode us/step, bs128 ctx4K H28 d_c256 bf16, 1 GPU",
+    "C5": "MLA decode us/step, bs4 ctx128K fp8 cache, 1 GPU",
+}
+WORKLOADS = {
+    "C2": "C2: LLaMA-2-7B-shaped converted layer, batch 16 x context 8192, H=32 d_head=128 d_c=512 "
+          "d_rope=64, bf16 cache in 64-token pages (random placement), 16 KV chunks per sequence",
+    "C1": "C1: batch 1 x context 1024, H=32 d_c=512 d_rope=64, fp32 cache and io, identity page table",
+    "C3": "C3: batch 64, context uniform in [1024, 32768], bf16, random placement with 10% of the pool free",
+    "C4": "C4: batch 128 x context 4096, H=28 d_c=256 d_rope=64, bf16",
+    "C5": "C5: batch 4 x context 131072, fp8 e4m3 cache with one fp32 scale per token, 32 KV chunks",
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--copies", type=int, default=6, help="distinct cache copies cycled through")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="distinct cache copies cycled through (0 = enough to exceed 900 MB)")
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C2 is the headline configuration; the others are secondary rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
     ap.add_argument("--calib-copy", action="store_true",
@@ -63,23 +82,29 @@ def main():
     torch.cuda.set_device(0)
     mla.lib()
 
-    w = synth.config("C2")
+    w = synth.config(args.workload)
     d = DeviceWorkload(w, "cuda:0")
     B, H, d_c, S = w.B, w.H, w.d_c, w.num_splits
+    io_t = torch.bfloat16 if w.io_dtype == "bf16" else torch.float32
+    if args.copies <= 0:
+        args.copies = max(2, min(6, -(-900_000_000 // max(1, w.cache_bytes_per_step))))
     # distinct HBM copies of cache + page table (copy i: pages rotated by i within the pool)
-    pools, tables = [], []
+    pools, tables, scales = [], [], []
     for i in range(max(1, args.copies)):
         if i == 0:
             pools.append(d.pool)
             tables.append(d.page_table)
+            scales.append(d.kv_scale)
         else:
             shift = (i * 977) % w.num_pages
             pools.append(torch.roll(d.pool, shifts=shift, dims=0).contiguous())
-            tables.append(((d.page_table + shift) % w.num_pages).to(torch.int32).contiguous())
+            shifted = torch.where(d.page_table >= 0, (d.page_table + shift) % w.num_pages, d.page_table)
+            tables.append(shifted.to(torch.int32).contiguous())
+            scales.append(None if d.kv_scale is None else torch.roll(d.kv_scale, shifts=shift, dims=0).contiguous())
     ws = torch.empty(mla.decode_workspace_bytes(B, H, d_c, S), dtype=torch.uint8, device="cuda:0")
-    q_abs = torch.empty((B, H, d_c), dtype=torch.bfloat16, device="cuda:0")
-    o_lat = torch.empty((B, H, d_c), dtype=torch.bfloat16, device="cuda:0")
-    out = torch.empty((B, H, w.d_head), dtype=torch.bfloat16, device="cuda:0")
+    q_abs = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
+    o_lat = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
+    out = torch.empty((B, H, w.d_head), dtype=io_t, device="cuda:0")
 
     def step(i, events=None):
         k = i % len(pools)
@@ -87,10 +112,10 @@ def main():
         if events is not None:
             events[0].record()
         mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, workspace=ws, flags=mla.FLAG_SKIP_MERGE)
+                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE)
         if events is not None:
             events[1].record()
-        mla.merge_partials(ws, B, H, d_c, S, torch.bfloat16, out=o_lat)
+        mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat)
         if events is not None:
             events[2].record()
         mla.out_proj(o_lat, d.W_UV, out=out)
@@ -119,14 +144,14 @@ def main():
     dec_us = np.array([e[0].elapsed_time(e[1]) * 1e3 for e in evs])
     mrg_us = np.array([e[1].elapsed_time(e[2]) * 1e3 for e in evs])
 
-    cache_bytes = w.cache_bytes_per_step                      # 1152 B x 131072 tokens
+    cache_bytes = w.cache_bytes_per_step                      # C2: 1152 B x 131072 tokens
     dec_avg_us = float(dec_us.mean())
     achieved = cache_bytes / (dec_avg_us * 1e-6) / 1e9
     # HBM bytes per launch from the committed rocprofv3 counter summary; only valid while the
     # kernel source is the one the counters were taken on
     traffic = None
     tp = Path(args.traffic_json)
-    if tp.exists():
+    if tp.exists() and args.workload == "C2":
         try:
             import hashlib
             tj = json.loads(tp.read_text())
@@ -137,7 +162,7 @@ def main():
             traffic = None
 
     rec = {
-        "metric": "MLA decode us/step (absorb + paged split-KV decode + out-proj), bs16 ctx8K bf16, 1 GPU",
+        "metric": METRICS[args.workload],
         "value": round(ms_per_step * 1e3, 3),
         "unit": "us/step",
         "n_gpus": 1,
@@ -147,13 +172,11 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f32" if w.io_dtype == "f32" else "bf16",
         "data": "synthetic",
-        "config": {"workload": "C2: LLaMA-2-7B-shaped converted layer, batch 16 x context 8192, "
-                               "H=32 d_head=128 d_c=512 d_rope=64, bf16 cache in 64-token pages "
-                               "(random placement), 16 KV chunks per sequence",
-                   "batch": B, "context": int(w.seq_lens[0]), "num_splits": S,
-                   "cache_copies_cycled": len(pools)},
+        "config": {"workload": WORKLOADS[args.workload],
+                   "batch": B, "context_max": int(w.seq_lens.max()), "tokens": w.tokens,
+                   "cache_dtype": w.cache_dtype, "num_splits": S, "cache_copies_cycled": len(pools)},
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
         "step_hbm_GBps": round(cache_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_hbm_frac": round(cache_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -162,7 +185,8 @@ def main():
                                            "p50": round(float(np.percentile(dec_us, 50)), 2),
                                            "p90": round(float(np.percentile(dec_us, 90)), 2)},
                        "merge": {"avg": round(float(mrg_us.mean()), 2)}},
-        "roofline": {"bound": "hbm", "kernel": "decode_mfma_bf16_kernel<512>",
+        "roofline": {"bound": "hbm", "kernel": "split-KV decode kernel" if args.workload != "C2"
+                     else "decode_mfma_bf16_kernel<512>",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": cache_bytes},
@@ -175,14 +199,14 @@ def main():
         times = []
         for _ in range(3):
             t0 = time.perf_counter()
-            oracle.mla_step(w.q_nope[sel], w.q_rope[sel], w.W_UK, w.W_UV, w.pool, None,
+            oracle.mla_step(w.q_nope[sel], w.q_rope[sel], w.W_UK, w.W_UV, w.pool, w.kv_scale,
                             w.page_table[sel], w.seq_lens[sel], w.softmax_scale)
             times.append(time.perf_counter() - t0)
         t_cpu = sorted(times)[1]
         rec["cpu_baseline"] = {
             "value": round(t_cpu * (B / n) * 1e6, 1), "unit": "us/step",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{n} of {B} sequences (all 32 heads, 8192 tokens each), fp64 absorbed oracle "
+            "sample": f"{n} of {B} sequences (all {H} heads, {int(w.seq_lens[sel].sum())} tokens), fp64 absorbed oracle "
                       f"(absorb + decode + out-proj), median of 3 runs = {t_cpu:.2f} s, scaled by {B}/{n}"}
     print(json.dumps(rec))
 

@@ -103,7 +103,7 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
 
     hipError_t e;
     if (!(flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, io_dtype, cache_dtype))
-        e = launch_decode_mfma(p, stream);
+        e = launch_decode_mfma(p, cache_dtype, stream);
     else
         e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
     if (e != hipSuccess) return MLA_ERR_HIP;

@@ -1,4 +1,4 @@
-// Matrix-core paged decode for a bf16 latent cache (gfx950 / CDNA4).
+// Matrix-core paged decode for a bf16 or fp8 (e4m3 + per-row scale) latent cache (gfx950 / CDNA4).
 //
 // Second line of the absorbed attention equation (Sec. 3.3 of the paper): all
 // H heads score against the ONE shared row k_hat_j = [c_j ; k^R_j] and weight
@@ -84,8 +84,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int D_C>
-__global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_bf16_kernel(DecodeParams p)
+// FP8 = false: bf16 cache, tiles go HBM -> LDS directly (ring of four).
+// FP8 = true : OCP e4m3 cache with one fp32 scale per row.  Codes are widened exactly to bf16 on
+//              their way HBM -> registers -> LDS (two tiles), so the arithmetic below is the same;
+//              the row's scale multiplies its score and its weight instead of its 576 values.
+template <int D_C, bool FP8>
+__global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
@@ -185,6 +189,48 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
         return NLOAD;
     };
 
+    // ---- fp8 staging: 8-byte loads (8 codes) one tile ahead in registers, widened to bf16 and
+    // stored with the same swizzled layout the direct-to-LDS path produces
+    constexpr int ROWB8 = ROW;                       // bytes per fp8 cache row
+    constexpr int CPR8 = ROW / 8;                    // 8-code chunks per row (= 16-byte bf16 chunks)
+    constexpr int NLOAD8 = TILE_ROWS * CPR8 / MF_THREADS;   // 9 / 5
+    static_assert(TILE_ROWS * CPR8 % MF_THREADS == 0, "fp8 tile must split evenly over the loads");
+    __shared__ float scale_lds[2][TILE_ROWS];
+    u32x2 stg[FP8 ? NLOAD8 : 1];
+    float stg_scale = 0.f;
+    auto fetch_regs = [&](int t) {
+        const int nv = rows_valid(t);
+        const int page = nv > 0 ? ptab[t >> 1] : 0;
+        const unsigned char* src = kv + (size_t)page * (64 * ROWB8) + (size_t)(t & 1) * (TILE_ROWS * ROWB8);
+#pragma unroll
+        for (int k = 0; k < NLOAD8; ++k) {
+            const int c8 = k * MF_THREADS + tid;
+            const int r = c8 / CPR8, col = c8 % CPR8;
+            u32x2 v = (u32x2){0u, 0u};
+            if (r < nv) v = *reinterpret_cast<const u32x2*>(src + r * ROWB8 + col * 8);
+            stg[k] = v;
+        }
+        if (tid < TILE_ROWS)
+            stg_scale = tid < nv ? p.kv_scale[(size_t)page * 64 + (t & 1) * TILE_ROWS + tid] : 0.f;
+    };
+    auto store_regs = [&](int slot) {
+#pragma unroll
+        for (int k = 0; k < NLOAD8; ++k) {
+            const int c8 = k * MF_THREADS + tid;
+            const int r = c8 / CPR8, col = c8 % CPR8;
+            u32x4 w;
+#pragma unroll
+            for (int hw = 0; hw < 2; ++hw) {
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)stg[k][hw], false);
+                const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)stg[k][hw], true);
+                w[2 * hw]     = pack_bf16x2(lo[0], lo[1]);   // exact: e4m3 has 3 mantissa bits
+                w[2 * hw + 1] = pack_bf16x2(hi[0], hi[1]);
+            }
+            *(LDS_AS u32x4*)(lds + slot * TILE_B + r * ROWB + ((col ^ swz_key(r)) << 4)) = w;
+        }
+        if (tid < TILE_ROWS) scale_lds[slot][tid] = stg_scale;
+    };
+
     // ---- running softmax state: this lane's head = column n of the D tiles
     float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
     float l_run = 0.f;         // this lane's share of the running sum (its 4 rows per tile)
@@ -214,47 +260,71 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
     // `ahead` holds the loads issued for the tiles after the one being consumed, oldest first.
     int ahead[NBUF - 1];
 
+    auto slot_of = [&](int t) { return FP8 ? ((t - t0) & 1) : ((t - t0) % NBUF); };
+
     auto start_ring = [&]() {
+        if constexpr (FP8) {
+            fetch_regs(t0);
+            store_regs(0);
+            if (t0 + 1 < t1) fetch_regs(t0 + 1);
+        } else {
 #pragma unroll
-        for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
-        fetch_tile(t0);   // every chunk that gets here has at least one tile
+            for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
+            fetch_tile(t0);   // every chunk that gets here has at least one tile
 #pragma unroll
-        for (int i = 0; i < NBUF - 2; ++i)
-            if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+            for (int i = 0; i < NBUF - 2; ++i)
+                if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+        }
     };
 
-    // wait / barrier / refill step for tile t; returns its number of valid rows
+    // publish tile t (and keep the stream going); returns its number of valid rows
     auto stage_tile = [&](int t, LDS_AS unsigned char* tile) -> int {
         const int n_valid = rows_valid(t);
-        // wait until my loads of tile t have landed (younger tiles may stay in flight); after
-        // the barrier everybody's have, and every wave is done with tile t-1, whose ring slot
-        // now receives tile t + NBUF - 1
-        const int younger = ahead[0] + ahead[1];
-        if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
-        else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
-        else                       wait_vmcnt<0>();
-        __syncthreads();
-        const int tn = t + NBUF - 1;
-        ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
-        if (n_valid < TILE_ROWS) {
-            // ragged last tile (or a page id outside the pool): rows that are not part of the
-            // sequence become zeros so that whatever they hold stays out
-            for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
-                *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+        if constexpr (FP8) {
+            // tile t was stored by every wave before this barrier; the other slot is free
             __syncthreads();
-        }
-        // tile t+1 becomes the oldest one in flight
+            return n_valid;
+        } else {
+            // wait until my loads of tile t have landed (younger tiles may stay in flight);
+            // after the barrier everybody's have, and every wave is done with tile t-1, whose
+            // ring slot now receives tile t + NBUF - 1
+            const int younger = ahead[0] + ahead[1];
+            if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
+            else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
+            else                       wait_vmcnt<0>();
+            __syncthreads();
+            const int tn = t + NBUF - 1;
+            ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+            if (n_valid < TILE_ROWS) {
+                // ragged last tile (or a page id outside the pool): rows that are not part of
+                // the sequence become zeros so that whatever they hold stays out
+                for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
+                    *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+                __syncthreads();
+            }
+            // tile t+1 becomes the oldest one in flight
 #pragma unroll
-        for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
-        ahead[NBUF - 2] = 0;
-        return n_valid;
+            for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
+            ahead[NBUF - 2] = 0;
+            return n_valid;
+        }
+    };
+
+    // after tile t has been accumulated (fp8): hand tile t+1 over to LDS, request tile t+2
+    auto finish_tile = [&](int t) {
+        if constexpr (FP8) {
+            if (t + 1 < t1) {
+                store_regs(slot_of(t + 1));
+                if (t + 2 < t1) fetch_regs(t + 2);
+            }
+        }
     };
 
     // S^T = K . Q^T for this wave's 16 rows x 16 heads, scaled to log2 units, invalid rows at
     // -inf; returns the maximum over the wave's rows of this lane's head.  Operand reads run
     // one group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler from
     // sinking the reads back next to their uses.
-    auto score_tile = [&](LDS_AS unsigned char* tile, int n_valid, float (&x)[4]) -> float {
+    auto score_tile = [&](LDS_AS unsigned char* tile, int slot, int n_valid, float (&x)[4], float (&rs)[4]) -> float {
         f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
         bf16x8 a0[NKS];
 #pragma unroll
@@ -273,7 +343,10 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
+        for (int i = 0; i < 4; ++i) {
+            rs[i] = FP8 ? scale_lds[slot][tg * 16 + g * 4 + i] : 1.f;   // per-row dequantisation scale
+            x[i] = sacc[i] * (FP8 ? sc * rs[i] : sc);
+        }
         if (n_valid < TILE_ROWS) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -287,12 +360,24 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
 
     // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded
     // weights), then O^T += V^T . P^T with transposing reads one group of VG tiles ahead
-    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x)[4]) {
+    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x)[4], const float (&rs)[4]) {
         const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
-        const uint32_t p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
-        const uint32_t p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
-        l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
-                 (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
+        uint32_t p01, p23;
+        if constexpr (FP8) {
+            // the value rows are scale * codes: the scale rides on the weight; the normaliser
+            // sums the plain weights
+            const float e0 = fast_exp2(x[0] - m_use), e1 = fast_exp2(x[1] - m_use);
+            const float e2 = fast_exp2(x[2] - m_use), e3 = fast_exp2(x[3] - m_use);
+            l_run += (e0 + e1) + (e2 + e3);
+            p01 = pack_bf16x2(e0 * rs[0], e1 * rs[1]);
+            p23 = pack_bf16x2(e2 * rs[2], e3 * rs[3]);
+        } else {
+            p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
+            p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
+            // the normaliser sums exactly the rounded weights that get multiplied
+            l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                     (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
+        }
         const s16x4 pb = __builtin_bit_cast(s16x4, (u32x2){p01, p23});
         s16x4 va[NCT];
 #pragma unroll
@@ -331,13 +416,15 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
 
     bool jumped = false;
     for (int t = t0; t < t1; ++t) {
-        LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+        const int slot = slot_of(t);
+        LDS_AS unsigned char* tile = lds + slot * TILE_B;
         const int n_valid = stage_tile(t, tile);
-        float x[4];
-        const float tmax = score_tile(tile, n_valid, x);
+        float x[4], rs[4];
+        const float tmax = score_tile(tile, slot, n_valid, x, rs);
         if (m_run == -INFINITY) m_run = tmax;
         jumped |= tmax > m_run + FAST_GAP;
-        accumulate_tile(tile, x);
+        accumulate_tile(tile, x, rs);
+        finish_tile(t);
     }
 
     if (__builtin_expect(__syncthreads_or(jumped), 0)) {
@@ -349,6 +436,7 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
         l_run = 0.f;
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) oacc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if constexpr (FP8) __syncthreads();   // every wave is done reading both slots
         start_ring();
         int t = t0;
         bool staged = false;       // tile t has already been through its stage step
@@ -363,11 +451,12 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
             }
             bool rescale = false;
             for (; t < t1; ++t) {
-                LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+                const int slot = slot_of(t);
+                LDS_AS unsigned char* tile = lds + slot * TILE_B;
                 if (!staged) n_valid = stage_tile(t, tile);
                 staged = false;
-                float x[4];
-                const float tmax = score_tile(tile, n_valid, x);
+                float x[4], rs[4];
+                const float tmax = score_tile(tile, slot, n_valid, x, rs);
                 if (m_run == -INFINITY) m_run = tmax;     // nothing accumulated yet: nothing to rescale
                 if (__any(tmax > m_run + RESCALE_GAP)) {
                     const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
@@ -377,7 +466,8 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
                     rescale = true;
                     break;
                 }
-                accumulate_tile(tile, x);
+                accumulate_tile(tile, x, rs);
+                finish_tile(t);
             }
             if (!rescale) break;
         }
@@ -436,15 +526,18 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 ? 2 : 1)) void decode_mfma_
 
 bool decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache)
 {
-    return io == MLA_BF16 && cache == MLA_BF16 && p.page_size == 64 && p.d_rope == 64 &&
-           (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && p.H <= 32;
+    return io == MLA_BF16 && (cache == MLA_BF16 || cache == MLA_FP8_E4M3) && p.page_size == 64 &&
+           p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && p.H <= 32;
 }
 
-hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t s)
+hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s)
 {
     dim3 grid(p.num_splits, p.B), block(MF_THREADS);
-    if (p.d_c == 512)      decode_mfma_bf16_kernel<512><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_mfma_bf16_kernel<256><<<grid, block, 0, s>>>(p);
+    const bool fp8 = cache == MLA_FP8_E4M3;
+    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -162,8 +162,12 @@ def test_decode_bf16_C3_shrunk(mla):
 def test_decode_fp8_cache(mla):
     """fp8 e4m3 cache with one fp32 scale per token, bf16 and fp32 io."""
     w = synth.config("C5", shrink=32)
-    check_decode(mla, w, w.num_splits)
-    check_decode(mla, w, 3)
+    for flags in (0, 1):                      # matrix-core kernel and portable kernel
+        check_decode(mla, w, w.num_splits, flags)
+        check_decode(mla, w, 3, flags)
+    # ragged lengths, poisoned tails (NaN codes and NaN scales), 28 heads / d_c 256
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", seed=21), 5)
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", d_c=256, H=28, lens=[1, 64, 65, 1000, 31, 33], seed=22), 2)
     w2 = ragged_workload(cache="fp8_e4m3", io="f32", lens=[1, 65, 300, 64], seed=9)
     check_decode(mla, w2, 2, tol=1e-5)
 
