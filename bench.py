@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the absorbed MLA decode step on one MI355X.
 
-A step = mla_absorb_q -> mla_decode_paged (split-KV kernel + merge) ->
-mla_out_proj on one stream, for one batch of synthetic input already resident
+A step = mla_absorb_q -> mla_decode_paged (split-KV kernel, partials left in the
+workspace) -> mla_merge_out_proj (split-KV merge + W_UV, fused) on one stream, for one batch of synthetic input already resident
 in HBM.  Workload: LLaMA-2-7B-shaped converted layer, batch 16, every
 sequence at context 8192, bf16 storage / fp32 accumulate, 64-token pages in a
 random physical order (H=32, d_head=128, d_c=512, d_rope=64).
@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--copies", type=int, default=0,
                     help="distinct cache copies cycled through (0 = enough to exceed 900 MB)")
+    ap.add_argument("--unfused-tail", action="store_true",
+                    help="merge and out-projection as two calls instead of mla_merge_out_proj")
+    ap.add_argument("--splits", type=int, default=0, help="override the configuration's KV chunk count")
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
                     help="C2 is the headline configuration; the others are secondary rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,7 +87,7 @@ def main():
 
     w = synth.config(args.workload)
     d = DeviceWorkload(w, "cuda:0")
-    B, H, d_c, S = w.B, w.H, w.d_c, w.num_splits
+    B, H, d_c, S = w.B, w.H, w.d_c, (args.splits or w.num_splits)
     io_t = torch.bfloat16 if w.io_dtype == "bf16" else torch.float32
     if args.copies <= 0:
         args.copies = max(2, min(6, -(-900_000_000 // max(1, w.cache_bytes_per_step))))
@@ -115,10 +118,13 @@ def main():
                          num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE)
         if events is not None:
             events[1].record()
-        mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat)
+        if args.unfused_tail:
+            mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat)
+            mla.out_proj(o_lat, d.W_UV, out=out)
+        else:
+            mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out)
         if events is not None:
             events[2].record()
-        mla.out_proj(o_lat, d.W_UV, out=out)
 
     if args.calib_copy:
         for _ in range(3):
@@ -184,7 +190,8 @@ def main():
                                            "p10": round(float(np.percentile(dec_us, 10)), 2),
                                            "p50": round(float(np.percentile(dec_us, 50)), 2),
                                            "p90": round(float(np.percentile(dec_us, 90)), 2)},
-                       "merge": {"avg": round(float(mrg_us.mean()), 2)}},
+                       ("merge+out_proj" if args.unfused_tail else "merge_out_proj_fused"):
+                           {"avg": round(float(mrg_us.mean()), 2)}},
         "roofline": {"bound": "hbm", "kernel": "split-KV decode kernel" if args.workload != "C2"
                      else "decode_mfma_bf16_kernel<512>",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -174,6 +174,23 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes,
                        int num_splits, mla_dtype io_dtype, void* hip_stream);
 
 /*
+ * Fused tail: mla_merge_partials followed by mla_out_proj in one call (one
+ * kernel where the shapes allow: bf16 io, d_head 128, d_c 256 or 512, at most
+ * 64 chunks; otherwise the two kernels back to back).  Same results as the two
+ * calls: o_lat is the merged latent output rounded to the io dtype, and out is
+ * computed from that rounded o_lat.
+ *   workspace  [in]  as written by mla_decode_paged(..., MLA_FLAG_SKIP_MERGE)
+ *   W_UV       [H, d_c, d_head] io dtype
+ *   o_lat      [B, H, d_c] io dtype (output, required)
+ *   lse        [B, H] fp32 (output, may be NULL)
+ *   out        [B, H, d_head] io dtype (output)
+ */
+int mla_merge_out_proj(const void* workspace, size_t workspace_bytes,
+                       const void* W_UV, void* o_lat, float* lse, void* out,
+                       int B, int H, int d_c, int d_head, int num_splits,
+                       mla_dtype io_dtype, void* hip_stream);
+
+/*
  * Test hook: the logical (un-paged) view of the cache, byte for byte, using
  * the same page arithmetic as mla_decode_paged.
  *

@@ -135,6 +135,33 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_la
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 
+int mla_merge_out_proj(const void* workspace, size_t workspace_bytes, const void* W_UV, void* o_lat,
+                       float* lse, void* out, int B, int H, int d_c, int d_head, int num_splits,
+                       mla_dtype io_dtype, void* hip_stream)
+{
+    if (!o_lat || !W_UV || !out) return MLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || d_c <= 0 || d_head <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || B > 65535 || d_c % 4) return MLA_ERR_UNSUPPORTED;
+    const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return MLA_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    MergeParams m;
+    m.o_part = static_cast<const float*>(workspace);
+    m.lse_part = reinterpret_cast<const float*>(
+        static_cast<const char*>(workspace) + align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
+    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+    hipError_t e;
+    if (merge_out_proj_supported(m, d_head, io_dtype)) {
+        e = launch_merge_out_proj(m, W_UV, out, stream);
+    } else {
+        e = launch_merge(m, io_dtype, stream);
+        if (e == hipSuccess) e = launch_head_gemm(o_lat, W_UV, out, B, H, d_c, d_head, io_dtype, stream);
+    }
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
 int mla_gather_paged(const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens,
                      void* dense, int B, int max_len, int row_bytes, int page_size, int num_pages,
                      int max_pages_per_seq, void* hip_stream)

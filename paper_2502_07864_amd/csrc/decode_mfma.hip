@@ -57,7 +57,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int MF_THREADS = 256;
 constexpr int TILE_ROWS = 32;     // cached rows per tile (half a page)
-constexpr int NBUF = 4;           // tiles in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_GAP = 32.f;   // careful pass: move the reference when exceeded by this
@@ -88,8 +87,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // FP8 = true : OCP e4m3 cache with one fp32 scale per row.  Codes are widened exactly to bf16 on
 //              their way HBM -> registers -> LDS (two tiles), so the arithmetic below is the same;
 //              the row's scale multiplies its score and its weight instead of its 576 values.
-template <int D_C, bool FP8>
-__global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void decode_mfma_kernel(DecodeParams p)
+// NBUF = tiles in the LDS ring (bf16 path): 4 fills LDS with one workgroup per CU; 2 leaves room
+//        for two workgroups per CU (WPE = waves per SIMD the register budget is sized for).
+template <int D_C, bool FP8, int NBUF, int WPE>
+__global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void deco
     static_assert(TILE_B % (MF_THREADS * 16) == 0, "tile must split evenly over the loads");
     static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
     static_assert(NLOAD * (NBUF - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert(NBUF >= 2 && NBUF <= 4, "ring depth");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
@@ -288,10 +290,12 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void deco
             // wait until my loads of tile t have landed (younger tiles may stay in flight);
             // after the barrier everybody's have, and every wave is done with tile t-1, whose
             // ring slot now receives tile t + NBUF - 1
-            const int younger = ahead[0] + ahead[1];
-            if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
-            else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
-            else                       wait_vmcnt<0>();
+            int younger = 0;
+#pragma unroll
+            for (int i = 0; i < NBUF - 2; ++i) younger += ahead[i];
+            if (NBUF > 3 && younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
+            else if (NBUF > 2 && younger >= NLOAD) wait_vmcnt<NLOAD>();
+            else                                   wait_vmcnt<0>();
             __syncthreads();
             const int tn = t + NBUF - 1;
             ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
@@ -477,7 +481,8 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void deco
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
     __syncthreads();  // tiles no longer needed (nothing is in flight): reuse LDS as exchange space
-    constexpr int XCH = NCT * 1024 + 512;  // per head group: O tiles + m + l
+    constexpr int RSO = D_C * 4 + 16;      // row stride of the transposed output (padded: conflict-free both ways)
+    constexpr int XCH = (NCT * 1024 + 512) > 16 * RSO ? (NCT * 1024 + 512) : 16 * RSO;  // per head group
     static_assert(2 * XCH <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* xch = lds + hg * XCH;
     if (tg == 1) {
@@ -495,19 +500,21 @@ __global__ __launch_bounds__(MF_THREADS, (D_C <= 256 && !FP8 ? 2 : 1)) void deco
         const float w0 = fast_exp2(m_run - m_use), w1 = fast_exp2(m1 - m_use);
         const float lt = l_w * w0 + l1 * w1;
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        // The lane holds 4 consecutive columns of head n per column tile: writing that
-        // straight out would give 64-byte runs.  Transpose through a private LDS area (row
-        // stride padded by 16 bytes: conflict-free both ways) and store whole 1 KB runs.
-        constexpr int RSO = D_C * 4 + 16;
-        static_assert(2 * XCH + 2 * 16 * RSO <= NBUF * TILE_B, "transpose area must fit in the tile ring");
-        LDS_AS unsigned char* tr = lds + 2 * XCH + hg * 16 * RSO;
+        const float s0 = w0 * inv, s1 = w1 * inv;
+        // combine the halves in registers first; the exchange area of this head group is then
+        // free and is reused for the transposition below (only this wavefront touches it now,
+        // and LDS executes a wavefront's accesses in order)
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             f32x4 o1 = *(LDS_AS f32x4*)(xch + (ct * 64 + lane) * 16);
-            f32x4 o = (oacc[ct] * w0 + o1 * w1) * inv;
-            *(LDS_AS f32x4*)(tr + n * RSO + (ct * 16 + g * 4) * 4) = o;
+            oacc[ct] = oacc[ct] * s0 + o1 * s1;
         }
-        // same wavefront wrote and reads this area; LDS executes a wave's accesses in order
+        // The lane holds 4 consecutive columns of head n per column tile: writing that straight
+        // out would give 64-byte runs.  Transpose through LDS and store whole 1 KB runs.
+        LDS_AS unsigned char* tr = xch;
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+            *(LDS_AS f32x4*)(tr + n * RSO + (ct * 16 + g * 4) * 4) = oacc[ct];
         const int nrow = min(16, p.H - hg * 16);
         for (int r = 0; r < nrow; ++r) {
             float* dst = p.o_part + (part + hg * 16 + r) * D_C;
@@ -534,10 +541,10 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
 {
     dim3 grid(p.num_splits, p.B), block(MF_THREADS);
     const bool fp8 = cache == MLA_FP8_E4M3;
-    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -67,6 +67,8 @@ hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s);
 hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
                          void* dense, int B, int max_len, int row_bytes, int page_size,
                          int num_pages, int max_pages, hipStream_t s);
+bool       merge_out_proj_supported(const MergeParams& p, int d_head, mla_dtype io);
+hipError_t launch_merge_out_proj(const MergeParams& p, const void* W_UV, void* out, hipStream_t s);
 // Y[b,h,n] = sum_k X[b,h,k] * W[h,k,n]
 hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H, int K, int N,
                             mla_dtype io, hipStream_t s);

@@ -22,7 +22,7 @@ FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE = 0, 1, 2
 
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
-           "mla_gather_paged")
+           "mla_merge_out_proj", "mla_gather_paged")
 
 
 class MlaError(RuntimeError):
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
                                        i, i, i, i, i, i, i, i, f, i, i, u, vp]
         L.mla_merge_partials.restype = i
         L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, vp]
+        L.mla_merge_out_proj.restype = i
+        L.mla_merge_out_proj.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         L.mla_gather_paged.restype = i
         L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
         _lib = L
@@ -190,6 +192,26 @@ def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits
                                     _dev(out, "out"), _dev(lse, "lse"), B, H, d_c, num_splits,
                                     _io_code(out), _stream(workspace)), "mla_merge_partials")
     return (out, lse) if lse is not None else out
+
+
+def merge_out_proj(workspace: torch.Tensor, W_UV: torch.Tensor, B: int, num_splits: int,
+                   o_lat: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                   lse: Optional[torch.Tensor] = None, return_lse: bool = False):
+    """Merge the partials left by decode_paged(flags=FLAG_SKIP_MERGE) and apply W_UV [H,d_c,d_head].
+    Returns (o_lat [B,H,d_c], out [B,H,d_head][, lse])."""
+    H, d_c, d_head = W_UV.shape
+    if o_lat is None:
+        o_lat = torch.empty((B, H, d_c), dtype=W_UV.dtype, device=W_UV.device)
+    if out is None:
+        out = torch.empty((B, H, d_head), dtype=W_UV.dtype, device=W_UV.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, H), dtype=torch.float32, device=W_UV.device)
+    _check(lib().mla_merge_out_proj(_dev(workspace, "workspace"),
+                                    workspace.numel() * workspace.element_size(), _dev(W_UV, "W_UV"),
+                                    _dev(o_lat, "o_lat"), _dev(lse, "lse"), _dev(out, "out"), B, H, d_c,
+                                    d_head, num_splits, _io_code(W_UV), _stream(workspace)),
+           "mla_merge_out_proj")
+    return (o_lat, out, lse) if lse is not None else (o_lat, out)
 
 
 def gather_paged(kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: torch.Tensor,

@@ -189,6 +189,30 @@ def test_mfma_matches_portable_kernel(mla):
     assert max_abs_rel(a, b) <= 1e-2
 
 
+def test_fused_merge_out_proj_matches_separate_calls(mla):
+    """mla_merge_out_proj = mla_merge_partials + mla_out_proj: identical o_lat / lse bits, out within
+    rounding of the separate path and inside the bar against the oracle."""
+    import torch
+    cases = [(ragged_workload(seed=31), 7), (synth.config("C2", shrink=8), 4),
+             (ragged_workload(d_c=256, H=28, lens=[300, 1, 64, 0, 999], seed=32), 3),
+             (synth.config("C1", shrink=4), 2)]     # fp32: the unfused fallback inside the call
+    for w, S in cases:
+        d = DeviceWorkload(w)
+        q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+        ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                              num_splits=S, kv_scale=d.kv_scale, flags=mla.FLAG_SKIP_MERGE)
+        o1, l1 = mla.merge_partials(ws, w.B, w.H, w.d_c, S, q_abs.dtype, return_lse=True)
+        out1 = mla.out_proj(o1, d.W_UV)
+        o2, out2, l2 = mla.merge_out_proj(ws, d.W_UV, w.B, S, return_lse=True)
+        torch.cuda.synchronize()
+        assert storage_bits(o1).tobytes() == storage_bits(o2).tobytes()
+        assert storage_bits(l1).tobytes() == storage_bits(l2).tobytes()
+        ref = oracle.out_proj(q_abs_storage(o2), w.W_UV)
+        tol = TOL[w.io_dtype]
+        assert max_abs_rel(widen_gpu(out2), ref) <= tol
+        assert max_abs_rel(widen_gpu(out2), widen_gpu(out1)) <= tol / 2
+
+
 # ------------------------------------------------------------- edge cases
 
 def test_empty_and_single_token_sequences(mla):
