@@ -137,10 +137,14 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
     const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
 
-    // ---- this wave's 16 query rows as B operands, resident for the whole chunk
+    // ---- this wave's 16 query rows as B operands, resident for the whole chunk.
+    // fp8 path: plain global loads.  bf16 path: the rows [q_abs | q_rope] of all heads are laid
+    // out exactly like a cache tile (one row per head) and travel through the last ring slot as
+    // direct-to-LDS loads issued ahead of the first tiles (see below), so that waiting for them
+    // does not mean waiting for the tiles.
     const int head = hg * 16 + n;
     bf16x8 qreg[NKS];
-    {
+    if constexpr (FP8) {
         const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + head) * D_C;
         const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + head) * 64;
 #pragma unroll
@@ -262,6 +266,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // `ahead` holds the loads issued for the tiles after the one being consumed, oldest first.
     int ahead[NBUF - 1];
 
+    int first_issued = 0;   // loads issued for tile t0 by the last start_ring()
     auto slot_of = [&](int t) { return FP8 ? ((t - t0) & 1) : ((t - t0) % NBUF); };
 
     auto start_ring = [&]() {
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         } else {
 #pragma unroll
             for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
-            fetch_tile(t0);   // every chunk that gets here has at least one tile
+            first_issued = fetch_tile(t0);   // every chunk that gets here has at least one tile
 #pragma unroll
             for (int i = 0; i < NBUF - 2; ++i)
                 if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
@@ -409,14 +414,55 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // long as no later score exceeds the reference by more than FAST_GAP (log2 units): then
     // p <= 2^FAST_GAP and neither p, the normaliser nor the accumulators can overflow.  A
     // larger jump is only recorded here; the chunk is then recomputed by the careful pass.
-    start_ring();
-    // Pin the completion of the query loads here, outside the tile loop.  Left to itself the
-    // compiler would wait for them at their first use inside the loop, on every iteration, with
-    // a count that ignores the tile loads it does not know about - i.e. it would drain the
-    // prefetch ring each time.  (Vector loads return in order, so this one-time wait also
-    // covers the tiles requested just above.)
+    if constexpr (FP8) {
+        start_ring();
+        // Pin the completion of the query loads here, outside the tile loop: left to itself the
+        // compiler would wait for them at their first use inside the loop, on every iteration.
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
+        for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
+    } else {
+        // query rows -> ring slot NBUF-1 (free until the first tile has been consumed), one row
+        // per head, same chunk swizzle as a tile; rows of absent heads are zero-filled
+        LDS_AS unsigned char* qslot = lds + (NBUF - 1) * TILE_B;
+        {
+            const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + (size_t)b * p.H * D_C * 2;
+            const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + (size_t)b * p.H * 128;
+            const uint32_t dst = lds_base + (uint32_t)((NBUF - 1) * TILE_B + wave * 1024);
+#pragma unroll
+            for (int k = 0; k < NLOAD; ++k) {
+                const int P = (k * 4 + wave) * 64 + lane;
+                const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
+                if (r < p.H) {
+                    const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
+                                                          : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
+                    const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                                 :: "s"(m0v), "v"(gp) : "memory");
+                } else {
+                    *(LDS_AS u32x4*)(qslot + P * 16) = (u32x4){0u, 0u, 0u, 0u};
+                }
+            }
+        }
+        start_ring();
+        // wait for the query rows only: the tile loads requested after them stay in flight
+        {
+            int later = first_issued;   // tile t0
+#pragma unroll
+            for (int i = 0; i < NBUF - 2; ++i) later += ahead[i];
+            if (NBUF > 3 && later >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+            else if (NBUF > 2 && later >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
+            else if (later >= NLOAD)                 wait_vmcnt<NLOAD>();
+            else                                     wait_vmcnt<0>();
+        }
+        __syncthreads();
+        const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
+        const uint32_t q_key = (uint32_t)swz_key(n);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            qreg[ks] = *(LDS_AS bf16x8*)(qslot + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
+        // the slot is handed to tile t0 + NBUF - 1 after the next barrier, which every wave
+        // passes only once these reads have completed
+    }
 
     bool jumped = false;
     for (int t = t0; t < t1; ++t) {
