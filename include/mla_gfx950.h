@@ -133,12 +133,14 @@ size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
  *              may be NULL);  seq_len 0 gives -inf
  *   workspace  at least mla_decode_workspace_bytes(B, H, d_c, num_splits)
  *              bytes, 256-byte aligned; contents are scratch
- *   num_splits >= 1: each sequence's page list is cut into num_splits
- *              contiguous chunks of ceil(max_pages_per_seq / num_splits)
- *              pages (trailing chunks of short sequences are empty); every
- *              chunk is reduced with its own running softmax and the chunks
- *              are merged by log-sum-exp.  The result does not depend on
- *              num_splits beyond fp32 rounding.
+ *   num_splits >= 1: each sequence's page list is cut into S contiguous
+ *              chunks of ceil(max_pages_per_seq / S) pages (trailing chunks of
+ *              short sequences are empty), S = num_splits, or 2x / 4x that
+ *              while B * S stays below 256 (so a small batch still gives
+ *              every compute unit a workgroup; mla_decode_workspace_bytes
+ *              accounts for it).  Every chunk is reduced with its own running
+ *              softmax and the chunks are merged by log-sum-exp.  The result
+ *              does not depend on the chunking beyond fp32 rounding.
  *   softmax_scale  the paper uses 1/sqrt(d_head + d_rope) for MLA
  *
  * Supported: io/cache dtype pairs (F32,F32), (BF16,BF16), (BF16,FP8_E4M3),

@@ -11,6 +11,21 @@ bool io_ok(mla_dtype t) { return t == MLA_F32 || t == MLA_BF16; }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Chunks actually used for a request of num_splits chunks per sequence: when the batch is too
+// small for num_splits chunks to give every CU a workgroup, each requested chunk is cut again
+// (x2 or x4).  Every entry point derives the workspace layout from this same rule.
+int effective_splits(int B, int num_splits)
+{
+    int m = 1;
+    while (m < 4 && (long)B * num_splits * m < 256) m *= 2;
+    return num_splits * m;
+}
+
+size_t partial_out_bytes(int B, int H, int d_c, int eff_splits)
+{
+    return align_up((size_t)B * eff_splits * H * d_c * sizeof(float), 256);
+}
+
 }  // namespace
 
 extern "C" {
@@ -57,9 +72,8 @@ int mla_out_proj(const void* o_lat, const void* W_UV, void* out, int B, int H, i
 size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits)
 {
     if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return 0;
-    size_t o = (size_t)B * num_splits * H * d_c * sizeof(float);
-    size_t l = (size_t)B * num_splits * H * sizeof(float);
-    return align_up(o, 256) + align_up(l, 256);
+    const int S = effective_splits(B, num_splits);
+    return partial_out_bytes(B, H, d_c, S) + align_up((size_t)B * S * H * sizeof(float), 256);
 }
 
 int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache,
@@ -84,7 +98,7 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
     if (cache_dtype == MLA_FP8_E4M3 && !kv_scale) return MLA_ERR_NULL;
     if (cache_dtype != MLA_FP8_E4M3 && kv_scale) return MLA_ERR_SHAPE;
     if (H > 64 || d_c > 512 || d_c % 8 || d_rope > 64 || d_rope % 8) return MLA_ERR_UNSUPPORTED;
-    if (B > 65535 || num_splits > 65535) return MLA_ERR_UNSUPPORTED;
+    if (B > 65535 || num_splits > 16383) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
@@ -94,11 +108,11 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
     p.q_abs = q_abs; p.q_rope = q_rope; p.kv = kv_cache; p.kv_scale = kv_scale;
     p.page_table = page_table; p.seq_lens = seq_lens;
     p.o_part = static_cast<float*>(workspace);
-    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) +
-                                          align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
+    const int S = effective_splits(B, num_splits);
+    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + partial_out_bytes(B, H, d_c, S));
     p.B = B; p.H = H; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
-    p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = num_splits;
-    p.chunk_pages = (max_pages_per_seq + num_splits - 1) / num_splits;
+    p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = S;
+    p.chunk_pages = (max_pages_per_seq + S - 1) / S;
     p.scale = softmax_scale;
 
     hipError_t e;
@@ -111,7 +125,7 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
 
     MergeParams m;
     m.o_part = p.o_part; m.lse_part = p.lse_part; m.o_lat = o_lat; m.lse = lse;
-    m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+    m.B = B; m.H = H; m.d_c = d_c; m.num_splits = S;
     e = launch_merge(m, io_dtype, stream);
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
@@ -129,8 +143,8 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_la
     MergeParams m;
     m.o_part = static_cast<const float*>(workspace);
     m.lse_part = reinterpret_cast<const float*>(
-        static_cast<const char*>(workspace) + align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
-    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+        static_cast<const char*>(workspace) + partial_out_bytes(B, H, d_c, effective_splits(B, num_splits)));
+    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = effective_splits(B, num_splits);
     hipError_t e = launch_merge(m, io_dtype, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
@@ -150,8 +164,8 @@ int mla_merge_out_proj(const void* workspace, size_t workspace_bytes, const void
     MergeParams m;
     m.o_part = static_cast<const float*>(workspace);
     m.lse_part = reinterpret_cast<const float*>(
-        static_cast<const char*>(workspace) + align_up((size_t)B * num_splits * H * d_c * sizeof(float), 256));
-    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = num_splits;
+        static_cast<const char*>(workspace) + partial_out_bytes(B, H, d_c, effective_splits(B, num_splits)));
+    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = effective_splits(B, num_splits);
     hipError_t e;
     if (merge_out_proj_supported(m, d_head, io_dtype)) {
         e = launch_merge_out_proj(m, W_UV, out, stream);
