@@ -192,8 +192,9 @@ def main():
                                            "p90": round(float(np.percentile(dec_us, 90)), 2)},
                        ("merge+out_proj" if args.unfused_tail else "merge_out_proj_fused"):
                            {"avg": round(float(mrg_us.mean()), 2)}},
-        "roofline": {"bound": "hbm", "kernel": "split-KV decode kernel" if args.workload != "C2"
-                     else "decode_mfma_bf16_kernel<512>",
+        "roofline": {"bound": "hbm", "kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1>", "C3": "decode_mfma_kernel<512, false, 4, 1>",
+                                "C4": "decode_mfma_kernel<256, false, 4, 1>", "C5": "decode_mfma_kernel<512, true, 4, 1>",
+                                "C1": "decode_portable_kernel<float, float>"}[args.workload],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": cache_bytes},

@@ -40,6 +40,7 @@
 // reads of 16 consecutive rows hit 16 different bank groups, and each half-wave
 // of a transposing read (8 rows x 32 bytes) covers all 64 banks once.
 #include "mla_internal.h"
+#include <type_traits>
 
 namespace mla {
 namespace {
@@ -523,56 +524,69 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         }
     }
 
-    // ---- merge the two row halves of each head group, normalise, write the partial
+    // ---- merge the two row halves of each head group, normalise, write the partial.
+    // Both wavefronts of a head group hold all D_C columns for their 16 tile rows.  Each hands the
+    // column half it does not finish to its partner through LDS and finishes the other half:
+    // combine, transpose (a lane holds 4 consecutive columns of head n per column tile, which
+    // written straight out would give 64-byte runs) and store whole 1 KB runs.
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
     __syncthreads();  // tiles no longer needed (nothing is in flight): reuse LDS as exchange space
-    constexpr int RSO = D_C * 4 + 16;      // row stride of the transposed output (padded: conflict-free both ways)
-    constexpr int XCH = (NCT * 1024 + 512) > 16 * RSO ? (NCT * 1024 + 512) : 16 * RSO;  // per head group
-    static_assert(2 * XCH <= NBUF * TILE_B, "exchange space must fit in the tile ring");
-    LDS_AS unsigned char* xch = lds + hg * XCH;
-    if (tg == 1) {
+    constexpr int HCT = NCT / 2;             // column tiles each wavefront finishes
+    constexpr int RSO = HCT * 64 + 16;       // row stride of the transposed half (padded: conflict-free both ways)
+    constexpr int XCH = (HCT * 1024 + 512) > 16 * RSO ? (HCT * 1024 + 512) : 16 * RSO;  // per wavefront
+    static_assert(4 * XCH <= NBUF * TILE_B, "exchange space must fit in the tile ring");
+    LDS_AS unsigned char* mine = lds + (hg * 2 + tg) * XCH;          // written by the partner
+    LDS_AS unsigned char* theirs = lds + (hg * 2 + (tg ^ 1)) * XCH;  // written by this wavefront
+    auto hand_over = [&](auto first) {
+        constexpr int C0 = decltype(first)::value;
 #pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) *(LDS_AS f32x4*)(xch + (ct * 64 + lane) * 16) = oacc[ct];
-        *(LDS_AS float*)(xch + NCT * 1024 + lane * 4) = m_run;
-        *(LDS_AS float*)(xch + NCT * 1024 + 256 + lane * 4) = l_w;
-    }
+        for (int i = 0; i < HCT; ++i) *(LDS_AS f32x4*)(theirs + (i * 64 + lane) * 16) = oacc[C0 + i];
+    };
+    if (tg == 0) hand_over(std::integral_constant<int, HCT>{});
+    else         hand_over(std::integral_constant<int, 0>{});
+    *(LDS_AS float*)(theirs + HCT * 1024 + lane * 4) = m_run;
+    *(LDS_AS float*)(theirs + HCT * 1024 + 256 + lane * 4) = l_w;
     __syncthreads();
-    if (tg == 0) {
-        const float m1 = *(LDS_AS float*)(xch + NCT * 1024 + lane * 4);
-        const float l1 = *(LDS_AS float*)(xch + NCT * 1024 + 256 + lane * 4);
-        const float m_all = fmaxf(m_run, m1);
-        const float m_use = m_all == -INFINITY ? 0.f : m_all;
-        const float w0 = fast_exp2(m_run - m_use), w1 = fast_exp2(m1 - m_use);
-        const float lt = l_w * w0 + l1 * w1;
-        const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        const float s0 = w0 * inv, s1 = w1 * inv;
-        // combine the halves in registers first; the exchange area of this head group is then
-        // free and is reused for the transposition below (only this wavefront touches it now,
-        // and LDS executes a wavefront's accesses in order)
+    const float m1 = *(LDS_AS float*)(mine + HCT * 1024 + lane * 4);
+    const float l1 = *(LDS_AS float*)(mine + HCT * 1024 + 256 + lane * 4);
+    const float m_all = fmaxf(m_run, m1);
+    const float m_use = m_all == -INFINITY ? 0.f : m_all;
+    const float w0 = fast_exp2(m_run - m_use), w1 = fast_exp2(m1 - m_use);
+    const float lt = l_w * w0 + l1 * w1;
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const float s0 = w0 * inv, s1 = w1 * inv;
+    // combine in registers first; this wavefront's area is then free and is reused for the
+    // transposition (only this wavefront touches it now, and LDS executes a wavefront's
+    // accesses in order)
+    auto finish_half = [&](auto first) {
+        constexpr int C0 = decltype(first)::value;
 #pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            f32x4 o1 = *(LDS_AS f32x4*)(xch + (ct * 64 + lane) * 16);
-            oacc[ct] = oacc[ct] * s0 + o1 * s1;
+        for (int i = 0; i < HCT; ++i) {
+            f32x4 o1 = *(LDS_AS f32x4*)(mine + (i * 64 + lane) * 16);
+            oacc[C0 + i] = oacc[C0 + i] * s0 + o1 * s1;
         }
-        // The lane holds 4 consecutive columns of head n per column tile: writing that straight
-        // out would give 64-byte runs.  Transpose through LDS and store whole 1 KB runs.
-        LDS_AS unsigned char* tr = xch;
 #pragma unroll
-        for (int ct = 0; ct < NCT; ++ct)
-            *(LDS_AS f32x4*)(tr + n * RSO + (ct * 16 + g * 4) * 4) = oacc[ct];
-        const int nrow = min(16, p.H - hg * 16);
-        for (int r = 0; r < nrow; ++r) {
-            float* dst = p.o_part + (part + hg * 16 + r) * D_C;
-#pragma unroll
-            for (int c = 0; c < D_C / 256; ++c) {
-                f32x4 v = *(LDS_AS f32x4*)(tr + r * RSO + (c * 64 + lane) * 16);
-                *reinterpret_cast<f32x4*>(dst + (c * 64 + lane) * 4) = v;
-            }
+        for (int i = 0; i < HCT; ++i)
+            *(LDS_AS f32x4*)(mine + n * RSO + (i * 16 + g * 4) * 4) = oacc[C0 + i];
+    };
+    if (tg == 0) finish_half(std::integral_constant<int, 0>{});
+    else         finish_half(std::integral_constant<int, HCT>{});
+    const int nrow = min(16, p.H - hg * 16);
+    constexpr int LPR = HCT * 4;             // lanes (of 16 bytes) covering one row of the half
+    constexpr int RPI = 64 / LPR;            // rows one store instruction covers (1 or 2)
+    static_assert(LPR == 64 || LPR == 32, "half a latent row is 1 KB or 512 B");
+#pragma unroll 4
+    for (int r0 = 0; r0 < 16; r0 += RPI) {
+        const int r = r0 + lane / LPR, c = lane % LPR;
+        if (r < nrow) {
+            f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
+            float* dst = p.o_part + (part + hg * 16 + r) * D_C + tg * (HCT * 16) + c * 4;
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
         }
-        if (head < p.H && g == 0)
-            p.lse_part[part + head] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
     }
+    if (tg == 0 && head < p.H && g == 0)
+        p.lse_part[part + head] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
 }
 
 }  // namespace
