@@ -105,7 +105,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     constexpr int VG = 8;                       // column tiles per read-ahead group (value)
     static_assert(TILE_B % (MF_THREADS * 16) == 0, "tile must split evenly over the loads");
     static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
-    static_assert(NLOAD * (NBUF - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert(NLOAD * NBUF < 64, "vmcnt is a 6-bit counter");
     static_assert(NBUF >= 2 && NBUF <= 4, "ring depth");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
@@ -125,24 +125,50 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // touch this chunk's first page-table line now, in parallel with the sequence length
     // (both are scalar loads): the later look-ups then hit the scalar cache
     const int warm = ptab[min(split * p.chunk_pages, p.max_pages - 1)];
-    asm volatile("" :: "s"(warm));
     int L = seq_lens_c[b];
+
+    // ---- this wave's 16 query rows as B operands, resident for the whole chunk.
+    // fp8 path: plain global loads.  bf16 path: the rows [q_abs | q_rope] of all heads are laid
+    // out exactly like a cache tile (one row per head, same chunk swizzle; rows of absent heads
+    // zero-filled) and travel through the last ring slot, which is free until the first tile
+    // has been consumed, as direct-to-LDS loads.  They are requested here, while the two scalar
+    // loads above are still on their way, and ahead of the first tiles, so that waiting for
+    // them does not mean waiting for the tiles.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    LDS_AS unsigned char* qslot = lds + (NBUF - 1) * TILE_B;
+    if constexpr (!FP8) {
+        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + (size_t)b * p.H * D_C * 2;
+        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + (size_t)b * p.H * 128;
+        const uint32_t dst = lds_base + (uint32_t)((NBUF - 1) * TILE_B + wave * 1024);
+#pragma unroll
+        for (int k = 0; k < NLOAD; ++k) {
+            const int P = (k * 4 + wave) * 64 + lane;
+            const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
+            if (r < p.H) {
+                const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
+                                                      : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            } else {
+                *(LDS_AS u32x4*)(qslot + P * 16) = (u32x4){0u, 0u, 0u, 0u};
+            }
+        }
+    }
+
+    asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
     const int row0 = split * p.chunk_pages * 64;                    // first cached row of this chunk
     const int row1 = min(row0 + p.chunk_pages * 64, L);             // one past its last row
     const size_t part = ((size_t)b * p.num_splits + split) * p.H;
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
         if (tid < p.H) p.lse_part[part + tid] = -INFINITY;
+        wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
     const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
     const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
 
-    // ---- this wave's 16 query rows as B operands, resident for the whole chunk.
-    // fp8 path: plain global loads.  bf16 path: the rows [q_abs | q_rope] of all heads are laid
-    // out exactly like a cache tile (one row per head) and travel through the last ring slot as
-    // direct-to-LDS loads issued ahead of the first tiles (see below), so that waiting for them
-    // does not mean waiting for the tiles.
     const int head = hg * 16 + n;
     bf16x8 qreg[NKS];
     if constexpr (FP8) {
@@ -173,7 +199,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         int r = P / CPR, pc = P % CPR;
         goff[k] = (uint32_t)(r * ROWB + ((pc ^ swz_key(r)) << 4));
     }
-    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     const unsigned char* kv = static_cast<const unsigned char*>(p.kv);
 
     // rows of tile t that belong to this chunk (0 if its page id is outside the pool)
@@ -270,7 +295,14 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     int first_issued = 0;   // loads issued for tile t0 by the last start_ring()
     auto slot_of = [&](int t) { return FP8 ? ((t - t0) & 1) : ((t - t0) % NBUF); };
 
-    auto start_ring = [&]() {
+    bool ring_full = false;   // tile t0 + NBUF - 1 has been requested ahead of the first stage step
+    // request tile t0 + NBUF - 1 into the last ring slot before the first stage step (which
+    // then must not request it again); only once nobody reads the query rows there any more
+    auto fill_last_slot = [&]() {
+        ahead[NBUF - 2] = t0 + NBUF - 1 < t1 ? fetch_tile(t0 + NBUF - 1) : 0;
+        ring_full = true;
+    };
+    auto start_ring = [&](bool whole_ring) {
         if constexpr (FP8) {
             fetch_regs(t0);
             store_regs(0);
@@ -282,6 +314,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 #pragma unroll
             for (int i = 0; i < NBUF - 2; ++i)
                 if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+            ring_full = false;
+            if (whole_ring) fill_last_slot();
         }
     };
 
@@ -298,13 +332,17 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
             // ring slot now receives tile t + NBUF - 1
             int younger = 0;
 #pragma unroll
-            for (int i = 0; i < NBUF - 2; ++i) younger += ahead[i];
-            if (NBUF > 3 && younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
-            else if (NBUF > 2 && younger >= NLOAD) wait_vmcnt<NLOAD>();
-            else                                   wait_vmcnt<0>();
+            for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];   // the last entry is 0 unless ring_full
+            if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+            else if (NBUF > 2 && younger >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
+            else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
+            else                                       wait_vmcnt<0>();
             __syncthreads();
-            const int tn = t + NBUF - 1;
-            ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+            if (!ring_full) {
+                const int tn = t + NBUF - 1;
+                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+            }
+            ring_full = false;
             if (n_valid < TILE_ROWS) {
                 // ragged last tile (or a page id outside the pool): rows that are not part of
                 // the sequence become zeros so that whatever they hold stays out
@@ -416,35 +454,13 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // p <= 2^FAST_GAP and neither p, the normaliser nor the accumulators can overflow.  A
     // larger jump is only recorded here; the chunk is then recomputed by the careful pass.
     if constexpr (FP8) {
-        start_ring();
+        start_ring(false);
         // Pin the completion of the query loads here, outside the tile loop: left to itself the
         // compiler would wait for them at their first use inside the loop, on every iteration.
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
     } else {
-        // query rows -> ring slot NBUF-1 (free until the first tile has been consumed), one row
-        // per head, same chunk swizzle as a tile; rows of absent heads are zero-filled
-        LDS_AS unsigned char* qslot = lds + (NBUF - 1) * TILE_B;
-        {
-            const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + (size_t)b * p.H * D_C * 2;
-            const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + (size_t)b * p.H * 128;
-            const uint32_t dst = lds_base + (uint32_t)((NBUF - 1) * TILE_B + wave * 1024);
-#pragma unroll
-            for (int k = 0; k < NLOAD; ++k) {
-                const int P = (k * 4 + wave) * 64 + lane;
-                const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
-                if (r < p.H) {
-                    const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
-                                                          : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
-                    const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                                 :: "s"(m0v), "v"(gp) : "memory");
-                } else {
-                    *(LDS_AS u32x4*)(qslot + P * 16) = (u32x4){0u, 0u, 0u, 0u};
-                }
-            }
-        }
-        start_ring();
+        start_ring(false);
         // wait for the query rows only: the tile loads requested after them stay in flight
         {
             int later = first_issued;   // tile t0
@@ -461,8 +477,10 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
             qreg[ks] = *(LDS_AS bf16x8*)(qslot + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
-        // the slot is handed to tile t0 + NBUF - 1 after the next barrier, which every wave
-        // passes only once these reads have completed
+        // once every wave has its query rows in registers the slot joins the ring: its first
+        // tile is requested right away instead of after the first tile has arrived
+        __syncthreads();
+        fill_last_slot();
     }
 
     bool jumped = false;
@@ -488,7 +506,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) oacc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
         if constexpr (FP8) __syncthreads();   // every wave is done reading both slots
-        start_ring();
+        start_ring(true);
         int t = t0;
         bool staged = false;       // tile t has already been through its stage step
         int n_valid = 0;
