@@ -98,7 +98,7 @@ int mla_out_proj(const void* o_lat, const void* W_UV, void* out,
 
 /*
  * Bytes of device workspace mla_decode_paged needs for these sizes (split-KV
- * partial results: fp32 [B, num_splits, H, d_c] + fp32 [B, num_splits, H]).
+ * partial results: fp32 [B, H, num_splits, d_c] + fp32 [B, H, num_splits]).
  * Pure host function; returns 0 if an argument is <= 0.
  */
 size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);

@@ -160,9 +160,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     L = max(0, min(L, p.max_pages * 64));
     const int row0 = split * p.chunk_pages * 64;                    // first cached row of this chunk
     const int row1 = min(row0 + p.chunk_pages * 64, L);             // one past its last row
-    const size_t part = ((size_t)b * p.num_splits + split) * p.H;
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < p.H) p.lse_part[part + tid] = -INFINITY;
+        if (tid < p.H) p.lse_part[part_index(b, tid, split, p.H, p.num_splits)] = -INFINITY;
         wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
@@ -540,6 +539,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
             }
             if (!rescale) break;
         }
+        __syncthreads();  // every wave is done with the tiles of the second pass too
     }
 
     // ---- merge the two row halves of each head group, normalise, write the partial.
@@ -549,7 +549,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // written straight out would give 64-byte runs) and store whole 1 KB runs.
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
-    __syncthreads();  // tiles no longer needed (nothing is in flight): reuse LDS as exchange space
+    // Every wave has passed a barrier after its last tile read and nothing is in flight: the
+    // tile ring is free and serves as exchange space.
     constexpr int HCT = NCT / 2;             // column tiles each wavefront finishes
     constexpr int RSO = HCT * 64 + 16;       // row stride of the transposed half (padded: conflict-free both ways)
     constexpr int XCH = (HCT * 1024 + 512) > 16 * RSO ? (HCT * 1024 + 512) : 16 * RSO;  // per wavefront
@@ -599,12 +600,12 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
             f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = p.o_part + (part + hg * 16 + r) * D_C + tg * (HCT * 16) + c * 4;
+            float* dst = p.o_part + part_index(b, hg * 16 + r, split, p.H, p.num_splits) * D_C + tg * (HCT * 16) + c * 4;
             __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
         }
     }
     if (tg == 0 && head < p.H && g == 0)
-        p.lse_part[part + head] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+        p.lse_part[part_index(b, head, split, p.H, p.num_splits)] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
 }
 
 }  // namespace

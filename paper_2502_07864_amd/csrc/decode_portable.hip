@@ -88,10 +88,8 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
     const long j0l = min((long)L, (long)split * chunk_tok);
     const long j1l = min((long)L, j0l + chunk_tok);
     const int j0 = (int)j0l, j1 = (int)j1l;
-    const size_t part = ((size_t)b * p.num_splits + split) * p.H;
-
     if (j0 >= j1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < nh) p.lse_part[part + h0 + tid] = -INFINITY;
+        if (tid < nh) p.lse_part[part_index(b, h0 + tid, split, p.H, p.num_splits)] = -INFINITY;
         return;
     }
 
@@ -194,13 +192,13 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         if (c < p.d_c) {
             for (int h = 0; h < nh; ++h) {
                 float l = l_s[h];
-                p.o_part[(part + h0 + h) * p.d_c + c] = l > 0.f ? acc[i][h] / l : 0.f;
+                p.o_part[part_index(b, h0 + h, split, p.H, p.num_splits) * p.d_c + c] = l > 0.f ? acc[i][h] / l : 0.f;
             }
         }
     }
     if (tid < nh) {
         float l = l_s[tid];
-        p.lse_part[part + h0 + tid] = l > 0.f ? m_s[tid] + logf(l) : -INFINITY;
+        p.lse_part[part_index(b, h0 + tid, split, p.H, p.num_splits)] = l > 0.f ? m_s[tid] + logf(l) : -INFINITY;
     }
 }
 
@@ -210,22 +208,22 @@ __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
 {
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int S = p.num_splits;
-    const float* lp = p.lse_part + (size_t)b * S * p.H + h;  // stride H over s
+    const float* lp = p.lse_part + part_index(b, h, 0, p.H, S);
     float m = -INFINITY;
-    for (int s = 0; s < S; ++s) m = fmaxf(m, lp[(size_t)s * p.H]);
+    for (int s = 0; s < S; ++s) m = fmaxf(m, lp[s]);
     float z = 0.f;
     if (m != -INFINITY)
-        for (int s = 0; s < S; ++s) z += expf(lp[(size_t)s * p.H] - m);  // exp(-inf) = 0
+        for (int s = 0; s < S; ++s) z += expf(lp[s] - m);  // exp(-inf) = 0
     const float inv = z > 0.f ? 1.f / z : 0.f;
     const size_t out_base = ((size_t)b * p.H + h) * p.d_c;
     for (int c = tid * 4; c < p.d_c; c += 128 * 4) {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int s = 0; s < S; ++s) {
-            float ls = lp[(size_t)s * p.H];
+            float ls = lp[s];
             if (ls == -INFINITY) continue;  // empty chunk: its partial output was never written
             float w = expf(ls - m) * inv;
             const float4 v = *reinterpret_cast<const float4*>(
-                p.o_part + (((size_t)b * S + s) * p.H + h) * p.d_c + c);
+                p.o_part + part_index(b, h, s, p.H, S) * p.d_c + c);
             acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
             acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
         }
@@ -242,9 +240,8 @@ __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
 }
 
 // Streaming variant for d_c a multiple of 256 and at most 64 chunks: one wavefront per
-// (sequence, head, block of 256 columns).  Lane s owns the log-sum-exp of chunk s, so the
-// weights come from two wave reductions; every lane streams one float4 per chunk with the
-// loads of up to 16 chunks in flight.
+// (sequence, head, block of 256 columns).  Lane s owns the log-sum-exp of chunk s; every lane
+// streams one float4 per chunk with the loads of up to 16 chunks in flight.
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
 {
@@ -258,42 +255,33 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
     const int b = bh / p.H, h = bh % p.H;
     const int S = p.num_splits;
 
-    // Start streaming the first chunks' partial rows before their weights are known (the
-    // weights need a load and two wave reductions).  Rows of empty chunks were never written:
-    // whatever is read there is discarded by a select, not multiplied by zero.
+    // Start streaming the first chunks' partial rows before their weights are known.  Rows of
+    // empty chunks were never written: whatever is read there is discarded by a select, not
+    // multiplied by zero.
     constexpr int BATCH = 16;
-    const size_t stride = (size_t)p.H * p.d_c;
-    const float* base = p.o_part + ((size_t)b * S * p.H + h) * p.d_c + cb * 256 + lane * 4;
+    const size_t stride = (size_t)p.d_c;
+    const float* base = p.o_part + part_index(b, h, 0, p.H, S) * p.d_c + cb * 256 + lane * 4;
+    const float ls = lane < S ? p.lse_part[part_index(b, h, lane, p.H, S)] : -INFINITY;
     float4 v[BATCH];
 #pragma unroll
-    for (int i = 0; i < BATCH; ++i)
-        if (i < S) v[i] = *reinterpret_cast<const float4*>(base + (size_t)i * stride);
+    for (int i = 0; i < BATCH; ++i)   // rows past the last chunk re-read it (weight zero)
+        v[i] = *reinterpret_cast<const float4*>(base + (size_t)min(i, S - 1) * stride);
 
-    const float ls = lane < S ? p.lse_part[((size_t)b * S + lane) * p.H + h] : -INFINITY;
-    float m = ls;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    const float e = m == -INFINITY ? 0.f : expf(ls - m);   // exp(-inf) = 0 for empty chunks
-    float z = e;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-    const float w = z > 0.f ? e / z : 0.f;
+    const ChunkWeights cw = chunk_weights(ls, S);
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = 0; s0 < S; s0 += BATCH) {
         if (s0 > 0) {
 #pragma unroll
             for (int i = 0; i < BATCH; ++i)
-                if (s0 + i < S) v[i] = *reinterpret_cast<const float4*>(base + (size_t)(s0 + i) * stride);
+                v[i] = *reinterpret_cast<const float4*>(base + (size_t)min(s0 + i, S - 1) * stride);
         }
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-            if (s0 + i < S) {
-                const float ws = __shfl(w, s0 + i);
-                const bool live = ws != 0.f;
-                acc.x = fmaf(ws, live ? v[i].x : 0.f, acc.x); acc.y = fmaf(ws, live ? v[i].y : 0.f, acc.y);
-                acc.z = fmaf(ws, live ? v[i].z : 0.f, acc.z); acc.w = fmaf(ws, live ? v[i].w : 0.f, acc.w);
-            }
+            const float ws = chunk_weight_at(cw, ls, s0 + i);   // 0 at and past S
+            const bool live = ws != 0.f;
+            acc.x = fmaf(ws, live ? v[i].x : 0.f, acc.x); acc.y = fmaf(ws, live ? v[i].y : 0.f, acc.y);
+            acc.z = fmaf(ws, live ? v[i].z : 0.f, acc.z); acc.w = fmaf(ws, live ? v[i].w : 0.f, acc.w);
         }
     }
     const size_t o = (size_t)bh * p.d_c + cb * 256 + lane * 4;
@@ -305,7 +293,7 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
     } else {
         *reinterpret_cast<float4*>(static_cast<float*>(p.o_lat) + o) = acc;
     }
-    if (p.lse && cb == 0 && lane == 0) p.lse[bh] = z > 0.f ? m + logf(z) : -INFINITY;
+    if (p.lse && cb == 0 && lane == 0) p.lse[bh] = cw.z > 0.f ? cw.m + logf(cw.z) : -INFINITY;
 }
 
 // ---- page gather (byte exact) ---------------------------------------------

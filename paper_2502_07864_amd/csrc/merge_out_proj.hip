@@ -3,8 +3,8 @@
 // writes the same product as part of W'^O):
 //     o_lat[b,h,:] = sum_s e^{lse_s - lse} o_s[b,h,:]          out[b,h,:] = o_lat[b,h,:] . W_UV[h]
 // One workgroup = one head x BG batch rows.  The whole W_UV[h] slab ([d_c x 128] bf16, 128 KB at
-// d_c = 512) is requested first as direct-to-LDS loads; while it is in flight the four
-// wavefronts merge the partial rows (one wavefront per row and block of 256 columns, as in the
+// d_c = 512) is requested as direct-to-LDS loads right after each wavefront's first partial rows;
+// while it is in flight the four wavefronts merge the partial rows (one wavefront per row and block of 256 columns, as in the
 // stand-alone merge kernel), write o_lat and leave a bf16 copy in LDS as the A operand.  The
 // product then runs on v_mfma_f32_16x16x32_bf16 with the B operand read by transposing LDS
 // loads (W is stored k-major).  Compared with the two separate kernels this saves a launch and
@@ -46,17 +46,43 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    // workgroup ids that differ by a multiple of H share a head: they land on the same XCD
-    // (ids are dealt round-robin over the 8 XCDs and H is a multiple of 8 for the usual shapes)
-    const int h = blockIdx.x % p.H;
-    const int b0 = (blockIdx.x / p.H) * BG;
+    // workgroups of one head have linear ids that differ by a multiple of H: they land on the
+    // same XCD (ids are dealt round-robin over the 8 XCDs and H is a multiple of 8 for the
+    // usual shapes) and share the slab in its L2
+    const int h = blockIdx.x;
+    const int b0 = blockIdx.y * BG;
     const int nb = min(BG, p.B - b0);
 
-    // ---- (1) request W_UV[h]: LDS chunk P = row P/16, position P%16 holds chunk (P%16) ^ key(row)
+    const int S = p.num_splits;
+    constexpr int CB = D_C / 256;
+    constexpr int BATCH = 16;
+    // wave task = (batch row, block of 256 columns); partial rows [s0, s0 + BATCH) of a task
+    auto task_base = [&](int task) {
+        const int bl = task / CB, cb = task % CB;
+        return p.o_part + part_index(b0 + bl, h, 0, p.H, S) * D_C + cb * 256 + lane * 4;
+    };
+    // rows past the last chunk re-read the last one (their weight is zero): no branches, the
+    // kernel's code stays short and straight, which matters for a kernel this brief
+    auto load_rows = [&](const float* base, int s0, f32x4 (&v)[BATCH]) {
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i)
+            v[i] = *reinterpret_cast<const f32x4*>(base + (size_t)min(s0 + i, S - 1) * D_C);
+    };
+
+    // ---- (1) the first task's chunk weights and partial rows are requested ahead of everything
+    // else: they come from HBM, the slab mostly from L2 (the workgroups of a head share it)
+    f32x4 v[BATCH];
+    float ls_first = -INFINITY;
+    if (wave / CB < nb) {
+        if (lane < S) ls_first = p.lse_part[part_index(b0 + wave / CB, h, lane, p.H, S)];
+        load_rows(task_base(wave), 0, v);
+    }
+
+    // ---- (2) request W_UV[h]: LDS chunk P = row P/16, position P%16 holds chunk (P%16) ^ key(row)
     {
         const unsigned char* src = reinterpret_cast<const unsigned char*>(W_UV + (size_t)h * D_C * FT_N);
         const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-#pragma unroll
+#pragma unroll 4
         for (int k = 0; k < NLOAD; ++k) {
             const int P = (k * 4 + wave) * 64 + lane;
             const int r = P >> 4, pc = P & 15;
@@ -67,59 +93,45 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
         }
     }
 
-    // ---- (2) merge: wave task = (batch row, block of 256 columns)
-    const int S = p.num_splits;
-    constexpr int CB = D_C / 256;
+    // ---- (3) merge (same arithmetic as the stand-alone merge kernel)
     for (int task = wave; task < FT_MAXB * CB; task += 4) {
         const int bl = task / CB, cb = task % CB;
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
         if (bl < nb) {
             const int b = b0 + bl;
-            constexpr int BATCH = 16;
-            const size_t stride = (size_t)p.H * D_C;
-            const float* base = p.o_part + ((size_t)b * S * p.H + h) * D_C + cb * 256 + lane * 4;
-            f32x4 v[BATCH];
-#pragma unroll
-            for (int i = 0; i < BATCH; ++i)
-                if (i < S) v[i] = *reinterpret_cast<const f32x4*>(base + (size_t)i * stride);
-            const float ls = lane < S ? p.lse_part[((size_t)b * S + lane) * p.H + h] : -INFINITY;
-            float m = ls;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-            const float e = m == -INFINITY ? 0.f : expf(ls - m);
-            float z = e;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-            const float w = z > 0.f ? e / z : 0.f;
+            const float* base = task_base(task);
+            float ls = ls_first;
+            if (task != wave) {
+                ls = lane < S ? p.lse_part[part_index(b, h, lane, p.H, S)] : -INFINITY;
+                load_rows(base, 0, v);
+            }
+            const ChunkWeights cw = chunk_weights(ls, S);
             for (int s0 = 0; s0 < S; s0 += BATCH) {
-                if (s0 > 0) {
-#pragma unroll
-                    for (int i = 0; i < BATCH; ++i)
-                        if (s0 + i < S) v[i] = *reinterpret_cast<const f32x4*>(base + (size_t)(s0 + i) * stride);
-                }
+                if (s0 > 0) load_rows(base, s0, v);
 #pragma unroll
                 for (int i = 0; i < BATCH; ++i) {
-                    if (s0 + i < S) {
-                        const float ws = __shfl(w, s0 + i);
-                        if (ws != 0.f) acc += ws * v[i];    // rows of empty chunks were never written
-                    }
+                    // the weight is 0 at and past S; rows of empty chunks were never written,
+                    // so what was read there is discarded, not multiplied by zero
+                    const float ws = chunk_weight_at(cw, ls, s0 + i);
+                    const f32x4 zero = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    acc += ws * (ws != 0.f ? v[i] : zero);
                 }
             }
             const u32x2 packed = (u32x2){f32_to_bf16_bits(acc[0]) | (f32_to_bf16_bits(acc[1]) << 16),
                                         f32_to_bf16_bits(acc[2]) | (f32_to_bf16_bits(acc[3]) << 16)};
             *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.o_lat) + ((size_t)b * p.H + h) * D_C + cb * 256 + lane * 4) = packed;
             *(LDS_AS u32x2*)(atile + bl * ARS + (cb * 256 + lane * 4) * 2) = packed;
-            if (p.lse && cb == 0 && lane == 0) p.lse[(size_t)b * p.H + h] = z > 0.f ? m + logf(z) : -INFINITY;
+            if (p.lse && cb == 0 && lane == 0) p.lse[(size_t)b * p.H + h] = cw.z > 0.f ? cw.m + logf(cw.z) : -INFINITY;
         } else {
             *(LDS_AS u32x2*)(atile + bl * ARS + (cb * 256 + lane * 4) * 2) = (u32x2){0u, 0u};
         }
     }
 
-    // ---- (3) slab landed (my loads), then everybody's, and the A tile is complete
+    // ---- (4) slab landed (my loads), then everybody's, and the A tile is complete
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
 
-    // ---- (4) out = o_lat . W_UV[h]: each wave owns two 16-column tiles
+    // ---- (5) out = o_lat . W_UV[h]: each wave owns two 16-column tiles
     f32x4 acc[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
     // transposing read: the lane supplies slab row 32ks + 8g + (n>>2) (+4), 8 bytes at column 4(n&3)
 #pragma unroll 4
@@ -162,7 +174,7 @@ hipError_t launch_merge_out_proj(const MergeParams& p, const void* W_UV, void* o
     // batch rows per workgroup: as few as still gives about one workgroup per CU
     int BG = 1;
     while (BG < FT_MAXB && (long)p.H * ((p.B + BG - 1) / BG) > 256) BG *= 2;
-    dim3 grid(p.H * ((p.B + BG - 1) / BG)), block(256);
+    dim3 grid(p.H, (p.B + BG - 1) / BG), block(256);
     if (p.d_c == 512)
         merge_out_proj_kernel<512><<<grid, block, 0, s>>>(p, static_cast<const uint16_t*>(W_UV), static_cast<uint16_t*>(out), BG);
     else

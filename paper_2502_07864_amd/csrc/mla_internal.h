@@ -16,8 +16,8 @@ struct DecodeParams {
     const float* kv_scale;      // [num_pages, page_size] (fp8 cache) or nullptr
     const int32_t* page_table;  // [B, max_pages]
     const int32_t* seq_lens;    // [B]
-    float* o_part;              // [B, S, H, d_c]  chunk-normalised partial outputs
-    float* lse_part;            // [B, S, H]       natural-log LSE per chunk (-inf = empty)
+    float* o_part;              // [B, H, S, d_c]  chunk-normalised partial outputs
+    float* lse_part;            // [B, H, S]       natural-log LSE per chunk (-inf = empty)
     int B, H, d_c, d_rope, page_size, num_pages, max_pages, num_splits, chunk_pages;
     float scale;
 };
@@ -30,7 +30,54 @@ struct MergeParams {
     int B, H, d_c, num_splits;
 };
 
+// Index of chunk s of (sequence b, head h) in the partial buffers: all chunks of one (b, h) are
+// adjacent, so the merge reads one contiguous block per output row.
+__host__ __device__ __forceinline__ size_t part_index(int b, int h, int s, int H, int S)
+{
+    return ((size_t)b * H + h) * S + s;
+}
+
 // ---- small device helpers ------------------------------------------------
+
+// value of v on lane `lane` (wave-uniform index), as a uniform value on every lane
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Split-KV merge weights of one output row.  Lane s of the wave holds the log-sum-exp of
+// chunk s (-inf for s >= S and for empty chunks).  Every lane computes the same reference
+// (the maximum) and normaliser by reading the S values lane by lane, 16 at a time with
+// compile-time offsets and in index order: no chain of cross-lane shuffles, and a result that
+// does not depend on which wave computes it.  lse = m + log z (z = 0: every chunk empty).
+struct ChunkWeights {
+    float m, z;      // maximum and sum_s e^{lse_s - m}
+    float ref, inv;  // m (0 if every chunk is empty) and 1/z (0 if z = 0)
+};
+
+__device__ __forceinline__ ChunkWeights chunk_weights(float ls, int S)
+{
+    ChunkWeights cw;
+    cw.m = -INFINITY;
+    for (int s0 = 0; s0 < S; s0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cw.m = fmaxf(cw.m, lane_value(ls, s0 + i));
+    }
+    cw.ref = cw.m == -INFINITY ? 0.f : cw.m;
+    cw.z = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cw.z += __expf(lane_value(ls, s0 + i) - cw.ref);   // e^{-inf} = 0
+    }
+    cw.inv = cw.z > 0.f ? 1.f / cw.z : 0.f;
+    return cw;
+}
+
+// weight e^{lse_s - lse} of chunk s (s < 64; 0 for s >= S and for empty chunks), on every lane
+__device__ __forceinline__ float chunk_weight_at(const ChunkWeights& cw, float ls, int s)
+{
+    return __expf(lane_value(ls, s) - cw.ref) * cw.inv;
+}
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16)
 {
