@@ -116,7 +116,15 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hg = wave & 1, tg = wave >> 1;
     const int n = lane & 15, g = lane >> 4;
-    const int split = blockIdx.x, b = blockIdx.y;
+    // Workgroup -> (sequence, chunk).  Linear ids run over the sequences first, chunk by chunk,
+    // with the sequence rotated by the chunk index.  Ids are dealt round-robin to the 8 XCDs and,
+    // inside an XCD, to its CUs in a fixed order, so any regular pattern in the ids repeats on
+    // the hardware: with the chunks of a sequence adjacent, the empty trailing chunks of short
+    // sequences fell on the same CUs every time and left half the chip idle, and a sequence's
+    // chunks all went to the XCDs of its low chunk indices.  This order puts the empty chunks
+    // (high chunk indices) at the end of the grid and spreads every sequence over the XCDs.
+    const int split = blockIdx.y;
+    const int b = (int)((blockIdx.x + blockIdx.y) % (unsigned)p.B);
 
     // Read-only tables go through the scalar cache: scalar loads do not count against the
     // vector-memory counter, so looking up a page id never waits on an in-flight prefetch.
@@ -618,7 +626,7 @@ bool decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache)
 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s)
 {
-    dim3 grid(p.num_splits, p.B), block(MF_THREADS);
+    dim3 grid(p.B, p.num_splits), block(MF_THREADS);
     const bool fp8 = cache == MLA_FP8_E4M3;
     if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1><<<grid, block, 0, s>>>(p);
     else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1><<<grid, block, 0, s>>>(p);
