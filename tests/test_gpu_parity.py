@@ -100,6 +100,26 @@ def test_absorb_and_out_proj(mla, io, B, H, d_head, d_c):
     assert max_abs_rel(widen_gpu(got_o), oracle.out_proj(o, Wv)) <= TOL[io]
 
 
+def test_offline_fold_of_W_UK_into_the_query_projection(mla):
+    """App. A.2.2: W'^Q_h = (W^{UK}_h)^T W^Q_h can be built offline with the absorb call itself,
+    by passing the rows of W^Q (one per model dimension) as the batch:  fold[D, h, :] =
+    W^Q[D, h, :] . W_UK[h].  The folded route x . fold then equals absorb(x . W^Q)."""
+    import torch
+    D, H, d_head, d_c, B = 384, 8, 128, 512, 5
+    r = synth.stream(11, 3)
+    WQ = synth.store(synth.normal(r, (D, H, d_head), 1 / math.sqrt(D)), "bf16")     # [D, H, d_head]
+    Wk = synth.store(synth.normal(r, (H, d_head, d_c), 1 / math.sqrt(d_c)), "bf16")
+    x = synth.normal(r, (B, D)).astype(np.float64)
+    fold = mla.absorb_q(to_torch(WQ, "bf16"), to_torch(Wk, "bf16"))                 # [D, H, d_c] on the GPU
+    torch.cuda.synchronize()
+    want_fold = oracle.absorb_q(WQ, Wk)                                             # fp64, from the stored values
+    assert max_abs_rel(widen_gpu(fold), want_fold) <= TOL["bf16"]
+    q_folded = np.einsum("bD,Dhc->bhc", x, widen_gpu(fold).astype(np.float64))
+    q_nope = np.einsum("bD,Dhk->bhk", x, oracle.widen(WQ).astype(np.float64))
+    q_two_step = np.einsum("bhk,hkc->bhc", q_nope, oracle.widen(Wk).astype(np.float64))
+    assert max_abs_rel(q_folded, q_two_step) <= TOL["bf16"]
+
+
 # ------------------------------------------------------------ decode, fp32
 
 @pytest.mark.parametrize("num_splits", [1, 4, 16])
@@ -211,6 +231,18 @@ def test_fused_merge_out_proj_matches_separate_calls(mla):
         tol = TOL[w.io_dtype]
         assert max_abs_rel(widen_gpu(out2), ref) <= tol
         assert max_abs_rel(widen_gpu(out2), widen_gpu(out1)) <= tol / 2
+
+
+def test_page_table_longer_than_any_sequence(mla):
+    """Every sequence uses only the first part of its page-table row, so the trailing chunks of
+    every sequence are empty (regular pattern of empty workgroups in the grid): results as usual,
+    for chunk counts that leave a quarter, half and most of the chunks empty."""
+    w = synth.make_workload("wide-table", B=6, H=32, d_head=128, d_c=512, d_rope=64,
+                            seq_lens=[1500, 2048, 700, 2047, 64, 1], io_dtype="bf16", cache_dtype="bf16",
+                            placement="random", max_pages_per_seq=128, num_splits=8, seed=41)
+    for S in (4, 8, 32):
+        check_decode(mla, w, S)
+    check_decode(mla, w, 8, flags=1)
 
 
 # ------------------------------------------------------------- edge cases
