@@ -55,6 +55,10 @@ def _c():
         lib.oracle_widen_e4m3.restype = ctypes.c_double
         lib.oracle_widen_e4m3.argtypes = [ctypes.c_uint8]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_encode_bf16.restype = ctypes.c_uint16
+        lib.oracle_encode_bf16.argtypes = [ctypes.c_float]
+        lib.oracle_encode_e4m3.restype = ctypes.c_uint8
+        lib.oracle_encode_e4m3.argtypes = [ctypes.c_float]
         _lib = lib
     return _lib
 
@@ -285,3 +289,68 @@ def mla_step(q_nope, q_rope, W_UK, W_UV, pool, kv_scale, page_table, seq_lens,
                                  seq_lens, softmax_scale)
     out = out_proj(o_lat, W_UV)
     return {"q_abs": q_abs, "o_lat": o_lat, "lse": lse, "out": out}
+
+
+# --------------------------------------------------------------------------
+# cache append (Sec. 3.2 MLA equations: c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t))
+# --------------------------------------------------------------------------
+
+def rope(v, pos: float, base: float = 10000.0) -> np.ndarray:
+    """Sec. 3.1 Eq. 1 on the last axis of v (even length) at position pos; fp64."""
+    out = _f64(v).copy()
+    flat = out.reshape(-1, out.shape[-1])
+    for i in range(flat.shape[0]):
+        r = np.ascontiguousarray(flat[i])
+        rc = _c().oracle_rope(_dp(r), ctypes.c_int(r.shape[0]), ctypes.c_double(pos), ctypes.c_double(base))
+        if rc != 0:
+            raise ValueError("rope needs an even length")
+        flat[i] = r
+    return out
+
+
+def encode_bf16(x32) -> np.ndarray:
+    """float32 -> bf16 bit patterns (uint16), round to nearest even."""
+    a = np.ascontiguousarray(x32, dtype=np.float32)
+    f = _c().oracle_encode_bf16
+    return np.array([f(ctypes.c_float(float(v))) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def encode_e4m3(x32) -> np.ndarray:
+    """float32 -> OCP e4m3 codes (uint8): nearest, ties to even, saturating."""
+    a = np.ascontiguousarray(x32, dtype=np.float32)
+    f = _c().oracle_encode_e4m3
+    return np.array([f(ctypes.c_float(float(v))) for v in a.ravel()], dtype=np.uint8).reshape(a.shape)
+
+
+def encode_row(row32, dtype: int):
+    """One token's fp32 row -> (stored row, scale or None)."""
+    r = np.ascontiguousarray(row32, dtype=np.float32)
+    n = r.shape[0]
+    dst = np.empty(n, dtype={F32: np.float32, BF16: np.uint16, FP8_E4M3: np.uint8}[dtype])
+    sc = ctypes.c_float(0.0)
+    _c().oracle_encode_row(r.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), ctypes.c_int(n), ctypes.c_int(dtype),
+                           _vp(dst), ctypes.byref(sc))
+    return dst, (float(np.float32(sc.value)) if dtype == FP8_E4M3 else None)
+
+
+def cache_append(x, W, pool, kv_scale, page_table, positions, d_c: int, rope_base: float = 10000.0):
+    """Append one token per sequence.  x [B, D], W [D, d_c + d_rope] (stored dtypes or floats;
+    widened exactly), pool / kv_scale / page_table as for the decode.  Returns
+    (new pool, new kv_scale or None, fp64 rows [B, d_c + d_rope]); the inputs are not modified."""
+    pool, sc, dt = _pool_args(pool, kv_scale)
+    pool = pool.copy()
+    sc = None if sc is None else sc.copy()
+    xw, Ww = _f64(widen(x)), _f64(widen(W))
+    B, D = xw.shape
+    n = Ww.shape[1]
+    assert Ww.shape[0] == D and n == pool.shape[2]
+    pt, ps = _i32(page_table), _i32(positions)
+    rows = np.empty((B, n), dtype=np.float64)
+    rc = _c().oracle_cache_append(
+        _dp(xw), _dp(Ww), _vp(pool), None if sc is None else sc.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+        ctypes.c_int(dt), _ip(pt), _ip(ps), ctypes.c_int(B), ctypes.c_int(D), ctypes.c_int(d_c),
+        ctypes.c_int(n - d_c), ctypes.c_int(pool.shape[1]), ctypes.c_int(pool.shape[0]),
+        ctypes.c_int(pt.shape[1]), ctypes.c_double(rope_base), _dp(rows))
+    if rc != 0:
+        raise RuntimeError("oracle_cache_append failed")
+    return pool, sc, rows

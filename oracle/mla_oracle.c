@@ -379,4 +379,121 @@ int oracle_decode_split(const double* q_abs, const double* q_rope,
     return 0;
 }
 
+/* ======================================================================
+ * Cache append: the step that produces the row the decode reads.
+ * Sec. 3.2 (MLA equations, left column):
+ *     c_t^{KV} = W^{DKV} x_t          k_t^R = RoPE(W^{KR} x_t, t)
+ * and the row kept per token is their concatenation [c^{KV} ; k^R]
+ * (App. D.2: the r_kv-dimensional latent is what the cache stores).
+ * RoPE is Sec. 3.1, Eq. 1: consecutive pairs (real, imaginary), pair i
+ * rotated by the angle t * base^(-2i/d).
+ * Storage encoders take their rounding decision on the fp32 value, the
+ * precision the GPU library holds the row in before it stores it.
+ * ====================================================================== */
+
+/* row[j] = sum_k x[k] W[k][j] : W is [D][n], column j of it is row j of
+ * the stacked matrix (W^{DKV} ; W^{KR}) (row-vector storage). */
+int oracle_kv_row(const double* x, const double* W, int D, int n, double* row)
+{
+    for (int j = 0; j < n; ++j) {
+        double acc = 0.0;
+        for (int k = 0; k < D; ++k) acc += x[k] * W[(size_t)k * n + j];
+        row[j] = acc;
+    }
+    return 0;
+}
+
+/* Eq. 1 on a vector of even length d at position pos, in place. */
+int oracle_rope(double* v, int d, double pos, double base)
+{
+    if (d % 2) return -1;
+    for (int i = 0; i < d / 2; ++i) {
+        double theta = pow(base, -2.0 * (double)i / (double)d);
+        double c = cos(pos * theta), s = sin(pos * theta);
+        double re = v[2 * i], im = v[2 * i + 1];
+        v[2 * i]     = re * c - im * s;
+        v[2 * i + 1] = re * s + im * c;
+    }
+    return 0;
+}
+
+/* fp32 -> bfloat16 bits, round to nearest, ties to even (NaN kept quiet). */
+uint16_t oracle_encode_bf16(float f)
+{
+    if (f != f) return 0x7FC0;
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t lo = u & 0xFFFFu, hi = u >> 16;
+    if (lo > 0x8000u || (lo == 0x8000u && (hi & 1u))) hi += 1;  /* carries into the exponent as it must */
+    return (uint16_t)hi;
+}
+
+/* fp32 -> OCP e4m3 code: the nearest representable value, ties to the code
+ * with even mantissa, magnitudes beyond 448 saturate to 448 (the format has
+ * no infinity).  Brute force over the 254 finite codes. */
+uint8_t oracle_encode_e4m3(float f)
+{
+    if (f != f) return 0x7F;
+    double a = fabs((double)f);
+    int best = 0;
+    double best_err = INFINITY;
+    for (int c = 0; c < 0x7F; ++c) {          /* positive codes, 0x7F is NaN */
+        double err = fabs(widen_e4m3((uint8_t)c) - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
+    }
+    return (uint8_t)(best | (signbit(f) ? 0x80 : 0));
+}
+
+/* One token's row in fp32 -> storage.  fp8: one scale per token over the
+ * whole row, scale = absmax/448 (1 for an all-zero row), code =
+ * encode(value/scale), both divisions in fp32. */
+int oracle_encode_row(const float* row, int n, int dtype, void* dst, float* scale_out)
+{
+    if (dtype == ORC_F32) {
+        memcpy(dst, row, (size_t)n * 4);
+    } else if (dtype == ORC_BF16) {
+        for (int j = 0; j < n; ++j) ((uint16_t*)dst)[j] = oracle_encode_bf16(row[j]);
+    } else {
+        float amax = 0.f;
+        for (int j = 0; j < n; ++j) { float a = fabsf(row[j]); if (a > amax) amax = a; }
+        float scale = amax > 0.f ? amax / 448.0f : 1.0f;
+        for (int j = 0; j < n; ++j) ((uint8_t*)dst)[j] = oracle_encode_e4m3(row[j] / scale);
+        if (scale_out) *scale_out = scale;
+    }
+    return 0;
+}
+
+/* For every sequence b: row = [W^{DKV} x_b ; RoPE(W^{KR} x_b, pos_b)] written
+ * to logical position pos_b of that sequence (page page_table[b][pos_b /
+ * page_size], slot pos_b % page_size).  x [B][D], W [D][d_c + d_rope] fp64
+ * (already widened); rows_out (optional) receives the fp64 rows.  A
+ * position outside the table, or a page id outside the pool, leaves that
+ * sequence untouched. */
+int oracle_cache_append(const double* x, const double* W, void* pool, float* kv_scale,
+                        int dtype, const int32_t* page_table, const int32_t* positions,
+                        int B, int D, int d_c, int d_rope, int page_size, int num_pages,
+                        int max_pages_per_seq, double rope_base, double* rows_out)
+{
+    const int n = d_c + d_rope;
+    double* row = (double*)malloc((size_t)n * sizeof(double));
+    float* row32 = (float*)malloc((size_t)n * sizeof(float));
+    if (!row || !row32) { free(row); free(row32); return -1; }
+    for (int b = 0; b < B; ++b) {
+        oracle_kv_row(x + (size_t)b * D, W, D, n, row);
+        oracle_rope(row + d_c, d_rope, (double)positions[b], rope_base);
+        if (rows_out) memcpy(rows_out + (size_t)b * n, row, (size_t)n * sizeof(double));
+        int pos = positions[b];
+        if (pos < 0 || pos >= max_pages_per_seq * page_size) continue;
+        int32_t page = page_table[(size_t)b * max_pages_per_seq + pos / page_size];
+        if (page < 0 || page >= num_pages) continue;
+        size_t r = (size_t)page * page_size + (size_t)(pos % page_size);
+        for (int j = 0; j < n; ++j) row32[j] = (float)row[j];
+        oracle_encode_row(row32, n, dtype, (uint8_t*)pool + r * n * elem_bytes(dtype),
+                          kv_scale ? kv_scale + r : NULL);
+    }
+    free(row);
+    free(row32);
+    return 0;
+}
+
 size_t oracle_elem_bytes(int dtype) { return elem_bytes(dtype); }

@@ -662,3 +662,163 @@ def test_stored_cache_values_are_widened_exactly():
         np.testing.assert_array_equal(o[b], np.broadcast_to(dec[p, :d_c], (H, d_c)))
         np.testing.assert_allclose(lse[b], 0.5 * (qa[b] @ dec[p, :d_c] + qr[b] @ dec[p, d_c:]), rtol=1e-13)
     assert np.abs(dec - x.reshape(B, -1)).max() <= np.abs(x).max() * 2 ** -4  # sanity: it is a quantisation of x
+
+
+# ------------------------------------------------------------ cache append
+# Sec. 3.2 (MLA equations): c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t); Sec. 3.1 Eq. 1 for RoPE.
+
+def test_A1_rope_closed_forms():
+    """Eq. 1: position 0 is the identity; the first pair (theta = 1) of (1, 0) at position
+    pi/2 is (0, 1); with base 1 every pair turns by the position itself; pair norms are kept."""
+    v = RNG.standard_normal(64)
+    assert np.array_equal(oracle.rope(v, 0.0), v)
+    e = np.zeros(8); e[0] = 1.0
+    np.testing.assert_allclose(oracle.rope(e, math.pi / 2)[:2], [0.0, 1.0], atol=1e-15)
+    r = oracle.rope(v, 0.75, base=1.0)
+    z = (v[0::2] + 1j * v[1::2]) * np.exp(1j * 0.75)          # complex multiplication, base 1
+    np.testing.assert_allclose(r[0::2] + 1j * r[1::2], z, rtol=0, atol=1e-14)
+    w = oracle.rope(v, 1234.0)
+    np.testing.assert_allclose(np.hypot(w[0::2], w[1::2]), np.hypot(v[0::2], v[1::2]), rtol=1e-13)
+
+
+def test_A2_rope_group_and_relative_position_properties():
+    """Rotations compose additively in the position, and <RoPE(q, m), RoPE(k, n)> depends on
+    m - n only (the property App. B builds on)."""
+    q, k = RNG.standard_normal(64), RNG.standard_normal(64)
+    np.testing.assert_allclose(oracle.rope(oracle.rope(q, 17.0), 25.0), oracle.rope(q, 42.0), atol=1e-12)
+    d1 = oracle.rope(q, 100.0) @ oracle.rope(k, 93.0)
+    d2 = oracle.rope(q, 5007.0) @ oracle.rope(k, 5000.0)
+    d3 = oracle.rope(q, 7.0) @ k
+    np.testing.assert_allclose([d1, d2], [d3, d3], atol=1e-9)
+
+
+def test_A3_rope_frequencies_against_the_input_generator():
+    """Independent implementation (the workload generator's vectorised numpy RoPE) at the
+    frequencies of Eq. 1, theta_i = 10000^(-2i/d)."""
+    v = RNG.standard_normal((5, 64))
+    for pos in (1.0, 63.0, 8191.0, 131071.0):
+        np.testing.assert_allclose(oracle.rope(v, pos), synth.rope(v, np.full(5, pos)), rtol=0, atol=1e-9)
+
+
+def test_A4_bf16_encoder_against_the_tensor_library_and_ties():
+    import torch
+    x = np.concatenate([RNG.standard_normal(4000).astype(np.float32) * 3,
+                        np.float32([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40, -65504.0])])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.encode_bf16(x), want)
+    # ties go to the even mantissa: 1 + 2^-8 -> 1.0, 1 + 3*2^-8 -> 1 + 2^-6
+    assert oracle.encode_bf16(np.float32([1.00390625]))[0] == 0x3F80
+    assert oracle.encode_bf16(np.float32([1.01171875]))[0] == 0x3F82
+
+
+def test_A5_e4m3_encoder_round_trip_ties_saturation():
+    """Every finite code's value encodes to that code (table of the OCP format in
+    tests/golden); the midpoint of two neighbours goes to the even mantissa; beyond 448 -> 448."""
+    for code, sval in _golden_pairs("e4m3_ocp_values.txt"):
+        if sval == "nan":
+            continue
+        got = int(oracle.encode_e4m3(np.float32([float(sval)]))[0])
+        assert got == code, (hex(code), sval, hex(got))
+    # all neighbouring finite codes (their values come from the decoder pinned by P10)
+    for c0 in range(0x00, 0x7E):
+        v0, v1 = oracle.widen_e4m3_code(c0), oracle.widen_e4m3_code(c0 + 1)
+        assert int(oracle.encode_e4m3(np.float32([v0]))[0]) == c0
+        mid = np.float32((v0 + v1) / 2)                      # exact in fp32
+        want = c0 if c0 % 2 == 0 else c0 + 1
+        assert int(oracle.encode_e4m3(np.float32([mid]))[0]) == want
+        assert int(oracle.encode_e4m3(np.float32([-mid]))[0]) == (want | 0x80)
+        eps = np.float32((v1 - v0) / 64)
+        assert int(oracle.encode_e4m3(np.float32([mid - eps]))[0]) == c0
+        assert int(oracle.encode_e4m3(np.float32([mid + eps]))[0]) == c0 + 1
+    assert list(oracle.encode_e4m3(np.float32([449.0, 1e9, -1e9, 464.0]))) == [0x7E, 0x7E, 0xFE, 0x7E]
+
+
+def test_A6_e4m3_encoder_and_row_scale_against_the_tensor_library():
+    import torch
+    x = (RNG.standard_normal(6000) * 100).astype(np.float32)
+    want = torch.from_numpy(np.clip(x, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(oracle.encode_e4m3(x), want)
+    row = RNG.standard_normal(576).astype(np.float32)
+    codes, scale = oracle.encode_row(row, oracle.FP8_E4M3)
+    wc, ws = synth.quant_e4m3_per_token(row[None])
+    assert np.array_equal(codes, wc[0]) and np.float32(scale) == ws[0]
+    assert int(codes[np.argmax(np.abs(row))]) & 0x7F == 0x7E     # the largest magnitude lands on 448
+    codes0, scale0 = oracle.encode_row(np.zeros(16, np.float32), oracle.FP8_E4M3)
+    assert scale0 == 1.0 and not codes0.any()
+
+
+def _append_case(cache_dtype, seed=5):
+    w = synth.make_workload("append", B=3, H=2, d_head=8, d_c=32, d_rope=8, seq_lens=[5, 64, 130],
+                            io_dtype="bf16", cache_dtype=cache_dtype, page_size=64, placement="random",
+                            free_frac=0.5, max_pages_per_seq=3, seed=seed)
+    r = synth.stream(seed, 77)
+    D = 24
+    x = synth.normal(r, (w.B, D))
+    W = synth.normal(r, (D, w.d_c + w.d_rope), 1 / math.sqrt(D))
+    return w, x, W
+
+
+@pytest.mark.parametrize("cache_dtype", ["f32", "bf16", "fp8_e4m3"])
+def test_A7_append_writes_exactly_one_row_per_sequence(cache_dtype):
+    """After the append the logical view holds the new row at position seq_len and every
+    other byte of the pool (and scale pool) is unchanged; the row is [x W_c ; RoPE(x W_r, t)]
+    computed here with numpy and the generator's RoPE."""
+    w, x, W = _append_case(cache_dtype)
+    # sequence 1 is exactly one full page: its new token opens page index 1 of its table
+    pt = w.page_table.copy()
+    used = set(pt[pt >= 0].tolist())
+    free = [p for p in range(w.pool.shape[0]) if p not in used]
+    if pt[1, 1] < 0:
+        assert free, "the generator leaves a spare page"
+        pt[1, 1] = free[0]
+    pool2, sc2, rows = oracle.cache_append(x, W, w.pool, w.kv_scale, pt, w.seq_lens, w.d_c)
+    y = x.astype(np.float64) @ W.astype(np.float64)
+    want = y.copy()
+    for b in range(w.B):
+        want[b, w.d_c:] = synth.rope(y[b, w.d_c:][None], np.array([float(w.seq_lens[b])]))[0]
+    np.testing.assert_allclose(rows, want, rtol=0, atol=1e-10)
+    changed = np.zeros(w.pool.shape[:2], dtype=bool)
+    for b in range(w.B):
+        t = int(w.seq_lens[b])
+        changed[pt[b, t // 64], t % 64] = True
+        stored = oracle.widen(pool2[pt[b, t // 64], t % 64]) if cache_dtype != "fp8_e4m3" else None
+        if cache_dtype == "f32":
+            assert np.array_equal(pool2[pt[b, t // 64], t % 64], want[b].astype(np.float32))
+        elif cache_dtype == "bf16":
+            np.testing.assert_allclose(stored, want[b], rtol=2 ** -8, atol=1e-30)
+        else:
+            s = sc2[pt[b, t // 64], t % 64]
+            dec = np.array([oracle.widen_e4m3_code(int(c)) for c in pool2[pt[b, t // 64], t % 64]]) * float(s)
+            assert abs(float(s) - np.abs(want[b]).max() / 448) <= 1e-6 * float(s)
+            np.testing.assert_allclose(dec, want[b], rtol=0, atol=np.abs(want[b]).max() / 448 * 16 + 1e-12)
+    a, b2 = w.pool.view(np.uint8).reshape(*w.pool.shape[:2], -1), pool2.view(np.uint8).reshape(*w.pool.shape[:2], -1)
+    same = (a == b2).all(axis=-1) | (np.isnan(w.pool).all(axis=-1) & np.isnan(pool2).all(axis=-1) if cache_dtype == "f32" else False)
+    assert same[~changed].all()
+    if sc2 is not None:
+        assert np.array_equal(sc2[~changed], w.kv_scale[~changed], equal_nan=True)
+
+
+def test_A8_append_then_decode_sees_the_new_token():
+    """x = 64 e_3 picks 64 times a row of W exactly; that row dwarfs the cached ones, so a query
+    aligned with it puts all the weight on the appended token: o_lat equals its latent part."""
+    w, x, W = _append_case("f32", seed=9)
+    x = np.zeros_like(x); x[:, 3] = 64.0
+    pt = w.page_table.copy()
+    if pt[1, 1] < 0:
+        used = set(pt[pt >= 0].tolist())
+        pt[1, 1] = [p for p in range(w.pool.shape[0]) if p not in used][0]
+    pool2, _, rows = oracle.cache_append(x, W, w.pool, None, pt, w.seq_lens, w.d_c)
+    np.testing.assert_allclose(rows[:, :w.d_c], np.tile(64.0 * W[3, :w.d_c].astype(np.float64), (w.B, 1)), atol=0)
+    q_abs = np.repeat(rows[:, None, :w.d_c], w.H, axis=1)
+    q_rope = np.zeros((w.B, w.H, w.d_rope))
+    o, _ = oracle.decode_absorbed(q_abs, q_rope, pool2, None, pt, w.seq_lens + 1, 1.0)
+    np.testing.assert_allclose(o, np.repeat(rows[:, None, :w.d_c].astype(np.float32), w.H, axis=1), rtol=1e-6, atol=1e-7)
+
+
+def test_A9_append_skips_positions_outside_the_table_or_pool():
+    w, x, W = _append_case("bf16")
+    pos = w.seq_lens.copy(); pos[0] = 3 * 64            # one past the table
+    pt = w.page_table.copy(); pt[2, 130 // 64] = w.pool.shape[0] + 7     # page id outside the pool
+    pt[1, 1] = -1
+    pool2, _, _ = oracle.cache_append(x, W, w.pool, None, pt, pos, w.d_c)
+    assert np.array_equal(pool2, w.pool)
