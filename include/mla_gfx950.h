@@ -2,7 +2,7 @@
  * mla_gfx950.h -- C ABI of the absorbed multi-head latent attention (MLA)
  * decode library for AMD MI355X (gfx950).
  *
- * The three compute calls are the three lines of the paper's absorbed
+ * The three main compute calls are the three lines of the paper's absorbed
  * ("MQA paradigm") attention equation in Sec. 3.3:
  *
  *   q_hat_i = [ (W^{UK}_i)^T q^C_i ; q^R_i ]                    mla_absorb_q
@@ -11,10 +11,11 @@
  *   o_i     = W^{UV}_i o_hat_i                                  mla_out_proj
  *
  * Notation: H query heads (paper: h), d_head (d), latent rank d_c (r_kv),
- * decoupled-RoPE width d_rope (d^R).  The final W^O projection and every
- * projection that produces q^C, q^R, c^{KV}, k^R are outside this library.
- * q_rope and the k_rope part of the cache are passed ALREADY rotated by RoPE;
- * no call here applies RoPE.
+ * decoupled-RoPE width d_rope (d^R).  The final W^O projection and the
+ * projections that produce q^C and q^R are outside this library.
+ * q_rope and the k_rope part of the cache are passed ALREADY rotated by RoPE
+ * to the three calls above; mla_cache_append is the one call that produces a
+ * cache row (c^{KV} and the rotated k^R of a new token) and applies RoPE.
  *
  * General conventions
  *  - Every pointer is a DEVICE pointer unless the comment says "host".
@@ -191,6 +192,51 @@ int mla_merge_out_proj(const void* workspace, size_t workspace_bytes,
                        const void* W_UV, void* o_lat, float* lse, void* out,
                        int B, int H, int d_c, int d_head, int num_splits,
                        mla_dtype io_dtype, void* hip_stream);
+
+/*
+ * Bytes of device workspace mla_cache_append needs (fp32 partial rows of the
+ * projection, one per slice of the model dimension).  Pure host function;
+ * returns 0 if an argument is invalid.
+ */
+size_t mla_append_workspace_bytes(int B, int D, int d_c, int d_rope, mla_dtype io_dtype);
+
+/*
+ * Cache append: produces and stores the cache row of one new token per
+ * sequence (Sec. 3.2, MLA equations: c^{KV}_t = W^{DKV} x_t,
+ * k^R_t = RoPE(W^{KR} x_t, t); App. D.2: the latent is what the cache keeps;
+ * RoPE as in Sec. 3.1 Eq. 1, consecutive (real, imaginary) pairs, pair i
+ * turned by t * rope_base^(-2i/d_rope)):
+ *
+ *   row_b = [ x_b . W[:, :d_c]  |  RoPE( x_b . W[:, d_c:], positions[b] ) ]
+ *
+ * written to logical position positions[b] of sequence b, i.e. row
+ * positions[b] % page_size of page page_table[b][positions[b] / page_size].
+ * The caller passes positions[b] = the sequence's length before the append
+ * and raises its seq_lens afterwards; the page must already be in the table.
+ *
+ *   x          [B, D] io dtype: the hidden state of the new token
+ *   W_DKVR     [D, d_c + d_rope] io dtype: columns 0..d_c-1 are (W^{DKV})^T,
+ *              the rest (W^{KR})^T
+ *   kv_cache   pool as in mla_decode_paged (cache dtype); only the B rows
+ *              named above are written
+ *   kv_scale   [num_pages, page_size] fp32: required iff the cache dtype is
+ *              MLA_FP8_E4M3: receives absmax(row)/448 (1 for an all-zero
+ *              row); the codes are round-to-nearest-even of row/scale,
+ *              saturating at +-448.  NULL otherwise.
+ *   positions  [B] int32.  A position outside [0, max_pages_per_seq *
+ *              page_size), or a page id outside [0, num_pages), is not an
+ *              error code (both are device memory): that sequence is skipped.
+ *   workspace  at least mla_append_workspace_bytes(...) bytes, 16-byte aligned
+ *
+ * Rounding: fp32 accumulation, one rounding to the cache dtype; the rotation
+ * angle is formed in fp64.  d_rope even, d_c + d_rope <= 1024; any B, D.
+ */
+int mla_cache_append(const void* x, const void* W_DKVR, void* kv_cache, float* kv_scale,
+                     const int32_t* page_table, const int32_t* positions,
+                     void* workspace, size_t workspace_bytes,
+                     int B, int D, int d_c, int d_rope, int page_size,
+                     int num_pages, int max_pages_per_seq, float rope_base,
+                     mla_dtype io_dtype, mla_dtype cache_dtype, void* hip_stream);
 
 /*
  * Test hook: the logical (un-paged) view of the cache, byte for byte, using

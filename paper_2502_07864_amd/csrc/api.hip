@@ -176,6 +176,45 @@ int mla_merge_out_proj(const void* workspace, size_t workspace_bytes, const void
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 
+size_t mla_append_workspace_bytes(int B, int D, int d_c, int d_rope, mla_dtype io_dtype)
+{
+    if (B <= 0 || D <= 0 || d_c <= 0 || d_rope < 0 || !io_ok(io_dtype)) return 0;
+    const int n = d_c + d_rope;
+    return align_up((size_t)B * append_slices(B, D, n, io_dtype) * n * sizeof(float), 256);
+}
+
+int mla_cache_append(const void* x, const void* W_DKVR, void* kv_cache, float* kv_scale,
+                     const int32_t* page_table, const int32_t* positions, void* workspace,
+                     size_t workspace_bytes, int B, int D, int d_c, int d_rope, int page_size,
+                     int num_pages, int max_pages_per_seq, float rope_base, mla_dtype io_dtype,
+                     mla_dtype cache_dtype, void* hip_stream)
+{
+    if (!x || !W_DKVR || !kv_cache || !page_table || !positions) return MLA_ERR_NULL;
+    if (B <= 0 || D <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
+        max_pages_per_seq <= 0 || !(rope_base > 0.f))
+        return MLA_ERR_SHAPE;
+    if (d_rope % 2) return MLA_ERR_SHAPE;                    // RoPE turns pairs
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (cache_dtype != MLA_F32 && cache_dtype != MLA_BF16 && cache_dtype != MLA_FP8_E4M3)
+        return MLA_ERR_UNSUPPORTED;
+    if ((cache_dtype == MLA_FP8_E4M3) != (kv_scale != nullptr)) return MLA_ERR_NULL;
+    if (d_c + d_rope > 1024 || B > 65535 * 16) return MLA_ERR_UNSUPPORTED;
+    if ((long)max_pages_per_seq * page_size > 0x7FFFFFFFL) return MLA_ERR_SHAPE;
+    const size_t need = mla_append_workspace_bytes(B, D, d_c, d_rope, io_dtype);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return MLA_ERR_WORKSPACE;
+    AppendParams p;
+    p.x = x; p.W = W_DKVR; p.part = static_cast<float*>(workspace);
+    p.kv = kv_cache; p.kv_scale = kv_scale; p.page_table = page_table; p.positions = positions;
+    p.B = B; p.D = D; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
+    p.num_pages = num_pages; p.max_pages = max_pages_per_seq;
+    p.slices = append_slices(B, D, d_c + d_rope, io_dtype);
+    p.rope_base = rope_base;
+    if (p.slices > 65535) return MLA_ERR_UNSUPPORTED;
+    hipError_t e = launch_cache_append(p, io_dtype, cache_dtype, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
 int mla_gather_paged(const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens,
                      void* dense, int B, int max_len, int row_bytes, int page_size, int num_pages,
                      int max_pages_per_seq, void* hip_stream)

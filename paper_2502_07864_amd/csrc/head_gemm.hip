@@ -23,7 +23,7 @@ __device__ __forceinline__ float ld(const void* p, size_t i)
     return static_cast<const float*>(p)[i];
 }
 
-template <bool BF16>
+template <bool BF16, bool Y_F32>
 __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, const void* W, void* Y,
                                                                 int B, int H, int K, int N)
 {
@@ -67,8 +67,8 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
         if (bb < nb && col < N) {
             float v = (red_s[0][bb][nn] + red_s[1][bb][nn]) + (red_s[2][bb][nn] + red_s[3][bb][nn]);
             size_t o = ((size_t)(b0 + bb) * H + h) * N + col;
-            if (BF16) static_cast<uint16_t*>(Y)[o] = (uint16_t)f32_to_bf16_bits(v);
-            else      static_cast<float*>(Y)[o] = v;
+            if (BF16 && !Y_F32) static_cast<uint16_t*>(Y)[o] = (uint16_t)f32_to_bf16_bits(v);
+            else                static_cast<float*>(Y)[o] = v;
         }
     }
 }
@@ -89,8 +89,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int HM_LDS_BYTES = 40 * 1024;
 
-template <int NT>
-__global__ __launch_bounds__(256) void head_gemm_mfma_kernel(const uint16_t* X, const uint16_t* W, uint16_t* Y,
+template <int NT, bool Y_F32>
+__global__ __launch_bounds__(256) void head_gemm_mfma_kernel(const uint16_t* X, const uint16_t* W, void* Y,
                                                              int B, int H, int K, int N)
 {
     constexpr int RS = NT * 2 + 16;          // LDS row stride in bytes (padded: rows shift banks)
@@ -153,19 +153,24 @@ __global__ __launch_bounds__(256) void head_gemm_mfma_kernel(const uint16_t* X, 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int bb = (blockIdx.y * 4 + wave) * 16 + g * 4 + i;
-            if (bb < B) Y[((size_t)bb * H + h) * N + n0 + j * 16 + n] = (uint16_t)f32_to_bf16_bits(acc[j][i]);
+            if (bb < B) {
+                const size_t o = ((size_t)bb * H + h) * N + n0 + j * 16 + n;
+                if (Y_F32) static_cast<float*>(Y)[o] = acc[j][i];
+                else       static_cast<uint16_t*>(Y)[o] = (uint16_t)f32_to_bf16_bits(acc[j][i]);
+            }
         }
 }
 
 template <int NT>
-bool try_launch_mfma(const void* X, const void* W, void* Y, int B, int H, int K, int N, hipStream_t s,
-                     hipError_t* err)
+bool try_launch_mfma(const void* X, const void* W, void* Y, int B, int H, int K, int N, bool y_f32,
+                     hipStream_t s, hipError_t* err)
 {
     if (N % NT || K % 32 || K > 512 || (size_t)K * (NT * 2 + 16) > (size_t)HM_LDS_BYTES) return false;
     dim3 grid(H * (N / NT), (B + 63) / 64), block(256);
-    head_gemm_mfma_kernel<NT><<<grid, block, 0, s>>>(static_cast<const uint16_t*>(X),
-                                                     static_cast<const uint16_t*>(W),
-                                                     static_cast<uint16_t*>(Y), B, H, K, N);
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    const uint16_t* w = static_cast<const uint16_t*>(W);
+    if (y_f32) head_gemm_mfma_kernel<NT, true><<<grid, block, 0, s>>>(x, w, Y, B, H, K, N);
+    else       head_gemm_mfma_kernel<NT, false><<<grid, block, 0, s>>>(x, w, Y, B, H, K, N);
     *err = hipGetLastError();
     return true;
 }
@@ -173,21 +178,22 @@ bool try_launch_mfma(const void* X, const void* W, void* Y, int B, int H, int K,
 }  // namespace
 
 hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H, int K, int N,
-                            mla_dtype io, hipStream_t s)
+                            mla_dtype io, hipStream_t s, bool y_f32)
 {
     if (io == MLA_BF16 && (size_t)H * (N / 16 + 1) < 60000) {
         // widest column tile that still gives the chip a workgroup per CU
         const long by = (B + 63) / 64;
         hipError_t err = hipSuccess;
-        if (N % 64 == 0 && (long)H * (N / 64) * by >= 256 && try_launch_mfma<64>(X, W, Y, B, H, K, N, s, &err)) return err;
-        if (N % 32 == 0 && (long)H * (N / 32) * by >= 256 && try_launch_mfma<32>(X, W, Y, B, H, K, N, s, &err)) return err;
-        if (try_launch_mfma<16>(X, W, Y, B, H, K, N, s, &err)) return err;
-        if (try_launch_mfma<32>(X, W, Y, B, H, K, N, s, &err)) return err;
-        if (try_launch_mfma<64>(X, W, Y, B, H, K, N, s, &err)) return err;
+        if (N % 64 == 0 && (long)H * (N / 64) * by >= 256 && try_launch_mfma<64>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
+        if (N % 32 == 0 && (long)H * (N / 32) * by >= 256 && try_launch_mfma<32>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
+        if (try_launch_mfma<16>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
+        if (try_launch_mfma<32>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
+        if (try_launch_mfma<64>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
     }
     dim3 grid((N + HG_NT - 1) / HG_NT, H, (B + HG_BT - 1) / HG_BT), block(HG_THREADS);
-    if (io == MLA_BF16) head_gemm_kernel<true><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
-    else                head_gemm_kernel<false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
+    if (io == MLA_BF16 && y_f32) head_gemm_kernel<true, true><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
+    else if (io == MLA_BF16)     head_gemm_kernel<true, false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
+    else                         head_gemm_kernel<false, false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
     return hipGetLastError();
 }
 

@@ -117,7 +117,25 @@ hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_
 bool       merge_out_proj_supported(const MergeParams& p, int d_head, mla_dtype io);
 hipError_t launch_merge_out_proj(const MergeParams& p, const void* W_UV, void* out, hipStream_t s);
 // Y[b,h,n] = sum_k X[b,h,k] * W[h,k,n]
+// (y_f32: Y is fp32 whatever the io dtype)
 hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H, int K, int N,
-                            mla_dtype io, hipStream_t s);
+                            mla_dtype io, hipStream_t s, bool y_f32 = false);
+
+// Cache append.  The projection x . W is cut into `slices` slices of the model dimension (fp32
+// partial rows [B, slices, n] in the workspace); the finishing kernel adds them, rotates the
+// rope part and stores one row per sequence.
+struct AppendParams {
+    const void* x;              // [B, D] io dtype
+    const void* W;              // [D, n] io dtype, n = d_c + d_rope
+    float* part;                // [B, slices, n] fp32 (workspace)
+    void* kv;                   // cache pool
+    float* kv_scale;            // [num_pages, page_size] (fp8 cache) or nullptr
+    const int32_t* page_table;  // [B, max_pages]
+    const int32_t* positions;   // [B]
+    int B, D, d_c, d_rope, page_size, num_pages, max_pages, slices;
+    float rope_base;
+};
+int        append_slices(int B, int D, int n, mla_dtype io);
+hipError_t launch_cache_append(const AppendParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
 
 }  // namespace mla

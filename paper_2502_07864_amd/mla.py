@@ -59,6 +59,11 @@ def lib() -> ctypes.CDLL:
         L.mla_merge_out_proj.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         L.mla_gather_paged.restype = i
         L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        L.mla_append_workspace_bytes.restype = ctypes.c_size_t
+        L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
+        L.mla_cache_append.restype = i
+        L.mla_cache_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
+                                       i, i, i, i, i, i, i, f, i, i, vp]
         _lib = L
     return _lib
 
@@ -226,3 +231,30 @@ def gather_paged(kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: tor
                                   row_bytes, page_size, num_pages, page_table.shape[1],
                                   _stream(kv_cache)), "mla_gather_paged")
     return dense
+
+
+def append_workspace_bytes(B: int, D: int, d_c: int, d_rope: int, io_dtype: torch.dtype = torch.bfloat16) -> int:
+    code = F32 if io_dtype == torch.float32 else BF16
+    return int(lib().mla_append_workspace_bytes(B, D, d_c, d_rope, code))
+
+
+def cache_append(x: torch.Tensor, W_DKVR: torch.Tensor, kv_cache: torch.Tensor, page_table: torch.Tensor,
+                 positions: torch.Tensor, d_c: int, kv_scale: Optional[torch.Tensor] = None,
+                 rope_base: float = 10000.0, workspace: Optional[torch.Tensor] = None) -> None:
+    """Writes row [x . W[:, :d_c] | RoPE(x . W[:, d_c:], positions)] of one new token per sequence
+    into kv_cache (in place) at logical position positions[b];  x [B, D], W_DKVR [D, d_c + d_rope]."""
+    B, D = x.shape
+    D2, n = W_DKVR.shape
+    num_pages, page_size, row = kv_cache.shape
+    if D2 != D or n != row or W_DKVR.dtype != x.dtype:
+        raise ValueError("W_DKVR must be [D, d_c + d_rope] of x's dtype, matching the cache row")
+    d_rope = n - d_c
+    if workspace is None:
+        workspace = torch.empty(max(16, append_workspace_bytes(B, D, d_c, d_rope, x.dtype)),
+                                dtype=torch.uint8, device=x.device)
+    _check(lib().mla_cache_append(_dev(x, "x"), _dev(W_DKVR, "W_DKVR"), _dev(kv_cache, "kv_cache"),
+                                  _dev(kv_scale, "kv_scale"), _dev(page_table, "page_table"),
+                                  _dev(positions, "positions"), _dev(workspace, "workspace"),
+                                  workspace.numel(), B, D, d_c, d_rope, page_size, num_pages,
+                                  page_table.shape[1], float(rope_base), _io_code(x),
+                                  _cache_code(kv_cache), _stream(x)), "mla_cache_append")

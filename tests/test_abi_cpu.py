@@ -30,6 +30,9 @@ def lib():
     L.mla_decode_workspace_bytes.argtypes = [i, i, i, i]
     L.mla_decode_paged.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 8 + [f, i, i, u, vp]
     L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.mla_append_workspace_bytes.restype = ctypes.c_size_t
+    L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.mla_cache_append.argtypes = [vp] * 7 + [ctypes.c_size_t] + [i] * 7 + [f, i, i, vp]
     return L
 
 
@@ -120,6 +123,38 @@ def test_gather_validation(lib):
     assert g(P, P, P, P, 1, 0, 64, 4, 2, 1, None) == E_SHAPE
     assert g(P, P, P, P, 1, 4, 0, 4, 2, 1, None) == E_SHAPE
     assert g(P, P, P, P, 1, 4, 6, 4, 2, 1, None) == E_UNSUP
+
+
+def append_args(**kw):
+    a = dict(x=P, W=P, kv=P, kv_scale=None, table=P, pos=P, ws=P, ws_bytes=1 << 30, B=4, D=4096,
+             d_c=512, d_rope=64, page=64, num_pages=8, max_pages=4, base=10000.0, io=BF16, cache=BF16,
+             stream=None)
+    a.update(kw)
+    return [a[k] for k in ("x", "W", "kv", "kv_scale", "table", "pos", "ws", "ws_bytes", "B", "D", "d_c",
+                           "d_rope", "page", "num_pages", "max_pages", "base", "io", "cache", "stream")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(x=None), E_NULL), (dict(W=None), E_NULL), (dict(kv=None), E_NULL), (dict(table=None), E_NULL),
+    (dict(pos=None), E_NULL), (dict(cache=FP8), E_NULL), (dict(kv_scale=P), E_NULL),
+    (dict(B=0), E_SHAPE), (dict(D=0), E_SHAPE), (dict(d_c=0), E_SHAPE), (dict(d_rope=-2), E_SHAPE),
+    (dict(d_rope=63), E_SHAPE), (dict(page=0), E_SHAPE), (dict(num_pages=0), E_SHAPE),
+    (dict(max_pages=0), E_SHAPE), (dict(base=0.0), E_SHAPE), (dict(base=float("nan")), E_SHAPE),
+    (dict(max_pages=1 << 30), E_SHAPE),
+    (dict(io=FP8), E_UNSUP), (dict(cache=9), E_UNSUP), (dict(d_c=1000), E_UNSUP),
+    (dict(ws=None), E_WS), (dict(ws_bytes=64), E_WS), (dict(ws=P + 4), E_WS),
+])
+def test_append_validation(lib, kw, want):
+    assert lib.mla_cache_append(*append_args(**kw)) == want
+
+
+def test_append_workspace_bytes(lib):
+    n = lib.mla_append_workspace_bytes(16, 4096, 512, 64, BF16)
+    assert n % 256 == 0 and n >= 16 * 576 * 4            # at least one fp32 partial row per sequence
+    assert n <= 16 * (4096 // 32) * 576 * 4 + 256        # at most one per 32 model dimensions
+    assert lib.mla_append_workspace_bytes(0, 4096, 512, 64, BF16) == 0
+    assert lib.mla_append_workspace_bytes(16, 4096, 512, 64, FP8) == 0
+    assert lib.mla_append_workspace_bytes(3, 100, 40, 8, F32) >= 3 * 48 * 4
 
 
 def test_product_path_does_not_use_the_oracle():

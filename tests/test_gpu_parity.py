@@ -421,3 +421,137 @@ def test_decode_C5_full_sampled(mla):
     """fp8 cache, 131072-token context, 32 chunks; one of the four sequences checked."""
     w = synth.config("C5")
     check_decode(mla, w, w.num_splits, b_sel=[2])
+
+
+# ------------------------------------------------------------ cache append
+
+def _append_inputs(cache_dtype, D, seed, lens=(0, 63, 64, 1000, 4095), page_size=64):
+    io = "f32" if cache_dtype == "f32" else "bf16"
+    w = synth.make_workload("append", B=len(lens), H=4, d_head=128, d_c=512, d_rope=64, seq_lens=list(lens),
+                            io_dtype=io, cache_dtype=cache_dtype, placement="random", free_frac=0.3,
+                            max_pages_per_seq=65, seed=seed)
+    pt = w.page_table.copy()
+    used = set(pt[pt >= 0].tolist())
+    free = [p for p in range(w.pool.shape[0]) if p not in used]
+    for b, L in enumerate(lens):            # the page the new token goes to must be in the table
+        if pt[b, L // page_size] < 0:
+            pt[b, L // page_size] = free.pop()
+    r = synth.stream(seed, 91)
+    x = synth.store(synth.normal(r, (len(lens), D)), io)
+    W = synth.store(synth.normal(r, (D, 576), 1 / math.sqrt(D)), io)
+    return w, pt, x, W, io
+
+
+def _decoded_rows(pool_np, scale_np, pt, pos):
+    rows = []
+    for b in range(len(pos)):
+        p, s = pt[b, pos[b] // 64], pos[b] % 64
+        if pool_np.dtype == np.uint8:
+            rows.append(np.array([oracle.widen_e4m3_code(int(c)) for c in pool_np[p, s]]) * float(scale_np[p, s]))
+        else:
+            rows.append(oracle.widen(pool_np[p, s]))
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("cache_dtype,D", [("bf16", 4096), ("bf16", 1024), ("bf16", 200), ("fp8_e4m3", 4096),
+                                           ("f32", 1024), ("f32", 96)])
+def test_cache_append_matches_oracle(mla, cache_dtype, D):
+    """New rows against the fp64 oracle rows (one rounding to the cache dtype apart); every other
+    byte of the pool and of the scale pool untouched."""
+    import torch
+    w, pt, x, W, io = _append_inputs(cache_dtype, D, seed=61)
+    d = DeviceWorkload(w)
+    pool = d.pool.clone()
+    scale = None if d.kv_scale is None else d.kv_scale.clone()
+    pos = w.seq_lens.copy()
+    mla.cache_append(to_torch(x, io), to_torch(W, io), pool, to_torch(pt, "i32"), to_torch(pos, "i32"), 512,
+                     kv_scale=scale)
+    torch.cuda.synchronize()
+    ref_pool, ref_scale, rows = oracle.cache_append(x, W, w.pool, w.kv_scale, pt, pos, 512)
+    got_pool = storage_bits(pool) if cache_dtype != "f32" else pool.cpu().numpy()
+    got_scale = None if scale is None else scale.cpu().numpy()
+    got = _decoded_rows(got_pool, got_scale, pt, pos)
+    if cache_dtype == "f32":
+        assert max_abs_rel(got, rows) <= 1e-5
+    elif cache_dtype == "bf16":
+        assert max_abs_rel(got, rows) <= 2 ** -8        # one bf16 rounding (2^-9) and fp32 accumulation
+        assert (np.abs(got - rows) <= 2 ** -8 * np.abs(rows) + 1e-6).all()
+    else:
+        sref = np.array([ref_scale[pt[b, pos[b] // 64], pos[b] % 64] for b in range(w.B)])
+        sgot = np.array([got_scale[pt[b, pos[b] // 64], pos[b] % 64] for b in range(w.B)])
+        assert np.abs(sgot - sref).max() <= 1e-5 * sref.max()
+        assert (np.abs(got - rows) <= 2 ** -4 * np.abs(rows) + sgot[:, None] * 2 ** -9 * 1.01).all()   # half a step
+        ref_codes = np.stack([ref_pool[pt[b, pos[b] // 64], pos[b] % 64] for b in range(w.B)])
+        got_codes = np.stack([got_pool[pt[b, pos[b] // 64], pos[b] % 64] for b in range(w.B)])
+        assert (ref_codes != got_codes).mean() < 0.02   # only values within rounding of a code boundary differ
+    changed = np.zeros(w.pool.shape[:2], dtype=bool)
+    for b in range(w.B):
+        changed[pt[b, pos[b] // 64], pos[b] % 64] = True
+    a = w.pool.view(np.uint8).reshape(*w.pool.shape[:2], -1)
+    g = np.ascontiguousarray(got_pool).view(np.uint8).reshape(*w.pool.shape[:2], -1)
+    assert (a[~changed] == g[~changed]).all()
+    if got_scale is not None:
+        assert np.array_equal(got_scale[~changed], w.kv_scale[~changed], equal_nan=True)
+
+
+@pytest.mark.parametrize("cache_dtype", ["bf16", "fp8_e4m3", "f32"])
+def test_cache_append_encoders_bitwise(mla, cache_dtype):
+    """x = 64 e_k makes the projection exact (one product per column) and position 0 makes the
+    rotation the identity: the stored row must then equal the oracle's bit for bit (bf16 rounding,
+    e4m3 codes and per-token scale take their decisions on the same fp32 values)."""
+    import torch
+    w, pt, x, W, io = _append_inputs(cache_dtype, 256, seed=62, lens=(3, 3, 3))   # position 0 is overwritten
+    xf = np.zeros((3, 256), dtype=np.float32)
+    xf[0, 5], xf[1, 200], xf[2, 77] = 64.0, -0.5, 1024.0
+    x = synth.store(xf, io)
+    Wf = synth.normal(synth.stream(62, 5), (256, 576), 37.0)      # spread over many binades
+    Wf[200, :8] = 0.0
+    Wf[77, 100:108] = [448.0, 449.0, 1e-3, -1e-3, 3.0e-3, 0.0, -0.0, 464.0]
+    W = synth.store(Wf, io)
+    d = DeviceWorkload(w)
+    pool = d.pool.clone()
+    scale = None if d.kv_scale is None else d.kv_scale.clone()
+    pos = np.zeros(3, dtype=np.int32)
+    mla.cache_append(to_torch(x, io), to_torch(W, io), pool, to_torch(pt, "i32"), to_torch(pos, "i32"), 512,
+                     kv_scale=scale)
+    torch.cuda.synchronize()
+    ref_pool, ref_scale, _ = oracle.cache_append(x, W, w.pool, w.kv_scale, pt, pos, 512)
+    got_pool = storage_bits(pool) if cache_dtype != "f32" else pool.cpu().numpy()
+    for b in range(3):
+        p = pt[b, 0]
+        assert np.array_equal(np.ascontiguousarray(got_pool[p, 0]).view(np.uint8),
+                              np.ascontiguousarray(ref_pool[p, 0]).view(np.uint8)), (cache_dtype, b)
+        if scale is not None:
+            assert scale.cpu().numpy()[p, 0] == ref_scale[p, 0]
+
+
+def test_cache_append_then_decode(mla):
+    """Append on the GPU, then decode over seq_len + 1 tokens: equals the oracle's decode over the
+    oracle-appended cache (the new token is part of the softmax)."""
+    import torch
+    w, pt, x, W, io = _append_inputs("bf16", 1024, seed=63, lens=(0, 63, 64, 700, 2048))
+    d = DeviceWorkload(w)
+    pool = d.pool.clone()
+    pos = w.seq_lens.copy()
+    mla.cache_append(to_torch(x, io), to_torch(W, io), pool, to_torch(pt, "i32"), to_torch(pos, "i32"), 512)
+    q_abs = gpu_q_abs(mla, d)
+    lens1 = (w.seq_lens + 1).astype(np.int32)
+    o, lse = mla.decode_paged(q_abs, d.q_rope, pool, to_torch(pt, "i32"), to_torch(lens1, "i32"), w.softmax_scale,
+                              num_splits=4, return_lse=True)
+    torch.cuda.synchronize()
+    ref_pool, _, _ = oracle.cache_append(x, W, w.pool, None, pt, pos, 512)
+    ref_o, ref_lse = oracle.decode_absorbed(q_abs_storage(q_abs), w.q_rope, ref_pool, None, pt, lens1, w.softmax_scale)
+    assert max_abs_rel(widen_gpu(o), ref_o) <= TOL["bf16"]
+    assert lse_err(widen_gpu(lse), ref_lse) <= 2e-2
+
+
+def test_cache_append_skips_bad_positions(mla):
+    import torch
+    w, pt, x, W, io = _append_inputs("bf16", 256, seed=64, lens=(5, 70, 130))
+    pos = np.array([65 * 64, 70, 130], dtype=np.int32)       # first: one past the table
+    pt2 = pt.copy(); pt2[1, 1] = w.pool.shape[0] + 3; pt2[2, 2] = -1
+    d = DeviceWorkload(w)
+    pool = d.pool.clone()
+    mla.cache_append(to_torch(x, io), to_torch(W, io), pool, to_torch(pt2, "i32"), to_torch(pos, "i32"), 512)
+    torch.cuda.synchronize()
+    assert np.array_equal(storage_bits(pool), w.pool)
