@@ -228,25 +228,41 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         return NLOAD;
     };
 
-    // ---- fp8 staging: 8-byte loads (8 codes) one tile ahead in registers, widened to bf16 and
-    // stored with the same swizzled layout the direct-to-LDS path produces
-    constexpr int ROWB8 = ROW;                       // bytes per fp8 cache row
+    // ---- fp8 staging: 16-byte loads (16 codes) one tile ahead in registers, widened to bf16 and
+    // stored with the same swizzled layout the direct-to-LDS path produces.  The address unit
+    // takes as long over a narrow load as over a wide one, so the tile is fetched in as few
+    // instructions as its size allows.
     constexpr int CPR8 = ROW / 8;                    // 8-code chunks per row (= 16-byte bf16 chunks)
-    constexpr int NLOAD8 = TILE_ROWS * CPR8 / MF_THREADS;   // 9 / 5
-    static_assert(TILE_ROWS * CPR8 % MF_THREADS == 0, "fp8 tile must split evenly over the loads");
+    constexpr int RAW_B = TILE_ROWS * ROW;           // bytes of a tile of codes (18432 / 10240)
+    constexpr int N16 = RAW_B / 16;                  // 16-byte pieces per tile (1152 / 640)
+    constexpr int NLOAD8 = (N16 + MF_THREADS - 1) / MF_THREADS;   // loads per thread per tile (5 / 3; the last is half used)
+    static_assert(CPR8 % 2 == 0, "a 16-byte piece must not straddle two rows");
     __shared__ float scale_lds[2][TILE_ROWS];
-    u32x2 stg[FP8 ? NLOAD8 : 1];
+    u32x4 stg[FP8 ? NLOAD8 : 1];
     float stg_scale = 0.f;
-    auto fetch_regs = [&](int t) {
-        const int nv = rows_valid(t);
-        const int page = nv > 0 ? ptab[t >> 1] : 0;
-        const unsigned char* src = kv + (size_t)page * (64 * ROWB8) + (size_t)(t & 1) * (TILE_ROWS * ROWB8);
+    // piece c16 = k * 256 + tid sits at byte c16 * 16 of the tile's rows in HBM (rows are
+    // contiguous); its two 8-code halves go to LDS row r = 2 c16 / CPR8, swizzled 16-byte positions
+    // col and col + 1 (col even, so the second is the first with address bit 4 flipped)
+    uint32_t loff8[FP8 ? NLOAD8 : 1];
+    if constexpr (FP8) {
 #pragma unroll
         for (int k = 0; k < NLOAD8; ++k) {
-            const int c8 = k * MF_THREADS + tid;
+            const int c8 = 2 * (k * MF_THREADS + tid);
             const int r = c8 / CPR8, col = c8 % CPR8;
-            u32x2 v = (u32x2){0u, 0u};
-            if (r < nv) v = *reinterpret_cast<const u32x2*>(src + r * ROWB8 + col * 8);
+            loff8[k] = (uint32_t)(r * ROWB + ((col ^ swz_key(r)) << 4));
+        }
+    }
+    // `page` is the page id of tile t, looked up by the caller well ahead of this call (a scalar
+    // load that would otherwise be waited for right here, once per tile)
+    auto fetch_regs = [&](int t, int page) {
+        const int nv = (page >= 0 && page < p.num_pages) ? min(TILE_ROWS, row1 - t * TILE_ROWS) : 0;
+        if (nv <= 0) page = 0;
+        const unsigned char* src = kv + (size_t)page * (64 * ROW) + (size_t)(t & 1) * RAW_B + tid * 16;
+        const int limit = nv * (CPR8 / 2);   // pieces that belong to valid rows
+#pragma unroll
+        for (int k = 0; k < NLOAD8; ++k) {
+            u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+            if (k * MF_THREADS + tid < limit) v = *reinterpret_cast<const u32x4*>(src + k * (MF_THREADS * 16));
             stg[k] = v;
         }
         if (tid < TILE_ROWS)
@@ -255,17 +271,17 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     auto store_regs = [&](int slot) {
 #pragma unroll
         for (int k = 0; k < NLOAD8; ++k) {
-            const int c8 = k * MF_THREADS + tid;
-            const int r = c8 / CPR8, col = c8 % CPR8;
-            u32x4 w;
+            if (k * MF_THREADS + tid < N16) {
+                u32x4 w[2];
 #pragma unroll
-            for (int hw = 0; hw < 2; ++hw) {
-                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)stg[k][hw], false);
-                const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)stg[k][hw], true);
-                w[2 * hw]     = pack_bf16x2(lo[0], lo[1]);   // exact: e4m3 has 3 mantissa bits
-                w[2 * hw + 1] = pack_bf16x2(hi[0], hi[1]);
+                for (int j = 0; j < 4; ++j) {
+                    // two codes -> two bf16 in one instruction (scale 1: exact, e4m3 has 3 mantissa bits)
+                    w[j >> 1][2 * (j & 1)]     = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(stg[k][j], 1.0f, false));
+                    w[j >> 1][2 * (j & 1) + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(stg[k][j], 1.0f, true));
+                }
+                *(LDS_AS u32x4*)(lds + slot * TILE_B + loff8[k]) = w[0];
+                *(LDS_AS u32x4*)(lds + slot * TILE_B + (loff8[k] ^ 16u)) = w[1];
             }
-            *(LDS_AS u32x4*)(lds + slot * TILE_B + r * ROWB + ((col ^ swz_key(r)) << 4)) = w;
         }
         if (tid < TILE_ROWS) scale_lds[slot][tid] = stg_scale;
     };
@@ -311,9 +327,9 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     };
     auto start_ring = [&](bool whole_ring) {
         if constexpr (FP8) {
-            fetch_regs(t0);
+            fetch_regs(t0, ptab[t0 >> 1]);
             store_regs(0);
-            if (t0 + 1 < t1) fetch_regs(t0 + 1);
+            if (t0 + 1 < t1) fetch_regs(t0 + 1, ptab[(t0 + 1) >> 1]);
         } else {
 #pragma unroll
             for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
@@ -366,14 +382,16 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     };
 
     // after tile t has been accumulated (fp8): hand tile t+1 over to LDS, request tile t+2
-    auto finish_tile = [&](int t) {
+    auto finish_tile = [&](int t, int page_t2) {
         if constexpr (FP8) {
             if (t + 1 < t1) {
                 store_regs(slot_of(t + 1));
-                if (t + 2 < t1) fetch_regs(t + 2);
+                if (t + 2 < t1) fetch_regs(t + 2, page_t2);
             }
         }
     };
+    // page id of tile t + 2, requested at the top of tile t's iteration (fp8 path)
+    auto page_ahead = [&](int t) { return FP8 ? ptab[min((t + 2) >> 1, p.max_pages - 1)] : 0; };
 
     // S^T = K . Q^T for this wave's 16 rows x 16 heads, scaled to log2 units, invalid rows at
     // -inf; returns the maximum over the wave's rows of this lane's head.  Operand reads run
@@ -494,13 +512,14 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     for (int t = t0; t < t1; ++t) {
         const int slot = slot_of(t);
         LDS_AS unsigned char* tile = lds + slot * TILE_B;
+        const int page_t2 = page_ahead(t);
         const int n_valid = stage_tile(t, tile);
         float x[4], rs[4];
         const float tmax = score_tile(tile, slot, n_valid, x, rs);
         if (m_run == -INFINITY) m_run = tmax;
         jumped |= tmax > m_run + FAST_GAP;
         accumulate_tile(tile, x, rs);
-        finish_tile(t);
+        finish_tile(t, page_t2);
     }
 
     if (__builtin_expect(__syncthreads_or(jumped), 0)) {
@@ -543,7 +562,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
                     break;
                 }
                 accumulate_tile(tile, x, rs);
-                finish_tile(t);
+                finish_tile(t, page_ahead(t));
             }
             if (!rescale) break;
         }
