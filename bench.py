@@ -294,11 +294,22 @@ def main():
                             w.page_table[sel], w.seq_lens[sel], w.softmax_scale)
             times.append(time.perf_counter() - t0)
         t_cpu = sorted(times)[1]
+        # the same routine on one thread, one sequence (bounded: a few tenths of a second at C2)
+        oracle.set_num_threads(1)
+        t0 = time.perf_counter()
+        oracle.mla_step(w.q_nope[:1], w.q_rope[:1], w.W_UK, w.W_UV, w.pool, w.kv_scale,
+                        w.page_table[:1], w.seq_lens[:1], w.softmax_scale)
+        t_one = time.perf_counter() - t0
+        oracle.set_num_threads(0)
+        tok1 = max(1, int(w.seq_lens[0]))
         rec["cpu_baseline"] = {
             "value": round(t_cpu * (B / n) * 1e6, 1), "unit": "us/step",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n} of {B} sequences (all {H} heads, {int(w.seq_lens[sel].sum())} tokens), fp64 absorbed oracle "
-                      f"(absorb + decode + out-proj), median of 3 runs = {t_cpu:.2f} s, scaled by {B}/{n}"}
+                      f"(absorb + decode + out-proj), median of 3 runs = {t_cpu:.2f} s, scaled by {B}/{n}",
+            "single_thread": {"value": round(t_one * (w.tokens / tok1) * 1e6, 1), "unit": "us/step", "cores": 1,
+                              "sample": f"sequence 0 ({tok1} tokens, all {H} heads) = {t_one:.2f} s, scaled by tokens "
+                                        f"{w.tokens}/{tok1}"}}
     print(json.dumps(rec))
 
 

@@ -67,6 +67,11 @@ def num_threads() -> int:
     return int(_c().oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads for the (b, h) loops; 0 restores the default."""
+    _c().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
 # --------------------------------------------------------------------------
 # exact widening of stored values
 # --------------------------------------------------------------------------

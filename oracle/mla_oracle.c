@@ -91,6 +91,18 @@ static size_t phys_row(const int32_t* page_table, int max_pages_per_seq,
     return (size_t)page * page_size + (size_t)(j % page_size);
 }
 
+/* Threads the (b, h) loops may use from now on (n >= 1); 0 restores the default. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    static int dflt = 0;
+    if (dflt == 0) dflt = omp_get_max_threads();
+    omp_set_num_threads(n > 0 ? n : dflt);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

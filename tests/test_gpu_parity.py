@@ -403,6 +403,16 @@ def test_step_C2_full_three_calls(mla):
     chain = oracle.mla_step(w.q_nope, w.q_rope, w.W_UK, w.W_UV, w.pool, None, w.page_table,
                             w.seq_lens, w.softmax_scale)
     assert max_abs_rel(widen_gpu(out), chain["out"]) <= 2e-2
+    # the benchmark's own call sequence: split-KV kernel with the partials left in the workspace,
+    # then merge + W_UV in one kernel -- same o_lat / lse bits, out against the oracle
+    ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                          num_splits=w.num_splits, flags=mla.FLAG_SKIP_MERGE)
+    o2, out2, lse2 = mla.merge_out_proj(ws, d.W_UV, w.B, w.num_splits, return_lse=True)
+    torch.cuda.synchronize()
+    assert storage_bits(o2).tobytes() == storage_bits(o_lat).tobytes()
+    assert storage_bits(lse2).tobytes() == storage_bits(lse).tobytes()
+    assert max_abs_rel(widen_gpu(out2), ref_out) <= 2e-2
+    assert max_abs_rel(widen_gpu(out2), chain["out"]) <= 2e-2
 
 
 def test_decode_C4_full_sampled(mla):
