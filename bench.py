@@ -61,6 +61,10 @@ def parse():
     ap.add_argument("--splits", type=int, default=0, help="override the configuration's KV chunk count")
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
                     help="C2 is the headline configuration; the others are secondary rows")
+    ap.add_argument("--partition", default="auto", choices=["auto", "uniform", "balanced"],
+                    help="uniform: equal chunks per sequence; balanced (MLA_FLAG_BALANCED): equal page ranges "
+                         "per workgroup over the concatenated sequences, --splits workgroups per sequence on "
+                         "average; auto: balanced with 4 per sequence for the ragged batch C3, uniform otherwise")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
     ap.add_argument("--calib-copy", action="store_true",
@@ -87,6 +91,9 @@ def main():
     torch.cuda.set_device(0)
     mla.lib()
 
+    args.balanced = args.partition == "balanced" or (args.partition == "auto" and args.workload == "C3")
+    if args.balanced and args.partition == "auto" and not args.splits:
+        args.splits = 4          # 64 sequences x 4 = one workgroup per CU
     w = synth.config(args.workload)
     d = DeviceWorkload(w, "cuda:0")
     B, H, d_c, S = w.B, w.H, w.d_c, (args.splits or w.num_splits)
@@ -111,20 +118,22 @@ def main():
     o_lat = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
     out = torch.empty((B, H, w.d_head), dtype=io_t, device="cuda:0")
 
+    bal = mla.FLAG_BALANCED if args.balanced else 0
+
     def step(i, events=None):
         k = i % len(pools)
         mla.absorb_q(d.q_nope, d.W_UK, out=q_abs)
         if events is not None:
             events[0].record()
         mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE)
+                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
         if events is not None:
             events[1].record()
         if args.unfused_tail:
-            mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat)
+            mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat, flags=bal)
             mla.out_proj(o_lat, d.W_UV, out=out)
         else:
-            mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out)
+            mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out, flags=bal)
         if events is not None:
             events[2].record()
 
@@ -159,7 +168,7 @@ def main():
     def decode_only(i):
         k = i % len(pools)
         mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE)
+                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
     for i in range(min(args.warmup, 10)):
         decode_only(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -174,7 +183,7 @@ def main():
     def decode_call(i):
         k = i % len(pools)
         mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, out=o_lat)
+                         num_splits=S, kv_scale=scales[k], workspace=ws, out=o_lat, flags=bal)
     for i in range(min(args.warmup, 10)):
         decode_call(i)
     e0.record()
@@ -258,7 +267,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": WORKLOADS[args.workload],
                    "batch": B, "context_max": int(w.seq_lens.max()), "tokens": w.tokens,
-                   "cache_dtype": w.cache_dtype, "num_splits": S, "cache_copies_cycled": len(pools)},
+                   "cache_dtype": w.cache_dtype, "num_splits": S, "cache_copies_cycled": len(pools),
+                   "partition": "balanced" if args.balanced else "uniform"},
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
         "step_hbm_GBps": round(cache_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_hbm_frac": round(cache_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

@@ -60,10 +60,13 @@ enum {
     MLA_FLAG_DEFAULT        = 0,
     MLA_FLAG_PORTABLE_KERNEL = 1, /* force the scalar-FMA kernel even where the
                                      matrix-core kernel applies (cross-check)  */
-    MLA_FLAG_SKIP_MERGE      = 2  /* leave the per-chunk partial results in the
+    MLA_FLAG_SKIP_MERGE      = 2, /* leave the per-chunk partial results in the
                                      workspace and do not write o_lat / lse: the
                                      caller merges them with mla_merge_partials
                                      (o_lat may then be NULL)                  */
+    MLA_FLAG_BALANCED        = 4  /* balanced partition (see mla_decode_paged);
+                                     the merge calls that consume the workspace
+                                     must be given the same flag               */
 };
 
 /* Human-readable name of a status code.  Static storage; never free it. */
@@ -99,7 +102,9 @@ int mla_out_proj(const void* o_lat, const void* W_UV, void* out,
 
 /*
  * Bytes of device workspace mla_decode_paged needs for these sizes (split-KV
- * partial results: fp32 [B, H, num_splits, d_c] + fp32 [B, H, num_splits]).
+ * partial results: fp32 partial outputs and log-sum-exps for B * (S + 1)
+ * chunks, S as described under num_splits, plus a [B, 2] int32 table the
+ * balanced partition uses).  The same size serves both partitions.
  * Pure host function; returns 0 if an argument is <= 0.
  */
 size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
@@ -142,6 +147,13 @@ size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
  *              accounts for it).  Every chunk is reduced with its own running
  *              softmax and the chunks are merged by log-sum-exp.  The result
  *              does not depend on the chunking beyond fp32 rounding.
+ *              With MLA_FLAG_BALANCED (matrix-core kernel only, otherwise
+ *              MLA_ERR_UNSUPPORTED) the cut is made differently: the page lists
+ *              of all sequences, laid end to end, are cut into B * S ranges of
+ *              equal length (+-1 page), one per workgroup; a range that
+ *              crosses sequence boundaries gives one chunk per sequence.  Every
+ *              workgroup then streams the same number of bytes whatever the
+ *              mix of sequence lengths.  Same results up to fp32 rounding.
  *   softmax_scale  the paper uses 1/sqrt(d_head + d_rope) for MLA
  *
  * Supported: io/cache dtype pairs (F32,F32), (BF16,BF16), (BF16,FP8_E4M3),
@@ -171,10 +183,12 @@ int mla_decode_paged(const void* q_abs, const void* q_rope,
  * time or overlap the two phases, or merge chunks computed elsewhere.
  *   workspace  [in]  as written by mla_decode_paged
  *   o_lat      [B, H, d_c] io dtype (output);  lse [B, H] fp32 (output, may be NULL)
+ *   flags      MLA_FLAG_BALANCED iff the decode call had it; other bits ignored
  */
 int mla_merge_partials(const void* workspace, size_t workspace_bytes,
                        void* o_lat, float* lse, int B, int H, int d_c,
-                       int num_splits, mla_dtype io_dtype, void* hip_stream);
+                       int num_splits, mla_dtype io_dtype, unsigned flags,
+                       void* hip_stream);
 
 /*
  * Fused tail: mla_merge_partials followed by mla_out_proj in one call (one
@@ -187,11 +201,13 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes,
  *   o_lat      [B, H, d_c] io dtype (output, required)
  *   lse        [B, H] fp32 (output, may be NULL)
  *   out        [B, H, d_head] io dtype (output)
+ *   flags      MLA_FLAG_BALANCED iff the decode call had it (the two kernels
+ *              then run back to back); other bits ignored
  */
 int mla_merge_out_proj(const void* workspace, size_t workspace_bytes,
                        const void* W_UV, void* o_lat, float* lse, void* out,
                        int B, int H, int d_c, int d_head, int num_splits,
-                       mla_dtype io_dtype, void* hip_stream);
+                       mla_dtype io_dtype, unsigned flags, void* hip_stream);
 
 /*
  * Bytes of device workspace mla_cache_append needs (fp32 partial rows of the

@@ -21,9 +21,32 @@ int effective_splits(int B, int num_splits)
     return num_splits * m;
 }
 
-size_t partial_out_bytes(int B, int H, int d_c, int eff_splits)
+// Workspace: partial outputs, partial log-sum-exps, plan.  Sized for B * (S + 1) partial slots:
+// the uniform partition uses B * S of them ([B, H, S, d_c]), the balanced one up to B * S + B - 1
+// ([slot, H, d_c]); the plan ([B, 2] int32) is written and read by the balanced partition only.
+struct WsLayout {
+    size_t lse_off, plan_off, total;
+};
+
+WsLayout ws_layout(int B, int H, int d_c, int eff_splits)
 {
-    return align_up((size_t)B * eff_splits * H * d_c * sizeof(float), 256);
+    const size_t slots = (size_t)B * (eff_splits + 1);
+    WsLayout l;
+    l.lse_off = align_up(slots * H * d_c * sizeof(float), 256);
+    l.plan_off = l.lse_off + align_up(slots * H * sizeof(float), 256);
+    l.total = l.plan_off + align_up((size_t)B * 2 * sizeof(int32_t), 256);
+    return l;
+}
+
+void fill_merge_params(MergeParams& m, const void* workspace, int B, int H, int d_c, int eff_splits,
+                       bool balanced)
+{
+    const WsLayout l = ws_layout(B, H, d_c, eff_splits);
+    m.o_part = static_cast<const float*>(workspace);
+    m.lse_part = reinterpret_cast<const float*>(static_cast<const char*>(workspace) + l.lse_off);
+    m.plan = balanced ? reinterpret_cast<const int32_t*>(static_cast<const char*>(workspace) + l.plan_off)
+                      : nullptr;
+    m.B = B; m.H = H; m.d_c = d_c; m.num_splits = eff_splits;
 }
 
 }  // namespace
@@ -73,7 +96,7 @@ size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits)
 {
     if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return 0;
     const int S = effective_splits(B, num_splits);
-    return partial_out_bytes(B, H, d_c, S) + align_up((size_t)B * S * H * sizeof(float), 256);
+    return ws_layout(B, H, d_c, S).total;
 }
 
 int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache,
@@ -109,63 +132,65 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
     p.page_table = page_table; p.seq_lens = seq_lens;
     p.o_part = static_cast<float*>(workspace);
     const int S = effective_splits(B, num_splits);
-    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + partial_out_bytes(B, H, d_c, S));
+    const WsLayout wl = ws_layout(B, H, d_c, S);
+    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.lse_off);
+    p.plan = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + wl.plan_off);
     p.B = B; p.H = H; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
     p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = S;
     p.chunk_pages = (max_pages_per_seq + S - 1) / S;
     p.scale = softmax_scale;
 
+    const bool balanced = (flags & MLA_FLAG_BALANCED) != 0;
+    const bool mfma = !(flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, io_dtype, cache_dtype);
+    if (balanced && !mfma) return MLA_ERR_UNSUPPORTED;   // only the matrix-core kernel has this partition
+    if (balanced && ((long long)B * S > 0x3FFFFF || (long long)B * max_pages_per_seq > 0x7FFFFFFFLL))
+        return MLA_ERR_UNSUPPORTED;   // grid size; page counts are summed in 32 bits
     hipError_t e;
-    if (!(flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, io_dtype, cache_dtype))
-        e = launch_decode_mfma(p, cache_dtype, stream);
-    else
-        e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
+    if (mfma) e = launch_decode_mfma(p, cache_dtype, stream, balanced);
+    else      e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
     if (e != hipSuccess) return MLA_ERR_HIP;
     if (skip_merge) return MLA_OK;
 
     MergeParams m;
-    m.o_part = p.o_part; m.lse_part = p.lse_part; m.o_lat = o_lat; m.lse = lse;
-    m.B = B; m.H = H; m.d_c = d_c; m.num_splits = S;
+    fill_merge_params(m, workspace, B, H, d_c, S, balanced);
+    m.o_lat = o_lat; m.lse = lse;
     e = launch_merge(m, io_dtype, stream);
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 
 int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_lat, float* lse,
-                       int B, int H, int d_c, int num_splits, mla_dtype io_dtype, void* hip_stream)
+                       int B, int H, int d_c, int num_splits, mla_dtype io_dtype, unsigned flags,
+                       void* hip_stream)
 {
     if (!o_lat) return MLA_ERR_NULL;
     if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
-    if (H > 65535 || B > 65535 || d_c % 4) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || B > 65535 || d_c % 4 || d_c > 2048) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
     MergeParams m;
-    m.o_part = static_cast<const float*>(workspace);
-    m.lse_part = reinterpret_cast<const float*>(
-        static_cast<const char*>(workspace) + partial_out_bytes(B, H, d_c, effective_splits(B, num_splits)));
-    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = effective_splits(B, num_splits);
+    fill_merge_params(m, workspace, B, H, d_c, effective_splits(B, num_splits), (flags & MLA_FLAG_BALANCED) != 0);
+    m.o_lat = o_lat; m.lse = lse;
     hipError_t e = launch_merge(m, io_dtype, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 
 int mla_merge_out_proj(const void* workspace, size_t workspace_bytes, const void* W_UV, void* o_lat,
                        float* lse, void* out, int B, int H, int d_c, int d_head, int num_splits,
-                       mla_dtype io_dtype, void* hip_stream)
+                       mla_dtype io_dtype, unsigned flags, void* hip_stream)
 {
     if (!o_lat || !W_UV || !out) return MLA_ERR_NULL;
     if (B <= 0 || H <= 0 || d_c <= 0 || d_head <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
-    if (H > 65535 || B > 65535 || d_c % 4) return MLA_ERR_UNSUPPORTED;
+    if (H > 65535 || B > 65535 || d_c % 4 || d_c > 2048) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     MergeParams m;
-    m.o_part = static_cast<const float*>(workspace);
-    m.lse_part = reinterpret_cast<const float*>(
-        static_cast<const char*>(workspace) + partial_out_bytes(B, H, d_c, effective_splits(B, num_splits)));
-    m.o_lat = o_lat; m.lse = lse; m.B = B; m.H = H; m.d_c = d_c; m.num_splits = effective_splits(B, num_splits);
+    fill_merge_params(m, workspace, B, H, d_c, effective_splits(B, num_splits), (flags & MLA_FLAG_BALANCED) != 0);
+    m.o_lat = o_lat; m.lse = lse;
     hipError_t e;
     if (merge_out_proj_supported(m, d_head, io_dtype)) {
         e = launch_merge_out_proj(m, W_UV, out, stream);

@@ -90,7 +90,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //              the row's scale multiplies its score and its weight instead of its 576 values.
 // NBUF = tiles in the LDS ring (bf16 path): 4 fills LDS with one workgroup per CU; 2 leaves room
 //        for two workgroups per CU (WPE = waves per SIMD the register budget is sized for).
-template <int D_C, bool FP8, int NBUF, int WPE>
+// BAL  = false: one workgroup per (sequence, chunk), chunks of the same number of pages.
+//        true : the page lists of all sequences, laid end to end, are cut into as many equal
+//               ranges as there are workgroups; a workgroup walks its range sequence by sequence
+//               (one segment each) and writes one partial result per segment.
+template <int D_C, bool FP8, int NBUF, int WPE, bool BAL>
 __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int ROW = D_C + 64;               // elements per cache row
@@ -109,6 +113,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     static_assert(NBUF >= 2 && NBUF <= 4, "ring depth");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
+    __shared__ float scale_lds[2][TILE_ROWS];        // fp8: row scales of the two widened tiles
+    __shared__ int seg_lds[BAL ? 64 : 1][3];         // balanced partition: (sequence, first row, end row) per segment
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
     const int tid = threadIdx.x;
@@ -116,15 +122,28 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hg = wave & 1, tg = wave >> 1;
     const int n = lane & 15, g = lane >> 4;
-    // Workgroup -> (sequence, chunk).  Linear ids run over the sequences first, chunk by chunk,
-    // with the sequence rotated by the chunk index.  Ids are dealt round-robin to the 8 XCDs and,
-    // inside an XCD, to its CUs in a fixed order, so any regular pattern in the ids repeats on
-    // the hardware: with the chunks of a sequence adjacent, the empty trailing chunks of short
-    // sequences fell on the same CUs every time and left half the chip idle, and a sequence's
-    // chunks all went to the XCDs of its low chunk indices.  This order puts the empty chunks
-    // (high chunk indices) at the end of the grid and spreads every sequence over the XCDs.
-    const int split = blockIdx.y;
-    const int b = (int)((blockIdx.x + blockIdx.y) % (unsigned)p.B);
+    // One segment = cached rows [row0, row1) of sequence b, reduced to one partial result.
+    // BAL = false: the rows are those of chunk `split` of the sequence (seg_row0/1 unused) and the
+    // result goes to partial (b, split); BAL = true: the caller gives the rows and the partial slot.
+    auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
+                           const size_t out_slot) {
+    // Balanced partition: the body runs in a loop.  Everything derived from the thread index is
+    // derived again here from a value the compiler cannot see through, so that none of it is
+    // hoisted out of that loop and kept in registers across the epilogue (which has none to spare).
+    int opaque_zero = 0;
+    if constexpr (BAL) asm volatile("" : "+v"(opaque_zero));
+    const int tid = (int)threadIdx.x + opaque_zero;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hg = wave & 1, tg = wave >> 1;
+    const int n = lane & 15, g = lane >> 4;
+    // where head h's partial row and log-sum-exp go
+    auto o_row = [&](int h) -> float* {
+        return p.o_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
+    };
+    auto lse_at = [&](int h) -> float* {
+        return p.lse_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits));
+    };
 
     // Read-only tables go through the scalar cache: scalar loads do not count against the
     // vector-memory counter, so looking up a page id never waits on an in-flight prefetch.
@@ -132,7 +151,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
     // touch this chunk's first page-table line now, in parallel with the sequence length
     // (both are scalar loads): the later look-ups then hit the scalar cache
-    const int warm = ptab[min(split * p.chunk_pages, p.max_pages - 1)];
+    const int warm = ptab[min(BAL ? seg_row0 / 64 : split * p.chunk_pages, p.max_pages - 1)];
     int L = seq_lens_c[b];
 
     // ---- this wave's 16 query rows as B operands, resident for the whole chunk.
@@ -166,10 +185,10 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 
     asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
-    const int row0 = split * p.chunk_pages * 64;                    // first cached row of this chunk
-    const int row1 = min(row0 + p.chunk_pages * 64, L);             // one past its last row
+    const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;             // first cached row of this segment
+    const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);  // one past its last row
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < p.H) p.lse_part[part_index(b, tid, split, p.H, p.num_splits)] = -INFINITY;
+        if (tid < p.H) *lse_at(tid) = -INFINITY;
         wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
@@ -237,7 +256,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     constexpr int N16 = RAW_B / 16;                  // 16-byte pieces per tile (1152 / 640)
     constexpr int NLOAD8 = (N16 + MF_THREADS - 1) / MF_THREADS;   // loads per thread per tile (5 / 3; the last is half used)
     static_assert(CPR8 % 2 == 0, "a 16-byte piece must not straddle two rows");
-    __shared__ float scale_lds[2][TILE_ROWS];
     u32x4 stg[FP8 ? NLOAD8 : 1];
     float stg_scale = 0.f;
     // piece c16 = k * 256 + tid sits at byte c16 * 16 of the tile's rows in HBM (rows are
@@ -627,12 +645,93 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
             f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = p.o_part + part_index(b, hg * 16 + r, split, p.H, p.num_splits) * D_C + tg * (HCT * 16) + c * 4;
+            float* dst = o_row(hg * 16 + r) + tg * (HCT * 16) + c * 4;
             __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
         }
     }
     if (tg == 0 && head < p.H && g == 0)
-        p.lse_part[part_index(b, head, split, p.H, p.num_splits)] = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+        *lse_at(head) = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+    };  // run_segment
+
+    if constexpr (!BAL) {
+        // Workgroup -> (sequence, chunk).  Linear ids run over the sequences first, chunk by
+        // chunk, with the sequence rotated by the chunk index.  Ids are dealt round-robin to the
+        // 8 XCDs and, inside an XCD, to its CUs in a fixed order, so any regular pattern in the ids
+        // repeats on the hardware: with the chunks of a sequence adjacent, the empty trailing
+        // chunks of short sequences fell on the same CUs every time and left half the chip idle,
+        // and a sequence's chunks all went to the XCDs of its low chunk indices.  This order puts
+        // the empty chunks (high chunk indices) at the end of the grid and spreads every
+        // sequence over the XCDs.
+        run_segment((int)((blockIdx.x + blockIdx.y) % (unsigned)p.B), (int)blockIdx.y, 0, 0, 0);
+    } else {
+        // ---- balanced partition.  Pages of sequence b: P_b = ceil(len_b / 64); workgroup w of G
+        // owns the global pages [P w / G, P (w+1) / G) of the concatenation, P = sum_b P_b (the
+        // host has checked that B * max_pages fits 31 bits).  Every wavefront derives the same
+        // plan by itself: lanes stand for sequences (64 at a time), a wave scan gives each
+        // sequence's first and last global page.  The segments of a block of 64 sequences are
+        // written to a small list in LDS first, so that nothing but a few wave-uniform counters
+        // stays live across the segment body (the kernel has no registers to spare).
+        const int wg = blockIdx.x, G = gridDim.x;
+        auto seq_len_of = [&](int bb) { return bb < p.B ? max(0, min(p.seq_lens[bb], p.max_pages * 64)) : 0; };
+        auto wave_scan = [&](int v) {                // inclusive prefix sum over the 64 lanes
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int u = __shfl_up(v, o);
+                if (lane >= o) v += u;
+            }
+            return v;
+        };
+        int total = 0;
+        for (int blk = 0; blk < p.B; blk += 64)
+            total += __shfl(wave_scan((seq_len_of(blk + lane) + 63) >> 6), 63);
+        total = __builtin_amdgcn_readfirstlane(total);
+        const int ps = __builtin_amdgcn_readfirstlane((int)((long long)total * wg / G));
+        const int pe = __builtin_amdgcn_readfirstlane((int)((long long)total * (wg + 1) / G));
+        int carry = 0;
+        for (int blk = 0; blk < p.B; blk += 64) {
+            int nseg = 0;
+            {
+                const int bb = blk + lane;
+                const int len = seq_len_of(bb);
+                const int pg = (len + 63) >> 6;
+                const int incl = carry + wave_scan(pg), excl = incl - pg;
+                // workgroup of global page x: the largest w with P w / G <= x
+                const int w0 = pg > 0 ? (int)((((long long)excl + 1) * G - 1) / total) : 0;
+                const int w1 = pg > 0 ? (int)(((long long)incl * G - 1) / total) : -1;
+                if (wg == 0 && wave == 0 && bb < p.B) {
+                    // the plan for the merge: sequence bb's partials are the slots first ..
+                    // first + cnt - 1 (slot of a segment = workgroup + sequence index: strictly
+                    // increasing along the concatenation, so no two segments share one)
+                    p.plan[2 * bb] = pg > 0 ? w0 + bb : 0;
+                    p.plan[2 * bb + 1] = w1 - w0 + 1;
+                }
+                if (ps == pe && pg > 0 && wave == 0 && w0 <= wg && wg <= w1) {
+                    // A workgroup with an empty range (more workgroups than pages) still owns a
+                    // slot if it lies inside a sequence's span: mark it empty for the merge.
+                    for (int h = 0; h < p.H; ++h) p.lse_part[((size_t)wg + bb) * p.H + h] = -INFINITY;
+                }
+                const int lo = max(ps, excl), hi = min(pe, incl);
+                const bool mine = pg > 0 && lo < hi;
+                const unsigned long long mask = __ballot(mine);
+                nseg = __builtin_popcountll(mask);
+                if (mine && wave == 0) {
+                    const int k = __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+                    seg_lds[k][0] = bb;
+                    seg_lds[k][1] = (lo - excl) * 64;
+                    seg_lds[k][2] = (hi - excl) * 64;     // clipped to the length inside the segment
+                }
+                carry = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+            }
+            __syncthreads();
+            for (int k = 0; k < nseg; ++k) {
+                const int sb = seg_lds[k][0], r0 = seg_lds[k][1], r1 = seg_lds[k][2];
+                run_segment(sb, 0, r0, r1, (size_t)wg + (size_t)sb);
+                __syncthreads();   // the next segment reuses the LDS the epilogue just read
+            }
+            if (carry >= pe && wg != 0) break;   // nothing further overlaps (workgroup 0 goes on: it writes the plan)
+            __syncthreads();                     // the list is rewritten for the next block
+        }
+    }
 }
 
 }  // namespace
@@ -643,14 +742,25 @@ bool decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache)
            p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && p.H <= 32;
 }
 
-hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s)
+hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced)
 {
-    dim3 grid(p.B, p.num_splits), block(MF_THREADS);
     const bool fp8 = cache == MLA_FP8_E4M3;
-    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1><<<grid, block, 0, s>>>(p);
+    dim3 block(MF_THREADS);
+    if (balanced) {
+        if (!p.plan) return hipErrorInvalidValue;
+        dim3 grid((unsigned)p.B * (unsigned)p.num_splits);   // workgroups = sequences x chunks per sequence
+        if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, true><<<grid, block, 0, s>>>(p);
+        else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, true><<<grid, block, 0, s>>>(p);
+        else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, true><<<grid, block, 0, s>>>(p);
+        else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1, true><<<grid, block, 0, s>>>(p);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
+    dim3 grid(p.B, p.num_splits);
+    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1, false><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

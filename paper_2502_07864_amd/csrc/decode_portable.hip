@@ -203,37 +203,98 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
 }
 
 // ---- split-KV merge: lse = log sum_s e^{lse_s}, o = sum_s e^{lse_s - lse} o_s ----
+// General kernel: any number of chunks, any d_c (multiple of 4), both partitions.  One workgroup
+// per (head, sequence): the chunk weights are computed once into LDS (up to MG_MAXS chunks; more
+// than that are handled MG_MAXS at a time with a running reference), then every thread streams
+// its four columns with eight partial rows in flight.
+constexpr int MG_MAXS = 1024;
+
 template <bool OUT_BF16>
 __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
 {
+    __shared__ float w_s[MG_MAXS];
+    __shared__ float red_s[2];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int S = p.num_splits;
-    const float* lp = p.lse_part + part_index(b, h, 0, p.H, S);
+    // chunks of (b, h): uniform partition: S adjacent entries; balanced partition: the slots the
+    // plan names, one every H entries ([slot, H] / [slot, H, d_c])
+    const bool planned = p.plan != nullptr;
+    const int S = planned ? p.plan[2 * b + 1] : p.num_splits;
+    const size_t first = planned ? (size_t)p.plan[2 * b] * p.H + h : part_index(b, h, 0, p.H, p.num_splits);
+    const size_t step = planned ? (size_t)p.H : 1;
+    const float* lp = p.lse_part + first;
+
+    auto block_max = [&](float v) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+        __syncthreads();
+        if ((tid & 63) == 0) red_s[tid >> 6] = v;
+        __syncthreads();
+        return fmaxf(red_s[0], red_s[1]);
+    };
+    auto block_sum = [&](float v) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        __syncthreads();
+        if ((tid & 63) == 0) red_s[tid >> 6] = v;
+        __syncthreads();
+        return red_s[0] + red_s[1];
+    };
+
+    // reference = the maximum over all chunks, normaliser = sum of e^{lse_s - max}
     float m = -INFINITY;
-    for (int s = 0; s < S; ++s) m = fmaxf(m, lp[s]);
+    for (int s = tid; s < S; s += 128) m = fmaxf(m, lp[s * step]);
+    m = block_max(m);
     float z = 0.f;
     if (m != -INFINITY)
-        for (int s = 0; s < S; ++s) z += expf(lp[s] - m);  // exp(-inf) = 0
+        for (int s = tid; s < S; s += 128) z += expf(lp[s * step] - m);  // exp(-inf) = 0
+    z = block_sum(z);
     const float inv = z > 0.f ? 1.f / z : 0.f;
-    const size_t out_base = ((size_t)b * p.H + h) * p.d_c;
-    for (int c = tid * 4; c < p.d_c; c += 128 * 4) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s = 0; s < S; ++s) {
-            float ls = lp[s];
-            if (ls == -INFINITY) continue;  // empty chunk: its partial output was never written
-            float w = expf(ls - m) * inv;
-            const float4 v = *reinterpret_cast<const float4*>(
-                p.o_part + part_index(b, h, s, p.H, S) * p.d_c + c);
-            acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
-            acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
+
+    float4 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < S; s0 += MG_MAXS) {
+        const int ns = min(MG_MAXS, S - s0);
+        __syncthreads();
+        for (int s = tid; s < ns; s += 128) {
+            const float ls = lp[(s0 + s) * step];
+            w_s[s] = ls == -INFINITY ? 0.f : expf(ls - m) * inv;
         }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {             // columns tid*4 + i*512 (d_c <= 2048 per pass)
+            const int c = tid * 4 + i * 512;
+            if (c >= p.d_c) break;
+            const float* src = p.o_part + (first + (size_t)s0 * step) * p.d_c + c;
+            for (int s = 0; s < ns; s += 8) {
+                float4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    v[j] = *reinterpret_cast<const float4*>(src + (size_t)min(s + j, ns - 1) * step * p.d_c);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    // weight 0 for empty chunks (their rows were never written: discarded by the
+                    // select, not multiplied) and past the last chunk
+                    const float w = s + j < ns ? w_s[s + j] : 0.f;
+                    const bool live = w != 0.f;
+                    acc[i].x = fmaf(w, live ? v[j].x : 0.f, acc[i].x); acc[i].y = fmaf(w, live ? v[j].y : 0.f, acc[i].y);
+                    acc[i].z = fmaf(w, live ? v[j].z : 0.f, acc[i].z); acc[i].w = fmaf(w, live ? v[j].w : 0.f, acc[i].w);
+                }
+            }
+        }
+    }
+    const size_t out_base = ((size_t)b * p.H + h) * p.d_c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid * 4 + i * 512;
+        if (c >= p.d_c) break;
         if (OUT_BF16) {
             uint2 o;
-            o.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
-            o.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+            o.x = f32_to_bf16_bits(acc[i].x) | (f32_to_bf16_bits(acc[i].y) << 16);
+            o.y = f32_to_bf16_bits(acc[i].z) | (f32_to_bf16_bits(acc[i].w) << 16);
             *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.o_lat) + out_base + c) = o;
         } else {
-            *reinterpret_cast<float4*>(static_cast<float*>(p.o_lat) + out_base + c) = acc;
+            *reinterpret_cast<float4*>(static_cast<float*>(p.o_lat) + out_base + c) = acc[i];
         }
     }
     if (p.lse && tid == 0) p.lse[(size_t)b * p.H + h] = z > 0.f ? m + logf(z) : -INFINITY;
@@ -339,7 +400,7 @@ hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype
 
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s)
 {
-    if (p.d_c % 256 == 0 && p.num_splits <= 64) {
+    if (!p.plan && p.d_c % 256 == 0 && p.num_splits <= 64) {
         const int waves = p.B * p.H * (p.d_c / 256);
         dim3 grid((waves + 3) / 4), block(256);
         if (io == MLA_BF16) merge_wave_kernel<true><<<grid, block, 0, s>>>(p);

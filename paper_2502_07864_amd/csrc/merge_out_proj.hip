@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
 
 bool merge_out_proj_supported(const MergeParams& p, int d_head, mla_dtype io)
 {
-    return io == MLA_BF16 && d_head == FT_N && (p.d_c == 256 || p.d_c == 512) && p.num_splits <= 64 &&
+    return !p.plan && io == MLA_BF16 && d_head == FT_N && (p.d_c == 256 || p.d_c == 512) && p.num_splits <= 64 &&
            p.H <= 4096;
 }
 

@@ -18,6 +18,8 @@ struct DecodeParams {
     const int32_t* seq_lens;    // [B]
     float* o_part;              // [B, H, S, d_c]  chunk-normalised partial outputs
     float* lse_part;            // [B, H, S]       natural-log LSE per chunk (-inf = empty)
+    int32_t* plan;              // balanced partition only: [B, 2] first partial slot and count per
+                                // sequence (the partials are then [slot, H, d_c] / [slot, H])
     int B, H, d_c, d_rope, page_size, num_pages, max_pages, num_splits, chunk_pages;
     float scale;
 };
@@ -25,6 +27,7 @@ struct DecodeParams {
 struct MergeParams {
     const float* o_part;
     const float* lse_part;
+    const int32_t* plan;   // nullptr, or (balanced partition) [B, 2] first slot and count per sequence
     void* o_lat;   // [B,H,d_c] io dtype
     float* lse;    // [B,H] or nullptr
     int B, H, d_c, num_splits;
@@ -109,7 +112,7 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code)
 
 hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
 bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
-hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s);
 hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
                          void* dense, int B, int max_len, int row_bytes, int page_size,

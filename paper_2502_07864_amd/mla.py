@@ -18,7 +18,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libmla_gfx950.so"
 _lib = None
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
-FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE = 0, 1, 2
+FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE, FLAG_BALANCED = 0, 1, 2, 4
 
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
@@ -54,9 +54,9 @@ def lib() -> ctypes.CDLL:
         L.mla_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        i, i, i, i, i, i, i, i, f, i, i, u, vp]
         L.mla_merge_partials.restype = i
-        L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, vp]
+        L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, u, vp]
         L.mla_merge_out_proj.restype = i
-        L.mla_merge_out_proj.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        L.mla_merge_out_proj.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, u, vp]
         L.mla_gather_paged.restype = i
         L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
         L.mla_append_workspace_bytes.restype = ctypes.c_size_t
@@ -186,8 +186,9 @@ def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: 
 
 def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits: int,
                    dtype: torch.dtype, out: Optional[torch.Tensor] = None,
-                   lse: Optional[torch.Tensor] = None, return_lse: bool = False):
-    """Merge the per-chunk partials left in `workspace` by decode_paged(flags=FLAG_SKIP_MERGE)."""
+                   lse: Optional[torch.Tensor] = None, return_lse: bool = False, flags: int = 0):
+    """Merge the per-chunk partials left in `workspace` by decode_paged(flags=FLAG_SKIP_MERGE);
+    pass FLAG_BALANCED here iff the decode call had it."""
     if out is None:
         out = torch.empty((B, H, d_c), dtype=dtype, device=workspace.device)
     if lse is None and return_lse:
@@ -195,14 +196,15 @@ def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits
     _check(lib().mla_merge_partials(_dev(workspace, "workspace"),
                                     workspace.numel() * workspace.element_size(),
                                     _dev(out, "out"), _dev(lse, "lse"), B, H, d_c, num_splits,
-                                    _io_code(out), _stream(workspace)), "mla_merge_partials")
+                                    _io_code(out), int(flags), _stream(workspace)), "mla_merge_partials")
     return (out, lse) if lse is not None else out
 
 
 def merge_out_proj(workspace: torch.Tensor, W_UV: torch.Tensor, B: int, num_splits: int,
                    o_lat: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                   lse: Optional[torch.Tensor] = None, return_lse: bool = False):
-    """Merge the partials left by decode_paged(flags=FLAG_SKIP_MERGE) and apply W_UV [H,d_c,d_head].
+                   lse: Optional[torch.Tensor] = None, return_lse: bool = False, flags: int = 0):
+    """Merge the partials left by decode_paged(flags=FLAG_SKIP_MERGE) and apply W_UV [H,d_c,d_head]
+    (pass FLAG_BALANCED here iff the decode call had it).
     Returns (o_lat [B,H,d_c], out [B,H,d_head][, lse])."""
     H, d_c, d_head = W_UV.shape
     if o_lat is None:
@@ -214,7 +216,7 @@ def merge_out_proj(workspace: torch.Tensor, W_UV: torch.Tensor, B: int, num_spli
     _check(lib().mla_merge_out_proj(_dev(workspace, "workspace"),
                                     workspace.numel() * workspace.element_size(), _dev(W_UV, "W_UV"),
                                     _dev(o_lat, "o_lat"), _dev(lse, "lse"), _dev(out, "out"), B, H, d_c,
-                                    d_head, num_splits, _io_code(W_UV), _stream(workspace)),
+                                    d_head, num_splits, _io_code(W_UV), int(flags), _stream(workspace)),
            "mla_merge_out_proj")
     return (o_lat, out, lse) if lse is not None else (o_lat, out)
 

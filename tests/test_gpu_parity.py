@@ -245,6 +245,69 @@ def test_page_table_longer_than_any_sequence(mla):
     check_decode(mla, w, 8, flags=1)
 
 
+# ------------------------------------------------ balanced partition (flag 4)
+
+BAL = 4
+
+
+@pytest.mark.parametrize("num_splits", [1, 2, 7, 32])
+def test_decode_balanced_ragged(mla, num_splits):
+    """Equal page ranges per workgroup over the concatenated page lists: ranges cross sequence
+    boundaries, short sequences share a workgroup, long ones span many."""
+    check_decode(mla, ragged_workload(seed=71), num_splits, flags=BAL)
+
+
+def test_decode_balanced_shapes_and_caches(mla):
+    check_decode(mla, ragged_workload(d_c=256, H=28, lens=[300, 1, 64, 0, 999, 4096], seed=72), 3, flags=BAL)
+    check_decode(mla, synth.config("C3", shrink=16), 4, flags=BAL)
+    check_decode(mla, synth.config("C5", shrink=64), 8, flags=BAL)          # fp8 cache
+    check_decode(mla, ragged_workload(lens=[5000], seed=73), 16, flags=BAL)  # one sequence, many workgroups
+    check_decode(mla, ragged_workload(lens=[3, 2, 1], seed=74), 64, flags=BAL)   # more workgroups than pages
+    check_decode(mla, ragged_workload(lens=[0, 1, 0, 64, 5, 0], seed=75), 3, flags=BAL)
+    w = ragged_workload(lens=[700] * 70, seed=76)                            # more than 64 sequences: two scan blocks
+    check_decode(mla, w, 2, flags=BAL, b_sel=[0, 1, 63, 64, 65, 69])
+
+
+def test_decode_balanced_all_sequences_empty(mla):
+    import torch
+    w = ragged_workload(lens=[0, 0, 0], seed=77)
+    d = DeviceWorkload(w)
+    o, lse = run_decode(mla, d, gpu_q_abs(mla, d), 2, BAL)
+    torch.cuda.synchronize()
+    assert not widen_gpu(o).any() and np.isneginf(widen_gpu(lse)).all()
+
+
+def test_balanced_matches_uniform_and_fused_tail_call(mla):
+    """Same inputs through both partitions: equal within fp32 merge rounding of the bf16 output;
+    and the separate merge / tail calls accept the balanced workspace."""
+    import torch
+    w = ragged_workload(seed=78)
+    d = DeviceWorkload(w)
+    q_abs = gpu_q_abs(mla, d)
+    o_u, lse_u = run_decode(mla, d, q_abs, 7, 0)
+    o_b, lse_b = run_decode(mla, d, q_abs, 7, BAL)
+    ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                          num_splits=7, flags=mla.FLAG_SKIP_MERGE | BAL)
+    o_m, lse_m = mla.merge_partials(ws, w.B, w.H, w.d_c, 7, q_abs.dtype, return_lse=True, flags=BAL)
+    o_t, out_t, lse_t = mla.merge_out_proj(ws, d.W_UV, w.B, 7, return_lse=True, flags=BAL)
+    torch.cuda.synchronize()
+    assert max_abs_rel(widen_gpu(o_b), widen_gpu(o_u)) <= 2 ** -7
+    assert lse_err(widen_gpu(lse_b), widen_gpu(lse_u)) <= 5e-3     # each sums bf16-rounded weights, chunked differently
+    for o_x, lse_x in ((o_m, lse_m), (o_t, lse_t)):
+        assert storage_bits(o_x).tobytes() == storage_bits(o_b).tobytes()
+        assert storage_bits(lse_x).tobytes() == storage_bits(lse_b).tobytes()
+    ref = oracle.out_proj(q_abs_storage(o_t), w.W_UV)
+    assert max_abs_rel(widen_gpu(out_t), ref) <= TOL["bf16"]
+
+
+def test_balanced_needs_the_matrix_core_kernel(mla):
+    w = synth.config("C1", shrink=4)          # fp32: portable kernel only
+    d = DeviceWorkload(w)
+    with pytest.raises(mla.MlaError) as e:
+        run_decode(mla, d, gpu_q_abs(mla, d), 2, BAL)
+    assert e.value.status == -3
+
+
 # ------------------------------------------------------------- edge cases
 
 def test_empty_and_single_token_sequences(mla):
