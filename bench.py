@@ -1,4 +1,6 @@
-#!/usr/bin/env python3
+"kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1, BAL>", "C3": "decode_mfma_kernel<512, false, 4, 1, BAL>",
+                                "C4": "decode_mfma_kernel<256, false, 4, 1, BAL>", "C5": "decode_mfma_kernel<512, true, 4, 1, BAL>",
+                                "C1": "decode_portable_kernel<float, float>"}#!/usr/bin/env python3
 """Benchmark of the absorbed MLA decode step on one MI355X.
 
 A step = mla_absorb_q -> mla_decode_paged (split-KV kernel, partials left in the
@@ -253,7 +255,7 @@ def main():
             traffic = None
 
     rec = {
-        "metric": METRICS[args.workload],
+        "metric": METRICS[args.workload].replace("BAL", "true" if args.balanced else "false"),
         "value": round(ms_per_step * 1e3, 3),
         "unit": "us/step",
         "n_gpus": 1,
