@@ -1,6 +1,4 @@
-"kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1, BAL>", "C3": "decode_mfma_kernel<512, false, 4, 1, BAL>",
-                                "C4": "decode_mfma_kernel<256, false, 4, 1, BAL>", "C5": "decode_mfma_kernel<512, true, 4, 1, BAL>",
-                                "C1": "decode_portable_kernel<float, float>"}#!/usr/bin/env python3
+#!/usr/bin/env python3
 """Benchmark of the absorbed MLA decode step on one MI355X.
 
 A step = mla_absorb_q -> mla_decode_paged (split-KV kernel, partials left in the
@@ -255,7 +253,7 @@ def main():
             traffic = None
 
     rec = {
-        "metric": METRICS[args.workload].replace("BAL", "true" if args.balanced else "false"),
+        "metric": METRICS[args.workload],
         "value": round(ms_per_step * 1e3, 3),
         "unit": "us/step",
         "n_gpus": 1,
@@ -282,9 +280,9 @@ def main():
                                            "p90": round(float(np.percentile(dec_us, 90)), 2)},
                        ("merge+out_proj" if args.unfused_tail else "merge_out_proj_fused"):
                            {"avg": round(float(mrg_us.mean()), 2)}},
-        "roofline": {"bound": "hbm", "kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1>", "C3": "decode_mfma_kernel<512, false, 4, 1>",
-                                "C4": "decode_mfma_kernel<256, false, 4, 1>", "C5": "decode_mfma_kernel<512, true, 4, 1>",
-                                "C1": "decode_portable_kernel<float, float>"}[args.workload],
+        "roofline": {"bound": "hbm", "kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1, BAL>", "C3": "decode_mfma_kernel<512, false, 4, 1, BAL>",
+                                "C4": "decode_mfma_kernel<256, false, 4, 1, BAL>", "C5": "decode_mfma_kernel<512, true, 4, 1, BAL>",
+                                "C1": "decode_portable_kernel<float, float>"}[args.workload].replace("BAL", "true" if args.balanced else "false"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": cache_bytes,
