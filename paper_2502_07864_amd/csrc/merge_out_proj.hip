@@ -70,13 +70,18 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
     };
 
     // ---- (1) the first task's chunk weights and partial rows are requested ahead of everything
-    // else: they come from HBM, the slab mostly from L2 (the workgroups of a head share it)
-    f32x4 v[BATCH];
-    float ls_first = -INFINITY;
-    if (wave / CB < nb) {
-        if (lane < S) ls_first = p.lse_part[part_index(b0 + wave / CB, h, lane, p.H, S)];
-        load_rows(task_base(wave), 0, v);
-    }
+    // else: they come from HBM, the slab mostly from L2 (the workgroups of a head share it).
+    // Tasks past the workgroup's batch rows only clear their part of the A tile.
+    const int T = nb * CB;                       // tasks with a batch row behind them
+    auto request = [&](int task, f32x4 (&v)[BATCH], float& ls) {
+        ls = lane < S ? p.lse_part[part_index(b0 + task / CB, h, lane, p.H, S)] : -INFINITY;
+        load_rows(task_base(task), 0, v);
+    };
+    f32x4 va[BATCH], vb[BATCH];
+    float lsa = -INFINITY, lsb = -INFINITY;
+    if (wave < T) request(wave, va, lsa);
+    for (int task = T + wave; task < FT_MAXB * CB; task += 4)
+        *(LDS_AS u32x2*)(atile + (task / CB) * ARS + ((task % CB) * 256 + lane * 4) * 2) = (u32x2){0u, 0u};
 
     // ---- (2) request W_UV[h]: LDS chunk P = row P/16, position P%16 holds chunk (P%16) ^ key(row)
     {
@@ -93,38 +98,37 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
         }
     }
 
-    // ---- (3) merge (same arithmetic as the stand-alone merge kernel)
-    for (int task = wave; task < FT_MAXB * CB; task += 4) {
-        const int bl = task / CB, cb = task % CB;
+    // ---- (3) merge (same arithmetic as the stand-alone merge kernel): this wave's tasks, the
+    // next one's rows requested before the current one is reduced
+    auto reduce = [&](int task, f32x4 (&v)[BATCH], float ls) {
+        const int bl = task / CB, cb = task % CB, b = b0 + bl;
+        const float* base = task_base(task);
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (bl < nb) {
-            const int b = b0 + bl;
-            const float* base = task_base(task);
-            float ls = ls_first;
-            if (task != wave) {
-                ls = lane < S ? p.lse_part[part_index(b, h, lane, p.H, S)] : -INFINITY;
-                load_rows(base, 0, v);
-            }
-            const ChunkWeights cw = chunk_weights(ls, S);
-            for (int s0 = 0; s0 < S; s0 += BATCH) {
-                if (s0 > 0) load_rows(base, s0, v);
+        const ChunkWeights cw = chunk_weights(ls, S);
+        for (int s0 = 0; s0 < S; s0 += BATCH) {
+            if (s0 > 0) load_rows(base, s0, v);
 #pragma unroll
-                for (int i = 0; i < BATCH; ++i) {
-                    // the weight is 0 at and past S; rows of empty chunks were never written,
-                    // so what was read there is discarded, not multiplied by zero
-                    const float ws = chunk_weight_at(cw, ls, s0 + i);
-                    const f32x4 zero = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    acc += ws * (ws != 0.f ? v[i] : zero);
-                }
+            for (int i = 0; i < BATCH; ++i) {
+                // the weight is 0 at and past S; rows of empty chunks were never written,
+                // so what was read there is discarded, not multiplied by zero
+                const float ws = chunk_weight_at(cw, ls, s0 + i);
+                const f32x4 zero = (f32x4){0.f, 0.f, 0.f, 0.f};
+                acc += ws * (ws != 0.f ? v[i] : zero);
             }
-            const u32x2 packed = (u32x2){f32_to_bf16_bits(acc[0]) | (f32_to_bf16_bits(acc[1]) << 16),
-                                        f32_to_bf16_bits(acc[2]) | (f32_to_bf16_bits(acc[3]) << 16)};
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.o_lat) + ((size_t)b * p.H + h) * D_C + cb * 256 + lane * 4) = packed;
-            *(LDS_AS u32x2*)(atile + bl * ARS + (cb * 256 + lane * 4) * 2) = packed;
-            if (p.lse && cb == 0 && lane == 0) p.lse[(size_t)b * p.H + h] = cw.z > 0.f ? cw.m + logf(cw.z) : -INFINITY;
-        } else {
-            *(LDS_AS u32x2*)(atile + bl * ARS + (cb * 256 + lane * 4) * 2) = (u32x2){0u, 0u};
         }
+        const u32x2 packed = (u32x2){f32_to_bf16_bits(acc[0]) | (f32_to_bf16_bits(acc[1]) << 16),
+                                    f32_to_bf16_bits(acc[2]) | (f32_to_bf16_bits(acc[3]) << 16)};
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.o_lat) + ((size_t)b * p.H + h) * D_C + cb * 256 + lane * 4) = packed;
+        *(LDS_AS u32x2*)(atile + bl * ARS + (cb * 256 + lane * 4) * 2) = packed;
+        if (p.lse && cb == 0 && lane == 0) p.lse[(size_t)b * p.H + h] = cw.z > 0.f ? cw.m + logf(cw.z) : -INFINITY;
+    };
+    for (int ta = wave; ta < T; ta += 8) {
+        const int tb = ta + 4;
+        if (tb < T) request(tb, vb, lsb);
+        reduce(ta, va, lsa);
+        if (tb >= T) break;
+        if (tb + 4 < T) request(tb + 4, va, lsa);
+        reduce(tb, vb, lsb);
     }
 
     // ---- (4) slab landed (my loads), then everybody's, and the A tile is complete
