@@ -628,3 +628,53 @@ def test_cache_append_skips_bad_positions(mla):
     mla.cache_append(to_torch(x, io), to_torch(W, io), pool, to_torch(pt2, "i32"), to_torch(pos, "i32"), 512)
     torch.cuda.synchronize()
     assert np.array_equal(storage_bits(pool), w.pool)
+
+
+# ------------------------------------------------------------- graph capture
+
+def test_step_captured_in_a_hip_graph(mla):
+    """The library only enqueues kernels on the current stream and allocates nothing, so the whole
+    step can be captured; every replay (with eager work and synchronisation in between, and with
+    the inputs changed between replays) must give the bits of the eager run on the same inputs."""
+    import torch
+    w = synth.config("C2", shrink=8)
+    d = DeviceWorkload(w)
+    B, H, d_c, S = w.B, w.H, w.d_c, w.num_splits
+    q_nope = d.q_nope.clone()
+    q_abs = torch.empty((B, H, d_c), dtype=torch.bfloat16, device="cuda")
+    o_lat = torch.empty_like(q_abs)
+    out = torch.empty((B, H, w.d_head), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(mla.decode_workspace_bytes(B, H, d_c, S), dtype=torch.uint8, device="cuda")
+
+    def step():
+        mla.absorb_q(q_nope, d.W_UK, out=q_abs)
+        mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                         num_splits=S, workspace=ws, flags=mla.FLAG_SKIP_MERGE)
+        mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out)
+
+    step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        q_nope.copy_(torch.roll(d.q_nope, shifts=rep, dims=1))       # new inputs, same buffers
+        step()
+        torch.cuda.synchronize()
+        want_o, want_out = storage_bits(o_lat).copy(), storage_bits(out).copy()
+        o_lat.zero_(); out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(storage_bits(o_lat), want_o), f"replay {rep}: o_lat differs"
+        assert np.array_equal(storage_bits(out), want_out), f"replay {rep}: out differs"
+    ref = oracle.mla_step(w.q_nope, w.q_rope, w.W_UK, w.W_UV, w.pool, None, w.page_table, w.seq_lens, w.softmax_scale)
+    q_nope.copy_(d.q_nope)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert max_abs_rel(widen_gpu(out), ref["out"]) <= TOL["bf16"]
