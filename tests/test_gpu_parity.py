@@ -678,3 +678,28 @@ def test_step_captured_in_a_hip_graph(mla):
     graph.replay()
     torch.cuda.synchronize()
     assert max_abs_rel(widen_gpu(out), ref["out"]) <= TOL["bf16"]
+
+
+# ------------------------------------------------------- seeded random sweep
+
+def test_random_shapes_partitions_and_caches(mla):
+    """Forty seeded random cases: batch 1..9, heads 1..32, d_c 256 / 512, lengths 0..3000 (many
+    of them around page and tile boundaries), bf16 / fp8 caches, 1..40 chunks, both partitions,
+    both kernels (the portable one with the uniform partition)."""
+    rng = np.random.default_rng(2024)
+    special = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 127, 128, 129, 191, 192, 193]
+    for case in range(40):
+        B = int(rng.integers(1, 10))
+        H = int(rng.choice([1, 5, 16, 17, 28, 32]))
+        d_c = int(rng.choice([256, 512]))
+        lens = [int(rng.choice(special)) if rng.random() < 0.5 else int(rng.integers(0, 3000)) for _ in range(B)]
+        cache = "fp8_e4m3" if rng.random() < 0.35 else "bf16"
+        S = int(rng.integers(1, 41))
+        flags = int(rng.choice([0, 0, 4, 4, 1]))
+        w = synth.make_workload(f"rand{case}", B=B, H=H, d_head=128, d_c=d_c, d_rope=64, seq_lens=lens,
+                                io_dtype="bf16", cache_dtype=cache, placement="random", free_frac=0.25,
+                                seed=1000 + case)
+        try:
+            check_decode(mla, w, S, flags=flags)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: B={B} H={H} d_c={d_c} lens={lens} cache={cache} S={S} flags={flags}: {e}")
