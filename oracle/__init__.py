@@ -249,6 +249,30 @@ def decode_absorbed(q_abs, q_rope, pool, kv_scale, page_table, seq_lens,
     return o, lse
 
 
+def decode_absorbed_multi(q_abs, q_rope, pool, kv_scale, page_table, seq_lens,
+                          softmax_scale: float):
+    """Eq. "mqa" for the T newest positions of every sequence at once (multi-token
+    prediction / speculative decoding): query token i of T sits at position
+    seq_len - T + i and sees the cached rows up to and including its own.
+
+    q_abs [B,T,H,d_c], q_rope [B,T,H,d_rope] -> (o_lat [B,T,H,d_c], lse [B,T,H])."""
+    qa, qr = widen(q_abs), widen(q_rope)
+    pool, sc, dt = _pool_args(pool, kv_scale)
+    pt, sl = _i32(page_table), _i32(seq_lens)
+    B, T, H, d_c = qa.shape
+    d_rope = pool.shape[2] - d_c
+    if d_rope == 0:
+        qr = np.zeros((B, T, H, 0))
+    assert qr.shape == (B, T, H, d_rope)
+    o = np.empty((B, T, H, d_c), dtype=np.float64)
+    lse = np.empty((B, T, H), dtype=np.float64)
+    _c().oracle_decode_absorbed_multi(
+        _dp(qa), _dp(qr), _vp(pool), _vp(sc), _ip(pt), _ip(sl), _dp(o), _dp(lse),
+        B, T, H, d_c, d_rope, pool.shape[1], pt.shape[1],
+        ctypes.c_double(softmax_scale), dt)
+    return o, lse
+
+
 def decode_split(q_abs, q_rope, pool, kv_scale, page_table, seq_lens,
                  softmax_scale: float, n_splits: int, chunk_pages: int,
                  return_partials: bool = False):

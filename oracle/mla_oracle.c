@@ -324,6 +324,42 @@ int oracle_decode_absorbed(const double* q_abs, const double* q_rope,
     return 0;
 }
 
+/* ---- several query tokens per sequence (multi-token prediction, speculative
+ * decoding: the abstract's "Multi-Token Prediction"; Eq. "mqa" read for the T
+ * newest positions at once) ------------------------------------------------
+ * The cache of sequence b holds L = seq_lens[b] rows, the last T of which
+ * belong to the T query tokens themselves.  Query token i (0 <= i < T) sits at
+ * position t_i = L - T + i (0-based) and, by the sum over j = 1..t of
+ * Eq. "mqa", attends to the cached rows 0 .. t_i, i.e. to the first
+ * L - (T - 1 - i) rows.  A query token whose position is negative (L < T)
+ * attends to nothing: o_hat = 0, lse = -inf.
+ * q_abs [B,T,H,d_c], q_rope [B,T,H,d_rope] -> o_lat [B,T,H,d_c], lse [B,T,H]. */
+int oracle_decode_absorbed_multi(const double* q_abs, const double* q_rope,
+                                 const void* pool, const float* kv_scale,
+                                 const int32_t* page_table, const int32_t* seq_lens,
+                                 double* o_lat, double* lse,
+                                 int B, int T, int H, int d_c, int d_rope,
+                                 int page_size, int max_pages_per_seq,
+                                 double softmax_scale, int cache_dtype)
+{
+    int n_task = B * T * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int task = 0; task < n_task; ++task) {
+        int b = task / (T * H);
+        int i = (task / H) % T;
+        int visible = seq_lens[b] - (T - 1 - i);   /* rows 0 .. t_i */
+        if (visible < 0) visible = 0;
+        double l = absorbed_range(q_abs + (size_t)task * d_c,
+                                  q_rope + (size_t)task * d_rope,
+                                  pool, kv_scale, page_table, b, 0, visible,
+                                  o_lat + (size_t)task * d_c, d_c, d_rope,
+                                  page_size, max_pages_per_seq, softmax_scale,
+                                  cache_dtype);
+        if (lse) lse[task] = l;
+    }
+    return 0;
+}
+
 /* ---- split-KV: chunk-local softmax, then log-sum-exp merge ------------- */
 
 /* lse = log sum_s exp(lse_s); o = sum_s exp(lse_s - lse) o_s.

@@ -822,3 +822,118 @@ def test_A9_append_skips_positions_outside_the_table_or_pool():
     pt[1, 1] = -1
     pool2, _, _ = oracle.cache_append(x, W, w.pool, None, pt, pos, w.d_c)
     assert np.array_equal(pool2, w.pool)
+
+
+# ---------------------------------------------------------------------------
+# M: several query tokens per sequence (multi-token prediction; Eq. "mqa" read for the T newest
+# positions at once, each with its own upper limit of the sum over j)
+# ---------------------------------------------------------------------------
+
+def _multi_case(T, lens, H=3, d_head=4, d_c=6, d_rope=2, page_size=2, seed=0):
+    r = np.random.default_rng(100 + seed)
+    B = len(lens)
+    c = [f32(r.standard_normal((L, d_c))) for L in lens]
+    k = [f32(r.standard_normal((L, d_rope))) for L in lens]
+    pool, table, sl = dense_cache(c, k, page_size, seed=seed)
+    return dict(c=c, k=k, pool=pool, table=table, sl=sl, d_c=d_c, d_rope=d_rope,
+                qn=f32(r.standard_normal((B, T, H, d_head))), qr=f32(r.standard_normal((B, T, H, d_rope))),
+                Wk=f32(r.standard_normal((H, d_head, d_c))), Wv=f32(r.standard_normal((H, d_c, d_head))),
+                scale=1.0 / math.sqrt(d_head + d_rope))
+
+
+def _multi_chain(cs):
+    """absorb -> multi-token decode -> up-projection, all through the oracle."""
+    B, T, H, d_head = cs["qn"].shape
+    qa = oracle.absorb_q(cs["qn"].reshape(B * T, H, d_head), cs["Wk"]).reshape(B, T, H, cs["d_c"])
+    o, lse = oracle.decode_absorbed_multi(qa, cs["qr"], cs["pool"], None, cs["table"], cs["sl"], cs["scale"])
+    out = oracle.out_proj(o.reshape(B * T, H, cs["d_c"]), cs["Wv"]).reshape(B, T, H, d_head)
+    return qa, o, lse, out
+
+
+@pytest.mark.parametrize("T,lens,page_size,seed", [(2, (7, 4), 2, 0), (3, (9, 3, 5), 4, 1), (4, (6, 13), 3, 2),
+                                                   (1, (5, 3), 2, 3)])
+def test_M1_multi_token_equals_masked_attention_in_the_MHA_paradigm(T, lens, page_size, seed):
+    """Eq. "mha" written as the textbook masked attention of a whole sequence: keys and values
+    materialised per head, one score matrix [T x L], entry (i, j) allowed iff j <= L - T + i."""
+    cs = _multi_case(T, lens, page_size=page_size, seed=seed)
+    _, _, lse, out = _multi_chain(cs)
+    for b, L in enumerate(lens):
+        for h in range(cs["Wk"].shape[0]):
+            K = np.concatenate([cs["c"][b] @ cs["Wk"][h].T, cs["k"][b]], axis=1)     # [L, d + d^R]
+            V = cs["c"][b] @ cs["Wv"][h]                                               # [L, d]
+            Q = np.concatenate([cs["qn"][b, :, h], cs["qr"][b, :, h]], axis=1)         # [T, d + d^R]
+            S = (Q @ K.T) * cs["scale"]
+            allowed = np.arange(L)[None, :] <= (L - T + np.arange(T))[:, None]
+            S = np.where(allowed, S, -np.inf)
+            m = S.max(axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = E.sum(axis=1, keepdims=True)
+            np.testing.assert_allclose(out[b, :, h], (E / Z) @ V, rtol=1e-11, atol=1e-12)
+            np.testing.assert_allclose(lse[b, :, h], (m + np.log(Z))[:, 0], rtol=1e-12, atol=1e-12)
+
+
+def test_M2_each_token_is_a_single_token_decode_of_the_truncated_sequence():
+    """Token i of T is the (separately pinned) one-token decode at length L - (T-1-i)."""
+    T = 3
+    cs = _multi_case(T, (10, 6, 3), page_size=4, seed=5)
+    qa, o, lse, _ = _multi_chain(cs)
+    for i in range(T):
+        sl_i = np.maximum(cs["sl"] - (T - 1 - i), 0).astype(np.int32)
+        o1, l1 = oracle.decode_absorbed(qa[:, i], cs["qr"][:, i], cs["pool"], None, cs["table"], sl_i, cs["scale"])
+        assert np.array_equal(o[:, i], o1) and np.array_equal(lse[:, i], l1)
+
+
+def test_M3_multi_token_closed_forms():
+    T, H, d_c, d_r = 3, 2, 6, 2
+    r = np.random.default_rng(77)
+    scale = 0.3
+    # L = T: token 0 sees row 0 alone -> o = c_0, lse = its score; token 1 sees rows 0 and 1 ...
+    L = T
+    c = [f32(r.standard_normal((L, d_c)))]
+    k = [f32(r.standard_normal((L, d_r)))]
+    pool, table, sl = dense_cache(c, k, page_size=2)
+    qa = f32(r.standard_normal((1, T, H, d_c)))
+    qr = f32(r.standard_normal((1, T, H, d_r)))
+    o, lse = oracle.decode_absorbed_multi(qa, qr, pool, None, table, sl, scale)
+    np.testing.assert_allclose(o[0, 0], np.broadcast_to(c[0][0], (H, d_c)), rtol=1e-15)
+    np.testing.assert_allclose(lse[0, 0], scale * (qa[0, 0] @ c[0][0] + qr[0, 0] @ k[0][0]), rtol=1e-13)
+    s01 = scale * (qa[0, 1] @ c[0][:2].T + qr[0, 1] @ k[0][:2].T)                     # [H, 2]
+    w = np.exp(s01 - s01.max(1, keepdims=True)); w /= w.sum(1, keepdims=True)
+    np.testing.assert_allclose(o[0, 1], w @ c[0][:2], rtol=1e-13, atol=1e-14)
+    # zero queries: token i averages the first L - (T-1-i) rows, lse = log of that count
+    L = 9
+    c = [f32(r.standard_normal((L, d_c)))]
+    k = [f32(r.standard_normal((L, d_r)))]
+    pool, table, sl = dense_cache(c, k, page_size=4)
+    o, lse = oracle.decode_absorbed_multi(np.zeros((1, T, H, d_c)), np.zeros((1, T, H, d_r)), pool, None, table, sl, scale)
+    for i in range(T):
+        n = L - (T - 1 - i)
+        np.testing.assert_allclose(o[0, i], np.broadcast_to(c[0][:n].mean(0), (H, d_c)), rtol=1e-13, atol=1e-14)
+        np.testing.assert_allclose(lse[0, i], math.log(n), rtol=1e-14)
+    # fewer cached rows than query tokens: the tokens before position 0 see nothing
+    sl2 = np.array([2], dtype=np.int32)
+    o, lse = oracle.decode_absorbed_multi(qa, qr, pool, None, table, sl2, scale)
+    assert (o[0, 0] == 0).all() and np.isneginf(lse[0, 0]).all()
+    np.testing.assert_allclose(o[0, 1], np.broadcast_to(c[0][0], (H, d_c)), rtol=1e-15)
+    assert np.isfinite(lse[0, 1:]).all()
+
+
+def test_M4_later_rows_do_not_reach_an_earlier_token_and_its_own_row_does():
+    T = 3
+    cs = _multi_case(T, (8,), page_size=4, seed=8)
+    _, o, lse, _ = _multi_chain(cs)
+    L = 8
+    for i in range(T):
+        t_i = L - T + i
+        # overwrite every row after t_i: token i must not move by a bit
+        c2 = [cs["c"][0].copy()]; k2 = [cs["k"][0].copy()]
+        c2[0][t_i + 1:] = 1e6; k2[0][t_i + 1:] = -1e6
+        pool2, table2, sl2 = dense_cache(c2, k2, 4, seed=8)
+        cs2 = dict(cs, c=c2, k=k2, pool=pool2, table=table2, sl=sl2)
+        _, o2, lse2, _ = _multi_chain(cs2)
+        assert np.array_equal(o2[0, i], o[0, i]) and np.array_equal(lse2[0, i], lse[0, i])
+        # overwrite its own row: it must move (the limit is inclusive)
+        c3 = [cs["c"][0].copy()]; c3[0][t_i] += 1.0
+        pool3, table3, sl3 = dense_cache(c3, cs["k"], 4, seed=8)
+        _, o3, _, _ = _multi_chain(dict(cs, c=c3, pool=pool3, table=table3, sl=sl3))
+        assert np.abs(o3[0, i] - o[0, i]).max() > 1e-3
