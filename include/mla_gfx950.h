@@ -157,11 +157,12 @@ size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
  *   softmax_scale  the paper uses 1/sqrt(d_head + d_rope) for MLA
  *
  * Supported: io/cache dtype pairs (F32,F32), (BF16,BF16), (BF16,FP8_E4M3),
- * (F32,BF16), (F32,FP8_E4M3); 1 <= H <= 64; d_c a multiple of 8 up to 512;
+ * (F32,BF16), (F32,FP8_E4M3); 1 <= H <= 1024; d_c a multiple of 8 up to 512;
  * d_rope a multiple of 8 in [0, 64]; any page_size >= 1.
- * The matrix-core (MFMA) kernel is used for BF16 io with a BF16 cache,
- * page_size 64, d_rope 64, d_c in {256, 512} and H <= 32; everything else
- * runs on the portable scalar-FMA kernel.
+ * The matrix-core (MFMA) kernel is used for BF16 io with a BF16 or FP8 cache,
+ * page_size 64, d_rope 64 and d_c in {256, 512} (32 heads per workgroup; more
+ * heads go to further workgroups); everything else runs on the portable
+ * scalar-FMA kernel.
  */
 int mla_decode_paged(const void* q_abs, const void* q_rope,
                      const void* kv_cache, const float* kv_scale,
@@ -172,6 +173,39 @@ int mla_decode_paged(const void* q_abs, const void* q_rope,
                      int num_pages, int max_pages_per_seq, int num_splits,
                      float softmax_scale, mla_dtype io_dtype,
                      mla_dtype cache_dtype, unsigned flags, void* hip_stream);
+
+/*
+ * mla_decode_paged for q_len query tokens per sequence in one pass over the
+ * cache (multi-token prediction / speculative decoding, which the paper's
+ * abstract names as a further speed-up of the converted model; the second line
+ * of the absorbed equation in Sec. 3.3 read for the q_len newest positions at
+ * once).  The cache of sequence b already holds the rows of its q_len query
+ * tokens: they are its last q_len rows.  Query token i (0 <= i < q_len) sits
+ * at position seq_lens[b] - q_len + i and, as the sum over j = 1..t of that
+ * equation says, sees the cached rows up to and including its own, i.e. the
+ * first seq_lens[b] - (q_len - 1 - i) rows; a token whose position would be
+ * negative sees nothing (zeros, lse = -inf).
+ *
+ *   q_abs   [B, q_len, heads, d_c]     q_rope [B, q_len, heads, d_rope]
+ *   o_lat   [B, q_len, heads, d_c]     lse    [B, q_len, heads]
+ *   workspace  sized by mla_decode_workspace_bytes(B, q_len * heads, d_c,
+ *              num_splits); the same H = q_len * heads goes to
+ *              mla_merge_partials.  mla_absorb_q and mla_out_proj take the
+ *              query tokens as a batch of B * q_len.
+ * Everything else as for mla_decode_paged, which is this call with q_len 1.
+ * The cached rows are read from HBM once per group of 32 query rows
+ * (q_len * heads / 32 times in all).  q_len * heads <= 1024.
+ */
+int mla_decode_paged_multi(const void* q_abs, const void* q_rope,
+                           const void* kv_cache, const float* kv_scale,
+                           const int32_t* page_table, const int32_t* seq_lens,
+                           void* o_lat, float* lse,
+                           void* workspace, size_t workspace_bytes,
+                           int B, int q_len, int heads, int d_c, int d_rope,
+                           int page_size, int num_pages, int max_pages_per_seq,
+                           int num_splits, float softmax_scale,
+                           mla_dtype io_dtype, mla_dtype cache_dtype,
+                           unsigned flags, void* hip_stream);
 
 /*
  * Split-KV reduction on its own: merges the per-chunk partial results a
@@ -208,6 +242,19 @@ int mla_merge_out_proj(const void* workspace, size_t workspace_bytes,
                        const void* W_UV, void* o_lat, float* lse, void* out,
                        int B, int H, int d_c, int d_head, int num_splits,
                        mla_dtype io_dtype, unsigned flags, void* hip_stream);
+
+/*
+ * mla_merge_out_proj after mla_decode_paged_multi(..., MLA_FLAG_SKIP_MERGE)
+ * with the same B, q_len, heads, d_c, num_splits and workspace:
+ *   o_lat [B, q_len, heads, d_c], lse [B, q_len, heads] (may be NULL),
+ *   out   [B, q_len, heads, d_head];  W_UV [heads, d_c, d_head].
+ * mla_merge_out_proj is this call with q_len 1.
+ */
+int mla_merge_out_proj_multi(const void* workspace, size_t workspace_bytes,
+                             const void* W_UV, void* o_lat, float* lse, void* out,
+                             int B, int q_len, int heads, int d_c, int d_head,
+                             int num_splits, mla_dtype io_dtype, unsigned flags,
+                             void* hip_stream);
 
 /*
  * Bytes of device workspace mla_cache_append needs (fp32 partial rows of the

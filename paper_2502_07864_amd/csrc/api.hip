@@ -106,21 +106,36 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
                      int num_splits, float softmax_scale, mla_dtype io_dtype, mla_dtype cache_dtype,
                      unsigned flags, void* hip_stream)
 {
+    return mla_decode_paged_multi(q_abs, q_rope, kv_cache, kv_scale, page_table, seq_lens, o_lat, lse,
+                                  workspace, workspace_bytes, B, 1, H, d_c, d_rope, page_size, num_pages,
+                                  max_pages_per_seq, num_splits, softmax_scale, io_dtype, cache_dtype,
+                                  flags, hip_stream);
+}
+
+int mla_decode_paged_multi(const void* q_abs, const void* q_rope, const void* kv_cache,
+                           const float* kv_scale, const int32_t* page_table, const int32_t* seq_lens,
+                           void* o_lat, float* lse, void* workspace, size_t workspace_bytes, int B,
+                           int q_len, int heads, int d_c, int d_rope, int page_size, int num_pages,
+                           int max_pages_per_seq, int num_splits, float softmax_scale,
+                           mla_dtype io_dtype, mla_dtype cache_dtype, unsigned flags, void* hip_stream)
+{
     const bool skip_merge = (flags & MLA_FLAG_SKIP_MERGE) != 0;
     if (!q_abs || !kv_cache || !page_table || !seq_lens || (!o_lat && !skip_merge)) return MLA_ERR_NULL;
     if (d_rope > 0 && !q_rope) return MLA_ERR_NULL;
-    if (B <= 0 || H <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
+    if (B <= 0 || q_len <= 0 || heads <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
         max_pages_per_seq <= 0 || num_splits <= 0)
         return MLA_ERR_SHAPE;
     if ((long long)max_pages_per_seq * page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
     if (!(softmax_scale == softmax_scale)) return MLA_ERR_SHAPE;
+    if ((long long)q_len * heads > 1024) return MLA_ERR_UNSUPPORTED;
+    const int H = q_len * heads;   // query rows per sequence
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
     if (cache_dtype != MLA_F32 && cache_dtype != MLA_BF16 && cache_dtype != MLA_FP8_E4M3)
         return MLA_ERR_UNSUPPORTED;
     if (cache_dtype == MLA_F32 && io_dtype != MLA_F32) return MLA_ERR_UNSUPPORTED;
     if (cache_dtype == MLA_FP8_E4M3 && !kv_scale) return MLA_ERR_NULL;
     if (cache_dtype != MLA_FP8_E4M3 && kv_scale) return MLA_ERR_SHAPE;
-    if (H > 64 || d_c > 512 || d_c % 8 || d_rope > 64 || d_rope % 8) return MLA_ERR_UNSUPPORTED;
+    if (d_c > 512 || d_c % 8 || d_rope > 64 || d_rope % 8) return MLA_ERR_UNSUPPORTED;
     if (B > 65535 || num_splits > 16383) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -138,6 +153,7 @@ int mla_decode_paged(const void* q_abs, const void* q_rope, const void* kv_cache
     p.B = B; p.H = H; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
     p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = S;
     p.chunk_pages = (max_pages_per_seq + S - 1) / S;
+    p.q_len = q_len; p.heads = heads;
     p.scale = softmax_scale;
 
     const bool balanced = (flags & MLA_FLAG_BALANCED) != 0;
@@ -180,23 +196,40 @@ int mla_merge_out_proj(const void* workspace, size_t workspace_bytes, const void
                        float* lse, void* out, int B, int H, int d_c, int d_head, int num_splits,
                        mla_dtype io_dtype, unsigned flags, void* hip_stream)
 {
+    return mla_merge_out_proj_multi(workspace, workspace_bytes, W_UV, o_lat, lse, out, B, 1, H, d_c, d_head,
+                                    num_splits, io_dtype, flags, hip_stream);
+}
+
+int mla_merge_out_proj_multi(const void* workspace, size_t workspace_bytes, const void* W_UV, void* o_lat,
+                             float* lse, void* out, int B, int q_len, int heads, int d_c, int d_head,
+                             int num_splits, mla_dtype io_dtype, unsigned flags, void* hip_stream)
+{
     if (!o_lat || !W_UV || !out) return MLA_ERR_NULL;
-    if (B <= 0 || H <= 0 || d_c <= 0 || d_head <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
+    if (B <= 0 || q_len <= 0 || heads <= 0 || d_c <= 0 || d_head <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
-    if (H > 65535 || B > 65535 || d_c % 4 || d_c > 2048) return MLA_ERR_UNSUPPORTED;
-    const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
+    if ((long long)q_len * heads > 65535 || (long long)B * q_len > 65535 || d_c % 4 || d_c > 2048)
+        return MLA_ERR_UNSUPPORTED;
+    const size_t need = mla_decode_workspace_bytes(B, q_len * heads, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool balanced = (flags & MLA_FLAG_BALANCED) != 0;
+    const int S = effective_splits(B, num_splits);
+    // The partials of (sequence b, query token i, head h) lie where those of sequence b * q_len + i,
+    // head h of a batch of B * q_len one-token sequences would: the merge and the projection see
+    // that batch.  Only the balanced partition's plan is per sequence; with it and q_len > 1 the
+    // merge runs over the q_len * heads rows of each sequence and the projection follows it.
     MergeParams m;
-    fill_merge_params(m, workspace, B, H, d_c, effective_splits(B, num_splits), (flags & MLA_FLAG_BALANCED) != 0);
+    fill_merge_params(m, workspace, B, q_len * heads, d_c, S, balanced);
     m.o_lat = o_lat; m.lse = lse;
+    if (!(balanced && q_len > 1)) { m.B = B * q_len; m.H = heads; }
     hipError_t e;
-    if (merge_out_proj_supported(m, d_head, io_dtype)) {
+    if (m.H == heads && merge_out_proj_supported(m, d_head, io_dtype)) {
         e = launch_merge_out_proj(m, W_UV, out, stream);
     } else {
         e = launch_merge(m, io_dtype, stream);
-        if (e == hipSuccess) e = launch_head_gemm(o_lat, W_UV, out, B, H, d_c, d_head, io_dtype, stream);
+        if (e == hipSuccess)
+            e = launch_head_gemm(o_lat, W_UV, out, B * q_len, heads, d_c, d_head, io_dtype, stream);
     }
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }

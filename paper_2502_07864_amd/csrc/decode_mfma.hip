@@ -125,6 +125,9 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // One segment = cached rows [row0, row1) of sequence b, reduced to one partial result.
     // BAL = false: the rows are those of chunk `split` of the sequence (seg_row0/1 unused) and the
     // result goes to partial (b, split); BAL = true: the caller gives the rows and the partial slot.
+    // Query rows beyond 32 (several query tokens per sequence, or more than 32 heads) go to
+    // further workgroups: this one takes rows [hb, hb + 32) of every sequence.
+    const int hb = (BAL ? blockIdx.y : blockIdx.z) * 32;
     auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
                            const size_t out_slot) {
     // Balanced partition: the body runs in a loop.  Everything derived from the thread index is
@@ -137,7 +140,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hg = wave & 1, tg = wave >> 1;
     const int n = lane & 15, g = lane >> 4;
-    // where head h's partial row and log-sum-exp go
+    const int HL = min(32, p.H - hb);          // query rows of this workgroup
+    // where query row h's (h counted over the whole sequence) partial row and log-sum-exp go
     auto o_row = [&](int h) -> float* {
         return p.o_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
     };
@@ -164,14 +168,14 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     LDS_AS unsigned char* qslot = lds + (NBUF - 1) * TILE_B;
     if constexpr (!FP8) {
-        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + (size_t)b * p.H * D_C * 2;
-        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + (size_t)b * p.H * 128;
+        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
+        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
         const uint32_t dst = lds_base + (uint32_t)((NBUF - 1) * TILE_B + wave * 1024);
 #pragma unroll
         for (int k = 0; k < NLOAD; ++k) {
             const int P = (k * 4 + wave) * 64 + lane;
             const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
-            if (r < p.H) {
+            if (r < HL) {
                 const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
                                                       : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
                 const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;             // first cached row of this segment
     const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);  // one past its last row
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < p.H) *lse_at(tid) = -INFINITY;
+        if (tid < HL) *lse_at(hb + tid) = -INFINITY;
         wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
@@ -198,12 +202,12 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int head = hg * 16 + n;
     bf16x8 qreg[NKS];
     if constexpr (FP8) {
-        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + head) * D_C;
-        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + head) * 64;
+        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + hb + head) * D_C;
+        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + hb + head) * 64;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (head < p.H) {
+            if (head < HL) {
                 const uint16_t* src = ks < D_C / 32 ? qa + ks * 32 + g * 8 : qr + (ks - D_C / 32) * 32 + g * 8;
                 v = *reinterpret_cast<const uint4*>(src);
             }
@@ -415,7 +419,9 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // -inf; returns the maximum over the wave's rows of this lane's head.  Operand reads run
     // one group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler from
     // sinking the reads back next to their uses.
-    auto score_tile = [&](LDS_AS unsigned char* tile, int slot, int n_valid, float (&x)[4], float (&rs)[4]) -> float {
+    // first cached row (of the sequence) that some query row of the sequence must not see
+    const int causal_from = L - (p.q_len - 1);
+    auto score_tile = [&](LDS_AS unsigned char* tile, int slot, int t, int n_valid, float (&x)[4], float (&rs)[4]) -> float {
         f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
         bf16x8 a0[NKS];
 #pragma unroll
@@ -438,10 +444,13 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
             rs[i] = FP8 ? scale_lds[slot][tg * 16 + g * 4 + i] : 1.f;   // per-row dequantisation scale
             x[i] = sacc[i] * (FP8 ? sc * rs[i] : sc);
         }
-        if (n_valid < TILE_ROWS) {
+        if (n_valid < TILE_ROWS || (t + 1) * TILE_ROWS > causal_from) {
+            // ragged last tile, and the upper limit of this lane's query row (Eq. "mqa": the sum
+            // runs up to the query token's own position)
+            const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TILE_ROWS);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (tg * 16 + g * 4 + i >= n_valid) x[i] = -INFINITY;
+                if (tg * 16 + g * 4 + i >= seen) x[i] = -INFINITY;
         }
         float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
@@ -533,7 +542,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         const int page_t2 = page_ahead(t);
         const int n_valid = stage_tile(t, tile);
         float x[4], rs[4];
-        const float tmax = score_tile(tile, slot, n_valid, x, rs);
+        const float tmax = score_tile(tile, slot, t, n_valid, x, rs);
         if (m_run == -INFINITY) m_run = tmax;
         jumped |= tmax > m_run + FAST_GAP;
         accumulate_tile(tile, x, rs);
@@ -569,7 +578,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
                 if (!staged) n_valid = stage_tile(t, tile);
                 staged = false;
                 float x[4], rs[4];
-                const float tmax = score_tile(tile, slot, n_valid, x, rs);
+                const float tmax = score_tile(tile, slot, t, n_valid, x, rs);
                 if (m_run == -INFINITY) m_run = tmax;     // nothing accumulated yet: nothing to rescale
                 if (__any(tmax > m_run + RESCALE_GAP)) {
                     const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
@@ -636,7 +645,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     };
     if (tg == 0) finish_half(std::integral_constant<int, 0>{});
     else         finish_half(std::integral_constant<int, HCT>{});
-    const int nrow = min(16, p.H - hg * 16);
+    const int nrow = min(16, HL - hg * 16);
     constexpr int LPR = HCT * 4;             // lanes (of 16 bytes) covering one row of the half
     constexpr int RPI = 64 / LPR;            // rows one store instruction covers (1 or 2)
     static_assert(LPR == 64 || LPR == 32, "half a latent row is 1 KB or 512 B");
@@ -645,12 +654,12 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
             f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = o_row(hg * 16 + r) + tg * (HCT * 16) + c * 4;
+            float* dst = o_row(hb + hg * 16 + r) + tg * (HCT * 16) + c * 4;
             __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
         }
     }
-    if (tg == 0 && head < p.H && g == 0)
-        *lse_at(head) = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+    if (tg == 0 && head < HL && g == 0)
+        *lse_at(hb + head) = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
     };  // run_segment
 
     if constexpr (!BAL) {
@@ -739,7 +748,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 bool decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache)
 {
     return io == MLA_BF16 && (cache == MLA_BF16 || cache == MLA_FP8_E4M3) && p.page_size == 64 &&
-           p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && p.H <= 32;
+           p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && (p.H + 31) / 32 <= 65535;
 }
 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced)
@@ -748,7 +757,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     dim3 block(MF_THREADS);
     if (balanced) {
         if (!p.plan) return hipErrorInvalidValue;
-        dim3 grid((unsigned)p.B * (unsigned)p.num_splits);   // workgroups = sequences x chunks per sequence
+        // workgroups = sequences x chunks per sequence (x groups of 32 query rows)
+        dim3 grid((unsigned)p.B * (unsigned)p.num_splits, (unsigned)(p.H + 31) / 32);
         if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, true><<<grid, block, 0, s>>>(p);
         else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, true><<<grid, block, 0, s>>>(p);
         else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, true><<<grid, block, 0, s>>>(p);
@@ -756,7 +766,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
-    dim3 grid(p.B, p.num_splits);
+    dim3 grid(p.B, p.num_splits, (p.H + 31) / 32);
     if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, false><<<grid, block, 0, s>>>(p);
     else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, false><<<grid, block, 0, s>>>(p);
     else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, false><<<grid, block, 0, s>>>(p);

@@ -142,7 +142,9 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
             float dot = 0.f;
             for (int k = kb; k < ke; ++k) dot = fmaf(q_s[h][k], k_s[t][k], dot);
             dot += __shfl_xor(dot, 1);
-            if (half == 0) s_s[h][t] = valid_s[t] ? dot * p.scale : -INFINITY;
+            // the query row's own upper limit of the sum (several query tokens per sequence)
+            const bool seen = valid_s[t] && t0 + t < visible_rows(p, L, h0 + h);
+            if (half == 0) s_s[h][t] = seen ? dot * p.scale : -INFINITY;
         }
         __syncthreads();
         // ---- running softmax, one thread per head

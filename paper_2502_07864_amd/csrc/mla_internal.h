@@ -9,6 +9,10 @@
 namespace mla {
 
 // Everything a decode kernel needs; passed by value as the kernel argument.
+// Several query tokens per sequence (q_len > 1) are handled as more query rows: H counts the rows
+// of one sequence, token-major (row = token * heads + head), and the row of query token i sees
+// the cached rows below seq_len - (q_len - 1 - i) only (Eq. "mqa": the sum runs up to the query's
+// own position).
 struct DecodeParams {
     const void* q_abs;          // [B,H,d_c]      io dtype
     const void* q_rope;         // [B,H,d_rope]   io dtype
@@ -21,8 +25,15 @@ struct DecodeParams {
     int32_t* plan;              // balanced partition only: [B, 2] first partial slot and count per
                                 // sequence (the partials are then [slot, H, d_c] / [slot, H])
     int B, H, d_c, d_rope, page_size, num_pages, max_pages, num_splits, chunk_pages;
+    int q_len, heads;           // H = q_len * heads
     float scale;
 };
+
+// cached rows of a sequence of L rows that query row h may see
+__host__ __device__ __forceinline__ int visible_rows(const DecodeParams& p, int L, int h)
+{
+    return L - (p.q_len - 1 - h / p.heads);
+}
 
 struct MergeParams {
     const float* o_part;

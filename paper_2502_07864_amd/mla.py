@@ -22,7 +22,8 @@ FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE, FLAG_BALANCED = 0, 1, 2, 4
 
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
-           "mla_merge_out_proj", "mla_gather_paged")
+           "mla_merge_out_proj", "mla_gather_paged", "mla_append_workspace_bytes", "mla_cache_append",
+           "mla_decode_paged_multi", "mla_merge_out_proj_multi")
 
 
 class MlaError(RuntimeError):
@@ -53,6 +54,11 @@ def lib() -> ctypes.CDLL:
         L.mla_decode_paged.restype = i
         L.mla_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        i, i, i, i, i, i, i, i, f, i, i, u, vp]
+        L.mla_decode_paged_multi.restype = i
+        L.mla_decode_paged_multi.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
+                                             i, i, i, i, i, i, i, i, i, f, i, i, u, vp]
+        L.mla_merge_out_proj_multi.restype = i
+        L.mla_merge_out_proj_multi.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, i, u, vp]
         L.mla_merge_partials.restype = i
         L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, u, vp]
         L.mla_merge_out_proj.restype = i
@@ -182,6 +188,68 @@ def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: 
     if skip_merge:
         return workspace
     return (out, lse) if lse is not None else out
+
+
+def decode_paged_multi(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: torch.Tensor,
+                       page_table: torch.Tensor, seq_lens: torch.Tensor, softmax_scale: float,
+                       num_splits: int = 1, kv_scale: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                       lse: Optional[torch.Tensor] = None, return_lse: bool = False, flags: int = 0):
+    """Paged absorbed decode of q_len query tokens per sequence in one pass over the cache.
+    q_abs [B,q_len,H,d_c], q_rope [B,q_len,H,d_rope]; the cache already holds the query tokens'
+    own rows (the last q_len of each sequence) and token i sees rows < seq_len - (q_len-1-i).
+    Returns o_lat [B,q_len,H,d_c] (and lse [B,q_len,H] fp32 if return_lse or lse given)."""
+    B, T, H, d_c = q_abs.shape
+    num_pages, page_size, row = kv_cache.shape
+    d_rope = row - d_c
+    if d_rope < 0:
+        raise ValueError("cache rows are shorter than d_c")
+    if d_rope and (q_rope is None or tuple(q_rope.shape) != (B, T, H, d_rope) or q_rope.dtype != q_abs.dtype):
+        raise ValueError("q_rope must be [B, q_len, H, d_rope] of q_abs's dtype")
+    if page_table.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise TypeError("page_table and seq_lens must be int32")
+    if page_table.dim() != 2 or page_table.shape[0] != B or seq_lens.shape != (B,):
+        raise ValueError("page_table must be [B, max_pages_per_seq], seq_lens [B]")
+    if kv_scale is not None and (kv_scale.dtype != torch.float32 or tuple(kv_scale.shape) != (num_pages, page_size)):
+        raise ValueError("kv_scale must be float32 [num_pages, page_size]")
+    need = decode_workspace_bytes(B, T * H, d_c, num_splits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_abs.device)
+    skip_merge = bool(flags & FLAG_SKIP_MERGE)
+    if out is None and not skip_merge:
+        out = torch.empty((B, T, H, d_c), dtype=q_abs.dtype, device=q_abs.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, T, H), dtype=torch.float32, device=q_abs.device)
+    _check(lib().mla_decode_paged_multi(
+        _dev(q_abs, "q_abs"), _dev(q_rope, "q_rope"), _dev(kv_cache, "kv_cache"),
+        _dev(kv_scale, "kv_scale"), _dev(page_table, "page_table"), _dev(seq_lens, "seq_lens"),
+        _dev(out, "out"), _dev(lse, "lse"), _dev(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), B, T, H, d_c, d_rope, page_size, num_pages,
+        page_table.shape[1], num_splits, float(softmax_scale), _io_code(q_abs),
+        _cache_code(kv_cache), int(flags), _stream(q_abs)), "mla_decode_paged_multi")
+    if skip_merge:
+        return workspace
+    return (out, lse) if lse is not None else out
+
+
+def merge_out_proj_multi(workspace: torch.Tensor, W_UV: torch.Tensor, B: int, q_len: int, num_splits: int,
+                         o_lat: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                         lse: Optional[torch.Tensor] = None, return_lse: bool = False, flags: int = 0):
+    """merge_out_proj after decode_paged_multi(flags=FLAG_SKIP_MERGE).
+    Returns (o_lat [B,q_len,H,d_c], out [B,q_len,H,d_head][, lse [B,q_len,H]])."""
+    H, d_c, d_head = W_UV.shape
+    if o_lat is None:
+        o_lat = torch.empty((B, q_len, H, d_c), dtype=W_UV.dtype, device=W_UV.device)
+    if out is None:
+        out = torch.empty((B, q_len, H, d_head), dtype=W_UV.dtype, device=W_UV.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, q_len, H), dtype=torch.float32, device=W_UV.device)
+    _check(lib().mla_merge_out_proj_multi(_dev(workspace, "workspace"),
+                                          workspace.numel() * workspace.element_size(), _dev(W_UV, "W_UV"),
+                                          _dev(o_lat, "o_lat"), _dev(lse, "lse"), _dev(out, "out"), B, q_len, H,
+                                          d_c, d_head, num_splits, _io_code(W_UV), int(flags),
+                                          _stream(workspace)), "mla_merge_out_proj_multi")
+    return (o_lat, out, lse) if lse is not None else (o_lat, out)
 
 
 def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits: int,

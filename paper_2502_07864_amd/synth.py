@@ -267,6 +267,23 @@ def make_workload(name: str, *, B: int, H: int, d_head: int, d_c: int, d_rope: i
               "k_rope_gain": k_rope_gain})
 
 
+def multi_queries(w: Workload, q_len: int, seed: Optional[int] = None, rope_base: float = 10000.0):
+    """Queries of the q_len newest tokens of every sequence of `w` (multi-token prediction /
+    speculative decoding): the cache of `w` is taken to hold those tokens' rows already, token i
+    sits at position seq_len - q_len + i and its decoupled part is rotated there.
+
+    Returns (q_nope [B, q_len, H, d_head], q_rope [B, q_len, H, d_rope]) in w's io storage dtype."""
+    seed = w.meta.get("seed", 0) if seed is None else seed
+    q_nope = normal(stream(seed, 21), (w.B, q_len, w.H, w.d_head))
+    q_rope = normal(stream(seed, 22), (w.B, q_len, w.H, w.d_rope))
+    if w.d_rope:
+        pos = w.seq_lens.astype(np.int64)[:, None] - q_len + np.arange(q_len)[None, :]      # [B, q_len]
+        pos = np.maximum(pos, 0).reshape(-1)
+        flat = q_rope.reshape(w.B * q_len, w.H, w.d_rope).transpose(1, 0, 2)                 # [H, B*q_len, d]
+        q_rope = rope(flat, pos, rope_base).transpose(1, 0, 2).reshape(w.B, q_len, w.H, w.d_rope)
+    return store(q_nope, w.io_dtype), store(np.ascontiguousarray(q_rope), w.io_dtype)
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations (and scaled-down versions of them)
 # --------------------------------------------------------------------------

@@ -29,6 +29,8 @@ def lib():
     L.mla_decode_workspace_bytes.restype = ctypes.c_size_t
     L.mla_decode_workspace_bytes.argtypes = [i, i, i, i]
     L.mla_decode_paged.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 8 + [f, i, i, u, vp]
+    L.mla_decode_paged_multi.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, u, vp]
+    L.mla_merge_out_proj_multi.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp] + [i] * 7 + [u, vp]
     L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
     L.mla_append_workspace_bytes.restype = ctypes.c_size_t
     L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -107,12 +109,39 @@ def decode_args(**kw):
     (dict(splits=0), E_SHAPE), (dict(scale=float("nan")), E_SHAPE),
     (dict(max_pages=1 << 30, page=64), E_SHAPE),
     (dict(io=FP8), E_UNSUP), (dict(cache=5), E_UNSUP), (dict(io=BF16, cache=F32), E_UNSUP),
-    (dict(H=65), E_UNSUP), (dict(d_c=520), E_UNSUP), (dict(d_c=12), E_UNSUP),
+    (dict(H=1025), E_UNSUP), (dict(d_c=520), E_UNSUP), (dict(d_c=12), E_UNSUP),
     (dict(d_rope=72), E_UNSUP), (dict(d_rope=4), E_UNSUP), (dict(B=70000), E_UNSUP),
     (dict(ws=None), E_WS), (dict(ws_bytes=1024), E_WS), (dict(ws=P + 8), E_WS),
 ])
 def test_decode_validation(lib, kw, want):
     assert lib.mla_decode_paged(*decode_args(**kw)) == want
+
+
+@pytest.mark.parametrize("kw,q_len,want", [
+    (dict(), 0, E_SHAPE), (dict(), -2, E_SHAPE), (dict(H=0), 2, E_SHAPE),
+    (dict(H=32), 33, E_UNSUP), (dict(H=128), 9, E_UNSUP),       # more than 1024 query rows per sequence
+    (dict(q_abs=None), 2, E_NULL), (dict(lens=None), 4, E_NULL),
+    (dict(ws_bytes=2 * 3 * 32 * 513 * 4), 2, E_WS),             # sized for one query token only
+    (dict(d_c=12), 2, E_UNSUP),
+])
+def test_multi_token_decode_validation(lib, kw, q_len, want):
+    a = decode_args(**kw)
+    a.insert(11, q_len)          # ..., B, q_len, heads, ...
+    assert lib.mla_decode_paged_multi(*a) == want
+
+
+def test_multi_token_tail_validation(lib):
+    f = lib.mla_merge_out_proj_multi
+    def call(**kw):
+        d = dict(ws=P, ws_bytes=1 << 30, W=P, o=P, lse=None, out=P, B=2, q_len=2, H=32, d_c=512, d_head=128,
+                 splits=2, io=BF16, flags=0, stream=None)
+        d.update(kw)
+        return f(*[d[k] for k in ("ws", "ws_bytes", "W", "o", "lse", "out", "B", "q_len", "H", "d_c", "d_head",
+                                  "splits", "io", "flags", "stream")])
+    assert call(W=None) == E_NULL and call(o=None) == E_NULL and call(out=None) == E_NULL
+    assert call(q_len=0) == E_SHAPE and call(B=0) == E_SHAPE and call(d_head=0) == E_SHAPE
+    assert call(io=FP8) == E_UNSUP and call(d_c=6) == E_UNSUP and call(B=40000, q_len=2) == E_UNSUP
+    assert call(ws=None) == E_WS and call(ws_bytes=4096) == E_WS
 
 
 def test_gather_validation(lib):

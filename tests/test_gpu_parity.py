@@ -703,3 +703,101 @@ def test_random_shapes_partitions_and_caches(mla):
             check_decode(mla, w, S, flags=flags)
         except AssertionError as e:
             raise AssertionError(f"case {case}: B={B} H={H} d_c={d_c} lens={lens} cache={cache} S={S} flags={flags}: {e}")
+
+
+# ----------------------------------------------- several query tokens per sequence
+
+def check_multi(mla, w, T, num_splits, flags=0, tol=None, fused_tail=False):
+    """q_len = T query tokens per sequence against the oracle's Eq. "mqa" with one upper limit of
+    the sum per token; returns what the GPU produced."""
+    import torch
+    d = DeviceWorkload(w)
+    qn, qr = synth.multi_queries(w, T)
+    qn_t, qr_t = to_torch(qn, w.io_dtype), to_torch(qr, w.io_dtype)
+    q_abs = mla.absorb_q(qn_t.view(w.B * T, w.H, w.d_head), d.W_UK).view(w.B, T, w.H, w.d_c)
+    out = None
+    if fused_tail:
+        ws = mla.decode_paged_multi(q_abs, qr_t, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                    num_splits=num_splits, kv_scale=d.kv_scale, flags=flags | mla.FLAG_SKIP_MERGE)
+        o, out, lse = mla.merge_out_proj_multi(ws, d.W_UV, w.B, T, num_splits, return_lse=True, flags=flags)
+    else:
+        o, lse = mla.decode_paged_multi(q_abs, qr_t, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                        num_splits=num_splits, kv_scale=d.kv_scale, return_lse=True, flags=flags)
+    torch.cuda.synchronize()
+    ref_o, ref_lse = oracle.decode_absorbed_multi(q_abs_storage(q_abs), qr, w.pool, w.kv_scale, w.page_table,
+                                                  w.seq_lens, w.softmax_scale)
+    got_o, got_lse = widen_gpu(o), widen_gpu(lse)
+    assert got_o.shape == ref_o.shape and np.isfinite(got_o).all()
+    tol = tol or TOL[w.io_dtype]
+    err = max_abs_rel(got_o, ref_o)
+    assert err <= tol, f"{w.name} q_len={T} splits={num_splits} flags={flags}: o_lat err {err:.3e} > {tol}"
+    assert lse_err(got_lse, ref_lse) <= (1e-4 if w.io_dtype == "f32" else 2e-2)
+    if out is not None:
+        ref_out = oracle.out_proj(q_abs_storage(o).reshape(w.B * T, w.H, w.d_c), w.W_UV).reshape(w.B, T, w.H, w.d_head)
+        assert max_abs_rel(widen_gpu(out), ref_out) <= tol
+    return o, lse
+
+
+@pytest.mark.parametrize("T", [2, 3])
+def test_multi_token_fp32_portable(mla, T):
+    """fp32 cache and io (portable kernel), C1 shape and a ragged batch."""
+    check_multi(mla, synth.config("C1"), T, 4)
+    check_multi(mla, ragged_workload(cache="f32", io="f32", lens=[130, 64, 7, 1, 65], seed=31), T, 3)
+
+
+@pytest.mark.parametrize("T,flags", [(2, 0), (3, 0), (4, 0), (2, 1), (3, BAL)])
+def test_multi_token_bf16_ragged(mla, T, flags):
+    """Matrix-core kernel (64, 96, 128 query rows: 2 to 4 groups of 32), portable kernel and the
+    balanced partition on lengths around the tile, page and chunk boundaries: the newest T rows
+    straddle them, so the per-token limits fall in different tiles, pages and chunks."""
+    w = ragged_workload(lens=[64 * 3 + 1, 64 * 2 + 33, 32, 129, 64, 2, 1000, 31], seed=32)
+    check_multi(mla, w, T, 4, flags)
+    check_multi(mla, w, T, 1, flags)
+    check_multi(mla, w, T, 16, flags)
+
+
+def test_multi_token_few_heads_share_a_group(mla):
+    """5 heads x 3 tokens = 15 rows and 8 heads x 4 tokens = 32 rows in one group of 32: lanes of
+    one wavefront belong to different query tokens."""
+    check_multi(mla, ragged_workload(H=5, lens=[200, 66, 3, 64], seed=33), 3, 2)
+    check_multi(mla, ragged_workload(H=8, lens=[200, 66, 3, 64], seed=34), 4, 3)
+    check_multi(mla, ragged_workload(H=28, d_c=256, lens=[500, 65, 4096 // 4], seed=35), 2, 2)     # 56 rows: 32 + 24
+
+
+def test_multi_token_fewer_rows_than_tokens_and_empty(mla):
+    """seq_len < q_len: the tokens before position 0 see nothing (zeros, -inf); seq_len 0."""
+    w = ragged_workload(lens=[2, 0, 3, 70], seed=36)
+    o, lse = check_multi(mla, w, 4, 2)
+    o, lse = widen_gpu(o), widen_gpu(lse)
+    assert not o[0, :2].any() and np.isneginf(lse[0, :2]).all() and np.isfinite(lse[0, 2:]).all()
+    assert not o[1].any() and np.isneginf(lse[1]).all()
+    assert np.isneginf(lse[2, 0]).all() and np.isfinite(lse[2, 1:]).all()
+    check_multi(mla, w, 4, 2, flags=1)
+
+
+def test_multi_token_fp8_cache_and_fused_tail(mla):
+    check_multi(mla, synth.config("C5", shrink=64), 2, 8)
+    check_multi(mla, synth.config("C5", shrink=64), 2, 8, flags=1)
+    w = synth.config("C2", shrink=8)
+    check_multi(mla, w, 2, 4, fused_tail=True)                 # one kernel for merge + W_UV
+    check_multi(mla, w, 3, 4, flags=BAL, fused_tail=True)      # balanced: merge, then the projection
+    check_multi(mla, ragged_workload(cache="f32", io="f32", lens=[130, 7], seed=37), 2, 2, fused_tail=True)
+
+
+def test_multi_token_last_token_is_the_single_token_decode(mla):
+    """Token q_len - 1 sees the whole sequence: its result must equal the one-token call on the
+    same query bit for bit (same kernel, same chunks, same order of operations)."""
+    import torch
+    w = ragged_workload(lens=[300, 64, 129], seed=38)
+    T = 2
+    d = DeviceWorkload(w)
+    qn, qr = synth.multi_queries(w, T)
+    qn_t, qr_t = to_torch(qn, "bf16"), to_torch(qr, "bf16")
+    q_abs = mla.absorb_q(qn_t.view(w.B * T, w.H, w.d_head), d.W_UK).view(w.B, T, w.H, w.d_c)
+    o, lse = mla.decode_paged_multi(q_abs, qr_t, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                    num_splits=4, return_lse=True)
+    o1, lse1 = mla.decode_paged(q_abs[:, T - 1].contiguous(), qr_t[:, T - 1].contiguous(), d.pool, d.page_table,
+                                d.seq_lens, w.softmax_scale, num_splits=4, return_lse=True)
+    torch.cuda.synchronize()
+    assert storage_bits(o[:, T - 1]).tobytes() == storage_bits(o1).tobytes()
+    assert storage_bits(lse[:, T - 1]).tobytes() == storage_bits(lse1).tobytes()
