@@ -65,6 +65,10 @@ def parse():
                     help="uniform: equal chunks per sequence; balanced (MLA_FLAG_BALANCED): equal page ranges "
                          "per workgroup over the concatenated sequences, --splits workgroups per sequence on "
                          "average; auto: balanced with 4 per sequence for the ragged batch C3, uniform otherwise")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence and step (multi-token prediction / speculative decoding); "
+                         "above 1 the step uses mla_decode_paged_multi and mla_merge_out_proj_multi and is a "
+                         "secondary row, not the headline metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
     ap.add_argument("--calib-copy", action="store_true",
@@ -113,27 +117,51 @@ def main():
             shifted = torch.where(d.page_table >= 0, (d.page_table + shift) % w.num_pages, d.page_table)
             tables.append(shifted.to(torch.int32).contiguous())
             scales.append(None if d.kv_scale is None else torch.roll(d.kv_scale, shifts=shift, dims=0).contiguous())
-    ws = torch.empty(mla.decode_workspace_bytes(B, H, d_c, S), dtype=torch.uint8, device="cuda:0")
-    q_abs = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
-    o_lat = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
-    out = torch.empty((B, H, w.d_head), dtype=io_t, device="cuda:0")
-
+    T = args.q_len
+    assert T >= 1
+    ws = torch.empty(mla.decode_workspace_bytes(B, T * H, d_c, S), dtype=torch.uint8, device="cuda:0")
     bal = mla.FLAG_BALANCED if args.balanced else 0
+    if T == 1:
+        q_abs = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
+        o_lat = torch.empty((B, H, d_c), dtype=io_t, device="cuda:0")
+        out = torch.empty((B, H, w.d_head), dtype=io_t, device="cuda:0")
+        q_nope, q_rope = d.q_nope, d.q_rope
+        absorb = lambda: mla.absorb_q(q_nope, d.W_UK, out=q_abs)
+        decode = mla.decode_paged
+        def tail():
+            if args.unfused_tail:
+                mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat, flags=bal)
+                mla.out_proj(o_lat, d.W_UV, out=out)
+            else:
+                mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out, flags=bal)
+    else:
+        # the q_len newest tokens of every sequence query the cache at once; their own rows are
+        # the last q_len rows the cache already holds
+        from helpers import to_torch
+        qn, qr = synth.multi_queries(w, T)
+        q_nope, q_rope = to_torch(qn, w.io_dtype, "cuda:0"), to_torch(qr, w.io_dtype, "cuda:0")
+        q_abs = torch.empty((B, T, H, d_c), dtype=io_t, device="cuda:0")
+        o_lat = torch.empty((B, T, H, d_c), dtype=io_t, device="cuda:0")
+        out = torch.empty((B, T, H, w.d_head), dtype=io_t, device="cuda:0")
+        absorb = lambda: mla.absorb_q(q_nope.view(B * T, H, w.d_head), d.W_UK, out=q_abs.view(B * T, H, d_c))
+        decode = mla.decode_paged_multi
+        def tail():
+            if args.unfused_tail:
+                mla.merge_partials(ws, B, T * H, d_c, S, io_t, out=o_lat.view(B, T * H, d_c), flags=bal)
+                mla.out_proj(o_lat.view(B * T, H, d_c), d.W_UV, out=out.view(B * T, H, w.d_head))
+            else:
+                mla.merge_out_proj_multi(ws, d.W_UV, B, T, S, o_lat=o_lat, out=out, flags=bal)
 
     def step(i, events=None):
         k = i % len(pools)
-        mla.absorb_q(d.q_nope, d.W_UK, out=q_abs)
+        absorb()
         if events is not None:
             events[0].record()
-        mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
+        decode(q_abs, q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
+               num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
         if events is not None:
             events[1].record()
-        if args.unfused_tail:
-            mla.merge_partials(ws, B, H, d_c, S, io_t, out=o_lat, flags=bal)
-            mla.out_proj(o_lat, d.W_UV, out=out)
-        else:
-            mla.merge_out_proj(ws, d.W_UV, B, S, o_lat=o_lat, out=out, flags=bal)
+        tail()
         if events is not None:
             events[2].record()
 
@@ -167,8 +195,8 @@ def main():
     # roofline uses (it is the figure a kernel trace reports as the kernel's average duration).
     def decode_only(i):
         k = i % len(pools)
-        mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
+        decode(q_abs, q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
+               num_splits=S, kv_scale=scales[k], workspace=ws, flags=mla.FLAG_SKIP_MERGE | bal)
     for i in range(min(args.warmup, 10)):
         decode_only(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -182,8 +210,8 @@ def main():
     # fourth pass: the whole mla_decode_paged call (split-KV kernel + merge kernel), back to back
     def decode_call(i):
         k = i % len(pools)
-        mla.decode_paged(q_abs, d.q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
-                         num_splits=S, kv_scale=scales[k], workspace=ws, out=o_lat, flags=bal)
+        decode(q_abs, q_rope, pools[k], tables[k], d.seq_lens, w.softmax_scale,
+               num_splits=S, kv_scale=scales[k], workspace=ws, out=o_lat, flags=bal)
     for i in range(min(args.warmup, 10)):
         decode_call(i)
     e0.record()
@@ -253,7 +281,7 @@ def main():
             traffic = None
 
     rec = {
-        "metric": METRICS[args.workload],
+        "metric": METRICS[args.workload] + (f", {T} query tokens per sequence" if T > 1 else ""),
         "value": round(ms_per_step * 1e3, 3),
         "unit": "us/step",
         "n_gpus": 1,
@@ -268,8 +296,8 @@ def main():
         "config": {"workload": WORKLOADS[args.workload],
                    "batch": B, "context_max": int(w.seq_lens.max()), "tokens": w.tokens,
                    "cache_dtype": w.cache_dtype, "num_splits": S, "cache_copies_cycled": len(pools),
-                   "partition": "balanced" if args.balanced else "uniform"},
-        "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+                   "partition": "balanced" if args.balanced else "uniform", "q_len": T},
+        "tokens_per_s": round(B * T / (ms_per_step * 1e-3), 1),
         "step_hbm_GBps": round(cache_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_hbm_frac": round(cache_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "decode_call_us": round(float(dec_call_us), 2),
@@ -293,7 +321,21 @@ def main():
     if append is not None:
         rec["cache_append"] = append
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and T > 1:
+        import oracle
+        n = max(1, min(args.cpu_seqs, B))
+        t0 = time.perf_counter()
+        qa = oracle.absorb_q(qn[:n].reshape(n * T, H, w.d_head), w.W_UK).reshape(n, T, H, d_c)
+        o64, _ = oracle.decode_absorbed_multi(qa, qr[:n], w.pool, w.kv_scale, w.page_table[:n], w.seq_lens[:n],
+                                              w.softmax_scale)
+        oracle.out_proj(o64.reshape(n * T, H, d_c), w.W_UV)
+        t_cpu = time.perf_counter() - t0
+        rec["cpu_baseline"] = {
+            "value": round(t_cpu * (B / n) * 1e6, 1), "unit": "us/step", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{n} of {B} sequences, {T} query tokens each, fp64 absorbed oracle (absorb + decode + "
+                      f"out-proj), one run = {t_cpu:.2f} s, scaled by {B}/{n}"}
+    elif not args.no_cpu_baseline:
         import oracle
         n = max(1, min(args.cpu_seqs, B))
         sel = np.arange(n)

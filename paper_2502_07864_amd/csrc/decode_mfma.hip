@@ -126,8 +126,19 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // BAL = false: the rows are those of chunk `split` of the sequence (seg_row0/1 unused) and the
     // result goes to partial (b, split); BAL = true: the caller gives the rows and the partial slot.
     // Query rows beyond 32 (several query tokens per sequence, or more than 32 heads) go to
-    // further workgroups: this one takes rows [hb, hb + 32) of every sequence.
-    const int hb = (BAL ? blockIdx.y : blockIdx.z) * 32;
+    // further workgroups: this one takes rows [hb, hb + 32) of every sequence.  The grid is then
+    // one-dimensional and the workgroups that share a chunk of cached rows get linear ids 8 apart:
+    // ids are dealt round-robin to the 8 XCDs, so they run at the same time on CUs of one XCD and
+    // all but the first find the rows in that XCD's L2.
+    const int Z = (p.H + 31) / 32;
+    int wg_lin = blockIdx.x, zi = 0;
+    if (Z > 1) {
+        const int id = blockIdx.x, r = id >> 3;
+        zi = r % Z;
+        wg_lin = (r / Z) * 8 + (id & 7);
+        if (wg_lin >= p.B * p.num_splits) return;   // padding of the last group of 8
+    }
+    const int hb = zi * 32;
     auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
                            const size_t out_slot) {
     // Balanced partition: the body runs in a loop.  Everything derived from the thread index is
@@ -671,7 +682,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         // and a sequence's chunks all went to the XCDs of its low chunk indices.  This order puts
         // the empty chunks (high chunk indices) at the end of the grid and spreads every
         // sequence over the XCDs.
-        run_segment((int)((blockIdx.x + blockIdx.y) % (unsigned)p.B), (int)blockIdx.y, 0, 0, 0);
+        const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, cy = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
+        run_segment((cx + cy) % p.B, cy, 0, 0, 0);
     } else {
         // ---- balanced partition.  Pages of sequence b: P_b = ceil(len_b / 64); workgroup w of G
         // owns the global pages [P w / G, P (w+1) / G) of the concatenation, P = sum_b P_b (the
@@ -680,7 +692,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         // sequence's first and last global page.  The segments of a block of 64 sequences are
         // written to a small list in LDS first, so that nothing but a few wave-uniform counters
         // stays live across the segment body (the kernel has no registers to spare).
-        const int wg = blockIdx.x, G = gridDim.x;
+        const int wg = wg_lin, G = p.B * p.num_splits;
         auto seq_len_of = [&](int bb) { return bb < p.B ? max(0, min(p.seq_lens[bb], p.max_pages * 64)) : 0; };
         auto wave_scan = [&](int v) {                // inclusive prefix sum over the 64 lanes
 #pragma unroll
@@ -748,7 +760,15 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 bool decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache)
 {
     return io == MLA_BF16 && (cache == MLA_BF16 || cache == MLA_FP8_E4M3) && p.page_size == 64 &&
-           p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 && (p.H + 31) / 32 <= 65535;
+           p.d_rope == 64 && (p.d_c == 256 || p.d_c == 512) && p.H >= 1 &&
+           ((long long)p.B * p.num_splits + 7) / 8 * 8 * ((p.H + 31) / 32) <= 0x7FFFFFFFLL;
+}
+
+// one-dimensional grid: (sequence, chunk) pairs, padded to a multiple of 8, x groups of 32 query rows
+static unsigned grid_1d(const DecodeParams& p)
+{
+    const long long n = (long long)p.B * p.num_splits, Z = (p.H + 31) / 32;
+    return (unsigned)(Z > 1 ? (n + 7) / 8 * 8 * Z : n);
 }
 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced)
@@ -758,7 +778,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     if (balanced) {
         if (!p.plan) return hipErrorInvalidValue;
         // workgroups = sequences x chunks per sequence (x groups of 32 query rows)
-        dim3 grid((unsigned)p.B * (unsigned)p.num_splits, (unsigned)(p.H + 31) / 32);
+        dim3 grid(grid_1d(p));
         if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, true><<<grid, block, 0, s>>>(p);
         else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, true><<<grid, block, 0, s>>>(p);
         else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, true><<<grid, block, 0, s>>>(p);
@@ -766,7 +786,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
-    dim3 grid(p.B, p.num_splits, (p.H + 31) / 32);
+    dim3 grid(p.B, p.num_splits);
+    if (p.H > 32) grid = dim3(grid_1d(p));
     if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, false><<<grid, block, 0, s>>>(p);
     else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, false><<<grid, block, 0, s>>>(p);
     else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, false><<<grid, block, 0, s>>>(p);
