@@ -162,7 +162,9 @@ int mla_decode_paged_multi(const void* q_abs, const void* q_rope, const void* kv
     if (balanced && ((long long)B * S > 0x3FFFFF || (long long)B * max_pages_per_seq > 0x7FFFFFFFLL))
         return MLA_ERR_UNSUPPORTED;   // grid size; page counts are summed in 32 bits
     hipError_t e;
-    if (mfma) e = launch_decode_mfma(p, cache_dtype, stream, balanced);
+    if (mfma && !balanced && decode_mfma_wide_supported(p, io_dtype, cache_dtype))
+        e = launch_decode_mfma_wide(p, stream);
+    else if (mfma) e = launch_decode_mfma(p, cache_dtype, stream, balanced);
     else      e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
     if (e != hipSuccess) return MLA_ERR_HIP;
     if (skip_merge) return MLA_OK;

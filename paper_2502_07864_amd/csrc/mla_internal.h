@@ -124,6 +124,8 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code)
 hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
 bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
+bool       decode_mfma_wide_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
+hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s);   // 64 query rows per workgroup
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s);
 hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
                          void* dense, int B, int max_len, int row_bytes, int page_size,

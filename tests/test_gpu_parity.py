@@ -784,11 +784,14 @@ def test_multi_token_fp8_cache_and_fused_tail(mla):
     check_multi(mla, ragged_workload(cache="f32", io="f32", lens=[130, 7], seed=37), 2, 2, fused_tail=True)
 
 
-def test_multi_token_last_token_is_the_single_token_decode(mla):
-    """Token q_len - 1 sees the whole sequence: its result must equal the one-token call on the
-    same query bit for bit (same kernel, same chunks, same order of operations)."""
+@pytest.mark.parametrize("H,exact", [(8, True), (32, False)])
+def test_multi_token_last_token_is_the_single_token_decode(mla, H, exact):
+    """Token q_len - 1 sees the whole sequence: its result must equal the one-token call on the same
+    query.  16 query rows run on the same kernel as one token does (same chunks, same order of
+    operations per query row): bit for bit.  64 rows run on the 64-row kernel, which sums in another
+    order: equal within the rounding of the bf16 output."""
     import torch
-    w = ragged_workload(lens=[300, 64, 129], seed=38)
+    w = ragged_workload(H=H, lens=[300, 64, 129], seed=38)
     T = 2
     d = DeviceWorkload(w)
     qn, qr = synth.multi_queries(w, T)
@@ -799,5 +802,39 @@ def test_multi_token_last_token_is_the_single_token_decode(mla):
     o1, lse1 = mla.decode_paged(q_abs[:, T - 1].contiguous(), qr_t[:, T - 1].contiguous(), d.pool, d.page_table,
                                 d.seq_lens, w.softmax_scale, num_splits=4, return_lse=True)
     torch.cuda.synchronize()
-    assert storage_bits(o[:, T - 1]).tobytes() == storage_bits(o1).tobytes()
-    assert storage_bits(lse[:, T - 1]).tobytes() == storage_bits(lse1).tobytes()
+    if exact:
+        assert storage_bits(o[:, T - 1]).tobytes() == storage_bits(o1).tobytes()
+        assert storage_bits(lse[:, T - 1]).tobytes() == storage_bits(lse1).tobytes()
+    else:
+        assert max_abs_rel(widen_gpu(o[:, T - 1]), widen_gpu(o1)) <= 2 ** -7
+        assert lse_err(widen_gpu(lse[:, T - 1]), widen_gpu(lse1)) <= 5e-3
+
+
+def test_multi_token_dominant_late_score_takes_the_careful_route(mla):
+    """A score far above the first tile's maximum, met late in the chunk, sends the 64-row kernel
+    through its second route (exact maxima first, then the accumulation): the query of token 0 is
+    40 x the latent of row 217, that of token 1 is 40 x the latent of the newest row (which token 0
+    must not see), both checked against the oracle and against the closed form (the dominant row)."""
+    import torch
+    L, T = 300, 2
+    w = ragged_workload(lens=[L, L], seed=39)
+    d = DeviceWorkload(w)
+    rows = oracle.widen(oracle.gather_paged(w.pool, w.page_table, w.seq_lens, L).view(np.uint16))
+    q = np.zeros((2, T, 32, 512), dtype=np.float32)
+    q[:, 0] = 40.0 * rows[:, 217, None, :512]
+    q[:, 1] = 40.0 * rows[:, L - 1, None, :512]
+    q_bits = synth.to_bf16_bits(q)
+    q1 = to_torch(q_bits, "bf16")
+    r0 = torch.zeros((2, T, 32, 64), dtype=torch.bfloat16, device="cuda")
+    for splits in (1, 2):
+        o, lse = mla.decode_paged_multi(q1, r0, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                        num_splits=splits, return_lse=True)
+        torch.cuda.synchronize()
+        got, got_lse = widen_gpu(o), widen_gpu(lse)
+        assert np.isfinite(got).all() and np.isfinite(got_lse).all()
+        ref_o, ref_lse = oracle.decode_absorbed_multi(q_bits, np.zeros((2, T, 32, 64), dtype=np.float32).view(np.float32),
+                                                      w.pool, None, w.page_table, w.seq_lens, w.softmax_scale)
+        assert max_abs_rel(got, ref_o) <= TOL["bf16"]
+        assert np.abs(got_lse - ref_lse).max() <= 2e-2 * np.abs(ref_lse).max()
+        assert np.abs(got[:, 0] - rows[:, 217, None, :512]).max() <= 2e-2 * np.abs(rows[:, 217, :512]).max()
+        assert np.abs(got[:, 1] - rows[:, L - 1, None, :512]).max() <= 2e-2 * np.abs(rows[:, L - 1, :512]).max()
