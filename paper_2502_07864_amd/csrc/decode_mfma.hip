@@ -389,7 +389,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     auto page_ahead = [&](int t) { return FP8 ? ptab[min((t + 2) >> 1, p.max_pages - 1)] : 0; };
 
     // S^T = K . Q^T for this wave's 16 rows x 16 heads, scaled to log2 units, invalid rows at
-    // -inf; returns the maximum over the wave's rows of this lane's head.  Operand reads run
+    // -inf; returns the maximum over this lane's 4 rows of its head.  Operand reads run
     // one group of SG k-steps ahead of the MFMAs; the scheduling fences keep the compiler from
     // sinking the reads back next to their uses.
     // first cached row (of the sequence) that some query row of the sequence must not see
@@ -425,10 +425,13 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
             for (int i = 0; i < 4; ++i)
                 if (tg * 16 + g * 4 + i >= seen) x[i] = -INFINITY;
         }
-        float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        return tmax;
+        return fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+    };
+    // maximum over the four lane groups (the wave's 16 tile rows), on every lane: two LDS round
+    // trips, taken only where that maximum is needed
+    auto over_groups = [&](float v) {
+        v = fmaxf(v, __shfl_xor(v, 16));
+        return fmaxf(v, __shfl_xor(v, 32));
     };
 
     // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded
@@ -515,9 +518,12 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         const int page_t2 = page_ahead(t);
         const int n_valid = stage_tile(t, tile);
         float x[4], rs[4];
-        const float tmax = score_tile(tile, slot, t, n_valid, x, rs);
-        if (m_run == -INFINITY) m_run = tmax;
-        jumped |= tmax > m_run + FAST_GAP;
+        const float lmax = score_tile(tile, slot, t, n_valid, x, rs);
+        if (__any(m_run == -INFINITY)) {       // first tile with a visible row (as a rule: the first tile)
+            const float tmax = over_groups(lmax);
+            if (m_run == -INFINITY) m_run = tmax;
+        }
+        jumped |= lmax > m_run + FAST_GAP;
         accumulate_tile(tile, x, rs);
         finish_tile(t, page_t2);
     }
@@ -551,7 +557,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
                 if (!staged) n_valid = stage_tile(t, tile);
                 staged = false;
                 float x[4], rs[4];
-                const float tmax = score_tile(tile, slot, t, n_valid, x, rs);
+                const float tmax = over_groups(score_tile(tile, slot, t, n_valid, x, rs));
                 if (m_run == -INFINITY) m_run = tmax;     // nothing accumulated yet: nothing to rescale
                 if (__any(tmax > m_run + RESCALE_GAP)) {
                     const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
