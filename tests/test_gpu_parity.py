@@ -838,3 +838,30 @@ def test_multi_token_dominant_late_score_takes_the_careful_route(mla):
         assert np.abs(got_lse - ref_lse).max() <= 2e-2 * np.abs(ref_lse).max()
         assert np.abs(got[:, 0] - rows[:, 217, None, :512]).max() <= 2e-2 * np.abs(rows[:, 217, :512]).max()
         assert np.abs(got[:, 1] - rows[:, L - 1, None, :512]).max() <= 2e-2 * np.abs(rows[:, L - 1, :512]).max()
+
+
+def test_multi_token_random_sweep(mla):
+    """Thirty seeded random cases with 2..5 query tokens: batch 1..6, heads 1..40 (so 2..200 query
+    rows: one to four groups on either matrix-core kernel, lanes of mixed tokens), d_c 256 / 512,
+    lengths 0..2000 around page, tile and chunk boundaries and below q_len, bf16 / fp8 caches,
+    1..24 chunks, both partitions, both kernel families, with and without the fused tail."""
+    rng = np.random.default_rng(4048)
+    special = [0, 1, 2, 3, 31, 32, 33, 34, 63, 64, 65, 66, 67, 127, 128, 129, 130, 192, 193, 194]
+    for case in range(30):
+        B = int(rng.integers(1, 7))
+        H = int(rng.choice([1, 5, 8, 16, 17, 28, 32, 40]))
+        T = int(rng.integers(2, 6))
+        d_c = int(rng.choice([256, 512]))
+        lens = [int(rng.choice(special)) if rng.random() < 0.6 else int(rng.integers(0, 2000)) for _ in range(B)]
+        cache = "fp8_e4m3" if rng.random() < 0.3 else "bf16"
+        S = int(rng.integers(1, 25))
+        flags = int(rng.choice([0, 0, 0, 4, 1]))
+        fused = bool(rng.random() < 0.4)
+        w = synth.make_workload(f"mrand{case}", B=B, H=H, d_head=128, d_c=d_c, d_rope=64, seq_lens=lens,
+                                io_dtype="bf16", cache_dtype=cache, placement="random", free_frac=0.25,
+                                seed=3000 + case)
+        try:
+            check_multi(mla, w, T, S, flags=flags, fused_tail=fused)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: B={B} H={H} T={T} d_c={d_c} lens={lens} cache={cache} S={S} "
+                                 f"flags={flags} fused={fused}: {e}")
