@@ -113,6 +113,9 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         for (int h = 0; h < PT_HG; ++h) acc[i][h] = 0.f;
 
     const int chunks_per_row = row / 8;
+    // softmax step (one thread per head): the head's own upper limit of the sum (several query
+    // tokens per sequence)
+    const int my_limit = visible_rows(p, L, h0 + min(tid, PT_HG - 1));
     for (int t0 = j0; t0 < j1; t0 += PT_TOK) {
         __syncthreads();  // previous tile fully consumed (and q_s / m_s written)
         // ---- stage the tile: widen to fp32; rows outside the chunk or on a bad page are zero
@@ -142,17 +145,19 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
             float dot = 0.f;
             for (int k = kb; k < ke; ++k) dot = fmaf(q_s[h][k], k_s[t][k], dot);
             dot += __shfl_xor(dot, 1);
-            // the query row's own upper limit of the sum (several query tokens per sequence)
-            const bool seen = valid_s[t] && t0 + t < visible_rows(p, L, h0 + h);
-            if (half == 0) s_s[h][t] = seen ? dot * p.scale : -INFINITY;
+            if (half == 0) s_s[h][t] = valid_s[t] ? dot * p.scale : -INFINITY;
         }
         __syncthreads();
         // ---- running softmax, one thread per head
         if (tid < PT_HG) {
             int h = tid;
             float m_old = m_s[h], tmax = -INFINITY;
+            float sv[PT_TOK];
 #pragma unroll
-            for (int t = 0; t < PT_TOK; ++t) tmax = fmaxf(tmax, s_s[h][t]);
+            for (int t = 0; t < PT_TOK; ++t) {
+                sv[t] = t0 + t < my_limit ? s_s[h][t] : -INFINITY;
+                tmax = fmaxf(tmax, sv[t]);
+            }
             float m_new = fmaxf(m_old, tmax);
             float a = 1.f, sum = 0.f;
             if (m_new == -INFINITY) {
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
                 a = expf(m_old - m_new);  // exp(-inf) = 0 on the first tile
 #pragma unroll
                 for (int t = 0; t < PT_TOK; ++t) {
-                    float e = expf(s_s[h][t] - m_new);
+                    float e = expf(sv[t] - m_new);
                     p_s[h][t] = e;
                     sum += e;
                 }
