@@ -273,6 +273,33 @@ def decode_absorbed_multi(q_abs, q_rope, pool, kv_scale, page_table, seq_lens,
     return o, lse
 
 
+def prefill_explicit(q_nope, q_rope, W_UK, W_UV, pool, kv_scale, page_table, seq_lens,
+                     softmax_scale: float, d_c: int):
+    """Eq. "mha" (the MHA paradigm of Sec. 3.3) for the T newest positions of every sequence:
+    keys [W_UK c_j ; k_rope_j] and values W_UV c_j materialised per head, query token i of T at
+    position seq_len - T + i attends to the keys up to and including its own.  T = seq_len is the
+    prefill of a whole prompt.
+
+    q_nope [B,T,H,d_head], q_rope [B,T,H,d_rope] -> (out [B,T,H,d_head], lse [B,T,H])."""
+    qn, qr = widen(q_nope), widen(q_rope)
+    Wk, Wv = widen(W_UK), widen(W_UV)
+    pool, sc, dt = _pool_args(pool, kv_scale)
+    pt, sl = _i32(page_table), _i32(seq_lens)
+    B, T, H, d_head = qn.shape
+    d_rope = pool.shape[2] - d_c
+    if d_rope == 0:
+        qr = np.zeros((B, T, H, 0))
+    assert qr.shape == (B, T, H, d_rope)
+    assert Wk.shape == (H, d_head, d_c) and Wv.shape == (H, d_c, d_head)
+    out = np.empty((B, T, H, d_head), dtype=np.float64)
+    lse = np.empty((B, T, H), dtype=np.float64)
+    _c().oracle_prefill_explicit(
+        _dp(qn), _dp(qr), _dp(Wk), _dp(Wv), _vp(pool), _vp(sc), _ip(pt), _ip(sl), _dp(out), _dp(lse),
+        B, T, H, d_head, d_c, d_rope, pool.shape[1], pt.shape[1],
+        ctypes.c_double(softmax_scale), dt)
+    return out, lse
+
+
 def decode_split(q_abs, q_rope, pool, kv_scale, page_table, seq_lens,
                  softmax_scale: float, n_splits: int, chunk_pages: int,
                  return_partials: bool = False):

@@ -360,6 +360,78 @@ int oracle_decode_absorbed_multi(const double* q_abs, const double* q_rope,
     return 0;
 }
 
+/* ---- prefill in the "MHA paradigm" (Eq. "mha"; Sec. 3.3 names it the form for
+ * the compute-intensive phase): keys and values are materialised per head,
+ *     k_{j,h} = [W^{UK}_h c_j ; k^R_j],    v_{j,h} = W^{UV}_h c_j,
+ * and query token i of T (position t_i = L - T + i, as in the multi-token
+ * decode above) attends to j = 0 .. t_i:
+ *     o_{i,h} = sum_{j <= t_i} softmax_j( q_{i,h} . k_{j,h} * scale ) v_{j,h}.
+ * T = L is the prefill of a whole prompt, T < L a later chunk of it.
+ * q_nope [B,T,H,d_head], q_rope [B,T,H,d_rope] -> out [B,T,H,d_head], lse [B,T,H].
+ * Threads run over (b,h); keys and values of one (b,h) are built once. */
+int oracle_prefill_explicit(const double* q_nope, const double* q_rope,
+                            const double* W_UK, const double* W_UV,
+                            const void* pool, const float* kv_scale,
+                            const int32_t* page_table, const int32_t* seq_lens,
+                            double* out, double* lse,
+                            int B, int T, int H, int d_head, int d_c, int d_rope,
+                            int page_size, int max_pages_per_seq,
+                            double softmax_scale, int cache_dtype)
+{
+    int row_len = d_c + d_rope;
+    int dk = d_head + d_rope;
+    int n_task = B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int task = 0; task < n_task; ++task) {
+        int b = task / H, h = task % H;
+        int L = seq_lens[b];
+        if (L < 0) L = 0;
+        const double* Wk = W_UK + (size_t)h * d_head * d_c;
+        const double* Wv = W_UV + (size_t)h * d_c * d_head;
+        size_t n = (size_t)(L > 0 ? L : 1);
+        double* row = (double*)malloc(sizeof(double) * row_len);
+        double* K   = (double*)malloc(sizeof(double) * n * dk);
+        double* V   = (double*)malloc(sizeof(double) * n * d_head);
+        double* s   = (double*)malloc(sizeof(double) * n);
+        for (int j = 0; j < L; ++j) {
+            size_t r = phys_row(page_table, max_pages_per_seq, page_size, b, j);
+            widen_row(pool, kv_scale, cache_dtype, r, row_len, row);
+            for (int d = 0; d < d_head; ++d) {          /* k^C_{j,h} = W^{UK}_h c_j */
+                double acc = 0.0;
+                for (int c = 0; c < d_c; ++c) acc += Wk[(size_t)d * d_c + c] * row[c];
+                K[(size_t)j * dk + d] = acc;
+            }
+            for (int r2 = 0; r2 < d_rope; ++r2) K[(size_t)j * dk + d_head + r2] = row[d_c + r2];
+            for (int d = 0; d < d_head; ++d) {          /* v_{j,h} = W^{UV}_h c_j */
+                double acc = 0.0;
+                for (int c = 0; c < d_c; ++c) acc += row[c] * Wv[(size_t)c * d_head + d];
+                V[(size_t)j * d_head + d] = acc;
+            }
+        }
+        for (int i = 0; i < T; ++i) {
+            size_t qi = ((size_t)b * T + i) * H + h;
+            const double* qc = q_nope + qi * d_head;
+            const double* qr = q_rope + qi * d_rope;
+            int visible = L - (T - 1 - i);               /* keys 0 .. t_i */
+            if (visible < 0) visible = 0;
+            for (int j = 0; j < visible; ++j) {
+                double dot = 0.0;
+                for (int d = 0; d < d_head; ++d) dot += qc[d] * K[(size_t)j * dk + d];
+                for (int r2 = 0; r2 < d_rope; ++r2) dot += qr[r2] * K[(size_t)j * dk + d_head + r2];
+                s[j] = softmax_scale * dot;
+            }
+            double l = softmax_inplace(s, visible);
+            double* o = out + qi * d_head;
+            for (int d = 0; d < d_head; ++d) o[d] = 0.0;
+            for (int j = 0; j < visible; ++j)
+                for (int d = 0; d < d_head; ++d) o[d] += s[j] * V[(size_t)j * d_head + d];
+            if (lse) lse[qi] = l;
+        }
+        free(row); free(K); free(V); free(s);
+    }
+    return 0;
+}
+
 /* ---- split-KV: chunk-local softmax, then log-sum-exp merge ------------- */
 
 /* lse = log sum_s exp(lse_s); o = sum_s exp(lse_s - lse) o_s.

@@ -937,3 +937,77 @@ def test_M4_later_rows_do_not_reach_an_earlier_token_and_its_own_row_does():
         pool3, table3, sl3 = dense_cache(c3, cs["k"], 4, seed=8)
         _, o3, _, _ = _multi_chain(dict(cs, c=c3, pool=pool3, table=table3, sl=sl3))
         assert np.abs(o3[0, i] - o[0, i]).max() > 1e-3
+
+
+# ---------------------------------------------------------------------------
+# F: prefill in the MHA paradigm (Eq. "mha" with keys and values materialised per head)
+# ---------------------------------------------------------------------------
+
+def _prefill(cs):
+    return oracle.prefill_explicit(cs["qn"], cs["qr"], cs["Wk"], cs["Wv"], cs["pool"], None, cs["table"],
+                                   cs["sl"], cs["scale"], cs["d_c"])
+
+
+def test_F1_prefill_scalar_brute_force():
+    """Pure-Python scalar evaluation of Eq. "mha" with exactly rounded sums, every query token with
+    its own upper limit j <= t_i."""
+    T, lens = 3, (5, 3, 2)
+    cs = _multi_case(T, lens, page_size=2, seed=11)
+    out, lse = _prefill(cs)
+    B, _, H, d_head = cs["qn"].shape
+    for b, L in enumerate(lens):
+        for h in range(H):
+            keys, vals = [], []
+            for j in range(L):
+                cj = [float(x) for x in cs["c"][b][j]]
+                kc = [math.fsum(float(cs["Wk"][h, d, c]) * cj[c] for c in range(cs["d_c"])) for d in range(d_head)]
+                keys.append(kc + [float(x) for x in cs["k"][b][j]])
+                vals.append([math.fsum(cj[c] * float(cs["Wv"][h, c, d]) for c in range(cs["d_c"])) for d in range(d_head)])
+            for i in range(T):
+                vis = max(0, L - (T - 1 - i))
+                q = [float(x) for x in cs["qn"][b, i, h]] + [float(x) for x in cs["qr"][b, i, h]]
+                sc = [cs["scale"] * math.fsum(q[d] * keys[j][d] for d in range(len(q))) for j in range(vis)]
+                if vis == 0:
+                    assert (out[b, i, h] == 0).all() and np.isneginf(lse[b, i, h])
+                    continue
+                m = max(sc)
+                e = [math.exp(x - m) for x in sc]
+                z = math.fsum(e)
+                want = [math.fsum(e[j] / z * vals[j][d] for j in range(vis)) for d in range(d_head)]
+                np.testing.assert_allclose(out[b, i, h], want, rtol=1e-12, atol=1e-13)
+                np.testing.assert_allclose(lse[b, i, h], m + math.log(z), rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("T,lens,page_size,seed", [(1, (6, 2), 2, 0), (4, (9, 4, 6), 4, 1), (7, (7, 12), 3, 2)])
+def test_F2_prefill_equals_the_absorbed_form(T, lens, page_size, seed):
+    """Sec. 3.3: the two paradigms compute the same function (the Absorb operation only moves
+    W^{UK} to the query side and W^{UV} behind the sum)."""
+    cs = _multi_case(T, lens, page_size=page_size, seed=seed)
+    out, lse = _prefill(cs)
+    _, _, lse_abs, out_abs = _multi_chain(cs)
+    np.testing.assert_allclose(out, out_abs, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(lse, lse_abs, rtol=1e-12, atol=1e-12)
+
+
+def test_F3_whole_prompt_against_the_tensor_library_causal_attention():
+    """T = L (prefill of a whole prompt) is textbook causal self-attention over the materialised
+    keys and values: checked against torch's scaled_dot_product_attention(is_causal=True) in fp64.
+    T = 1 is the one-token explicit decode (pinned separately)."""
+    import torch
+    L = 11
+    cs = _multi_case(L, (L, L), H=2, page_size=4, seed=21)
+    out, _ = _prefill(cs)
+    for b in range(2):
+        for h in range(2):
+            K = torch.from_numpy(np.concatenate([cs["c"][b] @ cs["Wk"][h].T, cs["k"][b]], axis=1))
+            V = torch.from_numpy(cs["c"][b] @ cs["Wv"][h])
+            Q = torch.from_numpy(np.concatenate([cs["qn"][b, :, h], cs["qr"][b, :, h]], axis=1))
+            want = torch.nn.functional.scaled_dot_product_attention(Q[None], K[None], V[None], is_causal=True,
+                                                                    scale=cs["scale"])[0].numpy()
+            np.testing.assert_allclose(out[b, :, h], want, rtol=1e-10, atol=1e-11)
+    cs1 = _multi_case(1, (6, 3), page_size=2, seed=22)
+    out1, lse1 = _prefill(cs1)
+    want, want_lse = oracle.decode_explicit(cs1["qn"][:, 0], cs1["qr"][:, 0], cs1["Wk"], cs1["Wv"], cs1["pool"], None,
+                                            cs1["table"], cs1["sl"], cs1["scale"], cs1["d_c"])
+    np.testing.assert_allclose(out1[:, 0], want, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(lse1[:, 0], want_lse, rtol=1e-13, atol=1e-14)
