@@ -257,6 +257,54 @@ int mla_merge_out_proj_multi(const void* workspace, size_t workspace_bytes,
                              void* hip_stream);
 
 /*
+ * Bytes of device workspace mla_prefill_mha needs: the concatenated per-head
+ * projections, the materialised keys and values (B * heads * max_pages_per_seq
+ * pages of 64 rows of 320 bf16 values: 40 KB per page and head), and the page
+ * table and lengths of the (sequence, head) pairs.  Pure host function; 0 if an
+ * argument is invalid.
+ */
+size_t mla_prefill_workspace_bytes(int B, int heads, int d_c, int max_pages_per_seq);
+
+/*
+ * Prefill in the "MHA paradigm" (Sec. 3.3, first of the two side-by-side
+ * attention equations; the text before them names it the form for the
+ * compute-intensive phase): keys and values are materialised per head from the
+ * cached latent rows,
+ *     k_{j,h} = [ W^{UK}_h c_j ; k^R_j ],     v_{j,h} = W^{UV}_h c_j,
+ * and query token i of q_len (position seq_lens[b] - q_len + i; the cache
+ * already holds the rows of all q_len tokens, as for mla_decode_paged_multi)
+ * attends to the keys 0 .. its own position:
+ *     out[b,i,h,:] = sum_j softmax_j( [q_nope ; q_rope] . k_{j,h} * scale ) v_{j,h}.
+ * q_len = seq_len is the prefill of a whole prompt, q_len < seq_len a later
+ * chunk of it.  Same function as mla_absorb_q -> mla_decode_paged_multi ->
+ * mla_out_proj, at (2 (d_head + d_rope) + 2 d_head) instead of
+ * (2 (d_c + d_rope) + 2 d_c) flop per (query, key, head), plus the
+ * materialisation, 4 d_c d_head flop per (key, head).
+ *
+ *   q_nope [B, q_len, heads, d_head]   q_rope [B, q_len, heads, d_rope]   io dtype
+ *   W_UK   [heads, d_head, d_c]        W_UV   [heads, d_c, d_head]
+ *   kv_cache, page_table, seq_lens     as for mla_decode_paged
+ *   out    [B, q_len, heads, d_head] io dtype (output); tokens that see no key
+ *          (seq_len < q_len) give zeros
+ *   lse    [B, q_len, heads] fp32 (output, may be NULL)
+ *   workspace  mla_prefill_workspace_bytes(B, heads, d_c, max_pages_per_seq)
+ *          bytes, 256-byte aligned; scratch
+ * The materialised keys and values are rounded to bf16 (a rounding the absorbed
+ * form does not have).  Supported: BF16 io and cache, d_head 128, d_rope 64,
+ * page_size 64, d_c 256 or 512, B * heads <= 65535; otherwise
+ * MLA_ERR_UNSUPPORTED (use the absorbed calls).
+ */
+int mla_prefill_mha(const void* q_nope, const void* q_rope,
+                    const void* W_UK, const void* W_UV,
+                    const void* kv_cache, const int32_t* page_table,
+                    const int32_t* seq_lens, void* out, float* lse,
+                    void* workspace, size_t workspace_bytes,
+                    int B, int q_len, int heads, int d_head, int d_c, int d_rope,
+                    int page_size, int num_pages, int max_pages_per_seq,
+                    float softmax_scale, mla_dtype io_dtype,
+                    mla_dtype cache_dtype, void* hip_stream);
+
+/*
  * Bytes of device workspace mla_cache_append needs (fp32 partial rows of the
  * projection, one per slice of the model dimension).  Pure host function;
  * returns 0 if an argument is invalid.

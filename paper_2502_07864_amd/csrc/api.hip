@@ -154,6 +154,7 @@ int mla_decode_paged_multi(const void* q_abs, const void* q_rope, const void* kv
     p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = S;
     p.chunk_pages = (max_pages_per_seq + S - 1) / S;
     p.q_len = q_len; p.heads = heads;
+    p.q_inner = 1; p.o_final = nullptr; p.lse_final = nullptr;
     p.scale = softmax_scale;
 
     const bool balanced = (flags & MLA_FLAG_BALANCED) != 0;
@@ -233,6 +234,71 @@ int mla_merge_out_proj_multi(const void* workspace, size_t workspace_bytes, cons
         if (e == hipSuccess)
             e = launch_head_gemm(o_lat, W_UV, out, B * q_len, heads, d_c, d_head, io_dtype, stream);
     }
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
+namespace {
+struct PrefillWs {
+    size_t pool_off, table_off, lens_off, total;
+};
+PrefillWs prefill_ws(int B, int heads, int d_c, int max_pages)
+{
+    PrefillWs w;
+    w.pool_off = align_up((size_t)heads * 256 * d_c * 2, 256);                                   // after Wcat
+    w.table_off = w.pool_off + align_up((size_t)B * heads * max_pages * 64 * 320 * 2, 256);      // after the pool
+    w.lens_off = w.table_off + align_up((size_t)B * heads * max_pages * sizeof(int32_t), 256);
+    w.total = w.lens_off + align_up((size_t)B * heads * sizeof(int32_t), 256);
+    return w;
+}
+}  // namespace
+
+size_t mla_prefill_workspace_bytes(int B, int heads, int d_c, int max_pages_per_seq)
+{
+    if (B <= 0 || heads <= 0 || d_c <= 0 || max_pages_per_seq <= 0) return 0;
+    return prefill_ws(B, heads, d_c, max_pages_per_seq).total;
+}
+
+int mla_prefill_mha(const void* q_nope, const void* q_rope, const void* W_UK, const void* W_UV,
+                    const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens, void* out,
+                    float* lse, void* workspace, size_t workspace_bytes, int B, int q_len, int heads,
+                    int d_head, int d_c, int d_rope, int page_size, int num_pages, int max_pages_per_seq,
+                    float softmax_scale, mla_dtype io_dtype, mla_dtype cache_dtype, void* hip_stream)
+{
+    if (!q_nope || !q_rope || !W_UK || !W_UV || !kv_cache || !page_table || !seq_lens || !out) return MLA_ERR_NULL;
+    if (B <= 0 || q_len <= 0 || heads <= 0 || d_head <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 ||
+        num_pages <= 0 || max_pages_per_seq <= 0)
+        return MLA_ERR_SHAPE;
+    if ((long long)max_pages_per_seq * page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
+    if (!(softmax_scale == softmax_scale)) return MLA_ERR_SHAPE;
+    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (cache_dtype != MLA_F32 && cache_dtype != MLA_BF16 && cache_dtype != MLA_FP8_E4M3) return MLA_ERR_UNSUPPORTED;
+    if (!prefill_supported(d_head, d_c, d_rope, page_size, io_dtype, cache_dtype)) return MLA_ERR_UNSUPPORTED;
+    const long long pseudo = (long long)B * heads;                     // (sequence, head) pairs
+    if (pseudo > 65535 || max_pages_per_seq > 65535 * 16 || pseudo * max_pages_per_seq > 0x7FFFFFFFLL ||
+        (pseudo + 7) / 8 * 8 * ((q_len + 63) / 64) > 0x7FFFFFFFLL)
+        return MLA_ERR_UNSUPPORTED;
+    const PrefillWs wl = prefill_ws(B, heads, d_c, max_pages_per_seq);
+    if (!workspace || workspace_bytes < wl.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return MLA_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    void* pool2 = ws + wl.pool_off;
+    int32_t* table2 = reinterpret_cast<int32_t*>(ws + wl.table_off);
+    int32_t* lens2 = reinterpret_cast<int32_t*>(ws + wl.lens_off);
+    hipError_t e = launch_prefill_materialise(kv_cache, page_table, seq_lens, W_UK, W_UV, ws, pool2, table2, lens2,
+                                              B, heads, d_c, num_pages, max_pages_per_seq, stream);
+    if (e != hipSuccess) return MLA_ERR_HIP;
+    // the attention: every (sequence, head) pair is a sequence of q_len query rows over its own rows
+    DecodeParams p;
+    p.q_abs = q_nope; p.q_rope = q_rope; p.kv = pool2; p.kv_scale = nullptr;
+    p.page_table = table2; p.seq_lens = lens2;
+    p.o_part = nullptr; p.lse_part = nullptr; p.plan = nullptr;
+    p.B = (int)pseudo; p.H = q_len; p.d_c = d_head; p.d_rope = d_rope; p.page_size = page_size;
+    p.num_pages = (int)(pseudo * max_pages_per_seq); p.max_pages = max_pages_per_seq;
+    p.num_splits = 1; p.chunk_pages = max_pages_per_seq;
+    p.q_len = q_len; p.heads = 1; p.q_inner = heads; p.o_final = out; p.lse_final = lse;
+    p.scale = softmax_scale;
+    e = launch_prefill_attention(p, stream);
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 

@@ -35,18 +35,31 @@ namespace {
 constexpr int WD_ROWS = 64;      // query rows per workgroup
 constexpr int WD_NBUF = 4;       // tiles in the LDS ring
 
-template <int D_C>
+// DQ   = width of the first part of a query row (d_c in the absorbed form); the second part is the
+//        64 decoupled-rope values, and the score contraction runs over the first DQ + 64 columns of
+//        a cached row.
+// VOFF, DV = first column and width of the value part of a cached row (0, d_c in the absorbed form:
+//        the values are the latent rows themselves).
+// FINAL = false: the chunk's partial result goes to the split-KV workspace (fp32, merged later).
+//         true : one chunk per sequence; the normalised result is rounded to bf16 and stored where
+//                the query row came from (o_final), no merge.
+// The MHA-paradigm prefill (Sec. 3.3, first of the two attention equations) runs on the same
+// kernel: its "cached rows" are the keys and values materialised per (sequence, head),
+// [W^{UK}_h c_j ; k^R_j | W^{UV}_h c_j] = 128 + 64 | 128 values, one pseudo-sequence per (sequence,
+// head), whose query rows are the prompt's tokens (DQ = 128, VOFF = 192, DV = 128, FINAL).
+template <int DQ, int VOFF, int DV, bool FINAL>
 __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeParams p)
 {
     constexpr int NBUF = WD_NBUF;
-    constexpr int ROW = D_C + 64;               // elements per cache row
+    constexpr int ROW = DQ + 64 > VOFF + DV ? DQ + 64 : VOFF + DV;   // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
     constexpr int PAGE_B = 64 * ROWB;           // bytes per page
     constexpr int TILE_B = TILE_ROWS * ROWB;    // bytes per tile
     constexpr int NLOAD = TILE_B / (MF_THREADS * 16);  // 16-byte loads per thread per tile (9 / 5)
-    constexpr int NKS = ROW / 32;               // k-steps of the score contraction (18 / 10)
-    constexpr int CTW = D_C / 32;               // column tiles of the value contraction per wavefront (16 / 8)
+    constexpr int NKS = (DQ + 64) / 32;         // k-steps of the score contraction (18 / 10 / 6)
+    constexpr int CTW = DV / 32;                // column tiles of the value contraction per wavefront (16 / 8 / 4)
+    static_assert(VOFF % 64 == 0 && DV % 64 == 0 && DQ % 64 == 0, "parts of a row start on whole swizzle groups");
     constexpr int SG = NKS % 3 == 0 ? 3 : 2;    // k-steps per read-ahead group (score)
     constexpr int VG = 4;                       // column tiles per read-ahead group (value)
     constexpr int AH = 2;                       // groups the LDS reads run ahead of the MFMAs
@@ -82,7 +95,12 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     const int hb = zi * WD_ROWS;
     const int HL = min(WD_ROWS, p.H - hb);     // query rows of this workgroup
 
-    auto o_row = [&](int h) -> float* { return p.o_part + part_index(b, h, split, p.H, p.num_splits) * D_C; };
+    auto o_row = [&](int h) -> float* { return p.o_part + part_index(b, h, split, p.H, p.num_splits) * DV; };
+    // Index of query row h of this (pseudo-)sequence in the caller's q and output arrays.  Absorbed
+    // decode: the rows of a sequence are adjacent (q_inner = 1).  Prefill: sequence b stands for
+    // (sequence b / q_inner, head b % q_inner) and its rows (tokens) are q_inner rows apart.
+    const size_t io_base = (size_t)(b / p.q_inner) * p.H * p.q_inner + (size_t)(b % p.q_inner);
+    auto io_row = [&](int h) -> size_t { return io_base + (size_t)h * p.q_inner; };
     auto lse_at = [&](int h) -> float* { return p.lse_part + part_index(b, h, split, p.H, p.num_splits); };
 
     // read-only tables through the scalar cache (no vector-memory counter involved)
@@ -96,16 +114,19 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     LDS_AS unsigned char* qslot = lds + (NBUF - 2) * TILE_B;
     {
-        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
-        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
+        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs);
+        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope);
+        const size_t q_row0 = io_row(hb);
         const uint32_t dst = lds_base + (uint32_t)((NBUF - 2) * TILE_B + wave * 1024);
 #pragma unroll
         for (int k = 0; k < 2 * NLOAD; ++k) {
             const int P = (k * 4 + wave) * 64 + lane;
             const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
+            if (c >= (DQ + 64) / 8) continue;      // columns past the score part are never read from a query row
             if (r < HL) {
-                const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
-                                                      : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
+                const size_t qrow = q_row0 + (size_t)r * p.q_inner;
+                const unsigned char* gp = c < DQ / 8 ? qa + (qrow * DQ + c * 8) * 2
+                                                     : qr + (qrow * 64 + (c - DQ / 8) * 8) * 2;
                 const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
                 asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                              :: "s"(m0v), "v"(gp) : "memory");
@@ -118,16 +139,24 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
     const int row0 = split * p.chunk_pages * 64;              // first cached row of this chunk
-    const int row1 = min(row0 + p.chunk_pages * 64, L);       // one past its last row
-    if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < HL) *lse_at(hb + tid) = -INFINITY;
+    // one past its last row that some query row of this workgroup sees (the query rows are ordered
+    // by token, so the last one sees the most)
+    const int row1 = min(min(row0 + p.chunk_pages * 64, L), visible_rows(p, L, min(hb + WD_ROWS, p.H) - 1));
+    if (row0 >= row1) {  // nothing to see
+        if constexpr (FINAL) {   // the result itself: zeros and -inf
+            for (int i = tid; i < HL * (DV / 4); i += MF_THREADS)
+                *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.o_final) + io_row(hb + i / (DV / 4)) * DV + (i % (DV / 4)) * 4) = (u32x2){0u, 0u};
+            if (tid < HL && p.lse_final) p.lse_final[io_row(hb + tid)] = -INFINITY;
+        } else {                 // weight zero in the merge, partial output never read
+            if (tid < HL) *lse_at(hb + tid) = -INFINITY;
+        }
         wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
     const int t0 = row0 / TILE_ROWS;                          // tiles [t0, t1) of the sequence
     const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
-    // first cached row that some query row of the sequence must not see
-    const int causal_from = L - (p.q_len - 1);
+    // first cached row that some query row of this workgroup must not see (its first row sees the least)
+    const int causal_from = visible_rows(p, L, hb);
 
     // ---- tile staging: HBM -> LDS with direct-to-LDS 128-bit loads (as in the 32-row kernel)
     uint32_t goff[NLOAD];
@@ -253,7 +282,7 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8) +
-                    (uint32_t)(a * D_C);     // column half a starts d_c/2 elements = d_c bytes into the row
+                    (uint32_t)(VOFF * 2 + a * DV);   // value part; column half a starts DV/2 elements = DV bytes into it
 
     // S^T for this wave's 16 tile rows x 32 query rows, log2 units, rows a query row must not see
     // (or that are not there) at -inf; lmax = maximum over this lane's 4 tile rows per query row
@@ -434,7 +463,7 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     }
     // transpose through LDS (a lane holds 4 consecutive columns of query row n per column tile,
     // which written straight out would give 16-byte pieces) and store whole runs
-    constexpr int CW = D_C / 2;                 // columns per wavefront
+    constexpr int CW = DV / 2;                  // columns per wavefront
     constexpr int RSO = CW * 4 + 16;            // row stride of the transposed block (padded)
     static_assert(4 * 32 * RSO <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* mine = lds + wave * (32 * RSO);
@@ -451,15 +480,26 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
             f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = o_row(hb + hp * 32 + r) + a * CW + c * 4;
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+            if constexpr (FINAL) {
+                uint16_t* dst = static_cast<uint16_t*>(p.o_final) + io_row(hb + hp * 32 + r) * DV + a * CW + c * 4;
+                *reinterpret_cast<u32x2*>(dst) = (u32x2){pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+            } else {
+                float* dst = o_row(hb + hp * 32 + r) + a * CW + c * 4;
+                __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+            }
         }
     }
     if (a == 0 && g == 0) {
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi)
-            if (head0 + hi * 16 < HL)
-                *lse_at(hb + head0 + hi * 16) = lt[hi] > 0.f ? (m_ref[hi] + __builtin_amdgcn_logf(lt[hi])) * LN2 : -INFINITY;
+            if (head0 + hi * 16 < HL) {
+                const float l = lt[hi] > 0.f ? (m_ref[hi] + __builtin_amdgcn_logf(lt[hi])) * LN2 : -INFINITY;
+                if constexpr (FINAL) {
+                    if (p.lse_final) p.lse_final[io_row(hb + head0 + hi * 16)] = l;
+                } else {
+                    *lse_at(hb + head0 + hi * 16) = l;
+                }
+            }
     }
 }
 
@@ -477,9 +517,21 @@ hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s)
     const long long nchunk = (long long)p.B * p.num_splits, Z = (p.H + WD_ROWS - 1) / WD_ROWS;
     dim3 grid(p.B, p.num_splits), block(MF_THREADS);
     if (Z > 1) grid = dim3((unsigned)((nchunk + 7) / 8 * 8 * Z));
-    if (p.d_c == 512)      decode_mfma_wide_kernel<512><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_mfma_wide_kernel<256><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_mfma_wide_kernel<512, 0, 512, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_mfma_wide_kernel<256, 0, 256, false><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// Causal attention over materialised keys and values (rows [k 128 + 64 | v 128]): p.B pseudo-sequences
+// of p.H query rows each, one chunk per sequence, results straight to o_final / lse_final.
+hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s)
+{
+    if (p.num_splits != 1 || !p.o_final || p.heads != 1) return hipErrorInvalidValue;
+    const long long Z = (p.H + WD_ROWS - 1) / WD_ROWS;
+    dim3 grid(p.B, 1), block(MF_THREADS);
+    if (Z > 1) grid = dim3((unsigned)(((long long)p.B + 7) / 8 * 8 * Z));
+    decode_mfma_wide_kernel<128, 192, 128, true><<<grid, block, 0, s>>>(p);
     return hipGetLastError();
 }
 

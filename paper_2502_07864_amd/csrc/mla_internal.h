@@ -26,6 +26,9 @@ struct DecodeParams {
                                 // sequence (the partials are then [slot, H, d_c] / [slot, H])
     int B, H, d_c, d_rope, page_size, num_pages, max_pages, num_splits, chunk_pages;
     int q_len, heads;           // H = q_len * heads
+    int q_inner;                // 1; prefill: heads of the model (sequence b stands for (b / q_inner, b % q_inner))
+    void* o_final;              // prefill only: [.., d_head] io dtype, rows indexed like the query rows
+    float* lse_final;           // prefill only, may be nullptr
     float scale;
 };
 
@@ -126,6 +129,13 @@ bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
 bool       decode_mfma_wide_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s);   // 64 query rows per workgroup
+hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s);  // same kernel over materialised keys / values
+// prefill: materialise [W_UK c ; k_rope | W_UV c] per (sequence, head) into a pool of its own
+bool       prefill_supported(int d_head, int d_c, int d_rope, int page_size, mla_dtype io, mla_dtype cache);
+hipError_t launch_prefill_materialise(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
+                                      const void* W_UK, const void* W_UV, void* Wcat, void* pool2, int32_t* table2,
+                                      int32_t* lens2, int B, int heads, int d_c, int num_pages, int max_pages,
+                                      hipStream_t s);
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s);
 hipError_t launch_gather(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
                          void* dense, int B, int max_len, int row_bytes, int page_size,

@@ -23,7 +23,7 @@ FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE, FLAG_BALANCED = 0, 1, 2, 4
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
            "mla_merge_out_proj", "mla_gather_paged", "mla_append_workspace_bytes", "mla_cache_append",
-           "mla_decode_paged_multi", "mla_merge_out_proj_multi")
+           "mla_decode_paged_multi", "mla_merge_out_proj_multi", "mla_prefill_workspace_bytes", "mla_prefill_mha")
 
 
 class MlaError(RuntimeError):
@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
                                              i, i, i, i, i, i, i, i, i, f, i, i, u, vp]
         L.mla_merge_out_proj_multi.restype = i
         L.mla_merge_out_proj_multi.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, i, u, vp]
+        L.mla_prefill_workspace_bytes.restype = ctypes.c_size_t
+        L.mla_prefill_workspace_bytes.argtypes = [i, i, i, i]
+        L.mla_prefill_mha.restype = i
+        L.mla_prefill_mha.argtypes = [vp] * 10 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, vp]
         L.mla_merge_partials.restype = i
         L.mla_merge_partials.argtypes = [vp, ctypes.c_size_t, vp, vp, i, i, i, i, i, u, vp]
         L.mla_merge_out_proj.restype = i
@@ -250,6 +254,46 @@ def merge_out_proj_multi(workspace: torch.Tensor, W_UV: torch.Tensor, B: int, q_
                                           d_c, d_head, num_splits, _io_code(W_UV), int(flags),
                                           _stream(workspace)), "mla_merge_out_proj_multi")
     return (o_lat, out, lse) if lse is not None else (o_lat, out)
+
+
+def prefill_workspace_bytes(B: int, heads: int, d_c: int, max_pages_per_seq: int) -> int:
+    return int(lib().mla_prefill_workspace_bytes(B, heads, d_c, max_pages_per_seq))
+
+
+def prefill_mha(q_nope: torch.Tensor, q_rope: torch.Tensor, W_UK: torch.Tensor, W_UV: torch.Tensor,
+                kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: torch.Tensor, softmax_scale: float,
+                workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                lse: Optional[torch.Tensor] = None, return_lse: bool = False):
+    """Prefill in the MHA paradigm: keys [W_UK c ; k_rope] and values W_UV c materialised per head,
+    causal attention of the q_len newest tokens of every sequence (the cache holds their rows).
+    q_nope [B,q_len,H,d_head], q_rope [B,q_len,H,d_rope] -> out [B,q_len,H,d_head] (and lse [B,q_len,H])."""
+    B, T, H, d_head = q_nope.shape
+    H2, d_head2, d_c = W_UK.shape
+    num_pages, page_size, row = kv_cache.shape
+    d_rope = row - d_c
+    if (H2, d_head2) != (H, d_head) or tuple(W_UV.shape) != (H, d_c, d_head):
+        raise ValueError("W_UK must be [H, d_head, d_c] and W_UV [H, d_c, d_head]")
+    if tuple(q_rope.shape) != (B, T, H, d_rope) or q_rope.dtype != q_nope.dtype:
+        raise ValueError("q_rope must be [B, q_len, H, d_rope] of q_nope's dtype")
+    if page_table.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise TypeError("page_table and seq_lens must be int32")
+    if page_table.dim() != 2 or page_table.shape[0] != B or seq_lens.shape != (B,):
+        raise ValueError("page_table must be [B, max_pages_per_seq], seq_lens [B]")
+    if workspace is None:
+        workspace = torch.empty(max(256, prefill_workspace_bytes(B, H, d_c, page_table.shape[1])),
+                                dtype=torch.uint8, device=q_nope.device)
+    if out is None:
+        out = torch.empty((B, T, H, d_head), dtype=q_nope.dtype, device=q_nope.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, T, H), dtype=torch.float32, device=q_nope.device)
+    _check(lib().mla_prefill_mha(
+        _dev(q_nope, "q_nope"), _dev(q_rope, "q_rope"), _dev(W_UK, "W_UK"), _dev(W_UV, "W_UV"),
+        _dev(kv_cache, "kv_cache"), _dev(page_table, "page_table"), _dev(seq_lens, "seq_lens"),
+        _dev(out, "out"), _dev(lse, "lse"), _dev(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), B, T, H, d_head, d_c, d_rope, page_size, num_pages,
+        page_table.shape[1], float(softmax_scale), _io_code(q_nope), _cache_code(kv_cache),
+        _stream(q_nope)), "mla_prefill_mha")
+    return (out, lse) if lse is not None else out
 
 
 def merge_partials(workspace: torch.Tensor, B: int, H: int, d_c: int, num_splits: int,

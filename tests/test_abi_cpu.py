@@ -31,6 +31,9 @@ def lib():
     L.mla_decode_paged.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 8 + [f, i, i, u, vp]
     L.mla_decode_paged_multi.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, u, vp]
     L.mla_merge_out_proj_multi.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp] + [i] * 7 + [u, vp]
+    L.mla_prefill_workspace_bytes.restype = ctypes.c_size_t
+    L.mla_prefill_workspace_bytes.argtypes = [i, i, i, i]
+    L.mla_prefill_mha.argtypes = [vp] * 10 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, vp]
     L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
     L.mla_append_workspace_bytes.restype = ctypes.c_size_t
     L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -142,6 +145,36 @@ def test_multi_token_tail_validation(lib):
     assert call(q_len=0) == E_SHAPE and call(B=0) == E_SHAPE and call(d_head=0) == E_SHAPE
     assert call(io=FP8) == E_UNSUP and call(d_c=6) == E_UNSUP and call(B=40000, q_len=2) == E_UNSUP
     assert call(ws=None) == E_WS and call(ws_bytes=4096) == E_WS
+
+
+def prefill_args(**kw):
+    a = dict(q_nope=P, q_rope=P, W_UK=P, W_UV=P, kv=P, table=P, lens=P, out=P, lse=None, ws=P, ws_bytes=1 << 40,
+             B=2, q_len=100, H=32, d_head=128, d_c=512, d_rope=64, page=64, num_pages=8, max_pages=4, scale=0.07,
+             io=BF16, cache=BF16, stream=None)
+    a.update(kw)
+    return [a[k] for k in ("q_nope", "q_rope", "W_UK", "W_UV", "kv", "table", "lens", "out", "lse", "ws", "ws_bytes",
+                           "B", "q_len", "H", "d_head", "d_c", "d_rope", "page", "num_pages", "max_pages", "scale",
+                           "io", "cache", "stream")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q_nope=None), E_NULL), (dict(q_rope=None), E_NULL), (dict(W_UK=None), E_NULL), (dict(W_UV=None), E_NULL),
+    (dict(kv=None), E_NULL), (dict(table=None), E_NULL), (dict(lens=None), E_NULL), (dict(out=None), E_NULL),
+    (dict(B=0), E_SHAPE), (dict(q_len=0), E_SHAPE), (dict(H=-1), E_SHAPE), (dict(d_c=0), E_SHAPE),
+    (dict(max_pages=0), E_SHAPE), (dict(scale=float("nan")), E_SHAPE), (dict(max_pages=1 << 30), E_SHAPE),
+    (dict(io=F32, cache=F32), E_UNSUP), (dict(cache=FP8), E_UNSUP), (dict(d_head=64), E_UNSUP),
+    (dict(d_c=384), E_UNSUP), (dict(d_rope=32), E_UNSUP), (dict(page=16), E_UNSUP), (dict(B=4096), E_UNSUP),
+    (dict(ws=None), E_WS), (dict(ws_bytes=1 << 20), E_WS), (dict(ws=P + 16), E_WS),
+])
+def test_prefill_validation(lib, kw, want):
+    assert lib.mla_prefill_mha(*prefill_args(**kw)) == want
+
+
+def test_prefill_workspace_bytes(lib):
+    n = lib.mla_prefill_workspace_bytes(2, 32, 512, 4)
+    assert n % 256 == 0
+    assert n >= 32 * 256 * 512 * 2 + 2 * 32 * 4 * 64 * 320 * 2 + 2 * 32 * 4 * 4 + 2 * 32 * 4
+    assert lib.mla_prefill_workspace_bytes(0, 32, 512, 4) == 0
 
 
 def test_gather_validation(lib):

@@ -865,3 +865,58 @@ def test_multi_token_random_sweep(mla):
         except AssertionError as e:
             raise AssertionError(f"case {case}: B={B} H={H} T={T} d_c={d_c} lens={lens} cache={cache} S={S} "
                                  f"flags={flags} fused={fused}: {e}")
+
+
+# ----------------------------------------------- prefill in the MHA paradigm
+
+def check_prefill(mla, w, T, tol=None):
+    """mla_prefill_mha for the T newest tokens of every sequence against the oracle's Eq. "mha"
+    (keys and values materialised per head in fp64); returns the GPU output."""
+    import torch
+    d = DeviceWorkload(w)
+    qn, qr = synth.multi_queries(w, T)
+    qn_t, qr_t = to_torch(qn, w.io_dtype), to_torch(qr, w.io_dtype)
+    out, lse = mla.prefill_mha(qn_t, qr_t, d.W_UK, d.W_UV, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                               return_lse=True)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.prefill_explicit(qn, qr, w.W_UK, w.W_UV, w.pool, None, w.page_table, w.seq_lens,
+                                           w.softmax_scale, w.d_c)
+    got, got_lse = widen_gpu(out), widen_gpu(lse)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    err = max_abs_rel(got, ref)
+    tol = tol or TOL["bf16"]
+    assert err <= tol, f"{w.name} q_len={T}: out err {err:.3e} > {tol}"
+    assert lse_err(got_lse, ref_lse) <= 2e-2
+    return out, lse, qn_t, qr_t, d
+
+
+@pytest.mark.parametrize("T", [1, 64, 200, 300])
+def test_prefill_mha_ragged(mla, T):
+    """Lengths around tile and page boundaries; q_len from one token to the whole prompt of the
+    longest sequence (shorter sequences then have tokens before position 0: zeros, -inf);
+    one to five groups of 64 query rows per (sequence, head)."""
+    w = ragged_workload(H=8, lens=[300, 64, 129, 1, 65, 33], seed=51)
+    check_prefill(mla, w, T)
+
+
+def test_prefill_mha_whole_prompts_32_heads_and_C4_shape(mla):
+    w = ragged_workload(H=32, lens=[256, 192], seed=52)
+    check_prefill(mla, w, 256)
+    w4 = ragged_workload(H=28, d_c=256, lens=[150, 70, 2], seed=53)
+    check_prefill(mla, w4, 150)
+
+
+def test_prefill_mha_matches_the_absorbed_calls_on_the_gpu(mla):
+    """Same inputs through both paradigms on the GPU (Sec. 3.3: the Absorb operation changes the
+    order of the products, not the function): equal within the bf16 roundings of either route."""
+    import torch
+    w = ragged_workload(H=16, lens=[200, 96, 40], seed=54)
+    T = 40
+    out, lse, qn_t, qr_t, d = check_prefill(mla, w, T)
+    q_abs = mla.absorb_q(qn_t.view(w.B * T, w.H, w.d_head), d.W_UK).view(w.B, T, w.H, w.d_c)
+    o_lat, lse_a = mla.decode_paged_multi(q_abs, qr_t, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                                          num_splits=2, return_lse=True)
+    out_a = mla.out_proj(o_lat.view(w.B * T, w.H, w.d_c), d.W_UV).view(w.B, T, w.H, w.d_head)
+    torch.cuda.synchronize()
+    assert max_abs_rel(widen_gpu(out), widen_gpu(out_a)) <= 2e-2
+    assert lse_err(widen_gpu(lse), widen_gpu(lse_a)) <= 2e-2
