@@ -69,6 +69,10 @@ def parse():
                     help="query tokens per sequence and step (multi-token prediction / speculative decoding); "
                          "above 1 the step uses mla_decode_paged_multi and mla_merge_out_proj_multi and is a "
                          "secondary row, not the headline metric")
+    ap.add_argument("--prefill-len", type=int, default=0,
+                    help="instead of the decode step, time mla_prefill_mha (MHA paradigm: keys and values "
+                         "materialised per head, causal attention) for this many newest tokens of every sequence "
+                         "of the workload (-1: the whole prompt); secondary row, MFMA roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
     ap.add_argument("--calib-copy", action="store_true",
@@ -95,6 +99,8 @@ def main():
     torch.cuda.set_device(0)
     mla.lib()
 
+    if args.prefill_len:
+        return prefill_main(args)
     args.balanced = args.partition == "balanced" or (args.partition == "auto" and args.workload == "C3")
     if args.balanced and args.partition == "auto" and not args.splits:
         args.splits = 4          # 64 sequences x 4 = one workgroup per CU
@@ -362,6 +368,61 @@ def main():
             "single_thread": {"value": round(t_one * (w.tokens / tok1) * 1e6, 1), "unit": "us/step", "cores": 1,
                               "sample": f"sequence 0 ({tok1} tokens, all {H} heads) = {t_one:.2f} s, scaled by tokens "
                                         f"{w.tokens}/{tok1}"}}
+    print(json.dumps(rec))
+
+
+def prefill_main(args):
+    """Secondary row: the MHA-paradigm prefill call on the workload's cache."""
+    import numpy as np
+    import torch
+    from helpers import DeviceWorkload, to_torch
+    from paper_2502_07864_amd import mla, synth
+
+    w = synth.config(args.workload)
+    assert w.io_dtype == "bf16" and w.cache_dtype == "bf16", "prefill runs on bf16 caches"
+    d = DeviceWorkload(w, "cuda:0")
+    B, H = w.B, w.H
+    T = int(w.seq_lens.max()) if args.prefill_len < 0 else args.prefill_len
+    qn, qr = synth.multi_queries(w, T)
+    qn_t, qr_t = to_torch(qn, "bf16", "cuda:0"), to_torch(qr, "bf16", "cuda:0")
+    ws = torch.empty(mla.prefill_workspace_bytes(B, H, w.d_c, w.max_pages_per_seq), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((B, T, H, w.d_head), dtype=torch.bfloat16, device="cuda:0")
+
+    def step():
+        mla.prefill_mha(qn_t, qr_t, d.W_UK, d.W_UV, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                        workspace=ws, out=out)
+    steps, warmup = max(1, min(args.steps, 20)), max(1, min(args.warmup, 3))
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    assert torch.isfinite(out.float()).all()
+    # algorithmic flops (Eq. "mha"): per (query, visible key, head) 2 (d_head + d_rope) + 2 d_head;
+    # materialisation per (key, head) 2 d_c * 2 d_head
+    lens = w.seq_lens.astype(np.int64)
+    i = np.arange(T, dtype=np.int64)
+    visible = np.maximum(lens[:, None] - (T - 1 - i)[None, :], 0).sum()
+    attn_flop = float(visible) * H * (2 * (w.d_head + w.d_rope) + 2 * w.d_head)
+    mat_flop = float(lens.sum()) * H * 2 * w.d_c * 2 * w.d_head
+    tflops = (attn_flop + mat_flop) / (ms * 1e-3) / 1e12
+    rec = {"metric": f"MLA prefill ms (MHA paradigm: materialise + causal attention), {args.workload} cache, "
+                     f"{T} newest tokens per sequence, 1 GPU",
+           "value": round(ms, 3), "unit": "ms/step", "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "ms_per_step": round(ms, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": WORKLOADS[args.workload], "batch": B, "q_len": T, "heads": H,
+                      "context_max": int(w.seq_lens.max())},
+           "tokens_per_s": round(B * T / (ms * 1e-3), 1),
+           "roofline": {"bound": "mfma", "kernel": "decode_mfma_wide_kernel<128, 192, 128, true> + prefill_materialise_kernel",
+                        "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": round(tflops / 2500.0, 4), "traffic": None,
+                        "algorithmic_flop_per_step": attn_flop + mat_flop,
+                        "timing": "wall clock around the whole call (weights, materialisation, attention), "
+                                  f"{steps} calls back to back"}}
     print(json.dumps(rec))
 
 

@@ -33,7 +33,6 @@ namespace mla {
 namespace {
 
 constexpr int WD_ROWS = 64;      // query rows per workgroup
-constexpr int WD_NBUF = 4;       // tiles in the LDS ring
 
 // DQ   = width of the first part of a query row (d_c in the absorbed form); the second part is the
 //        64 decoupled-rope values, and the score contraction runs over the first DQ + 64 columns of
@@ -47,10 +46,11 @@ constexpr int WD_NBUF = 4;       // tiles in the LDS ring
 // kernel: its "cached rows" are the keys and values materialised per (sequence, head),
 // [W^{UK}_h c_j ; k^R_j | W^{UV}_h c_j] = 128 + 64 | 128 values, one pseudo-sequence per (sequence,
 // head), whose query rows are the prompt's tokens (DQ = 128, VOFF = 192, DV = 128, FINAL).
-template <int DQ, int VOFF, int DV, bool FINAL>
-__global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeParams p)
+// NBUF = tiles in the LDS ring, WPE = workgroups per CU the register and LDS budgets are sized for
+//        (the absorbed form fills a CU with one workgroup; the prefill rows are short enough for two).
+template <int DQ, int VOFF, int DV, bool FINAL, int NBUF, int WPE>
+__global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(DecodeParams p)
 {
-    constexpr int NBUF = WD_NBUF;
     constexpr int ROW = DQ + 64 > VOFF + DV ? DQ + 64 : VOFF + DV;   // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
@@ -63,7 +63,8 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     constexpr int SG = NKS % 3 == 0 ? 3 : 2;    // k-steps per read-ahead group (score)
     constexpr int VG = 4;                       // column tiles per read-ahead group (value)
     constexpr int AH = 2;                       // groups the LDS reads run ahead of the MFMAs
-    static_assert(2 * NLOAD * 2 < 64, "vmcnt is a 6-bit counter");
+    static_assert((NBUF + 2) * NLOAD < 64, "vmcnt is a 6-bit counter");
+    static_assert(NBUF >= 3 && NBUF <= 4, "ring depth (the query rows take two slots at first)");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     __shared__ __attribute__((aligned(16))) unsigned char p_smem[2][WD_ROWS * 64];   // weights of two tiles
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
         return first;
     };
     auto wait_younger = [&](int younger) {
-        if (younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+        if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
         else if (younger >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
         else if (younger >= NLOAD)     wait_vmcnt<NLOAD>();
         else                           wait_vmcnt<0>();
@@ -517,8 +518,8 @@ hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s)
     const long long nchunk = (long long)p.B * p.num_splits, Z = (p.H + WD_ROWS - 1) / WD_ROWS;
     dim3 grid(p.B, p.num_splits), block(MF_THREADS);
     if (Z > 1) grid = dim3((unsigned)((nchunk + 7) / 8 * 8 * Z));
-    if (p.d_c == 512)      decode_mfma_wide_kernel<512, 0, 512, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_mfma_wide_kernel<256, 0, 256, false><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_mfma_wide_kernel<512, 0, 512, false, 4, 1><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_mfma_wide_kernel<256, 0, 256, false, 4, 1><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -531,7 +532,7 @@ hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s)
     const long long Z = (p.H + WD_ROWS - 1) / WD_ROWS;
     dim3 grid(p.B, 1), block(MF_THREADS);
     if (Z > 1) grid = dim3((unsigned)(((long long)p.B + 7) / 8 * 8 * Z));
-    decode_mfma_wide_kernel<128, 192, 128, true><<<grid, block, 0, s>>>(p);
+    decode_mfma_wide_kernel<128, 192, 128, true, 3, 2><<<grid, block, 0, s>>>(p);
     return hipGetLastError();
 }
 
