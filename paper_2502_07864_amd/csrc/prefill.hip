@@ -8,11 +8,12 @@
 //   prefill_weights_kernel      Wcat[h] = [W^{UK}_h ; W^{UV}_h] as 256 rows of d_c values each (the
 //                               value projection is stored k-major by the caller and is transposed
 //                               here once), so that both products read their weights row-wise.
-//   prefill_materialise_kernel  one workgroup per (page, sequence, head):
-//                               Y^T [256 x 64 tokens] = Wcat[h] [256 x d_c] . C^T [d_c x 64 tokens]
-//                               on v_mfma_f32_16x16x32_bf16; a wavefront owns 16 tokens, keeps
+//   prefill_materialise_kernel  one workgroup per (pair of pages, sequence, head):
+//                               Y^T [256 x 128 tokens] = Wcat[h] [256 x d_c] . C^T [d_c x 128 tokens]
+//                               on v_mfma_f32_16x16x32_bf16; a wavefront owns 32 tokens, keeps
 //                               their latent rows in registers as the B operand and walks the 16
-//                               row tiles of Wcat[h]; rows are rounded to bf16 and stored as
+//                               row tiles of Wcat[h], which all four wavefronts read from LDS;
+//                               rows are rounded to bf16 and stored as
 //                               [k_nope | k_rope (copied from the cache) | v].
 #include "mla_internal.h"
 #include "mfma_tile.h"
@@ -34,55 +35,112 @@ __global__ __launch_bounds__(256) void prefill_weights_kernel(const uint16_t* W_
                            : W_UV[((size_t)h * d_c + c) * PF_DH + (r - PF_DH)];       // W_UV[h] is [d_c x d_head]
 }
 
+// One workgroup = two pages (128 tokens) of one (sequence, head).  Wcat[h] is streamed through LDS
+// in chunks of 32 rows (two row tiles, all d_c columns), double-buffered, rows padded by 16 bytes so
+// that the 16 rows of an A read fall in different banks; the four wavefronts share every chunk.
+// A wavefront owns 32 tokens (two column tiles) and keeps their latent rows in registers.
 template <int D_C>
-__global__ __launch_bounds__(256) void prefill_materialise_kernel(const uint16_t* kv, const int32_t* page_table,
-                                                                  const int32_t* seq_lens, const uint16_t* Wcat,
-                                                                  uint16_t* pool2, int32_t* table2, int32_t* lens2,
-                                                                  int heads, int num_pages, int max_pages)
+__global__ __launch_bounds__(256, 2) void prefill_materialise_kernel(const uint16_t* kv, const int32_t* page_table,
+                                                                     const int32_t* seq_lens, const uint16_t* Wcat,
+                                                                     uint16_t* pool2, int32_t* table2, int32_t* lens2,
+                                                                     int heads, int num_pages, int max_pages)
 {
     constexpr int ROW = D_C + 64;
     constexpr int NKS = D_C / 32;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int WROWB = D_C * 2 + 16;               // padded bytes per weight row in LDS
+    constexpr int CHUNK_ROWS = 32;
+    constexpr int NCHUNK = 256 / CHUNK_ROWS;          // 8
+    constexpr int PIECES = CHUNK_ROWS * (D_C / 8);    // 16-byte pieces per chunk (2048 / 1024)
+    constexpr int NPL = PIECES / 256;                 // pieces per thread (8 / 4)
+    __shared__ __attribute__((aligned(16))) unsigned char wbuf[2][CHUNK_ROWS * WROWB];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    const int pg = blockIdx.x, bh = blockIdx.y;
+    const int bh = blockIdx.y;
     const int b = bh / heads, h = bh % heads;
     const int L = max(0, min(seq_lens[b], max_pages * 64));
-    if (pg == 0 && tid == 0) lens2[bh] = L;
-    if (pg * 64 >= L) return;
-    const int page = page_table[(size_t)b * max_pages + pg];
-    const bool valid = page >= 0 && page < num_pages;
+    if (blockIdx.x == 0 && tid == 0) lens2[bh] = L;
+    if (blockIdx.x * 128 >= L) return;
+
+    // this wavefront's page (waves 0, 1: the first of the pair; 2, 3: the second)
+    const int pg = blockIdx.x * 2 + (wave >> 1);
+    const bool in_seq = pg < max_pages && pg * 64 < L;
+    const int page = in_seq ? page_table[(size_t)b * max_pages + pg] : -1;
+    const bool active = in_seq && page >= 0 && page < num_pages;
     // the pseudo-sequence (b, h) owns pages [bh * max_pages, +max_pages) of the materialised pool;
     // a page id outside the cache pool is passed on as "skip these tokens"
     const size_t page2 = (size_t)bh * max_pages + pg;
-    if (tid == 0) table2[page2] = valid ? (int32_t)page2 : -1;
-    if (!valid) return;
-    const uint16_t* src = kv + (size_t)page * 64 * ROW;
-    uint16_t* dst = pool2 + page2 * 64 * PF_ROW;
+    if (in_seq && (wave & 1) == 0 && lane == 0) table2[page2] = active ? (int32_t)page2 : -1;
+    const uint16_t* src = kv + (size_t)(active ? page : 0) * 64 * ROW;
+    uint16_t* dst = pool2 + (active ? page2 : 0) * 64 * PF_ROW;
+    const int tok0 = (wave & 1) * 32;                 // this wavefront's first token inside its page
 
-    // decoupled-rope part of the key: copied as it is
-    for (int i = tid; i < 64 * 8; i += 256) {
-        const int tok = i >> 3, ch = i & 7;
-        *reinterpret_cast<u32x4*>(dst + tok * PF_ROW + PF_DH + ch * 8) =
-            *reinterpret_cast<const u32x4*>(src + tok * ROW + D_C + ch * 8);
-    }
-    // B operand: latent row of token 16 wave + n, k = 32 ks + 8g .. + 7
-    bf16x8 cb[NKS];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-        cb[ks] = *reinterpret_cast<const bf16x8*>(src + (wave * 16 + n) * ROW + ks * 32 + g * 8);
-    const uint16_t* W = Wcat + (size_t)h * 256 * D_C;
-    uint16_t* out_row = dst + (wave * 16 + n) * PF_ROW;
-#pragma unroll 2
-    for (int mt = 0; mt < 16; ++mt) {
-        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(W + (size_t)(mt * 16 + n) * D_C + ks * 32 + g * 8);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cb[ks], acc, 0, 0, 0);
+    bf16x8 cb[2][NKS];
+    if (active) {
+        // decoupled-rope part of the key: copied as it is (32 tokens x 8 pieces per wavefront)
+        for (int i = lane; i < 32 * 8; i += 64) {
+            const int tok = tok0 + (i >> 3), ch = i & 7;
+            *reinterpret_cast<u32x4*>(dst + tok * PF_ROW + PF_DH + ch * 8) =
+                *reinterpret_cast<const u32x4*>(src + tok * ROW + D_C + ch * 8);
         }
-        // D: rows 4g .. 4g+3 of row tile mt (output dimensions), column n (token)
-        const int col = mt < 8 ? mt * 16 + g * 4 : PF_DH + 64 + (mt - 8) * 16 + g * 4;
-        *reinterpret_cast<u32x2*>(out_row + col) = (u32x2){pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+        // B operands: latent rows of tokens tok0 + 16 nt + n, k = 32 ks + 8g .. + 7
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                cb[nt][ks] = *reinterpret_cast<const bf16x8*>(src + (tok0 + nt * 16 + n) * ROW + ks * 32 + g * 8);
+    }
+
+    const unsigned char* W = reinterpret_cast<const unsigned char*>(Wcat + (size_t)h * 256 * D_C);
+    u32x4 stage[NPL];
+    auto load_chunk = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int q = i * 256 + tid;
+            stage[i] = *reinterpret_cast<const u32x4*>(W + ((size_t)(c * CHUNK_ROWS) * D_C + (size_t)q * 8) * 2);
+        }
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int q = i * 256 + tid;
+            const int row = q / (D_C / 8), col = q % (D_C / 8);
+            *reinterpret_cast<u32x4*>(&wbuf[buf][row * WROWB + col * 16]) = stage[i];
+        }
+    };
+    load_chunk(0);
+    store_chunk(0);
+    __syncthreads();
+    for (int c = 0; c < NCHUNK; ++c) {
+        if (c + 1 < NCHUNK) load_chunk(c + 1);        // in flight while this chunk is used
+        if (active) {
+            f32x4 acc[2][2];
+#pragma unroll
+            for (int ml = 0; ml < 2; ++ml)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) acc[ml][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                for (int ml = 0; ml < 2; ++ml) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&wbuf[c & 1][(ml * 16 + n) * WROWB + ks * 64 + g * 16]);
+                    acc[ml][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cb[0][ks], acc[ml][0], 0, 0, 0);
+                    acc[ml][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cb[1][ks], acc[ml][1], 0, 0, 0);
+                }
+            // D: rows 4g .. 4g+3 of row tile mt = 2c + ml (output dimensions), column n (token)
+#pragma unroll
+            for (int ml = 0; ml < 2; ++ml) {
+                const int mt = c * 2 + ml;
+                const int col = mt < 8 ? mt * 16 + g * 4 : PF_DH + 64 + (mt - 8) * 16 + g * 4;
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    *reinterpret_cast<u32x2*>(dst + (tok0 + nt * 16 + n) * PF_ROW + col) =
+                        (u32x2){pack_bf16x2(acc[ml][nt][0], acc[ml][nt][1]), pack_bf16x2(acc[ml][nt][2], acc[ml][nt][3])};
+            }
+        }
+        if (c + 1 < NCHUNK) store_chunk((c + 1) & 1); // the other buffer: last read before the previous barrier
+        __syncthreads();
     }
 }
 
@@ -104,7 +162,7 @@ hipError_t launch_prefill_materialise(const void* kv, const int32_t* page_table,
                                                            static_cast<uint16_t*>(Wcat), d_c);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dim3 grid(max_pages, B * heads);
+    dim3 grid((max_pages + 1) / 2, B * heads);
     if (d_c == 512)
         prefill_materialise_kernel<512><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(kv), page_table, seq_lens,
                                                              static_cast<const uint16_t*>(Wcat), static_cast<uint16_t*>(pool2),
