@@ -64,7 +64,10 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     constexpr int VG = 4;                       // column tiles per read-ahead group (value)
     constexpr int AH = 2;                       // groups the LDS reads run ahead of the MFMAs
     static_assert((NBUF + 2) * NLOAD < 64, "vmcnt is a 6-bit counter");
-    static_assert(NBUF >= 3 && NBUF <= 4, "ring depth (the query rows take two slots at first)");
+    // FINAL (prefill): the query rows go straight from global memory to registers; the loops are
+    // long, so the start is not worth two ring slots and the ring may be as short as two tiles
+    constexpr bool QDIRECT = FINAL;
+    static_assert(NBUF <= 4 && NBUF >= (QDIRECT ? 2 : 3), "ring depth (staged query rows take two slots at first)");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     __shared__ __attribute__((aligned(16))) unsigned char p_smem[2][WD_ROWS * 64];   // weights of two tiles
@@ -114,7 +117,23 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     // row, same chunk swizzle, absent rows zero), travel through the last two ring slots
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     LDS_AS unsigned char* qslot = lds + (NBUF - 2) * TILE_B;
-    {
+    bf16x8 qreg[2][NKS];
+    if constexpr (QDIRECT) {
+        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs);
+        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope);
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+            const int row = hp * 32 + hi * 16 + n;
+            const size_t qrow = io_row(hb + min(row, HL - 1));
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const uint16_t* src = ks < DQ / 32 ? qa + qrow * DQ + ks * 32 + g * 8
+                                                   : qr + qrow * 64 + (ks - DQ / 32) * 32 + g * 8;
+                const uint4 v = *reinterpret_cast<const uint4*>(src);
+                qreg[hi][ks] = __builtin_bit_cast(bf16x8, row < HL ? v : make_uint4(0u, 0u, 0u, 0u));
+            }
+        }
+    } else {
         const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs);
         const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope);
         const size_t q_row0 = io_row(hb);
@@ -233,6 +252,14 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     };
 
     // ---- query rows -> registers (B operands of the score contraction, resident for the chunk)
+    if constexpr (QDIRECT) {
+        start_ring(NBUF);
+        // pin the completion of the query loads here, outside the tile loop
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[hi][ks]));
+    } else {
     const int first_issued = start_ring(NBUF - 2);
     {
         int later = first_issued;
@@ -241,7 +268,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
         wait_younger(later);     // the query rows only: the tile loads requested after them stay in flight
     }
     __syncthreads();
-    bf16x8 qreg[2][NKS];
     {
         const uint32_t q_key = (uint32_t)swz_key(n);
 #pragma unroll
@@ -257,6 +283,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
 #pragma unroll
     for (int i = NBUF - 3; i < NBUF - 1; ++i) ahead[i] = t0 + 1 + i < t1 ? fetch_tile(t0 + 1 + i) : 0;
     ring_full = true;
+    }
 
     // ---- per-lane state.  Score phase: this lane's query rows = column n of the two D tiles.
     const int head0 = hp * 32 + n;                    // + 16 hi; local to the workgroup
@@ -532,7 +559,7 @@ hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s)
     const long long Z = (p.H + WD_ROWS - 1) / WD_ROWS;
     dim3 grid(p.B, 1), block(MF_THREADS);
     if (Z > 1) grid = dim3((unsigned)(((long long)p.B + 7) / 8 * 8 * Z));
-    decode_mfma_wide_kernel<128, 192, 128, true, 3, 2><<<grid, block, 0, s>>>(p);
+    decode_mfma_wide_kernel<128, 192, 128, true, 2, 3><<<grid, block, 0, s>>>(p);
     return hipGetLastError();
 }
 
