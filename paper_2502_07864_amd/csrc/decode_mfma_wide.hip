@@ -33,41 +33,24 @@ namespace mla {
 namespace {
 
 constexpr int WD_ROWS = 64;      // query rows per workgroup
+constexpr int WD_NBUF = 4;       // tiles in the LDS ring
 
-// DQ   = width of the first part of a query row (d_c in the absorbed form); the second part is the
-//        64 decoupled-rope values, and the score contraction runs over the first DQ + 64 columns of
-//        a cached row.
-// VOFF, DV = first column and width of the value part of a cached row (0, d_c in the absorbed form:
-//        the values are the latent rows themselves).
-// FINAL = false: the chunk's partial result goes to the split-KV workspace (fp32, merged later).
-//         true : one chunk per sequence; the normalised result is rounded to bf16 and stored where
-//                the query row came from (o_final), no merge.
-// The MHA-paradigm prefill (Sec. 3.3, first of the two attention equations) runs on the same
-// kernel: its "cached rows" are the keys and values materialised per (sequence, head),
-// [W^{UK}_h c_j ; k^R_j | W^{UV}_h c_j] = 128 + 64 | 128 values, one pseudo-sequence per (sequence,
-// head), whose query rows are the prompt's tokens (DQ = 128, VOFF = 192, DV = 128, FINAL).
-// NBUF = tiles in the LDS ring, WPE = workgroups per CU the register and LDS budgets are sized for
-//        (the absorbed form fills a CU with one workgroup; the prefill rows are short enough for two).
-template <int DQ, int VOFF, int DV, bool FINAL, int NBUF, int WPE>
-__global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(DecodeParams p)
+template <int D_C>
+__global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeParams p)
 {
-    constexpr int ROW = DQ + 64 > VOFF + DV ? DQ + 64 : VOFF + DV;   // elements per cache row
+    constexpr int NBUF = WD_NBUF;
+    constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
     constexpr int PAGE_B = 64 * ROWB;           // bytes per page
     constexpr int TILE_B = TILE_ROWS * ROWB;    // bytes per tile
     constexpr int NLOAD = TILE_B / (MF_THREADS * 16);  // 16-byte loads per thread per tile (9 / 5)
-    constexpr int NKS = (DQ + 64) / 32;         // k-steps of the score contraction (18 / 10 / 6)
-    constexpr int CTW = DV / 32;                // column tiles of the value contraction per wavefront (16 / 8 / 4)
-    static_assert(VOFF % 64 == 0 && DV % 64 == 0 && DQ % 64 == 0, "parts of a row start on whole swizzle groups");
+    constexpr int NKS = ROW / 32;               // k-steps of the score contraction (18 / 10)
+    constexpr int CTW = D_C / 32;               // column tiles of the value contraction per wavefront (16 / 8)
     constexpr int SG = NKS % 3 == 0 ? 3 : 2;    // k-steps per read-ahead group (score)
     constexpr int VG = 4;                       // column tiles per read-ahead group (value)
     constexpr int AH = 2;                       // groups the LDS reads run ahead of the MFMAs
-    static_assert((NBUF + 2) * NLOAD < 64, "vmcnt is a 6-bit counter");
-    // FINAL (prefill): the query rows go straight from global memory to registers; the loops are
-    // long, so the start is not worth two ring slots and the ring may be as short as two tiles
-    constexpr bool QDIRECT = FINAL;
-    static_assert(NBUF <= 4 && NBUF >= (QDIRECT ? 2 : 3), "ring depth (staged query rows take two slots at first)");
+    static_assert(2 * NLOAD * 2 < 64, "vmcnt is a 6-bit counter");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     __shared__ __attribute__((aligned(16))) unsigned char p_smem[2][WD_ROWS * 64];   // weights of two tiles
@@ -99,12 +82,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     const int hb = zi * WD_ROWS;
     const int HL = min(WD_ROWS, p.H - hb);     // query rows of this workgroup
 
-    auto o_row = [&](int h) -> float* { return p.o_part + part_index(b, h, split, p.H, p.num_splits) * DV; };
-    // Index of query row h of this (pseudo-)sequence in the caller's q and output arrays.  Absorbed
-    // decode: the rows of a sequence are adjacent (q_inner = 1).  Prefill: sequence b stands for
-    // (sequence b / q_inner, head b % q_inner) and its rows (tokens) are q_inner rows apart.
-    const size_t io_base = (size_t)(b / p.q_inner) * p.H * p.q_inner + (size_t)(b % p.q_inner);
-    auto io_row = [&](int h) -> size_t { return io_base + (size_t)h * p.q_inner; };
+    auto o_row = [&](int h) -> float* { return p.o_part + part_index(b, h, split, p.H, p.num_splits) * D_C; };
     auto lse_at = [&](int h) -> float* { return p.lse_part + part_index(b, h, split, p.H, p.num_splits); };
 
     // read-only tables through the scalar cache (no vector-memory counter involved)
@@ -117,36 +95,17 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     // row, same chunk swizzle, absent rows zero), travel through the last two ring slots
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     LDS_AS unsigned char* qslot = lds + (NBUF - 2) * TILE_B;
-    bf16x8 qreg[2][NKS];
-    if constexpr (QDIRECT) {
-        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs);
-        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope);
-#pragma unroll
-        for (int hi = 0; hi < 2; ++hi) {
-            const int row = hp * 32 + hi * 16 + n;
-            const size_t qrow = io_row(hb + min(row, HL - 1));
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                const uint16_t* src = ks < DQ / 32 ? qa + qrow * DQ + ks * 32 + g * 8
-                                                   : qr + qrow * 64 + (ks - DQ / 32) * 32 + g * 8;
-                const uint4 v = *reinterpret_cast<const uint4*>(src);
-                qreg[hi][ks] = __builtin_bit_cast(bf16x8, row < HL ? v : make_uint4(0u, 0u, 0u, 0u));
-            }
-        }
-    } else {
-        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs);
-        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope);
-        const size_t q_row0 = io_row(hb);
+    {
+        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
+        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
         const uint32_t dst = lds_base + (uint32_t)((NBUF - 2) * TILE_B + wave * 1024);
 #pragma unroll
         for (int k = 0; k < 2 * NLOAD; ++k) {
             const int P = (k * 4 + wave) * 64 + lane;
             const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
-            if (c >= (DQ + 64) / 8) continue;      // columns past the score part are never read from a query row
             if (r < HL) {
-                const size_t qrow = q_row0 + (size_t)r * p.q_inner;
-                const unsigned char* gp = c < DQ / 8 ? qa + (qrow * DQ + c * 8) * 2
-                                                     : qr + (qrow * 64 + (c - DQ / 8) * 8) * 2;
+                const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
+                                                      : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
                 const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
                 asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                              :: "s"(m0v), "v"(gp) : "memory");
@@ -162,14 +121,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     // one past its last row that some query row of this workgroup sees (the query rows are ordered
     // by token, so the last one sees the most)
     const int row1 = min(min(row0 + p.chunk_pages * 64, L), visible_rows(p, L, min(hb + WD_ROWS, p.H) - 1));
-    if (row0 >= row1) {  // nothing to see
-        if constexpr (FINAL) {   // the result itself: zeros and -inf
-            for (int i = tid; i < HL * (DV / 4); i += MF_THREADS)
-                *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.o_final) + io_row(hb + i / (DV / 4)) * DV + (i % (DV / 4)) * 4) = (u32x2){0u, 0u};
-            if (tid < HL && p.lse_final) p.lse_final[io_row(hb + tid)] = -INFINITY;
-        } else {                 // weight zero in the merge, partial output never read
-            if (tid < HL) *lse_at(hb + tid) = -INFINITY;
-        }
+    if (row0 >= row1) {  // nothing to see: weight zero in the merge, partial output never read
+        if (tid < HL) *lse_at(hb + tid) = -INFINITY;
         wait_vmcnt<0>();  // the workgroup's LDS must not be released with loads into it in flight
         return;
     }
@@ -220,7 +173,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
         return first;
     };
     auto wait_younger = [&](int younger) {
-        if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+        if (younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
         else if (younger >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
         else if (younger >= NLOAD)     wait_vmcnt<NLOAD>();
         else                           wait_vmcnt<0>();
@@ -252,14 +205,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     };
 
     // ---- query rows -> registers (B operands of the score contraction, resident for the chunk)
-    if constexpr (QDIRECT) {
-        start_ring(NBUF);
-        // pin the completion of the query loads here, outside the tile loop
-#pragma unroll
-        for (int hi = 0; hi < 2; ++hi)
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[hi][ks]));
-    } else {
     const int first_issued = start_ring(NBUF - 2);
     {
         int later = first_issued;
@@ -268,6 +213,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
         wait_younger(later);     // the query rows only: the tile loads requested after them stay in flight
     }
     __syncthreads();
+    bf16x8 qreg[2][NKS];
     {
         const uint32_t q_key = (uint32_t)swz_key(n);
 #pragma unroll
@@ -283,7 +229,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
 #pragma unroll
     for (int i = NBUF - 3; i < NBUF - 1; ++i) ahead[i] = t0 + 1 + i < t1 ? fetch_tile(t0 + 1 + i) : 0;
     ring_full = true;
-    }
 
     // ---- per-lane state.  Score phase: this lane's query rows = column n of the two D tiles.
     const int head0 = hp * 32 + n;                    // + 16 hi; local to the workgroup
@@ -310,7 +255,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8) +
-                    (uint32_t)(VOFF * 2 + a * DV);   // value part; column half a starts DV/2 elements = DV bytes into it
+                    (uint32_t)(a * D_C);     // column half a starts d_c/2 elements = d_c bytes into the row
 
     // S^T for this wave's 16 tile rows x 32 query rows, log2 units, rows a query row must not see
     // (or that are not there) at -inf; lmax = maximum over this lane's 4 tile rows per query row
@@ -491,7 +436,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
     }
     // transpose through LDS (a lane holds 4 consecutive columns of query row n per column tile,
     // which written straight out would give 16-byte pieces) and store whole runs
-    constexpr int CW = DV / 2;                  // columns per wavefront
+    constexpr int CW = D_C / 2;                 // columns per wavefront
     constexpr int RSO = CW * 4 + 16;            // row stride of the transposed block (padded)
     static_assert(4 * 32 * RSO <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* mine = lds + wave * (32 * RSO);
@@ -508,26 +453,15 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_wide_kernel(Decod
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
             f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            if constexpr (FINAL) {
-                uint16_t* dst = static_cast<uint16_t*>(p.o_final) + io_row(hb + hp * 32 + r) * DV + a * CW + c * 4;
-                *reinterpret_cast<u32x2*>(dst) = (u32x2){pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-            } else {
-                float* dst = o_row(hb + hp * 32 + r) + a * CW + c * 4;
-                __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
-            }
+            float* dst = o_row(hb + hp * 32 + r) + a * CW + c * 4;
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
         }
     }
     if (a == 0 && g == 0) {
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi)
-            if (head0 + hi * 16 < HL) {
-                const float l = lt[hi] > 0.f ? (m_ref[hi] + __builtin_amdgcn_logf(lt[hi])) * LN2 : -INFINITY;
-                if constexpr (FINAL) {
-                    if (p.lse_final) p.lse_final[io_row(hb + head0 + hi * 16)] = l;
-                } else {
-                    *lse_at(hb + head0 + hi * 16) = l;
-                }
-            }
+            if (head0 + hi * 16 < HL)
+                *lse_at(hb + head0 + hi * 16) = lt[hi] > 0.f ? (m_ref[hi] + __builtin_amdgcn_logf(lt[hi])) * LN2 : -INFINITY;
     }
 }
 
@@ -545,21 +479,9 @@ hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s)
     const long long nchunk = (long long)p.B * p.num_splits, Z = (p.H + WD_ROWS - 1) / WD_ROWS;
     dim3 grid(p.B, p.num_splits), block(MF_THREADS);
     if (Z > 1) grid = dim3((unsigned)((nchunk + 7) / 8 * 8 * Z));
-    if (p.d_c == 512)      decode_mfma_wide_kernel<512, 0, 512, false, 4, 1><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_mfma_wide_kernel<256, 0, 256, false, 4, 1><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_mfma_wide_kernel<512><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_mfma_wide_kernel<256><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-// Causal attention over materialised keys and values (rows [k 128 + 64 | v 128]): p.B pseudo-sequences
-// of p.H query rows each, one chunk per sequence, results straight to o_final / lse_final.
-hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s)
-{
-    if (p.num_splits != 1 || !p.o_final || p.heads != 1) return hipErrorInvalidValue;
-    const long long Z = (p.H + WD_ROWS - 1) / WD_ROWS;
-    dim3 grid(p.B, 1), block(MF_THREADS);
-    if (Z > 1) grid = dim3((unsigned)(((long long)p.B + 7) / 8 * 8 * Z));
-    decode_mfma_wide_kernel<128, 192, 128, true, 2, 3><<<grid, block, 0, s>>>(p);
     return hipGetLastError();
 }
 

@@ -129,7 +129,7 @@ bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
 bool       decode_mfma_wide_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s);   // 64 query rows per workgroup
-hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s);  // same kernel over materialised keys / values
+hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s);  // causal attention over materialised keys / values
 // prefill: materialise [W_UK c ; k_rope | W_UV c] per (sequence, head) into a pool of its own
 bool       prefill_supported(int d_head, int d_c, int d_rope, int page_size, mla_dtype io, mla_dtype cache);
 hipError_t launch_prefill_materialise(const void* kv, const int32_t* page_table, const int32_t* seq_lens,
