@@ -39,6 +39,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void prefill_attention_kernel(Deco
     constexpr int NLOAD = TILE_B / (MF_THREADS * 16);   // 5
     constexpr int NKS = PA_DK / 32;             // 6 k-steps of the score contraction
     constexpr int NCT = PA_DV / 16;             // 8 column tiles of the value contraction
+    constexpr int VGR = 2;                      // column tiles per read-ahead group (value)
     static_assert(NBUF >= 2 && NBUF <= 4 && (NBUF + 1) * NLOAD < 64, "ring depth; vmcnt is a 6-bit counter");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
@@ -274,21 +275,21 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void prefill_attention_kernel(Deco
         }
         s16x4 lo[NCT], up[NCT];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < VGR; ++ct) {
             lo[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
             up[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128 + 16 * ROWB));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c0 = 0; c0 < NCT; c0 += 4) {
+        for (int c0 = 0; c0 < NCT; c0 += VGR) {
 #pragma unroll
-            for (int ct = c0 + 4; ct < c0 + 8 && ct < NCT; ++ct) {
+            for (int ct = c0 + VGR; ct < c0 + 2 * VGR && ct < NCT; ++ct) {
                 lo[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128));
                 up[ct] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(tile + v_base[ct & 3] + (ct >> 2) * 128 + 16 * ROWB));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ct = c0; ct < c0 + 4 && ct < NCT; ++ct) {
+            for (int ct = c0; ct < c0 + VGR && ct < NCT; ++ct) {
                 const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[ct], up[ct], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int hi = 0; hi < 2; ++hi)

@@ -920,3 +920,35 @@ def test_prefill_mha_matches_the_absorbed_calls_on_the_gpu(mla):
     torch.cuda.synchronize()
     assert max_abs_rel(widen_gpu(out), widen_gpu(out_a)) <= 2e-2
     assert lse_err(widen_gpu(lse), widen_gpu(lse_a)) <= 2e-2
+
+
+def test_prefill_mha_empty_sequence_and_dominant_late_key(mla):
+    """seq_len 0 gives zeros and -inf.  A key whose score lies far above the first tile's maximum,
+    met late, sends the attention kernel through its second route (exact maxima first): queries
+    built from that key's own materialised k = W_UK c, checked against the oracle."""
+    import torch
+    w = ragged_workload(H=4, lens=[0, 200, 70], seed=55)
+    out, lse, _, _, _ = check_prefill(mla, w, 70)
+    assert not widen_gpu(out)[0].any() and np.isneginf(widen_gpu(lse)[0]).all()
+    # queries of every token = 10 x k_nope of row 150 of sequence 1 (row 50 of sequence 2), per head: its score lies
+    # ~90 powers of two above the first tile's maximum (more would only amplify the bf16 rounding of the keys)
+    T = 70
+    d = DeviceWorkload(w)
+    rows = oracle.widen(oracle.gather_paged(w.pool, w.page_table, w.seq_lens, 200).view(np.uint16))   # [B, 200, 576]
+    Wk = oracle.widen(w.W_UK)                                                                         # [H, 128, 512]
+    qn = np.zeros((3, T, 4, 128), dtype=np.float32)
+    qn[1] = 10.0 * np.einsum("hdc,c->hd", Wk, rows[1, 150, :512])[None]
+    qn[2] = 10.0 * np.einsum("hdc,c->hd", Wk, rows[2, 50, :512])[None]
+    qn_bits = synth.to_bf16_bits(qn)
+    qr = np.zeros((3, T, 4, 64), dtype=np.float32)
+    out, lse = mla.prefill_mha(to_torch(qn_bits, "bf16"), to_torch(synth.to_bf16_bits(qr), "bf16"), d.W_UK, d.W_UV,
+                               d.pool, d.page_table, d.seq_lens, w.softmax_scale, return_lse=True)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.prefill_explicit(qn_bits, synth.to_bf16_bits(qr), w.W_UK, w.W_UV, w.pool, None, w.page_table,
+                                           w.seq_lens, w.softmax_scale, w.d_c)
+    got = widen_gpu(out)
+    assert np.isfinite(got).all()
+    assert max_abs_rel(got, ref) <= TOL["bf16"]
+    fin = np.isfinite(ref_lse)
+    assert (np.isfinite(widen_gpu(lse)) == fin).all()
+    assert np.abs(widen_gpu(lse)[fin] - ref_lse[fin]).max() <= 2e-2 * np.abs(ref_lse[fin]).max()
