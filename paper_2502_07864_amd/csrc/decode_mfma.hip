@@ -34,11 +34,11 @@
 // transposes 4x16 blocks of 16-bit elements while reading LDS.
 //
 // LDS layout: row r of a tile occupies bytes [r*ROWB, (r+1)*ROWB); inside a row,
-// 16-byte chunk c is stored at chunk position c ^ key(r), key(r) = a 3-bit
-// permutation of row bits 1..3 (see swz_key).  ROWB is 32 banks mod 64, so row
-// parity picks the bank half and the key spreads the rest: the row-wise 128-bit
-// reads of 16 consecutive rows hit 16 different bank groups, and each half-wave
-// of a transposing read (8 rows x 32 bytes) covers all 64 banks once.
+// 16-byte chunk c is stored at chunk position c ^ key(r), key(r) = r & 6 (see swz_key for
+// the bank rule it answers).  ROWB is 128 bytes mod 256, so row parity picks the half of the
+// 256-byte bank window and the key spreads the rest: the row-wise 128-bit reads of the score
+// contraction run conflict-free, and a transposing read (4 rows x 32 bytes per 16 lanes) covers
+// 16 different 8-byte units.
 #include "mla_internal.h"
 #include "mfma_tile.h"
 #include <type_traits>

@@ -30,11 +30,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
 }
 
-// chunk swizzle key of tile row r: bits (r2, r1, r3).  Rows r and r+2 differ in bit 1 of the
-// key (different 32-byte block), rows r and r+4 in bit 2, rows r and r+8 in bit 0.
+// Chunk swizzle key of tile row r: row bits 2 and 1, as bits 2 and 1 of the key (r & 6).  Chunk c of
+// row r sits at chunk position c ^ key(r) of the row in LDS.
+// Measured on gfx950: a 128-bit LDS read is served 16 lanes per cycle, and the 16 lanes that share
+// a cycle are two blocks of 8 consecutive lanes, blocks (0, 3), (1, 2), (4, 7), (5, 6) of the
+// wavefront; they must fall into 16 different 16-byte units of a 256-byte window.  The rows of a
+// tile are 1152 or 640 bytes long (128 mod 256), so a row's parity picks the half of the window; the
+// score reads (lane 16g + n: row n, chunk 4e + g) then need { key(n) : n in a block of 8 rows,
+// each parity } to take four different even values, and the partner block (g + 1, the other 8
+// rows) lands on the odd positions by itself.  With a key that also used bit 3 of the row (as an
+// earlier version did) the two blocks of a cycle collided two-way and every score read took twice
+// as long (32 instead of 17 cycles per instruction and wavefront).  The transposing 64-bit reads
+// (4 rows x 32 bytes per 16 lanes) take ~26 cycles per instruction with either key.
 __device__ __forceinline__ constexpr int swz_key(int r)
 {
-    return (((r >> 2) & 1) << 2) | (((r >> 1) & 1) << 1) | ((r >> 3) & 1);
+    return r & 6;
 }
 
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
