@@ -193,8 +193,10 @@ int mla_decode_paged(const void* q_abs, const void* q_rope,
  *              mla_merge_partials.  mla_absorb_q and mla_out_proj take the
  *              query tokens as a batch of B * q_len.
  * Everything else as for mla_decode_paged, which is this call with q_len 1.
- * The cached rows are read from HBM once per group of 32 query rows
- * (q_len * heads / 32 times in all).  q_len * heads <= 1024.
+ * BF16 caches with the uniform partition: 64 query rows (e.g. two tokens of
+ * 32 heads) share one pass over the cached rows; further groups of 64 rows run
+ * beside the first on the same XCD and find the rows in its L2.  FP8 caches
+ * and MLA_FLAG_BALANCED: groups of 32 query rows.  q_len * heads <= 1024.
  */
 int mla_decode_paged_multi(const void* q_abs, const void* q_rope,
                            const void* kv_cache, const float* kv_scale,
