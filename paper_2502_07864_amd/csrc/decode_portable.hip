@@ -16,7 +16,8 @@ constexpr int PT_THREADS = 256;
 constexpr int PT_HG = 8;        // heads per workgroup
 constexpr int PT_TOK = 16;      // cached rows per tile
 constexpr int PT_MAX_ROW = 576; // max d_c + d_rope
-constexpr int PT_PAD = 1;       // LDS row padding (floats): rows start in different banks
+constexpr int PT_PAD = 4;       // LDS row padding (floats): rows stay 16-byte aligned (128-bit reads) and
+                                // consecutive rows start one 16-byte unit apart
 constexpr int PT_MAX_COLS = 2;  // d_c <= 512 = 2 * 256 threads
 
 template <typename T> struct Load8;
@@ -57,24 +58,28 @@ template <> struct Load8<fp8_tag> {
     }
 };
 
-template <typename QT> __device__ __forceinline__ float load_q(const void* p, size_t i);
-template <> __device__ __forceinline__ float load_q<float>(const void* p, size_t i)
+// four consecutive query values (element index a multiple of 4)
+template <typename QT> __device__ __forceinline__ float4 load_q4(const void* p, size_t i);
+template <> __device__ __forceinline__ float4 load_q4<float>(const void* p, size_t i)
 {
-    return static_cast<const float*>(p)[i];
+    return *reinterpret_cast<const float4*>(static_cast<const float*>(p) + i);
 }
-template <> __device__ __forceinline__ float load_q<bf16_tag>(const void* p, size_t i)
+template <> __device__ __forceinline__ float4 load_q4<bf16_tag>(const void* p, size_t i)
 {
-    return bf16_bits_to_f32(static_cast<const uint16_t*>(p)[i]);
+    const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p) + i);
+    return make_float4(bf16_bits_to_f32(v.x & 0xFFFFu), bf16_bits_to_f32(v.x >> 16),
+                       bf16_bits_to_f32(v.y & 0xFFFFu), bf16_bits_to_f32(v.y >> 16));
 }
 
 template <typename QT, typename CT>
 __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParams p)
 {
-    __shared__ float q_s[PT_HG][PT_MAX_ROW + PT_PAD];
-    __shared__ float k_s[PT_TOK][PT_MAX_ROW + PT_PAD];
-    __shared__ float s_s[PT_HG][PT_TOK];
-    __shared__ float p_s[PT_HG][PT_TOK];
-    __shared__ float alpha_s[PT_HG], m_s[PT_HG], l_s[PT_HG];
+    __shared__ __attribute__((aligned(16))) float q_s[PT_HG][PT_MAX_ROW + PT_PAD];
+    __shared__ __attribute__((aligned(16))) float k_s[PT_TOK][PT_MAX_ROW + PT_PAD];
+    __shared__ __attribute__((aligned(16))) float s_s[PT_HG][PT_TOK];
+    __shared__ __attribute__((aligned(16))) float p_s[PT_TOK][PT_HG];     // weights, token-major: the 8 heads of a token are adjacent
+    __shared__ __attribute__((aligned(16))) float alpha_s[PT_HG];
+    __shared__ float m_s[PT_HG], l_s[PT_HG];
     __shared__ int valid_s[PT_TOK];
 
     const int tid = threadIdx.x;
@@ -93,16 +98,30 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         return;
     }
 
-    // query rows [q_abs | q_rope] of this head group -> LDS (fp32)
-    for (int idx = tid; idx < PT_HG * row; idx += PT_THREADS) {
-        int h = idx / row, k = idx % row;
-        float v = 0.f;
-        if (h < nh) {
-            size_t bh = (size_t)b * p.H + h0 + h;
-            v = k < p.d_c ? load_q<QT>(p.q_abs, bh * p.d_c + k)
-                          : load_q<QT>(p.q_rope, bh * p.d_rope + (k - p.d_c));
+    // query rows [q_abs | q_rope] of this head group -> LDS (fp32), four values per load, all of a
+    // thread's loads requested before the first is used (one after the other they would each wait
+    // out the memory latency)
+    {
+        constexpr int PT_NQ = (PT_HG * (PT_MAX_ROW / 4) + PT_THREADS - 1) / PT_THREADS;   // 5
+        const int q4_per_row = row / 4;
+        float4 qv[PT_NQ];
+#pragma unroll
+        for (int i = 0; i < PT_NQ; ++i) {
+            const int idx = tid + i * PT_THREADS;
+            const int h = idx / q4_per_row, k = (idx % q4_per_row) * 4;
+            qv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (h < nh) {
+                const size_t bh = (size_t)b * p.H + h0 + h;
+                qv[i] = k < p.d_c ? load_q4<QT>(p.q_abs, bh * p.d_c + k)
+                                  : load_q4<QT>(p.q_rope, bh * p.d_rope + (k - p.d_c));
+            }
         }
-        q_s[h][k] = v;
+#pragma unroll
+        for (int i = 0; i < PT_NQ; ++i) {
+            const int idx = tid + i * PT_THREADS;
+            const int h = idx / q4_per_row, k = (idx % q4_per_row) * 4;
+            if (h < PT_HG) *static_cast<float4*>(__builtin_assume_aligned(&q_s[h][k], 16)) = qv[i];
+        }
     }
     if (tid < PT_HG) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; }
 
@@ -113,68 +132,97 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         for (int h = 0; h < PT_HG; ++h) acc[i][h] = 0.f;
 
     const int chunks_per_row = row / 8;
-    // softmax step (one thread per head): the head's own upper limit of the sum (several query
+    // softmax step (16 threads per head): the head's own upper limit of the sum (several query
     // tokens per sequence)
-    const int my_limit = visible_rows(p, L, h0 + min(tid, PT_HG - 1));
-    for (int t0 = j0; t0 < j1; t0 += PT_TOK) {
-        __syncthreads();  // previous tile fully consumed (and q_s / m_s written)
-        // ---- stage the tile: widen to fp32; rows outside the chunk or on a bad page are zero
-        for (int idx = tid; idx < PT_TOK * chunks_per_row; idx += PT_THREADS) {
-            int t = idx / chunks_per_row, c8 = (idx % chunks_per_row) * 8;
-            int j = t0 + t;
-            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            bool ok = j < j1;
+    const int my_limit = visible_rows(p, L, h0 + min(tid / PT_TOK, PT_HG - 1));
+    // ---- tile staging, one tile ahead in registers: a thread owns up to PT_NIT pieces (8 values of one
+    // row) of every tile; the next tile's pieces are requested before the current tile is used, so
+    // their latency runs under its arithmetic.  Rows outside the chunk or on a bad page are zero.
+    constexpr int PT_NIT = (PT_TOK * (PT_MAX_ROW / 8) + PT_THREADS - 1) / PT_THREADS;   // 5
+    int st_t[PT_NIT], st_c[PT_NIT];          // row of the tile and first column of each piece (-1: none)
+#pragma unroll
+    for (int i = 0; i < PT_NIT; ++i) {
+        const int idx = tid + i * PT_THREADS;
+        st_t[i] = idx < PT_TOK * chunks_per_row ? idx / chunks_per_row : -1;
+        st_c[i] = (idx % chunks_per_row) * 8;
+    }
+    float st_v[PT_NIT][8];
+    bool st_ok[PT_NIT];
+    auto fetch = [&](int t0) {
+#pragma unroll
+        for (int i = 0; i < PT_NIT; ++i) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st_v[i][e] = 0.f;
+            const int j = t0 + st_t[i];
+            bool ok = st_t[i] >= 0 && j < j1;
             if (ok) {
-                int page = p.page_table[(size_t)b * p.max_pages + j / p.page_size];
+                const int page = p.page_table[(size_t)b * p.max_pages + j / p.page_size];
                 ok = page >= 0 && page < p.num_pages;
                 if (ok) {
-                    size_t r = (size_t)page * p.page_size + (j % p.page_size);
-                    Load8<CT>::run(p.kv, r * row + c8, p.kv_scale, r, v);
+                    const size_t r = (size_t)page * p.page_size + (j % p.page_size);
+                    Load8<CT>::run(p.kv, r * row + st_c[i], p.kv_scale, r, st_v[i]);
                 }
             }
-            if (c8 == 0) valid_s[t] = ok ? 1 : 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) k_s[t][c8 + i] = v[i];
+            st_ok[i] = ok;
         }
+    };
+    fetch(j0);
+    for (int t0 = j0; t0 < j1; t0 += PT_TOK) {
+        __syncthreads();  // previous tile fully consumed (and q_s / m_s written)
+#pragma unroll
+        for (int i = 0; i < PT_NIT; ++i) {
+            if (st_t[i] >= 0) {
+                if (st_c[i] == 0) valid_s[st_t[i]] = st_ok[i] ? 1 : 0;
+                float4* dst = static_cast<float4*>(__builtin_assume_aligned(&k_s[st_t[i]][st_c[i]], 16));
+                dst[0] = make_float4(st_v[i][0], st_v[i][1], st_v[i][2], st_v[i][3]);
+                dst[1] = make_float4(st_v[i][4], st_v[i][5], st_v[i][6], st_v[i][7]);
+            }
+        }
+        if (t0 + PT_TOK < j1) fetch(t0 + PT_TOK);
         __syncthreads();
         // ---- scores: (head, token) pair per two threads, each half of the row
         if (tid < PT_HG * PT_TOK * 2) {
             int pair = tid >> 1, half = tid & 1;
             int h = pair / PT_TOK, t = pair % PT_TOK;
             int kb = half * (row / 2), ke = kb + row / 2;
-            float dot = 0.f;
-            for (int k = kb; k < ke; ++k) dot = fmaf(q_s[h][k], k_s[t][k], dot);
+            // 128-bit LDS reads (an LDS instruction costs the wavefront ~17 cycles of issue whatever
+            // its width), four partial sums
+            float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+#pragma unroll 8
+            for (int k = kb; k < ke; k += 4) {
+                // (rows are 16-byte aligned and row / 2 is a multiple of 4 values: said out loud, or the
+                // compiler falls back to 64-bit reads)
+                const float4 qv = *static_cast<const float4*>(__builtin_assume_aligned(&q_s[h][k], 16));
+                const float4 kv4 = *static_cast<const float4*>(__builtin_assume_aligned(&k_s[t][k], 16));
+                d0 = fmaf(qv.x, kv4.x, d0); d1 = fmaf(qv.y, kv4.y, d1);
+                d2 = fmaf(qv.z, kv4.z, d2); d3 = fmaf(qv.w, kv4.w, d3);
+            }
+            float dot = (d0 + d1) + (d2 + d3);
             dot += __shfl_xor(dot, 1);
             if (half == 0) s_s[h][t] = valid_s[t] ? dot * p.scale : -INFINITY;
         }
         __syncthreads();
-        // ---- running softmax, one thread per head
-        if (tid < PT_HG) {
-            int h = tid;
-            float m_old = m_s[h], tmax = -INFINITY;
-            float sv[PT_TOK];
+        // ---- running softmax: one thread per (head, token) of the tile, the 16 lanes of a head side
+        // by side in one wavefront (maximum and sum by lane shuffles)
+        if (tid < PT_HG * PT_TOK) {
+            const int h = tid / PT_TOK, t = tid % PT_TOK;
+            const float sv = t0 + t < my_limit ? s_s[h][t] : -INFINITY;
+            float tmax = sv;
 #pragma unroll
-            for (int t = 0; t < PT_TOK; ++t) {
-                sv[t] = t0 + t < my_limit ? s_s[h][t] : -INFINITY;
-                tmax = fmaxf(tmax, sv[t]);
+            for (int o = PT_TOK / 2; o > 0; o >>= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, o));
+            const float m_old = m_s[h];
+            const float m_new = fmaxf(m_old, tmax);
+            const float e = m_new == -INFINITY ? 0.f : expf(sv - m_new);
+            p_s[t][h] = e;
+            float sum = e;
+#pragma unroll
+            for (int o = PT_TOK / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if (t == 0) {
+                const float a = m_new == -INFINITY ? 1.f : expf(m_old - m_new);  // exp(-inf) = 0 on the first tile
+                alpha_s[h] = a;
+                l_s[h] = l_s[h] * a + sum;
+                m_s[h] = m_new;
             }
-            float m_new = fmaxf(m_old, tmax);
-            float a = 1.f, sum = 0.f;
-            if (m_new == -INFINITY) {
-#pragma unroll
-                for (int t = 0; t < PT_TOK; ++t) p_s[h][t] = 0.f;
-            } else {
-                a = expf(m_old - m_new);  // exp(-inf) = 0 on the first tile
-#pragma unroll
-                for (int t = 0; t < PT_TOK; ++t) {
-                    float e = expf(sv[t] - m_new);
-                    p_s[h][t] = e;
-                    sum += e;
-                }
-            }
-            alpha_s[h] = a;
-            l_s[h] = l_s[h] * a + sum;
-            m_s[h] = m_new;
         }
         __syncthreads();
         // ---- latent values: thread owns columns tid, tid+256
@@ -182,12 +230,22 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         for (int i = 0; i < PT_MAX_COLS; ++i) {
             int c = tid + i * PT_THREADS;
             if (c < p.d_c) {
+                static_assert(PT_HG == 8, "two 128-bit reads fetch the weights of a token");
+                {
+                    const float4 a0 = *reinterpret_cast<const float4*>(&alpha_s[0]);
+                    const float4 a1 = *reinterpret_cast<const float4*>(&alpha_s[4]);
+                    acc[i][0] *= a0.x; acc[i][1] *= a0.y; acc[i][2] *= a0.z; acc[i][3] *= a0.w;
+                    acc[i][4] *= a1.x; acc[i][5] *= a1.y; acc[i][6] *= a1.z; acc[i][7] *= a1.w;
+                }
 #pragma unroll
-                for (int h = 0; h < PT_HG; ++h) acc[i][h] *= alpha_s[h];
                 for (int t = 0; t < PT_TOK; ++t) {
-                    float v = k_s[t][c];
-#pragma unroll
-                    for (int h = 0; h < PT_HG; ++h) acc[i][h] = fmaf(p_s[h][t], v, acc[i][h]);
+                    const float v = k_s[t][c];
+                    const float4 w0 = *reinterpret_cast<const float4*>(&p_s[t][0]);
+                    const float4 w1 = *reinterpret_cast<const float4*>(&p_s[t][4]);
+                    acc[i][0] = fmaf(w0.x, v, acc[i][0]); acc[i][1] = fmaf(w0.y, v, acc[i][1]);
+                    acc[i][2] = fmaf(w0.z, v, acc[i][2]); acc[i][3] = fmaf(w0.w, v, acc[i][3]);
+                    acc[i][4] = fmaf(w1.x, v, acc[i][4]); acc[i][5] = fmaf(w1.y, v, acc[i][5]);
+                    acc[i][6] = fmaf(w1.z, v, acc[i][6]); acc[i][7] = fmaf(w1.w, v, acc[i][7]);
                 }
             }
         }

@@ -27,7 +27,10 @@ template <bool BF16, bool Y_F32>
 __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, const void* W, void* Y,
                                                                 int B, int H, int K, int N)
 {
-    __shared__ float x_s[HG_BT][HG_KC];
+    // batch rows of one k adjacent: a 128-bit LDS read fetches four of them (an LDS instruction
+    // costs the wavefront ~17 cycles of issue whatever its width), and groups of four rows past
+    // the batch are not read at all
+    __shared__ __attribute__((aligned(16))) float x_t[HG_KC][HG_BT];
     __shared__ float red_s[4][HG_BT][HG_NT];
 
     const int tid = threadIdx.x, lane = tid & 63, kg = tid >> 6;
@@ -35,6 +38,7 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
     const int h = blockIdx.y;
     const int b0 = blockIdx.z * HG_BT;
     const int nb = min(HG_BT, B - b0);
+    const int nb4 = (nb + 3) / 4;      // groups of four batch rows in use
 
     float acc[HG_BT];
 #pragma unroll
@@ -45,17 +49,35 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
         __syncthreads();
         for (int idx = tid; idx < HG_BT * kc; idx += HG_THREADS) {
             int bb = idx / kc, k = idx % kc;
-            x_s[bb][k] = bb < nb ? ld<BF16>(X, ((size_t)(b0 + bb) * H + h) * K + k0 + k) : 0.f;
+            x_t[k][bb] = bb < nb ? ld<BF16>(X, ((size_t)(b0 + bb) * H + h) * K + k0 + k) : 0.f;
         }
         __syncthreads();
         if (n < N) {
             const int per = (kc + 3) / 4;
             const int kb = kg * per, ke = min(kc, kb + per);
-            for (int k = kb; k < ke; ++k) {
-                float w = ld<BF16>(W, ((size_t)h * K + k0 + k) * N + n);
+            auto step = [&](int k, float w) {
 #pragma unroll
-                for (int i = 0; i < HG_BT; ++i) acc[i] = fmaf(x_s[i][k], w, acc[i]);
+                for (int g4 = 0; g4 < HG_BT / 4; ++g4) {
+                    if (g4 < nb4) {
+                        const float4 xv = *reinterpret_cast<const float4*>(&x_t[k][g4 * 4]);
+                        acc[g4 * 4 + 0] = fmaf(xv.x, w, acc[g4 * 4 + 0]);
+                        acc[g4 * 4 + 1] = fmaf(xv.y, w, acc[g4 * 4 + 1]);
+                        acc[g4 * 4 + 2] = fmaf(xv.z, w, acc[g4 * 4 + 2]);
+                        acc[g4 * 4 + 3] = fmaf(xv.w, w, acc[g4 * 4 + 3]);
+                    }
+                }
+            };
+            // eight weight loads in flight per lane: with one at a time the loop runs at the speed
+            // of the memory latency (a skinny batch gives the chip few wavefronts to hide it)
+            int k = kb;
+            for (; k + 8 <= ke; k += 8) {
+                float w[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = ld<BF16>(W, ((size_t)h * K + k0 + k + j) * N + n);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) step(k + j, w[j]);
             }
+            for (; k < ke; ++k) step(k, ld<BF16>(W, ((size_t)h * K + k0 + k) * N + n));
         }
     }
 #pragma unroll
