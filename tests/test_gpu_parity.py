@@ -952,3 +952,23 @@ def test_prefill_mha_empty_sequence_and_dominant_late_key(mla):
     fin = np.isfinite(ref_lse)
     assert (np.isfinite(widen_gpu(lse)) == fin).all()
     assert np.abs(widen_gpu(lse)[fin] - ref_lse[fin]).max() <= 2e-2 * np.abs(ref_lse[fin]).max()
+
+
+def test_prefill_mha_random_sweep(mla):
+    """Twenty seeded random prefill cases: batch 1..4, heads 1..32, d_c 256 / 512, lengths 0..700 around
+    tile, page and query-group boundaries, q_len from 1 to beyond the longest sequence."""
+    rng = np.random.default_rng(777)
+    special = [0, 1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 130, 191, 192, 193, 255, 256, 257]
+    for case in range(20):
+        B = int(rng.integers(1, 5))
+        H = int(rng.choice([1, 3, 8, 16, 28, 32]))
+        d_c = int(rng.choice([256, 512]))
+        lens = [int(rng.choice(special)) if rng.random() < 0.6 else int(rng.integers(0, 700)) for _ in range(B)]
+        T = int(rng.choice([1, 2, 17, 64, 127, 128, 129, 300, max(1, max(lens)), max(lens) + 5]))
+        w = synth.make_workload(f"prand{case}", B=B, H=H, d_head=128, d_c=d_c, d_rope=64, seq_lens=lens,
+                                io_dtype="bf16", cache_dtype="bf16", placement="random", free_frac=0.25,
+                                seed=5000 + case)
+        try:
+            check_prefill(mla, w, T)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: B={B} H={H} d_c={d_c} lens={lens} T={T}: {e}")
