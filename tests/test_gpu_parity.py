@@ -972,3 +972,20 @@ def test_prefill_mha_random_sweep(mla):
             check_prefill(mla, w, T)
         except AssertionError as e:
             raise AssertionError(f"case {case}: B={B} H={H} d_c={d_c} lens={lens} T={T}: {e}")
+
+
+# ----------------------------------------------- the new calls at full size
+
+def test_multi_token_C2_full_fused_tail(mla):
+    """Headline cache at full size (batch 16, context 8192, 16 chunks), two query tokens per sequence,
+    the call sequence bench.py --q-len 2 times: 64-row kernel with the partials left in the
+    workspace, then merge + W_UV in one kernel.  Every sequence, token and head against the oracle."""
+    w = synth.config("C2")
+    check_multi(mla, w, 2, w.num_splits, fused_tail=True)
+
+
+def test_prefill_mha_2048_token_prompts(mla):
+    """Whole prompts of 2048 and 2000 tokens, 32 heads: 16 groups of 128 queries per (sequence, head),
+    64 key tiles for the last group; every row against the oracle."""
+    w = ragged_workload(H=32, lens=[2048, 2000], seed=56)
+    check_prefill(mla, w, 2048)
