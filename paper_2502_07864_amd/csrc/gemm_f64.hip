@@ -1,0 +1,153 @@
+// fp64 matrix product on the gfx950 matrix cores, used by the offline conversion
+// (activations X W^T, second moments C^T C, block power iteration S Q, the low-rank
+// projections R^T W and W R of App. D.2).
+//
+// Workgroup tile 128 x 128, K step 16, four wavefronts in 2 x 2, each 64 x 64 =
+// 4 x 4 tiles of v_mfma_f64_16x16x4_f64.  Lane l of a wavefront supplies
+// A[l % 16][l / 16] and B[l / 16][l % 16] and receives D[4 r + l / 16][l % 16] in
+// element r of the result vector.  Both operands are staged k-major in LDS
+// ([k][m] and [k][n]) whichever way they lie in memory, so the inner loop is the
+// same for all four transpose combinations; the next K step is fetched into
+// registers while the current one is multiplied.
+#include "convert_internal.h"
+
+namespace mla {
+namespace conv {
+namespace {
+
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LD = 144;                       // row pitch of a staged k-row, in doubles
+constexpr int STAGE = BK * LD;                // one operand, one buffer
+
+// Fetch the 128 x 16 tile of an operand whose (mn, k) element is P[mn*s_mn + k*s_k].
+// K_CONTIG: s_k == 1, sixteen lanes read 128 consecutive bytes of one row;
+// otherwise s_mn == 1 and 128 lanes read consecutive elements of one k-row.
+template <bool K_CONTIG>
+__device__ __forceinline__ void fetch(const double* __restrict__ P, long s_mn, long s_k,
+                                      int mn0, int k0, int MN, int K, int tid, double (&r)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int mn, k;
+        if (K_CONTIG) { k = k0 + (tid & 15); mn = mn0 + (tid >> 4) + 16 * i; }
+        else          { mn = mn0 + (tid & 127); k = k0 + (tid >> 7) + 2 * i; }
+        r[i] = (mn < MN && k < K) ? P[(long)mn * s_mn + (long)k * s_k] : 0.0;
+    }
+}
+
+template <bool K_CONTIG>
+__device__ __forceinline__ void stage(double* S, int tid, const double (&r)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (K_CONTIG) S[(tid & 15) * LD + (tid >> 4) + 16 * i] = r[i];
+        else          S[((tid >> 7) + 2 * i) * LD + (tid & 127)] = r[i];
+    }
+}
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, int total) {
+    extern __shared__ double lds[];            // As[2][BK][LD], Bs[2][BK][LD]
+    double* As = lds;
+    double* Bs = lds + 2 * STAGE;
+
+    // consecutive tiles (same rows of A) share an XCD: workgroup ids 8 apart run on one XCD
+    const int per = (total + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (tile >= total) return;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int li = lane & 15, kq = lane >> 4;
+
+    f64x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+
+    double ra[8], rb[8];
+    fetch<A_KC>(g.A, g.sAm, g.sAk, m0, 0, g.M, g.K, tid, ra);
+    fetch<B_KC>(g.B, g.sBn, g.sBk, n0, 0, g.N, g.K, tid, rb);
+    stage<A_KC>(As, tid, ra);
+    stage<B_KC>(Bs, tid, rb);
+    __syncthreads();
+
+    const int nk = (g.K + BK - 1) / BK;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) {
+            fetch<A_KC>(g.A, g.sAm, g.sAk, m0, (kt + 1) * BK, g.M, g.K, tid, ra);
+            fetch<B_KC>(g.B, g.sBn, g.sBk, n0, (kt + 1) * BK, g.N, g.K, tid, rb);
+        }
+        const double* a_s = As + buf * STAGE + wm + li;
+        const double* b_s = Bs + buf * STAGE + wn + li;
+#pragma unroll
+        for (int ks = 0; ks < BK / 4; ++ks) {
+            double a[4], b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                a[t] = a_s[(ks * 4 + kq) * LD + t * 16];
+                b[t] = b_s[(ks * 4 + kq) * LD + t * 16];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            stage<A_KC>(As + (buf ^ 1) * STAGE, tid, ra);
+            stage<B_KC>(Bs + (buf ^ 1) * STAGE, tid, rb);
+        }
+        __syncthreads();
+    }
+
+    double scale = g.alpha;
+    if (g.dev_mode == 1) scale *= *g.alpha_dev;
+    else if (g.dev_mode == 2) scale /= *g.alpha_dev;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wm + i * 16 + 4 * r + kq;
+                const int col = n0 + wn + j * 16 + li;
+                if (row < g.M && col < g.N) g.C[(long)row * g.ldc + col] = scale * acc[i][j][r];
+            }
+}
+
+template <bool A_KC, bool B_KC>
+hipError_t run(const GemmF64& g, hipStream_t s) {
+    constexpr size_t lds_bytes = 4 * STAGE * sizeof(double);
+    static bool configured = false;            // raising the dynamic-LDS limit once per process is enough
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f64_kernel<A_KC, B_KC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    const int grid = ((total + 7) / 8) * 8;
+    gemm_f64_kernel<A_KC, B_KC><<<grid, 256, lds_bytes, s>>>(g, tiles_n, total);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_f64(const GemmF64& g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+    const bool a_kc = g.sAk == 1, b_kc = g.sBk == 1;
+    if ((!a_kc && g.sAm != 1) || (!b_kc && g.sBn != 1)) return hipErrorInvalidValue;
+    if (a_kc && b_kc) return run<true, true>(g, s);
+    if (a_kc) return run<true, false>(g, s);
+    if (b_kc) return run<false, true>(g, s);
+    return run<false, false>(g, s);
+}
+
+}  // namespace conv
+}  // namespace mla

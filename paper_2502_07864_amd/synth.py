@@ -321,3 +321,34 @@ def config(name: str, seed: int = 0, shrink: int = 1) -> Workload:
                              seq_lens=[max(1, 131072 // s)] * B, io_dtype=BF16,
                              cache_dtype=FP8_E4M3, placement="random", num_splits=32, seed=seed)
     raise KeyError(name)
+
+
+# --------------------------------------------------------------------------
+# calibration inputs of the offline conversion (Sec. 4.2, 4.3, App. B-D)
+# --------------------------------------------------------------------------
+
+def calibration(n: int, D: int, g: int, d: int, seed: int = 0, decay: float = 0.7,
+                key_gain: float = 3.0, outliers: int = 4, floor: float = 0.0):
+    """Synthetic stand-in for the hidden states of a calibration corpus and for the
+    key/value projections of one GQA layer, all float64.
+
+    X [n, D]: Gaussian factors with a power-law spectrum (factor k scaled by
+    (k+1)^-decay, plus `floor`), mixed by a random matrix, with a few outlier channels
+    scaled by 8 (large-magnitude channels are typical of transformer hidden states).
+    W_K, W_V [g*d, D] ~ N(0, 1/D), W_K times `key_gain` (keys carry larger norms than
+    values, the situation Sec. 4.3 balances)."""
+    k = min(n, D)
+    Z = stream(seed, 40).standard_normal((n, k))
+    s = (1.0 + np.arange(k)) ** (-decay) + floor
+    B = stream(seed, 41).standard_normal((k, D)) / np.sqrt(k)
+    X = (Z * s) @ B
+    ch = stream(seed, 42).choice(D, size=min(outliers, D), replace=False)
+    X[:, ch] *= 8.0
+    W_K = stream(seed, 43).standard_normal((g * d, D)) * (key_gain / np.sqrt(D))
+    W_V = stream(seed, 44).standard_normal((g * d, D)) / np.sqrt(D)
+    return X, W_K, W_V
+
+
+def start_block(m: int, p: int, seed: int = 0) -> np.ndarray:
+    """Gaussian start block of the block power iteration (random numbers are drawn here, not by the library)."""
+    return stream(seed, 45).standard_normal((m, p))

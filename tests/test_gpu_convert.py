@@ -1,0 +1,207 @@
+"""GPU parity of the offline conversion (include/mla_convert_gfx950.h) against the numpy
+oracle (oracle/convert_oracle.py), entry point by entry point and as a chain, through
+the C ABI.  Eigenvectors are unique up to sign (and inside a repeated eigenvalue up to a
+rotation), so those tests compare eigenvalues, projectors and sign-free products, and
+check orthonormality and the eigen-equation directly.
+
+Tolerances (fp64 on both sides; the two differ in summation order only): 1e-11 relative
+for sums of at most a few thousand products, 1e-9 for eigenvalues and for quantities that
+pass through an eigenbasis (error ~ rounding / relative gap)."""
+import numpy as np
+import pytest
+
+from oracle import convert_oracle as co
+from paper_2502_07864_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cv():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2502_07864_amd import convert
+    convert.lib()
+    return convert
+
+
+def dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float64)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def rel(a, b):
+    return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ------------------------------------------------------------------ matrix product (activations)
+
+@pytest.mark.parametrize("n,D,m", [(300, 200, 150), (1, 7, 3), (128, 16, 128), (129, 17, 257), (1000, 513, 64)])
+def test_project_matches_numpy(cv, n, D, m):
+    r = rng(n + D)
+    X, W = r.standard_normal((n, D)), r.standard_normal((m, D))
+    got = host(cv.project(dev(X), dev(W)))
+    assert rel(got, X @ W.T) < 1e-12
+
+
+# ------------------------------------------------------------------ App. B / C moments
+
+@pytest.mark.parametrize("g,d,M,n", [(4, 16, 1, 100), (4, 16, 2, 37), (3, 12, 3, 64), (8, 64, 4, 200),
+                                     (32, 128, 1, 130), (32, 128, 4, 48), (2, 8, 1, 1)])
+def test_rope_moments(cv, g, d, M, n):
+    K = rng(g * d + M).standard_normal((n, g * d))
+    got = host(cv.rope_moments(dev(K), g, d, M))
+    want = co.rope_moments(K, g, d, M)
+    assert got.shape == want.shape and rel(got, want) < 1e-12
+
+
+# ------------------------------------------------------------------ eigensolver
+
+def check_eig(A, evals, U, info, tol=1e-10):
+    m = A.shape[-1]
+    for b in range(A.shape[0]):
+        scale = max(np.linalg.norm(A[b]), 1e-300)
+        w_ref, _ = co.sym_eig_desc(A[b])
+        assert info[b] >= 1, f"matrix {b}: not converged"
+        assert np.abs(evals[b] - w_ref).max() <= tol * scale
+        assert (np.diff(evals[b]) <= 0).all()
+        assert np.abs(U[b].T @ U[b] - np.eye(m)).max() < 1e-12 * m
+        assert np.abs(A[b] @ U[b] - U[b] * evals[b]).max() <= tol * scale
+
+
+@pytest.mark.parametrize("batch,m", [(3, 2), (4, 5), (64, 32), (5, 64), (2, 80), (2, 96), (1, 257), (1, 512)])
+def test_sym_eig_random(cv, batch, m):
+    r = rng(m)
+    A = r.standard_normal((batch, m, m))
+    A = A + A.transpose(0, 2, 1)
+    if batch > 1:                                      # one positive semi-definite, rank-deficient member
+        B = r.standard_normal((m, max(1, m // 2)))
+        A[1] = B @ B.T
+    evals, U, info = cv.sym_eig(dev(A))
+    check_eig(A, host(evals), host(U), host(info))
+
+
+def test_sym_eig_degenerate_cases(cv):
+    m = 12
+    r = rng(99)
+    Q, _ = np.linalg.qr(r.standard_normal((m, m)))
+    A = np.stack([np.eye(m) * 3.0,                                   # all eigenvalues equal
+                  np.zeros((m, m)),                                  # zero matrix
+                  np.diag(np.arange(m, dtype=np.float64)),           # already diagonal, ascending
+                  Q @ np.diag([5.0] * 4 + [2.0] * 4 + [-1.0] * 4) @ Q.T,   # repeated eigenvalues
+                  np.full((m, m), 1.0)])                             # rank one
+    evals, U, info = cv.sym_eig(dev(A))
+    check_eig(A, host(evals), host(U), host(info))
+    assert np.allclose(host(evals)[2], np.arange(m)[::-1], atol=1e-13)
+
+
+def test_sym_eig_rorope_bases_have_the_oracles_projectors(cv):
+    """The use made of it in App. B: bases of the per-group moments of synthetic key activations."""
+    g, d, M, n = 8, 32, 2, 256
+    X, W_K, _ = synth.calibration(n, 96, g, d, seed=3)
+    sigma = co.rope_moments(X @ W_K.T, g, d, M)
+    evals, U, info = cv.sym_eig(dev(sigma))
+    evals, U = host(evals), host(U)
+    w_ref, U_ref = co.rorope_basis(sigma)
+    check_eig(sigma, evals, U, host(info))
+    for G in range(sigma.shape[0]):
+        for c in range(M * g):                          # distinct eigenvalues: columns agree up to sign
+            assert abs(abs(U[G][:, c] @ U_ref[G][:, c]) - 1.0) < 1e-8
+
+
+# ------------------------------------------------------------------ Sec. 4.2 / 4.3 / D.2 steps
+
+@pytest.mark.parametrize("g,d,M,cols", [(4, 16, 1, 50), (4, 16, 2, 33), (3, 12, 3, 7), (8, 64, 4, 100), (32, 128, 1, 40)])
+def test_rotate_rows(cv, g, d, M, cols):
+    r = rng(g + d + M)
+    W = r.standard_normal((g * d, cols))
+    U = r.standard_normal((d // (2 * M), M * g, M * g))
+    got = host(cv.rotate_rows(dev(W), dev(U), g, d, M))
+    assert rel(got, co.rotate_rows(W, U, g, d, M)) < 1e-12
+
+
+@pytest.mark.parametrize("n,a,b", [(100, 48, 64), (1, 3, 5), (333, 130, 7)])
+def test_kv_balance_and_joint_moment(cv, n, a, b):
+    r = rng(n + a)
+    K_nope, V = 2.5 * r.standard_normal((n, a)), r.standard_normal((n, b))
+    alpha, norms = cv.kv_balance(dev(K_nope), dev(V))
+    want = co.kv_balance(K_nope, V)
+    assert abs(host(alpha)[0] - want) < 1e-13 * want
+    assert rel(host(norms)[0], np.linalg.norm(K_nope, axis=1)) < 1e-13
+    S, C = cv.joint_moment(dev(K_nope), dev(V), alpha)
+    assert rel(host(S), co.joint_moment(K_nope, V, want)) < 1e-12
+    assert rel(host(C), np.concatenate([K_nope / want, V], axis=1)) < 1e-13
+
+
+def projector_gap(R, R_ref):
+    return np.abs(R @ R.T - R_ref @ R_ref.T).max()
+
+
+@pytest.mark.parametrize("m,r,p,iters", [(60, 8, 16, 40), (200, 40, 64, 60), (300, 17, 33, 60), (40, 40, 40, 2)])
+def test_top_eig_against_full_eigendecomposition(cv, m, r, p, iters):
+    rs = rng(m + r)
+    Q, _ = np.linalg.qr(rs.standard_normal((m, m)))
+    lam = (1.0 + np.arange(m)) ** -1.5
+    S = (Q * lam) @ Q.T
+    S = 0.5 * (S + S.T)
+    evals, R, info = cv.top_eig(dev(S), dev(synth.start_block(m, p, seed=m)), r, iters)
+    evals, R, info = host(evals), host(R), host(info)
+    w_ref, R_ref = co.joint_basis(S, r)
+    assert info[0] == 0 and info[1] >= 1
+    assert np.abs(R.T @ R - np.eye(r)).max() < 1e-12
+    assert np.abs(evals[:r] - w_ref[:r]).max() < 1e-10 * w_ref[0]
+    assert projector_gap(R, R_ref) < 1e-8
+    assert np.abs(S @ R - R * evals[:r]).max() < 1e-9 * w_ref[0]
+
+
+# ------------------------------------------------------------------ the chain
+
+def chain_case(g, h, d, D, n, M, r_kv, p, seed):
+    X, W_K, W_V = synth.calibration(n, D, g, d, seed=seed)
+    Q0 = synth.start_block((2 * g - 1) * d, p, seed=seed)
+    return X, W_K, W_V, Q0
+
+
+@pytest.mark.parametrize("g,h,d,D,n,M,r_kv,p", [(4, 8, 16, 96, 512, 1, 40, 56), (4, 8, 16, 96, 512, 2, 40, 56),
+                                                (2, 6, 8, 40, 200, 4, 12, 20), (8, 8, 32, 128, 300, 1, 64, 96)])
+def test_convert_layer_against_the_oracle_chain(cv, g, h, d, D, n, M, r_kv, p):
+    X, W_K, W_V, Q0 = chain_case(g, h, d, D, n, M, r_kv, p, seed=g + M)
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(Q0), g, h, d, M, r_kv, iters=80)
+    got = {k: host(v) for k, v in out.items()}
+    want = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    groups = d // (2 * M)
+    assert (got["info"][:groups] >= 1).all() and got["info"][groups] == 0 and got["info"][groups + 1] >= 1
+    assert abs(got["alpha"][0] - want["alpha"]) < 1e-11 * want["alpha"]
+    assert rel(got["evals_rope"], want["evals_rope"]) < 1e-10
+    assert np.abs(got["evals_joint"][:r_kv] - want["evals_joint"][:r_kv]).max() < 1e-9 * want["evals_joint"][0]
+    # A sign flip of a RoRoPE basis vector flips one coordinate of the rotated key, hence one row of
+    # R_KV: undo those flips (read off the two sets of bases) before comparing the projectors.
+    sign = np.sign(np.einsum("gcr,gcr->gr", got["U"], want["U"]))
+    out_x, out_y = co.placement_columns(g, d, M)
+    flip = np.ones((2 * g - 1) * d)
+    for G in range(groups):
+        for r in range(M * g):
+            for row in (out_x[G, r], out_y[G, r]):
+                if row >= d:
+                    flip[row - d] = sign[G, r]
+    assert projector_gap(got["R_KV"] * flip[:, None], want["R_KV"]) < 1e-7
+    # sign-free products.  Rope head: row a of W_QR[i] and row a of W_KR flip together.
+    for i in range(h):
+        assert rel(np.einsum("ab,ac->abc", got["W_QR"][i], got["W_KR"]),
+                   np.einsum("ab,ac->abc", want["W_QR"][i], want["W_KR"])) < 1e-8
+        # latent: W_UK[i] W_DKV and W_UV[i]^T W_DKV depend on the projector R R^T only
+        assert rel(got["W_UK"][i] @ got["W_DKV"], want["W_UK"][i] @ want["W_DKV"]) < 1e-7
+        assert rel(got["W_UV"][i].T @ got["W_DKV"], want["W_UV"][i].T @ want["W_DKV"]) < 1e-7
+    # and the properties that hold whatever the oracle says
+    R = got["R_KV"]
+    assert np.abs(R.T @ R - np.eye(r_kv)).max() < 1e-11
+    for G in range(groups):
+        assert np.abs(got["U"][G].T @ got["U"][G] - np.eye(M * g)).max() < 1e-11
