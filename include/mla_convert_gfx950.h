@@ -54,11 +54,12 @@ int mla_conv_rope_moments(const double* K, double* sigma,
 /*
  * Batched symmetric eigendecomposition (App. B: the columns of U are the eigenvectors
  * by descending eigenvalue; also the PCA of App. D.2).  Cyclic Jacobi rotations, one
- * workgroup per matrix.
+ * workgroup per matrix up to m = 128; a larger matrix is spread over the chip, one launch per
+ * rotation step, and the batch is then processed one matrix after the other.
  *   A      [batch, m, m]  in: symmetric matrices; out: eigenvectors in the COLUMNS, column c
  *                         belonging to evals[c]
  *   evals  [batch, m]     eigenvalues, descending
- *   work   [batch, m, m]  scratch (mla_conv_sym_eig_workspace_bytes)
+ *   work                  scratch of mla_conv_sym_eig_workspace_bytes(batch, m) bytes
  *   info   [batch] int    out: sweeps used (>= 1), or -1 if the off-diagonal part did not fall
  *                         below 1e-13 of the Frobenius norm within max_sweeps
  * 2 <= m <= 2048.
@@ -111,6 +112,10 @@ int mla_conv_joint_moment(const double* K_nope, int ldk, const double* V, int ld
  *                   lost rank); info[1]: sweeps of the final eigendecomposition, -1 if not converged
  */
 size_t mla_conv_top_eig_workspace_bytes(int m, int p);
+/* One application of the moment matrix to a block, Y = S Q (the product each step of the
+ * iteration above spends its time in; with Q = R it gives the residual S R - R diag(evals)).
+ *   S [m, m], Q [m, p], Y [m, p] (distinct from Q). */
+int mla_conv_apply(const double* S, const double* Q, double* Y, int m, int p, void* hip_stream);
 int mla_conv_top_eig(const double* S, const double* Q0, double* evals, double* R,
                      void* workspace, size_t workspace_bytes, int* info,
                      int m, int r, int p, int iters, void* hip_stream);

@@ -23,7 +23,8 @@ inline GemmF64 gemm_tn(const double* A, long lda, const double* B, long ldb, dou
     return GemmF64{A, 1, lda, B, ldb, 1, C, ldc, M, N, K, alpha, nullptr, 0};   // C = A^T B (A is K x M)
 }
 
-struct TopWs { double *Y, *Q, *G, *X, *T, *Z; size_t bytes; };
+constexpr int GRAM_SLICES = 16;     // K slices of the p x p products of tall blocks
+struct TopWs { double *Y, *Q, *G, *X, *T, *Z, *tmp, *part; size_t part_doubles; size_t bytes; };
 TopWs top_ws(void* base, int m, int p) {
     TopWs w{};
     size_t off = 0;
@@ -34,16 +35,22 @@ TopWs top_ws(void* base, int m, int p) {
     w.G = take((size_t)p * p);
     w.X = take((size_t)p * p);
     w.T = take((size_t)p * p);
-    w.Z = take((size_t)p * p);
+    w.Z = take(jacobi_work_bytes(1, p) / sizeof(double));
+    w.tmp = take((size_t)64 * p + 8);
+    w.part_doubles = (size_t)GRAM_SLICES * p * p;
+    w.part = take(w.part_doubles);
     w.bytes = off;
     return w;
 }
 
 // Q <- Y L^{-T} with L L^T = Y^T Y  (one Cholesky-QR pass); the result lands in `out`
 int chol_qr(const double* Y, double* out, const TopWs& w, int m, int p, int* bad, hipStream_t s) {
-    hipError_t e = launch_gemm_f64(gemm_tn(Y, p, Y, p, w.G, p, p, p, m, 1.0), s);
+    GemmF64 gram = gemm_tn(Y, p, Y, p, w.G, p, p, p, m, 1.0);
+    gram.partial = w.part;
+    gram.partial_doubles = w.part_doubles;
+    hipError_t e = launch_gemm_f64(gram, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
-    e = launch_chol_inverse(w.G, w.X, p, bad, s);
+    e = launch_chol_inverse(w.G, w.X, w.tmp, p, bad, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
     return st(launch_gemm_f64(gemm_nt(Y, p, w.X, p, out, p, m, p, p, 1.0), s));
 }
@@ -68,7 +75,10 @@ int top_eig(const double* S, const double* Q0, double* evals, double* R, const T
     // T = Q^T S Q, T = Z diag(evals) Z^T, R = Q Z[:, :r]
     e = launch_gemm_f64(gemm_nn(S, m, w.Q, p, w.Y, p, m, p, m, 1.0), s);
     if (e != hipSuccess) return MLA_ERR_HIP;
-    e = launch_gemm_f64(gemm_tn(w.Q, p, w.Y, p, w.T, p, p, p, m, 1.0), s);
+    GemmF64 ritz = gemm_tn(w.Q, p, w.Y, p, w.T, p, p, p, m, 1.0);
+    ritz.partial = w.part;
+    ritz.partial_doubles = w.part_doubles;
+    e = launch_gemm_f64(ritz, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
     e = launch_symmetrise(w.T, p, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
@@ -89,7 +99,7 @@ LayerWs layer_ws(void* base, int n, int D, int g, int h, int d, int M, int p) {
                                     off += align256(count * sizeof(double)); return ptr; };
     const size_t gd = (size_t)g * d, mj = (size_t)(2 * g - 1) * d, Mg = (size_t)M * g;
     w.K = take((size_t)n * gd);
-    w.sigma_work = take((size_t)(d / (2 * M)) * Mg * Mg);
+    w.sigma_work = take(jacobi_work_bytes(d / (2 * M), (int)Mg) / sizeof(double));
     w.W_K_rot = take(gd * D);
     w.E = take(gd * (size_t)h * d);
     w.E_rot = take(gd * (size_t)h * d);
@@ -130,7 +140,7 @@ int mla_conv_rope_moments(const double* K, double* sigma, int n, int g, int d, i
 
 size_t mla_conv_sym_eig_workspace_bytes(int batch, int m) {
     if (batch <= 0 || m < 2 || m > EIG_MAX_M) return 0;
-    return (size_t)batch * m * m * sizeof(double);
+    return jacobi_work_bytes(batch, m);
 }
 
 int mla_conv_sym_eig(double* A, double* evals, double* work, size_t work_bytes, int* info,
@@ -183,6 +193,12 @@ int mla_conv_top_eig(const double* S, const double* Q0, double* evals, double* R
     if (p > TOP_MAX_P) return MLA_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < mla_conv_top_eig_workspace_bytes(m, p)) return MLA_ERR_WORKSPACE;
     return top_eig(S, Q0, evals, R, top_ws(workspace, m, p), info, m, r, p, iters, static_cast<hipStream_t>(hip_stream));
+}
+
+int mla_conv_apply(const double* S, const double* Q, double* Y, int m, int p, void* hip_stream) {
+    if (!S || !Q || !Y) return MLA_ERR_NULL;
+    if (m <= 0 || p <= 0 || Q == Y) return MLA_ERR_SHAPE;
+    return st(launch_gemm_f64(gemm_nn(S, m, Q, p, Y, p, m, p, m, 1.0), static_cast<hipStream_t>(hip_stream)));
 }
 
 size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int r_kv, int p) {

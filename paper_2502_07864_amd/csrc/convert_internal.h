@@ -9,6 +9,9 @@ namespace conv {
 // C[m, n] = scale * sum_k A(m, k) B(k, n), where A(m, k) = A[m*sAm + k*sAk] and
 // B(k, n) = B[k*sBk + n*sBn]; for each operand one of the two strides is 1.
 // scale = alpha, times *alpha_dev (dev_mode 1) or divided by it (dev_mode 2).
+// accumulate: C += instead of C =.
+// partial / partial_doubles: optional scratch; when the tile count alone cannot fill the chip and K is
+// deep, the K range is cut into slices whose products go to the scratch and are summed in a fixed order.
 struct GemmF64 {
     const double* A; long sAm, sAk;
     const double* B; long sBk, sBn;
@@ -16,6 +19,8 @@ struct GemmF64 {
     int M, N, K;
     double alpha;
     const double* alpha_dev; int dev_mode;
+    int accumulate;
+    double* partial; size_t partial_doubles;
 };
 hipError_t launch_gemm_f64(const GemmF64& g, hipStream_t s);
 
@@ -30,9 +35,13 @@ hipError_t launch_row_norms(const double* K, int ldk, int a, const double* V, in
 hipError_t launch_alpha(const double* norms, double* alpha, int n, hipStream_t s);
 // C[t, 0:a] = K[t, 0:a] / *alpha, C[t, a:a+b] = V[t, 0:b]   (in place allowed)
 hipError_t launch_balance(const double* K, int ldk, const double* V, int ldv, const double* alpha, double* C, int n, int a, int b, hipStream_t s);
+// work: jacobi_work_bytes(batch, m) bytes
+size_t jacobi_work_bytes(int batch, int m);
 hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int batch, int m, int max_sweeps, hipStream_t s);
-// G (p x p, symmetric positive definite) -> lower Cholesky factor in place, X = its inverse; *bad += clamped pivots
-hipError_t launch_chol_inverse(double* G, double* X, int p, int* bad, hipStream_t s);
+// G (p x p, symmetric positive definite) -> lower Cholesky factor in place (blocks above the diagonal
+// are left undefined), X = its inverse (zero above the diagonal); *bad += clamped pivots.
+// tmp: 64 * p + 8 doubles of scratch.
+hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* bad, hipStream_t s);
 hipError_t launch_symmetrise(double* T, int p, hipStream_t s);
 hipError_t launch_fill_int(int* dst, int value, int count, hipStream_t s);
 // dst[r, c] = src[r*lds + c] * f, f = 1, *scale (mode 1) or 1 / *scale (mode 2)

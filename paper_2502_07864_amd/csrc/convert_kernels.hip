@@ -3,6 +3,7 @@
 // (Sec. 4.3), the batched Jacobi eigensolver, and the Cholesky step of the block
 // power iteration (App. D.2).  All fp64.
 #include "convert_internal.h"
+#include <algorithm>
 
 namespace mla {
 namespace conv {
@@ -253,70 +254,208 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(double* A_all, double* eva
     if (tid == 0) info[blockIdx.x] = used;
 }
 
-// ------------------------------------------------------------------ Cholesky factor and its inverse
-// One workgroup of 1024 threads on a p x p matrix in global memory (p <= 1024).
-// Right-looking: scale column j, then subtract its outer product from the trailing
-// lower triangle.  A pivot that is not above 1e-13 of the largest diagonal entry is clamped
-// to that floor and counted.  Then X = L^{-1}, one thread per column by forward substitution.
-__global__ __launch_bounds__(1024) void chol_inverse_kernel(double* G, double* X, int p, int* bad) {
-    __shared__ double piv, red[16], colj[TOP_MAX_P];
-    __shared__ int nbad;
-    const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
-    double mx = 0.0;
-    for (int i = tid; i < p; i += 1024) mx = fmax(mx, G[(long)i * p + i]);
-    // block maximum through the sum helper's LDS: take the max per wave, then over waves
-    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    if (tid == 0) nbad = 0;
-    __syncthreads();
-    mx = 0.0;
-    for (int w = 0; w < 16; ++w) mx = fmax(mx, red[w]);
-    const double floor_v = fmax(mx * 1e-13, 1e-300);
+// ------------------------------------------------------------------ Jacobi eigensolver, one large matrix
+// The same rotations as above, spread over the chip: per step one launch rotates the rows (one
+// workgroup per index pair; it also derives the pair's angle and publishes it) and one launch
+// rotates the columns of A and V.  Launch order on the stream is the only synchronisation.  A sweep
+// starts with a norm launch that raises `done` once the off-diagonal part is small; later launches
+// then return at once, so the host can enqueue the maximum number of sweeps without reading back.
+struct WideState { double tot; int done, sweeps; };
 
-    for (int j = 0; j < p; ++j) {
+__device__ __forceinline__ void round_robin_pair(int k, int step, int mp, int& p, int& q) {
+    if (k == 0) { p = mp - 1; q = step; }
+    else { p = (step + k) % (mp - 1); q = (step - k + (mp - 1)) % (mp - 1); }
+    if (p > q) { const int t = p; p = q; q = t; }
+}
+
+__global__ __launch_bounds__(256) void jw_init_kernel(double* __restrict__ V, int m, WideState* st) {
+    const long total = (long)m * m;
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256)
+        V[idx] = (idx / m == idx % m) ? 1.0 : 0.0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { st->tot = 0.0; st->done = 0; st->sweeps = -1; }
+}
+
+__global__ __launch_bounds__(1024) void jw_norm_kernel(const double* __restrict__ A, int m, int sweep, WideState* st) {
+    __shared__ double red[16];
+    if (st->done) return;
+    double off = 0.0, dia = 0.0;
+    for (int idx = threadIdx.x; idx < m * m; idx += 1024) {
+        const double v = A[idx];
+        if (idx / m == idx % m) dia += v * v; else off += v * v;
+    }
+    off = block_sum(off, red);
+    dia = block_sum(dia, red);
+    if (threadIdx.x == 0) {
+        if (sweep == 0) st->tot = off + dia;
+        if (off <= 1e-26 * st->tot) { st->done = 1; st->sweeps = sweep > 0 ? sweep : 1; }
+    }
+}
+
+__global__ __launch_bounds__(256) void jw_rows_kernel(double* A, int m, int mp, int step, double* __restrict__ cs, const WideState* st) {
+    if (st->done) return;
+    const int k = blockIdx.x;
+    int p, q;
+    round_robin_pair(k, step, mp, p, q);
+    double c = 1.0, s = 0.0;
+    if (q < m) {
+        const double apq = A[(long)p * m + q], app = A[(long)p * m + p], aqq = A[(long)q * m + q];
+        if (fabs(apq) > 1e-300 && fabs(apq) > 1e-18 * sqrt(fabs(app * aqq))) {
+            const double theta = (aqq - app) / (2.0 * apq);
+            const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+            c = 1.0 / sqrt(t * t + 1.0);
+            s = t * c;
+        }
+    }
+    __syncthreads();                                   // every thread holds the angle before a row changes
+    if (threadIdx.x == 0) { cs[2 * k] = c; cs[2 * k + 1] = s; }
+    if (s == 0.0) return;
+    for (int j = threadIdx.x; j < m; j += 256) {
+        const long ip = (long)p * m + j, iq = (long)q * m + j;
+        const double ap = A[ip], aq = A[iq];
+        A[ip] = c * ap - s * aq;
+        A[iq] = s * ap + c * aq;
+    }
+}
+
+__global__ __launch_bounds__(256) void jw_cols_kernel(double* A, double* V, int m, int mp, int step,
+                                                      const double* __restrict__ cs, const WideState* st) {
+    if (st->done) return;
+    const int half = mp / 2;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)half * m) return;
+    const int k = (int)(idx % half), i = (int)(idx / half);
+    const double c = cs[2 * k], s = cs[2 * k + 1];
+    if (s == 0.0) return;
+    int p, q;
+    round_robin_pair(k, step, mp, p, q);
+    const long ip = (long)i * m + p, iq = (long)i * m + q;
+    const double ap = A[ip], aq = A[iq];
+    A[ip] = i == q ? 0.0 : c * ap - s * aq;            // the annihilated pair gets exact zeros
+    A[iq] = i == p ? 0.0 : s * ap + c * aq;
+    const double vp = V[ip], vq = V[iq];
+    V[ip] = c * vp - s * vq;
+    V[iq] = s * vp + c * vq;
+}
+
+__global__ __launch_bounds__(1024) void jw_rank_kernel(const double* __restrict__ A, int m, double* __restrict__ evals,
+                                                       int* __restrict__ rank, const WideState* st, int* info) {
+    __shared__ double diag[EIG_MAX_M];
+    for (int i = threadIdx.x; i < m; i += 1024) diag[i] = A[(long)i * m + i];
+    __syncthreads();
+    for (int i = threadIdx.x; i < m; i += 1024) {
+        const double di = diag[i];
+        int r = 0;
+        for (int j = 0; j < m; ++j) { const double dj = diag[j]; r += (dj > di) || (dj == di && j < i); }
+        rank[i] = r;
+        evals[r] = di;
+    }
+    if (threadIdx.x == 0) *info = st->done ? st->sweeps : -1;
+}
+
+__global__ __launch_bounds__(256) void jw_permute_kernel(double* __restrict__ A_out, const double* __restrict__ V,
+                                                         const int* __restrict__ rank, int m) {
+    const long total = (long)m * m;
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256)
+        A_out[(idx / m) * m + rank[idx % m]] = V[idx];
+}
+
+// ------------------------------------------------------------------ Cholesky factor and its inverse
+// Blocked, 64 columns at a time; the matrix products between the blocks run on the matrix-core
+// kernel, the 64 x 64 pieces below in LDS.
+constexpr int NB = 64;
+
+// floor for the pivots: 1e-13 of the largest diagonal entry
+__global__ __launch_bounds__(1024) void max_diag_kernel(const double* __restrict__ G, int p, double* __restrict__ floor_out) {
+    __shared__ double red[16];
+    double mx = 0.0;
+    for (int i = threadIdx.x; i < p; i += 1024) mx = fmax(mx, G[(long)i * p + i]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = 0.0;
+        for (int w = 0; w < 16; ++w) mx = fmax(mx, red[w]);
+        *floor_out = fmax(mx * 1e-13, 1e-300);
+    }
+}
+
+// Block column k0, step 1: one workgroup factors the nb x nb diagonal block in LDS.
+__global__ __launch_bounds__(256) void chol_diag_kernel(double* G, int p, int k0, int nb,
+                                                        const double* __restrict__ floor_in, int* bad) {
+    __shared__ double D[NB][NB + 1];
+    __shared__ double piv;
+    __shared__ int nbad;
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    for (int idx = tid; idx < nb * nb; idx += 256) D[idx / nb][idx % nb] = G[(long)(k0 + idx / nb) * p + k0 + idx % nb];
+    if (tid == 0) nbad = 0;
+    const double floor_v = *floor_in;
+    __syncthreads();
+    for (int j = 0; j < nb; ++j) {
         if (tid == 0) {
-            double v = G[(long)j * p + j];
+            double v = D[j][j];
             if (!(v > floor_v)) { v = floor_v; ++nbad; }
             v = sqrt(v);
-            G[(long)j * p + j] = v;
+            D[j][j] = v;
             piv = v;
         }
         __syncthreads();
         const double inv = 1.0 / piv;
-        for (int i = j + 1 + tid; i < p; i += 1024) {
-            const double v = G[(long)i * p + j] * inv;
-            G[(long)i * p + j] = v;
-            colj[i] = v;
-        }
+        for (int i = j + 1 + tid; i < nb; i += 256) D[i][j] *= inv;
         __syncthreads();
-        const int cnt = p - j - 1;
-        for (int ii = ty; ii < cnt; ii += 32) {
-            const long i = j + 1 + ii;
-            const double lij = colj[i];
-            for (int kk = tx; kk <= ii; kk += 32) {
-                const long k = j + 1 + kk;
-                G[i * p + k] -= lij * colj[k];
-            }
+        for (int i = j + 1 + ty; i < nb; i += 16) {
+            const double lij = D[i][j];
+            for (int k = j + 1 + tx; k <= i; k += 16) D[i][k] -= lij * D[k][j];
         }
         __syncthreads();
     }
-    // X = L^{-1}: column c solves L x = e_c
-    for (int c = tid; c < p; c += 1024) {
-        for (int i = 0; i < c; ++i) X[(long)i * p + c] = 0.0;
-        X[(long)c * p + c] = 1.0 / G[(long)c * p + c];
-    }
-    __syncthreads();
-    for (int i = 1; i < p; ++i) {
-        // row i of X for all columns c < i:  x_ic = -(sum_{k=c}^{i-1} L_ik x_kc) / L_ii
-        const double lii = G[(long)i * p + i];
-        for (int c = tid; c < i; c += 1024) {
-            double a = 0.0;
-            for (int k = c; k < i; ++k) a += G[(long)i * p + k] * X[(long)k * p + c];
-            X[(long)i * p + c] = -a / lii;
-        }
-        // column c only reads its own earlier entries: no barrier needed between rows
+    for (int idx = tid; idx < nb * nb; idx += 256) {
+        const int i = idx / nb, k = idx % nb;
+        G[(long)(k0 + i) * p + k0 + k] = k <= i ? D[i][k] : 0.0;
     }
     if (tid == 0 && nbad) atomicAdd(bad, nbad);
+}
+
+// Step 2: workgroup w solves 64 rows of the panel below the factored block: L_rows = A_rows L_kk^{-T}.
+__global__ __launch_bounds__(256) void chol_solve_kernel(double* G, int p, int k0, int nb) {
+    __shared__ double D[NB][NB + 1], P[NB][NB + 1];
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < nb * nb; idx += 256) D[idx / nb][idx % nb] = G[(long)(k0 + idx / nb) * p + k0 + idx % nb];
+    const int r0 = k0 + nb + blockIdx.x * NB;
+    const int nr = min(NB, p - r0);
+    for (int idx = tid; idx < nr * nb; idx += 256) P[idx / nb][idx % nb] = G[(long)(r0 + idx / nb) * p + k0 + idx % nb];
+    __syncthreads();
+    if (tid < nr) {
+        for (int c = 0; c < nb; ++c) {
+            double v = P[tid][c];
+            for (int u = 0; u < c; ++u) v -= P[tid][u] * D[c][u];
+            P[tid][c] = v / D[c][c];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nr * nb; idx += 256) G[(long)(r0 + idx / nb) * p + k0 + idx % nb] = P[idx / nb][idx % nb];
+}
+
+// X_jj = L_jj^{-1} for every diagonal block j (one workgroup each); thread c solves L x = e_c.
+__global__ __launch_bounds__(64) void tri_inverse_diag_kernel(const double* __restrict__ G, double* __restrict__ X, int p) {
+    __shared__ double D[NB][NB + 1], Y[NB][NB + 1];
+    const int k0 = blockIdx.x * NB, nb = min(NB, p - k0), c = threadIdx.x;
+    for (int idx = c; idx < nb * nb; idx += 64) D[idx / nb][idx % nb] = G[(long)(k0 + idx / nb) * p + k0 + idx % nb];
+    __syncthreads();
+    if (c < nb) {
+        for (int i = 0; i < c; ++i) Y[i][c] = 0.0;
+        Y[c][c] = 1.0 / D[c][c];
+        for (int i = c + 1; i < nb; ++i) {
+            double a = 0.0;
+            for (int k = c; k < i; ++k) a += D[i][k] * Y[k][c];
+            Y[i][c] = -a / D[i][i];
+        }
+    }
+    __syncthreads();
+    for (int idx = c; idx < nb * nb; idx += 64) X[(long)(k0 + idx / nb) * p + k0 + idx % nb] = Y[idx / nb][idx % nb];
+}
+
+__global__ __launch_bounds__(256) void fill_double_kernel(double* dst, double value, long count) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long)gridDim.x * 256) dst[i] = value;
 }
 
 __global__ __launch_bounds__(256) void symmetrise_kernel(double* T, int p) {
@@ -399,7 +538,45 @@ hipError_t launch_balance(const double* K, int ldk, const double* V, int ldv, co
     return hipGetLastError();
 }
 
+// scratch behind the batch of V matrices: angles, ranks, state of the wide solver
+constexpr size_t JACOBI_EXTRA_BYTES = 2 * 1024 * sizeof(double) + EIG_MAX_M * sizeof(int) + 256;
+size_t jacobi_work_bytes(int batch, int m) { return (size_t)batch * m * m * sizeof(double) + JACOBI_EXTRA_BYTES; }
+
+static hipError_t launch_jacobi_wide(double* A, double* evals, double* V, void* extra, int* info, int m, int max_sweeps, hipStream_t s) {
+    double* cs = static_cast<double*>(extra);
+    int* rank = reinterpret_cast<int*>(cs + 2 * 1024);
+    WideState* st = reinterpret_cast<WideState*>(rank + EIG_MAX_M);
+    const int mp = m + (m & 1), half = mp / 2;
+    hipError_t e;
+    jw_init_kernel<<<grid_for((long)m * m), 256, 0, s>>>(V, m, st);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int col_grid = (int)(((long)half * m + 255) / 256);
+    for (int sweep = 0; sweep <= max_sweeps; ++sweep) {
+        jw_norm_kernel<<<1, 1024, 0, s>>>(A, m, sweep, st);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (sweep == max_sweeps) break;
+        for (int step = 0; step < mp - 1; ++step) {
+            jw_rows_kernel<<<half, 256, 0, s>>>(A, m, mp, step, cs, st);
+            jw_cols_kernel<<<col_grid, 256, 0, s>>>(A, V, m, mp, step, cs, st);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    jw_rank_kernel<<<1, 1024, 0, s>>>(A, m, evals, rank, st, info);
+    jw_permute_kernel<<<grid_for((long)m * m), 256, 0, s>>>(A, V, rank, m);
+    return hipGetLastError();
+}
+
 hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int batch, int m, int max_sweeps, hipStream_t s) {
+    if (m > 128) {                                     // large matrices: the whole chip works on one at a time
+        void* extra = work + (size_t)batch * m * m;
+        const int sweeps = std::min(max_sweeps, 16);
+        for (int b = 0; b < batch; ++b) {
+            hipError_t e = launch_jacobi_wide(A + (size_t)b * m * m, evals + (size_t)b * m, work + (size_t)b * m * m,
+                                              extra, info + b, m, sweeps, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     const size_t head = (sizeof(JacobiLds) + 15) & ~size_t(15);
     const size_t mats = 2 * (size_t)m * m * sizeof(double);
     const int in_lds = head + mats <= 128 * 1024;
@@ -416,9 +593,39 @@ hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int 
     return hipGetLastError();
 }
 
-hipError_t launch_chol_inverse(double* G, double* X, int p, int* bad, hipStream_t s) {
-    chol_inverse_kernel<<<1, 1024, 0, s>>>(G, X, p, bad);
-    return hipGetLastError();
+hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* bad, hipStream_t s) {
+    double* floor_v = tmp;                 // one double
+    double* T = tmp + 8;                   // 64 x p
+    hipError_t e;
+    max_diag_kernel<<<1, 1024, 0, s>>>(G, p, floor_v);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int nblk = (p + NB - 1) / NB;
+    // right-looking factorisation: panel, then trailing block  A22 -= L21 L21^T
+    for (int k = 0; k < nblk; ++k) {
+        const int k0 = k * NB, nb = std::min(NB, p - k0), rest = p - k0 - nb;
+        chol_diag_kernel<<<1, 256, 0, s>>>(G, p, k0, nb, floor_v, bad);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (rest > 0) {
+            chol_solve_kernel<<<(rest + NB - 1) / NB, 256, 0, s>>>(G, p, k0, nb);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            const double* L21 = G + (long)(k0 + nb) * p + k0;
+            GemmF64 g{L21, p, 1, L21, 1, p, G + (long)(k0 + nb) * (p + 1), p, rest, rest, nb, -1.0, nullptr, 0, 1, nullptr, 0};
+            if ((e = launch_gemm_f64(g, s)) != hipSuccess) return e;
+        }
+    }
+    // X = L^{-1}: diagonal blocks, then block row i:  X[i, :i] = -X_ii (L[i, :i] X[:i, :i])
+    fill_double_kernel<<<grid_for((long)p * p), 256, 0, s>>>(X, 0.0, (long)p * p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    tri_inverse_diag_kernel<<<nblk, 64, 0, s>>>(G, X, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    for (int i = 1; i < nblk; ++i) {
+        const int i0 = i * NB, nb = std::min(NB, p - i0);
+        GemmF64 t{G + (long)i0 * p, p, 1, X, p, 1, T, p, nb, i0, i0, 1.0, nullptr, 0, 0, nullptr, 0};
+        if ((e = launch_gemm_f64(t, s)) != hipSuccess) return e;
+        GemmF64 x{X + (long)i0 * (p + 1), p, 1, T, p, 1, X + (long)i0 * p, p, nb, i0, nb, -1.0, nullptr, 0, 0, nullptr, 0};
+        if ((e = launch_gemm_f64(x, s)) != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_symmetrise(double* T, int p, hipStream_t s) {

@@ -10,6 +10,7 @@
 // same for all four transpose combinations; the next K step is fetched into
 // registers while the current one is multiplied.
 #include "convert_internal.h"
+#include <algorithm>
 
 namespace mla {
 namespace conv {
@@ -46,16 +47,20 @@ __device__ __forceinline__ void stage(double* S, int tid, const double (&r)[8]) 
 }
 
 template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, int total) {
+__global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, int tiles, int splits, int kt_per) {
     extern __shared__ double lds[];            // As[2][BK][LD], Bs[2][BK][LD]
     double* As = lds;
     double* Bs = lds + 2 * STAGE;
 
     // consecutive tiles (same rows of A) share an XCD: workgroup ids 8 apart run on one XCD
+    const int total = tiles * splits;
     const int per = (total + 7) / 8;
-    const int tile = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (tile >= total) return;
+    const int item = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (item >= total) return;
+    const int tile = item % tiles, z = item / tiles;     // z: slice of the K range
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int nk_all = (g.K + BK - 1) / BK;
+    const int kt0 = z * kt_per, kt1 = min(nk_all, kt0 + kt_per);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -68,16 +73,15 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, i
         for (int j = 0; j < 4; ++j) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
     double ra[8], rb[8];
-    fetch<A_KC>(g.A, g.sAm, g.sAk, m0, 0, g.M, g.K, tid, ra);
-    fetch<B_KC>(g.B, g.sBn, g.sBk, n0, 0, g.N, g.K, tid, rb);
+    fetch<A_KC>(g.A, g.sAm, g.sAk, m0, kt0 * BK, g.M, g.K, tid, ra);
+    fetch<B_KC>(g.B, g.sBn, g.sBk, n0, kt0 * BK, g.N, g.K, tid, rb);
     stage<A_KC>(As, tid, ra);
     stage<B_KC>(Bs, tid, rb);
     __syncthreads();
 
-    const int nk = (g.K + BK - 1) / BK;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < nk;
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int buf = (kt - kt0) & 1;
+        const bool more = kt + 1 < kt1;
         if (more) {
             fetch<A_KC>(g.A, g.sAm, g.sAk, m0, (kt + 1) * BK, g.M, g.K, tid, ra);
             fetch<B_KC>(g.B, g.sBn, g.sBk, n0, (kt + 1) * BK, g.N, g.K, tid, rb);
@@ -105,6 +109,20 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, i
         __syncthreads();
     }
 
+    if (splits > 1) {                                    // raw slice product; the reduction kernel scales
+        double* part = g.partial + (size_t)z * g.M * g.N;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = m0 + wm + i * 16 + 4 * r + kq;
+                    const int col = n0 + wn + j * 16 + li;
+                    if (row < g.M && col < g.N) part[(size_t)row * g.N + col] = acc[i][j][r];
+                }
+        return;
+    }
     double scale = g.alpha;
     if (g.dev_mode == 1) scale *= *g.alpha_dev;
     else if (g.dev_mode == 2) scale /= *g.alpha_dev;
@@ -116,8 +134,25 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, i
             for (int r = 0; r < 4; ++r) {
                 const int row = m0 + wm + i * 16 + 4 * r + kq;
                 const int col = n0 + wn + j * 16 + li;
-                if (row < g.M && col < g.N) g.C[(long)row * g.ldc + col] = scale * acc[i][j][r];
+                if (row < g.M && col < g.N) {
+                    double* c = g.C + (long)row * g.ldc + col;
+                    *c = g.accumulate ? *c + scale * acc[i][j][r] : scale * acc[i][j][r];
+                }
             }
+}
+
+// C (=|+=) scale * sum over the K slices, slices added in index order
+__global__ __launch_bounds__(256) void gemm_f64_reduce_kernel(GemmF64 g, int splits) {
+    const long total = (long)g.M * g.N;
+    double scale = g.alpha;
+    if (g.dev_mode == 1) scale *= *g.alpha_dev;
+    else if (g.dev_mode == 2) scale /= *g.alpha_dev;
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+        double a = 0.0;
+        for (int z = 0; z < splits; ++z) a += g.partial[(size_t)z * total + idx];
+        double* c = g.C + (idx / g.N) * g.ldc + idx % g.N;
+        *c = g.accumulate ? *c + scale * a : scale * a;
+    }
 }
 
 template <bool A_KC, bool B_KC>
@@ -131,9 +166,25 @@ hipError_t run(const GemmF64& g, hipStream_t s) {
         configured = true;
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    const int total = tiles_m * tiles_n;
+    const int tiles = tiles_m * tiles_n;
+    const int nk = (g.K + BK - 1) / BK;
+    // K slices: only when scratch is there, the tiles leave most of the 256 CUs idle and every slice
+    // still has at least 8 K steps
+    int splits = 1;
+    if (g.partial && tiles <= 64 && nk >= 32) {
+        const size_t fit = g.partial_doubles / ((size_t)g.M * g.N);
+        splits = (int)std::min<size_t>(std::min<size_t>(fit, 256 / tiles), nk / 8);
+        if (splits < 2) splits = 1;
+    }
+    int kt_per = (nk + splits - 1) / splits;
+    splits = (nk + kt_per - 1) / kt_per;                 // no empty slice
+    const int total = tiles * splits;
     const int grid = ((total + 7) / 8) * 8;
-    gemm_f64_kernel<A_KC, B_KC><<<grid, 256, lds_bytes, s>>>(g, tiles_n, total);
+    gemm_f64_kernel<A_KC, B_KC><<<grid, 256, lds_bytes, s>>>(g, tiles_n, tiles, splits, kt_per);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    const long cells = (long)g.M * g.N;
+    gemm_f64_reduce_kernel<<<(int)std::min<long>((cells + 255) / 256, 4096), 256, 0, s>>>(g, splits);
     return hipGetLastError();
 }
 

@@ -8,7 +8,7 @@ from pathlib import Path
 import pytest
 
 ROOT = Path(__file__).resolve().parents[1]
-HEADER = ROOT / "include" / "mla_gfx950.h"
+HEADERS = sorted((ROOT / "include").glob("*.h"))
 LIBPATH = ROOT / "paper_2502_07864_amd" / "libmla_gfx950.so"
 
 OK, E_NULL, E_SHAPE, E_UNSUP, E_WS, E_HIP = 0, -1, -2, -3, -4, -6
@@ -42,8 +42,11 @@ def lib():
 
 
 def declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
-    return sorted(set(re.findall(r"\b(mla_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", header.read_text(), flags=re.S)
+        names |= set(re.findall(r"\b(mla_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_functions_are_exported(lib):
@@ -55,7 +58,7 @@ def test_header_functions_are_exported(lib):
 
 
 def test_binding_lists_the_same_entry_points():
-    src = (ROOT / "paper_2502_07864_amd" / "mla.py").read_text()
+    src = "".join((ROOT / "paper_2502_07864_amd" / f).read_text() for f in ("mla.py", "convert.py"))
     for n in declared_functions():
         assert n in src, f"{n} has no Python binding"
 
@@ -232,3 +235,98 @@ def test_product_path_does_not_use_the_oracle():
         if f.suffix in (".py", ".c"):
             t = f.read_text()
             assert "paper_2502_07864_amd" not in t and "mla_gfx950" not in t
+
+
+# ------------------------------------------------------------------ offline conversion (mla_convert_gfx950.h)
+
+def conv_lib(lib):
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.mla_conv_project.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.mla_conv_rope_moments.argtypes = [vp, vp, i, i, i, i, vp]
+    lib.mla_conv_sym_eig_workspace_bytes.restype = sz
+    lib.mla_conv_sym_eig_workspace_bytes.argtypes = [i, i]
+    lib.mla_conv_sym_eig.argtypes = [vp, vp, vp, sz, vp, i, i, i, vp]
+    lib.mla_conv_rotate_rows.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.mla_conv_kv_balance.argtypes = [vp, i, vp, i, vp, vp, i, i, i, vp]
+    lib.mla_conv_joint_moment.argtypes = [vp, i, vp, i, vp, vp, vp, i, i, i, vp]
+    lib.mla_conv_top_eig_workspace_bytes.restype = sz
+    lib.mla_conv_top_eig_workspace_bytes.argtypes = [i, i]
+    lib.mla_conv_top_eig.argtypes = [vp, vp, vp, vp, vp, sz, vp, i, i, i, i, vp]
+    lib.mla_conv_apply.argtypes = [vp, vp, vp, i, i, vp]
+    lib.mla_convert_layer_workspace_bytes.restype = sz
+    lib.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    lib.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 9 + [vp]
+    return lib
+
+
+P = 0x1000   # a non-NULL pointer value; every call below is rejected before it could be used
+
+
+def test_conversion_header_is_scanned():
+    assert {"mla_conv_project", "mla_conv_sym_eig", "mla_conv_top_eig", "mla_convert_layer"} <= set(declared_functions())
+
+
+def test_conversion_step_validation(lib):
+    L = conv_lib(lib)
+    assert L.mla_conv_project(None, P, P, 4, 4, 4, 4, None) == E_NULL
+    assert L.mla_conv_project(P, P, P, 4, 4, 4, 3, None) == E_SHAPE          # ldy < m
+    assert L.mla_conv_project(P, P, P, 0, 4, 4, 4, None) == E_SHAPE
+    assert L.mla_conv_rope_moments(P, None, 8, 2, 8, 1, None) == E_NULL
+    assert L.mla_conv_rope_moments(P, P, 8, 2, 7, 1, None) == E_SHAPE        # odd head dimension
+    assert L.mla_conv_rope_moments(P, P, 8, 2, 8, 3, None) == E_SHAPE        # 4 pairs do not fold by 3
+    assert L.mla_conv_rope_moments(P, P, 8, 32, 128, 8, None) == E_UNSUP     # M g = 256 > 128
+    assert L.mla_conv_rotate_rows(P, P, P, 2, 8, 1, 16, None) == E_SHAPE     # in place is not allowed
+    assert L.mla_conv_rotate_rows(P, P, P + 64, 2, 8, 1, 0, None) == E_SHAPE
+    assert L.mla_conv_kv_balance(P, 4, P, 4, None, P, 8, 4, 4, None) == E_NULL
+    assert L.mla_conv_kv_balance(P, 3, P, 4, P, P, 8, 4, 4, None) == E_SHAPE  # ldk < a
+    assert L.mla_conv_joint_moment(P, 4, P, 4, P, P, None, 8, 4, 4, None) == E_NULL
+    assert L.mla_conv_joint_moment(P, 4, P, 4, P, P, P, 0, 4, 4, None) == E_SHAPE
+
+
+def test_conversion_eigensolver_validation(lib):
+    L = conv_lib(lib)
+    need = L.mla_conv_sym_eig_workspace_bytes(3, 32)
+    assert 3 * 32 * 32 * 8 <= need <= 3 * 32 * 32 * 8 + (1 << 16)
+    assert L.mla_conv_sym_eig_workspace_bytes(1, 1) == 0 and L.mla_conv_sym_eig_workspace_bytes(1, 2049) == 0
+    assert L.mla_conv_sym_eig(P, P, P, 1 << 20, None, 1, 8, 30, None) == E_NULL
+    assert L.mla_conv_sym_eig(P, P, P, 1 << 20, P, 1, 1, 30, None) == E_SHAPE
+    assert L.mla_conv_sym_eig(P, P, P, 1 << 30, P, 1, 4096, 30, None) == E_UNSUP
+    assert L.mla_conv_sym_eig(P, P, P, L.mla_conv_sym_eig_workspace_bytes(1, 8) - 1, P, 1, 8, 30, None) == E_WS
+    assert L.mla_conv_sym_eig(P, P, None, 0, P, 1, 8, 30, None) == E_WS
+    n = L.mla_conv_top_eig_workspace_bytes(8064, 576)
+    assert n >= 2 * 8064 * 576 * 8 + 4 * 576 * 576 * 8 and n % 256 == 0
+    assert L.mla_conv_top_eig_workspace_bytes(100, 101) == 0 and L.mla_conv_top_eig_workspace_bytes(4096, 2048) == 0
+    assert L.mla_conv_top_eig(P, P, P, P, P, 1 << 30, P, 100, 20, 10, 5, None) == E_SHAPE      # p < r
+    assert L.mla_conv_top_eig(P, P, P, P, P, 1 << 30, P, 100, 20, 101, 5, None) == E_SHAPE     # p > m
+    assert L.mla_conv_top_eig(P, P, P, P, P, 1 << 40, P, 4096, 20, 2048, 5, None) == E_UNSUP   # p > 1024
+    assert L.mla_conv_top_eig(P, P, P, P, P, 16, P, 100, 20, 30, 5, None) == E_WS
+    assert L.mla_conv_top_eig(P, None, P, P, P, 1 << 30, P, 100, 20, 30, 5, None) == E_NULL
+    assert L.mla_conv_apply(P, P, None, 8, 4, None) == E_NULL
+    assert L.mla_conv_apply(P, P, P, 8, 4, None) == E_SHAPE       # in place is not allowed
+    assert L.mla_conv_apply(P, P, P + 64, 8, 0, None) == E_SHAPE
+
+
+def test_conversion_chain_validation(lib):
+    L = conv_lib(lib)
+    ok = dict(n=256, D=64, g=4, h=8, d=16, M=1, r_kv=24, p=32, iters=10)
+
+    def call(ws_bytes=1 << 40, null_at=None, **kw):
+        a = dict(ok, **kw)
+        ptrs = [P] * 14
+        if null_at is not None:
+            ptrs[null_at] = None
+        return L.mla_convert_layer(*ptrs, P, ws_bytes, P, a["n"], a["D"], a["g"], a["h"], a["d"], a["M"],
+                                   a["r_kv"], a["p"], a["iters"], None)
+
+    need = L.mla_convert_layer_workspace_bytes(256, 64, 4, 8, 16, 1, 24, 32)
+    assert need > 256 * (7 * 16) * 8 and need % 256 == 0
+    assert call(null_at=0) == E_NULL and call(null_at=13) == E_NULL
+    assert call(h=6) == E_SHAPE            # h not a multiple of g
+    assert call(d=15) == E_SHAPE
+    assert call(M=3) == E_SHAPE            # 8 pairs do not fold by 3
+    assert call(r_kv=40) == E_SHAPE        # r_kv > p
+    assert call(p=200) == E_SHAPE          # p > (2g-1)d = 112
+    assert call(g=1, h=8) == E_SHAPE       # nothing to merge
+    assert call(g=32, h=32, d=128, M=8, D=4096, r_kv=512, p=576) == E_UNSUP   # M g > 128
+    assert call(ws_bytes=need - 1) == E_WS
+    assert L.mla_convert_layer_workspace_bytes(256, 64, 4, 6, 16, 1, 24, 32) == 0

@@ -77,7 +77,8 @@ def check_eig(A, evals, U, info, tol=1e-10):
         assert np.abs(A[b] @ U[b] - U[b] * evals[b]).max() <= tol * scale
 
 
-@pytest.mark.parametrize("batch,m", [(3, 2), (4, 5), (64, 32), (5, 64), (2, 80), (2, 96), (1, 257), (1, 512)])
+@pytest.mark.parametrize("batch,m", [(3, 2), (4, 5), (64, 32), (5, 64), (2, 80), (2, 96), (3, 128), (2, 130),
+                                     (1, 257), (1, 512)])
 def test_sym_eig_random(cv, batch, m):
     r = rng(m)
     A = r.standard_normal((batch, m, m))
@@ -145,7 +146,8 @@ def projector_gap(R, R_ref):
     return np.abs(R @ R.T - R_ref @ R_ref.T).max()
 
 
-@pytest.mark.parametrize("m,r,p,iters", [(60, 8, 16, 40), (200, 40, 64, 60), (300, 17, 33, 60), (40, 40, 40, 2)])
+@pytest.mark.parametrize("m,r,p,iters", [(60, 8, 16, 40), (200, 40, 64, 60), (300, 17, 33, 60), (40, 40, 40, 2),
+                                         (700, 130, 160, 120), (1500, 64, 200, 30)])
 def test_top_eig_against_full_eigendecomposition(cv, m, r, p, iters):
     rs = rng(m + r)
     Q, _ = np.linalg.qr(rs.standard_normal((m, m)))
@@ -160,6 +162,7 @@ def test_top_eig_against_full_eigendecomposition(cv, m, r, p, iters):
     assert np.abs(evals[:r] - w_ref[:r]).max() < 1e-10 * w_ref[0]
     assert projector_gap(R, R_ref) < 1e-8
     assert np.abs(S @ R - R * evals[:r]).max() < 1e-9 * w_ref[0]
+    assert rel(host(cv.apply(dev(S), dev(R))), S @ R) < 1e-12
 
 
 # ------------------------------------------------------------------ the chain
