@@ -2,6 +2,7 @@
 // argument checks on the host, then launches on the caller's stream.
 #include "mla_convert_gfx950.h"
 #include "convert_internal.h"
+#include <algorithm>
 
 using namespace mla::conv;
 
@@ -37,7 +38,7 @@ TopWs top_ws(void* base, int m, int p) {
     w.T = take((size_t)p * p);
     w.Z = take(jacobi_work_bytes(1, p) / sizeof(double));
     w.tmp = take((size_t)64 * p + 8);
-    w.part_doubles = (size_t)GRAM_SLICES * p * p;
+    w.part_doubles = std::max((size_t)GRAM_SLICES * p * p, (size_t)4 * m * p);
     w.part = take(w.part_doubles);
     w.bytes = off;
     return w;
@@ -64,7 +65,10 @@ int top_eig(const double* S, const double* Q0, double* evals, double* R, const T
     if ((rc = chol_qr(Q0, w.Y, w, m, p, info, s)) != MLA_OK) return rc;
     if ((rc = chol_qr(w.Y, w.Q, w, m, p, info, s)) != MLA_OK) return rc;
     for (int it = 0; it < iters; ++it) {
-        e = launch_gemm_f64(gemm_nn(S, m, w.Q, p, w.Y, p, m, p, m, 1.0), s);
+        GemmF64 sq = gemm_nn(S, m, w.Q, p, w.Y, p, m, p, m, 1.0);
+        sq.partial = w.part;
+        sq.partial_doubles = w.part_doubles;
+        e = launch_gemm_f64(sq, s);
         if (e != hipSuccess) return MLA_ERR_HIP;
         if ((rc = chol_qr(w.Y, w.Q, w, m, p, info, s)) != MLA_OK) return rc;
     }

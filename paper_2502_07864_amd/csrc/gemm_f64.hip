@@ -11,6 +11,7 @@
 // registers while the current one is multiplied.
 #include "convert_internal.h"
 #include <algorithm>
+#include <cmath>
 
 namespace mla {
 namespace conv {
@@ -19,7 +20,8 @@ namespace {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LD = 144;                       // row pitch of a staged k-row, in doubles
+constexpr int LD = 132;                       // row pitch of a staged k-row, in doubles: 264 dwords = 8 (mod 64), so
+                                              // the 16 k-rows a wavefront writes at once fall on different banks
 constexpr int STAGE = BK * LD;                // one operand, one buffer
 
 // Fetch the 128 x 16 tile of an operand whose (mn, k) element is P[mn*s_mn + k*s_k].
@@ -47,7 +49,7 @@ __device__ __forceinline__ void stage(double* S, int tid, const double (&r)[8]) 
 }
 
 template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64 g, int tiles_n, int tiles, int splits, int kt_per) {
+__global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n, int tiles, int splits, int kt_per) {
     extern __shared__ double lds[];            // As[2][BK][LD], Bs[2][BK][LD]
     double* As = lds;
     double* Bs = lds + 2 * STAGE;
@@ -171,9 +173,17 @@ hipError_t run(const GemmF64& g, hipStream_t s) {
     // K slices: only when scratch is there, the tiles leave most of the 256 CUs idle and every slice
     // still has at least 8 K steps
     int splits = 1;
-    if (g.partial && tiles <= 64 && nk >= 32) {
+    if (g.partial && nk >= 32) {
         const size_t fit = g.partial_doubles / ((size_t)g.M * g.N);
-        splits = (int)std::min<size_t>(std::min<size_t>(fit, 256 / tiles), nk / 8);
+        const int most = (int)std::min<size_t>(std::min<size_t>(fit, 16), nk / 8);
+        if (tiles <= 64) {
+            splits = std::min(most, 256 / tiles);
+        } else if (tiles < 1024) {
+            // pick the fewest slices that keep at least 85 % of the CUs busy in the last round
+            auto fill = [&](int sp) { const double r = (double)tiles * sp / 256.0; return r / std::ceil(r); };
+            for (int sp = 1; sp <= std::min(most, 4); ++sp)
+                if (fill(sp) > fill(splits) + 0.05) { splits = sp; if (fill(sp) >= 0.85) break; }
+        }
         if (splits < 2) splits = 1;
     }
     int kt_per = (nk + splits - 1) / splits;
