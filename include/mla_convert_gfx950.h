@@ -114,8 +114,13 @@ int mla_conv_joint_moment(const double* K_nope, int ldk, const double* V, int ld
 size_t mla_conv_top_eig_workspace_bytes(int m, int p);
 /* One application of the moment matrix to a block, Y = S Q (the product each step of the
  * iteration above spends its time in; with Q = R it gives the residual S R - R diag(evals)).
- *   S [m, m], Q [m, p], Y [m, p] (distinct from Q). */
-int mla_conv_apply(const double* S, const double* Q, double* Y, int m, int p, void* hip_stream);
+ *   S [m, m], Q [m, p], Y [m, p] (distinct from Q).
+ *   workspace: optional scratch of mla_conv_apply_workspace_bytes(m, p) bytes (NULL, 0: none).  With
+ *   it, a product whose output tiles alone would leave CUs idle in the last round is computed in
+ *   slices of the K range that are summed in a fixed order, as inside mla_conv_top_eig. */
+size_t mla_conv_apply_workspace_bytes(int m, int p);
+int mla_conv_apply(const double* S, const double* Q, double* Y, void* workspace, size_t workspace_bytes,
+                   int m, int p, void* hip_stream);
 int mla_conv_top_eig(const double* S, const double* Q0, double* evals, double* R,
                      void* workspace, size_t workspace_bytes, int* info,
                      int m, int r, int p, int iters, void* hip_stream);

@@ -15,7 +15,7 @@ from .mla import _check, _stream, lib as _base_lib
 
 EXPORTS = ("mla_conv_project", "mla_conv_rope_moments", "mla_conv_sym_eig_workspace_bytes", "mla_conv_sym_eig",
            "mla_conv_rotate_rows", "mla_conv_kv_balance", "mla_conv_joint_moment",
-           "mla_conv_top_eig_workspace_bytes", "mla_conv_top_eig", "mla_conv_apply",
+           "mla_conv_top_eig_workspace_bytes", "mla_conv_top_eig", "mla_conv_apply_workspace_bytes", "mla_conv_apply",
            "mla_convert_layer_workspace_bytes", "mla_convert_layer")
 
 _ready = False
@@ -44,8 +44,10 @@ def lib() -> ctypes.CDLL:
         L.mla_conv_top_eig_workspace_bytes.argtypes = [i, i]
         L.mla_conv_top_eig.restype = i
         L.mla_conv_top_eig.argtypes = [vp, vp, vp, vp, vp, sz, vp, i, i, i, i, vp]
+        L.mla_conv_apply_workspace_bytes.restype = sz
+        L.mla_conv_apply_workspace_bytes.argtypes = [i, i]
         L.mla_conv_apply.restype = i
-        L.mla_conv_apply.argtypes = [vp, vp, vp, i, i, vp]
+        L.mla_conv_apply.argtypes = [vp, vp, vp, vp, sz, i, i, vp]
         L.mla_convert_layer_workspace_bytes.restype = sz
         L.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
         L.mla_convert_layer.restype = i
@@ -139,11 +141,18 @@ def top_eig(S: torch.Tensor, Q0: torch.Tensor, r: int, iters: int):
     return evals, R, info
 
 
-def apply(S: torch.Tensor, Q: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+def apply_workspace_bytes(m: int, p: int) -> int:
+    return lib().mla_conv_apply_workspace_bytes(m, p)
+
+
+def apply(S: torch.Tensor, Q: torch.Tensor, out: Optional[torch.Tensor] = None,
+          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     m, p = Q.shape
     assert S.shape == (m, m)
     Y = out if out is not None else _new(S, m, p)
-    _check(lib().mla_conv_apply(_f64(S, "S"), _f64(Q, "Q"), _f64(Y, "Y"), m, p, _stream(S)), "mla_conv_apply")
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(lib().mla_conv_apply(_f64(S, "S"), _f64(Q, "Q"), _f64(Y, "Y"), ws_ptr, ws_bytes, m, p, _stream(S)),
+           "mla_conv_apply")
     return Y
 
 

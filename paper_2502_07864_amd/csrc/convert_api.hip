@@ -77,7 +77,10 @@ int top_eig(const double* S, const double* Q0, double* evals, double* R, const T
     e = launch_copy_scaled(w.Y, p, w.Q, p, m, p, nullptr, 0, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
     // T = Q^T S Q, T = Z diag(evals) Z^T, R = Q Z[:, :r]
-    e = launch_gemm_f64(gemm_nn(S, m, w.Q, p, w.Y, p, m, p, m, 1.0), s);
+    GemmF64 sq = gemm_nn(S, m, w.Q, p, w.Y, p, m, p, m, 1.0);
+    sq.partial = w.part;
+    sq.partial_doubles = w.part_doubles;
+    e = launch_gemm_f64(sq, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
     GemmF64 ritz = gemm_tn(w.Q, p, w.Y, p, w.T, p, p, p, m, 1.0);
     ritz.partial = w.part;
@@ -199,10 +202,21 @@ int mla_conv_top_eig(const double* S, const double* Q0, double* evals, double* R
     return top_eig(S, Q0, evals, R, top_ws(workspace, m, p), info, m, r, p, iters, static_cast<hipStream_t>(hip_stream));
 }
 
-int mla_conv_apply(const double* S, const double* Q, double* Y, int m, int p, void* hip_stream) {
+size_t mla_conv_apply_workspace_bytes(int m, int p) {
+    if (m <= 0 || p <= 0) return 0;
+    return (size_t)4 * m * p * sizeof(double);
+}
+
+int mla_conv_apply(const double* S, const double* Q, double* Y, void* workspace, size_t workspace_bytes,
+                   int m, int p, void* hip_stream) {
     if (!S || !Q || !Y) return MLA_ERR_NULL;
     if (m <= 0 || p <= 0 || Q == Y) return MLA_ERR_SHAPE;
-    return st(launch_gemm_f64(gemm_nn(S, m, Q, p, Y, p, m, p, m, 1.0), static_cast<hipStream_t>(hip_stream)));
+    GemmF64 g = gemm_nn(S, m, Q, p, Y, p, m, p, m, 1.0);
+    if (workspace && workspace_bytes >= 2 * (size_t)m * p * sizeof(double)) {
+        g.partial = static_cast<double*>(workspace);
+        g.partial_doubles = workspace_bytes / sizeof(double);
+    }
+    return st(launch_gemm_f64(g, static_cast<hipStream_t>(hip_stream)));
 }
 
 size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int r_kv, int p) {

@@ -252,7 +252,9 @@ def conv_lib(lib):
     lib.mla_conv_top_eig_workspace_bytes.restype = sz
     lib.mla_conv_top_eig_workspace_bytes.argtypes = [i, i]
     lib.mla_conv_top_eig.argtypes = [vp, vp, vp, vp, vp, sz, vp, i, i, i, i, vp]
-    lib.mla_conv_apply.argtypes = [vp, vp, vp, i, i, vp]
+    lib.mla_conv_apply_workspace_bytes.restype = sz
+    lib.mla_conv_apply_workspace_bytes.argtypes = [i, i]
+    lib.mla_conv_apply.argtypes = [vp, vp, vp, vp, sz, i, i, vp]
     lib.mla_convert_layer_workspace_bytes.restype = sz
     lib.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     lib.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 9 + [vp]
@@ -301,9 +303,10 @@ def test_conversion_eigensolver_validation(lib):
     assert L.mla_conv_top_eig(P, P, P, P, P, 1 << 40, P, 4096, 20, 2048, 5, None) == E_UNSUP   # p > 1024
     assert L.mla_conv_top_eig(P, P, P, P, P, 16, P, 100, 20, 30, 5, None) == E_WS
     assert L.mla_conv_top_eig(P, None, P, P, P, 1 << 30, P, 100, 20, 30, 5, None) == E_NULL
-    assert L.mla_conv_apply(P, P, None, 8, 4, None) == E_NULL
-    assert L.mla_conv_apply(P, P, P, 8, 4, None) == E_SHAPE       # in place is not allowed
-    assert L.mla_conv_apply(P, P, P + 64, 8, 0, None) == E_SHAPE
+    assert L.mla_conv_apply(P, P, None, None, 0, 8, 4, None) == E_NULL
+    assert L.mla_conv_apply(P, P, P, None, 0, 8, 4, None) == E_SHAPE       # in place is not allowed
+    assert L.mla_conv_apply(P, P, P + 64, None, 0, 8, 0, None) == E_SHAPE
+    assert L.mla_conv_apply_workspace_bytes(8064, 576) == 4 * 8064 * 576 * 8
 
 
 def test_conversion_chain_validation(lib):

@@ -165,6 +165,20 @@ def test_top_eig_against_full_eigendecomposition(cv, m, r, p, iters):
     assert rel(host(cv.apply(dev(S), dev(R))), S @ R) < 1e-12
 
 
+def test_apply_with_k_slices_matches_the_plain_product(cv):
+    """A tall block on a matrix large enough that the library slices the K range when given scratch."""
+    import torch
+    m, p = 2304, 192                                    # 18 x 2 tiles: under a third of the CUs without slices
+    rs = rng(5)
+    S = rs.standard_normal((m, m))
+    S = S + S.T
+    Q = rs.standard_normal((m, p))
+    ws = torch.empty(cv.apply_workspace_bytes(m, p), dtype=torch.uint8, device="cuda")
+    want = S @ Q
+    assert rel(host(cv.apply(dev(S), dev(Q), workspace=ws)), want) < 1e-12
+    assert rel(host(cv.apply(dev(S), dev(Q))), want) < 1e-12
+
+
 # ------------------------------------------------------------------ the chain
 
 def chain_case(g, h, d, D, n, M, r_kv, p, seed):
