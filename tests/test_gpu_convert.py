@@ -222,3 +222,67 @@ def test_convert_layer_against_the_oracle_chain(cv, g, h, d, D, n, M, r_kv, p):
     assert np.abs(R.T @ R - np.eye(r_kv)).max() < 1e-11
     for G in range(groups):
         assert np.abs(got["U"][G].T @ got["U"][G] - np.eye(M * g)).max() < 1e-11
+
+
+# ------------------------------------------------------------------ converted layer through the decode calls
+
+def decode_converted_layer_on_gpu(out, X_ctx, q, d, pos_new, theta, page_size=64):
+    """Cache rows and queries of the converted layer (built here in numpy from the GPU's converted
+    weights: plain projections and RoPE, the inputs of the decode calls), then mla_absorb_q ->
+    mla_decode_paged -> mla_out_proj in fp32 on the GPU."""
+    import torch
+    from paper_2502_07864_amd import mla
+    from test_convert_oracle_pins import rope_hat
+    W = {k: host(v) for k, v in out.items()}
+    h = q.shape[0]
+    L = len(X_ctx)
+    c_kv = X_ctx @ W["W_DKV"].T
+    k_rope = np.stack([rope_hat(W["W_KR"] @ X_ctx[t], t, d, theta) for t in range(L)])
+    q_rope = np.stack([rope_hat(W["W_QR"][i] @ q[i], pos_new, d, theta) for i in range(h)])
+    d_c = c_kv.shape[1]
+    pages = (L + page_size - 1) // page_size
+    pool = np.zeros((pages + 1, page_size, d_c + d), dtype=np.float32)
+    order = np.arange(pages)[::-1] + 1                          # pages stored in reverse, page 0 unused
+    for t in range(L):
+        pool[order[t // page_size], t % page_size] = np.concatenate([c_kv[t], k_rope[t]])
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    q_abs = mla.absorb_q(f32(q[None]), f32(W["W_UK"]))
+    o_lat = mla.decode_paged(q_abs, f32(q_rope[None]), f32(pool), torch.from_numpy(order[None].astype(np.int32)).cuda(),
+                             torch.tensor([L], dtype=torch.int32, device="cuda"), 1.0 / np.sqrt(d), num_splits=2)
+    return host(mla.out_proj(o_lat, f32(W["W_UV"])))[0].astype(np.float64)
+
+
+def test_gpu_conversion_then_gpu_decode_reproduces_gqa_when_nothing_is_lost(cv):
+    """Positions zero (RoPE is the identity) and r_kv = (2g-1)d: the layer converted on the GPU and
+    decoded by the GPU's absorbed path must give the textbook GQA attention output."""
+    from test_convert_oracle_pins import gqa_attention
+    g, h, d, D, n, L = 2, 4, 8, 12, 64, 70
+    r = rng(37)
+    X = r.standard_normal((n, D))
+    W_Q, W_K, W_V = (r.standard_normal((m, D)) / np.sqrt(D) for m in (h * d, g * d, g * d))
+    theta = np.zeros(d // 2)
+    mj = (2 * g - 1) * d
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, mj, seed=2)), g, h, d, 1, mj, iters=2)
+    X_ctx = r.standard_normal((L, D))
+    want = gqa_attention(X_ctx[-1], X_ctx, W_Q, W_K, W_V, g, h, d, L - 1, theta)
+    got = decode_converted_layer_on_gpu(out, X_ctx, (W_Q @ X_ctx[-1]).reshape(h, d), d, L - 1, theta)
+    assert np.abs(got - want).max() < 2e-5 * max(1.0, np.abs(want).max())
+
+
+@pytest.mark.parametrize("M", [1, 2])
+def test_gpu_converted_layer_decodes_like_the_oracles_converted_layer(cv, M):
+    """Truncated rank and real positions: the attention output of the converted layer does not depend on
+    the signs of the bases, so GPU conversion + GPU decode must match numpy conversion + the decode oracle."""
+    from test_convert_oracle_pins import mla_attention_through_the_decode_oracle, std_theta
+    g, h, d, D, n, L, r_kv, p = 4, 8, 16, 64, 400, 150, 40, 56
+    X, W_K, W_V = synth.calibration(n, D, g, d, seed=11 + M)
+    r = rng(43)
+    W_Q = r.standard_normal((h * d, D)) / np.sqrt(D)
+    X_ctx = synth.calibration(L, D, g, d, seed=13)[0]
+    theta = std_theta(d)
+    mj = (2 * g - 1) * d
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=3)), g, h, d, M, r_kv, iters=80)
+    ref = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    want = mla_attention_through_the_decode_oracle(ref, X_ctx[-1], X_ctx, W_Q, h, d, L - 1, theta)
+    got = decode_converted_layer_on_gpu(out, X_ctx, (W_Q @ X_ctx[-1]).reshape(h, d), d, L - 1, theta)
+    assert np.abs(got - want).max() < 2e-5 * max(1.0, np.abs(want).max())
