@@ -37,7 +37,7 @@ TopWs top_ws(void* base, int m, int p) {
     w.X = take((size_t)p * p);
     w.T = take((size_t)p * p);
     w.Z = take(jacobi_work_bytes(1, p) / sizeof(double));
-    w.tmp = take((size_t)64 * p + 8);
+    w.tmp = take(chol_tmp_doubles(p));
     w.part_doubles = std::max((size_t)GRAM_SLICES * p * p, (size_t)4 * m * p);
     w.part = take(w.part_doubles);
     w.bytes = off;

@@ -40,7 +40,8 @@ size_t jacobi_work_bytes(int batch, int m);
 hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int batch, int m, int max_sweeps, hipStream_t s);
 // G (p x p, symmetric positive definite) -> lower Cholesky factor in place (blocks above the diagonal
 // are left undefined), X = its inverse (zero above the diagonal); *bad += clamped pivots.
-// tmp: 64 * p + 8 doubles of scratch.
+// tmp: chol_tmp_doubles(p) doubles of scratch.
+inline size_t chol_tmp_doubles(int p) { return 8 + (size_t)64 * p + (size_t)16 * 64 * p; }
 hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* bad, hipStream_t s);
 hipError_t launch_symmetrise(double* T, int p, hipStream_t s);
 hipError_t launch_fill_int(int* dst, int value, int count, hipStream_t s);

@@ -435,6 +435,67 @@ __global__ __launch_bounds__(256) void chol_solve_kernel(double* G, int p, int k
     for (int idx = tid; idx < nr * nb; idx += 256) G[(long)(r0 + idx / nb) * p + k0 + idx % nb] = P[idx / nb][idx % nb];
 }
 
+// The same two steps for full 64 x 64 blocks with the rows held in registers (every loop unrolled, so all
+// register indices are static).  Factorisation: one wavefront, lane i owns row i; the pivot and the
+// column entries travel between lanes through scalar registers (v_readlane), so there is no LDS
+// traffic and no barrier in the 64 dependent steps.  Entries above the diagonal are scratch.
+__device__ __forceinline__ double lane_value(double v, int lane) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+__global__ __launch_bounds__(64) void chol_diag64_kernel(double* G, int p, int k0,
+                                                         const double* __restrict__ floor_in, int* bad) {
+    const int i = threadIdx.x;
+    double* mine = G + (long)(k0 + i) * p + k0;
+    double row[NB];
+#pragma unroll
+    for (int k = 0; k < NB; ++k) row[k] = mine[k];
+    const double floor_v = *floor_in;
+    int nbad = 0;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        double d = lane_value(row[j], j);
+        if (!(d > floor_v)) { d = floor_v; ++nbad; }
+        const double piv = sqrt(d), inv = 1.0 / piv;
+        row[j] = i == j ? piv : row[j] * inv;
+#pragma unroll
+        for (int k = j + 1; k < NB; ++k) row[k] -= row[j] * lane_value(row[j], k);
+    }
+#pragma unroll
+    for (int k = 0; k < NB; ++k) mine[k] = k <= i ? row[k] : 0.0;
+    if (i == 0 && nbad) atomicAdd(bad, nbad);
+}
+
+// Panel solve: one wavefront per 64 rows, lane = row, the factored block (and the reciprocals of its
+// diagonal) broadcast from LDS.
+__global__ __launch_bounds__(64) void chol_solve64_kernel(double* G, int p, int k0) {
+    __shared__ double D[NB][NB], Dinv[NB];
+    const int tid = threadIdx.x;
+#pragma unroll 8
+    for (int idx = tid; idx < NB * NB; idx += 64) D[idx / NB][idx % NB] = G[(long)(k0 + idx / NB) * p + k0 + idx % NB];
+    __syncthreads();
+    Dinv[tid] = 1.0 / D[tid][tid];
+    __syncthreads();
+    const int r = k0 + NB + blockIdx.x * NB + tid;
+    if (r >= p) return;
+    double* mine = G + (long)r * p + k0;
+    double x[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) x[c] = mine[c];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        double v0 = x[c], v1 = 0.0;                    // two chains: the sums are short but dependent
+#pragma unroll
+        for (int u = 0; u + 1 < c; u += 2) { v0 -= x[u] * D[c][u]; v1 -= x[u + 1] * D[c][u + 1]; }
+        if (c & 1) v0 -= x[c - 1] * D[c][c - 1];
+        x[c] = (v0 + v1) * Dinv[c];
+    }
+#pragma unroll
+    for (int c = 0; c < NB; ++c) mine[c] = x[c];
+}
+
 // X_jj = L_jj^{-1} for every diagonal block j (one workgroup each); thread c solves L x = e_c.
 __global__ __launch_bounds__(64) void tri_inverse_diag_kernel(const double* __restrict__ G, double* __restrict__ X, int p) {
     __shared__ double D[NB][NB + 1], Y[NB][NB + 1];
@@ -596,6 +657,7 @@ hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int 
 hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* bad, hipStream_t s) {
     double* floor_v = tmp;                 // one double
     double* T = tmp + 8;                   // 64 x p
+    double* part = T + (size_t)NB * p;     // K slices of the products below: 16 x 64 x p
     hipError_t e;
     max_diag_kernel<<<1, 1024, 0, s>>>(G, p, floor_v);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -603,10 +665,12 @@ hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* ba
     // right-looking factorisation: panel, then trailing block  A22 -= L21 L21^T
     for (int k = 0; k < nblk; ++k) {
         const int k0 = k * NB, nb = std::min(NB, p - k0), rest = p - k0 - nb;
-        chol_diag_kernel<<<1, 256, 0, s>>>(G, p, k0, nb, floor_v, bad);
+        if (nb == NB) chol_diag64_kernel<<<1, 64, 0, s>>>(G, p, k0, floor_v, bad);
+        else chol_diag_kernel<<<1, 256, 0, s>>>(G, p, k0, nb, floor_v, bad);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (rest > 0) {
-            chol_solve_kernel<<<(rest + NB - 1) / NB, 256, 0, s>>>(G, p, k0, nb);
+            if (nb == NB) chol_solve64_kernel<<<(rest + NB - 1) / NB, 64, 0, s>>>(G, p, k0);
+            else chol_solve_kernel<<<(rest + NB - 1) / NB, 256, 0, s>>>(G, p, k0, nb);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             const double* L21 = G + (long)(k0 + nb) * p + k0;
             GemmF64 g{L21, p, 1, L21, 1, p, G + (long)(k0 + nb) * (p + 1), p, rest, rest, nb, -1.0, nullptr, 0, 1, nullptr, 0};
@@ -620,7 +684,7 @@ hipError_t launch_chol_inverse(double* G, double* X, double* tmp, int p, int* ba
     if ((e = hipGetLastError()) != hipSuccess) return e;
     for (int i = 1; i < nblk; ++i) {
         const int i0 = i * NB, nb = std::min(NB, p - i0);
-        GemmF64 t{G + (long)i0 * p, p, 1, X, p, 1, T, p, nb, i0, i0, 1.0, nullptr, 0, 0, nullptr, 0};
+        GemmF64 t{G + (long)i0 * p, p, 1, X, p, 1, T, p, nb, i0, i0, 1.0, nullptr, 0, 0, part, (size_t)16 * NB * p};
         if ((e = launch_gemm_f64(t, s)) != hipSuccess) return e;
         GemmF64 x{X + (long)i0 * (p + 1), p, 1, T, p, 1, X + (long)i0 * p, p, nb, i0, nb, -1.0, nullptr, 0, 0, nullptr, 0};
         if ((e = launch_gemm_f64(x, s)) != hipSuccess) return e;

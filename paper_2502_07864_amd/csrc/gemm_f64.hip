@@ -171,11 +171,11 @@ hipError_t run(const GemmF64& g, hipStream_t s) {
     const int tiles = tiles_m * tiles_n;
     const int nk = (g.K + BK - 1) / BK;
     // K slices: only when scratch is there, the tiles leave most of the 256 CUs idle and every slice
-    // still has at least 8 K steps
+    // still has at least 4 K steps
     int splits = 1;
-    if (g.partial && nk >= 32) {
+    if (g.partial && nk >= 8) {
         const size_t fit = g.partial_doubles / ((size_t)g.M * g.N);
-        const int most = (int)std::min<size_t>(std::min<size_t>(fit, 16), nk / 8);
+        const int most = (int)std::min<size_t>(std::min<size_t>(fit, 16), nk / 4);
         if (tiles <= 64) {
             splits = std::min(most, 256 / tiles);
         } else if (tiles < 1024) {
