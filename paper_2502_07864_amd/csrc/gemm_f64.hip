@@ -67,6 +67,8 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int li = lane & 15, kq = lane >> 4;
+    // a wavefront whose 64 x 64 part lies outside the matrix (edge tiles) stages data but multiplies nothing
+    const bool inside = m0 + wm < g.M && n0 + wn < g.N;
 
     f64x4 acc[4][4];
 #pragma unroll
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
         const double* a_s = As + buf * STAGE + wm + li;
         const double* b_s = Bs + buf * STAGE + wn + li;
 #pragma unroll
-        for (int ks = 0; ks < BK / 4; ++ks) {
+        for (int ks = 0; inside && ks < BK / 4; ++ks) {
             double a[4], b[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
