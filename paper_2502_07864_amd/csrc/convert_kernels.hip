@@ -436,17 +436,13 @@ __global__ __launch_bounds__(256) void chol_solve_kernel(double* G, int p, int k
 }
 
 // The same two steps for full 64 x 64 blocks with the rows held in registers (every loop unrolled, so all
-// register indices are static).  Factorisation: one wavefront, lane i owns row i; the pivot and the
-// column entries travel between lanes through scalar registers (v_readlane), so there is no LDS
-// traffic and no barrier in the 64 dependent steps.  Entries above the diagonal are scratch.
-__device__ __forceinline__ double lane_value(double v, int lane) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
-    return __hiloint2double(hi, lo);
-}
-
+// register indices are static).  Factorisation: one wavefront, lane i owns row i; per step every lane
+// publishes its entry of column j in LDS and reads the others back as broadcasts, so a step is one LDS
+// round trip and no barrier (a single wavefront's LDS accesses complete in order).  Entries above
+// the diagonal are scratch.
 __global__ __launch_bounds__(64) void chol_diag64_kernel(double* G, int p, int k0,
                                                          const double* __restrict__ floor_in, int* bad) {
+    __shared__ double col[NB];
     const int i = threadIdx.x;
     double* mine = G + (long)(k0 + i) * p + k0;
     double row[NB];
@@ -456,12 +452,17 @@ __global__ __launch_bounds__(64) void chol_diag64_kernel(double* G, int p, int k
     int nbad = 0;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        double d = lane_value(row[j], j);
+        col[i] = row[j];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        double d = col[j];
         if (!(d > floor_v)) { d = floor_v; ++nbad; }
         const double piv = sqrt(d), inv = 1.0 / piv;
         row[j] = i == j ? piv : row[j] * inv;
 #pragma unroll
-        for (int k = j + 1; k < NB; ++k) row[k] -= row[j] * lane_value(row[j], k);
+        for (int k = j + 1; k < NB; ++k) row[k] -= row[j] * (col[k] * inv);   // col[k] * inv: the bits lane k stores
+        __builtin_amdgcn_wave_barrier();
     }
 #pragma unroll
     for (int k = 0; k < NB; ++k) mine[k] = k <= i ? row[k] : 0.0;
