@@ -24,6 +24,9 @@ struct GemmF64 {
 };
 hipError_t launch_gemm_f64(const GemmF64& g, hipStream_t s);
 
+// Raise a kernel's dynamic-LDS limit; done once per (kernel, device), safe to call from several threads.
+hipError_t allow_dynamic_lds(const void* kernel, int bytes);
+
 // limits the host checks before launching
 constexpr int MOMENT_MAX_MG = 128;   // M*g of a FreqFold group
 constexpr int EIG_MAX_M = 2048;      // Jacobi: matrix order

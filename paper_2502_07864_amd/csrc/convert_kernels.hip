@@ -4,6 +4,9 @@
 // power iteration (App. D.2).  All fp64.
 #include "convert_internal.h"
 #include <algorithm>
+#include <mutex>
+#include <set>
+#include <utility>
 
 namespace mla {
 namespace conv {
@@ -145,7 +148,6 @@ struct JacobiLds {
     int pp[1024], qq[1024];
     double cc[1024], ss[1024];
     double red[16];
-    int flag;
 };
 
 __global__ __launch_bounds__(1024) void jacobi_kernel(double* A_all, double* evals_all, double* V_all, int* info,
@@ -574,6 +576,19 @@ inline int grid_for(long total) {
 
 }  // namespace
 
+hipError_t allow_dynamic_lds(const void* kernel, int bytes) {
+    static std::mutex lock;
+    static std::set<std::pair<const void*, int>> done;
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> hold(lock);
+    if (done.count({kernel, device})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.insert({kernel, device});
+    return e;
+}
+
 hipError_t launch_rope_moments(const double* K, double* sigma, int n, int g, int d, int M, hipStream_t s) {
     rope_moments_kernel<<<d / (2 * M), 256, 0, s>>>(K, sigma, n, g, d, M);
     return hipGetLastError();
@@ -643,13 +658,8 @@ hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int 
     const size_t mats = 2 * (size_t)m * m * sizeof(double);
     const int in_lds = head + mats <= 128 * 1024;
     const size_t bytes = head + (in_lds ? mats : 0);
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&jacobi_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    hipError_t e0 = allow_dynamic_lds(reinterpret_cast<const void*>(&jacobi_kernel), 128 * 1024);
+    if (e0 != hipSuccess) return e0;
     const int threads = m <= 64 ? 256 : 1024;
     jacobi_kernel<<<batch, threads, bytes, s>>>(A, evals, work, info, m, max_sweeps, in_lds);
     return hipGetLastError();

@@ -162,13 +162,8 @@ __global__ __launch_bounds__(256) void gemm_f64_reduce_kernel(GemmF64 g, int spl
 template <bool A_KC, bool B_KC>
 hipError_t run(const GemmF64& g, hipStream_t s) {
     constexpr size_t lds_bytes = 4 * STAGE * sizeof(double);
-    static bool configured = false;            // raising the dynamic-LDS limit once per process is enough
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f64_kernel<A_KC, B_KC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    hipError_t e0 = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_f64_kernel<A_KC, B_KC>), (int)lds_bytes);
+    if (e0 != hipSuccess) return e0;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int tiles = tiles_m * tiles_n;
     const int nk = (g.K + BK - 1) / BK;
