@@ -348,3 +348,44 @@ def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
     assert rel(got["W_UK"][i], alpha * E_rot[d:].T @ R[:(g - 1) * d]) < 1e-11
     assert rel(got["W_QR"][i], E_rot[:d]) < 1e-12
     assert rel(got["W_UV"][i], R[(g - 1) * d + i * d:(g - 1) * d + (i + 1) * d].T) == 0.0
+
+
+def test_whole_pipeline_on_the_gpu_conversion_append_decode(cv):
+    """Conversion, cache append (projection + RoPE + paged store) and absorbed decode all on the GPU,
+    token by token for three sequences of different lengths, against numpy conversion + numpy cache
+    rows + the decode oracle.  The attention output is independent of the signs of the bases."""
+    import torch
+    from paper_2502_07864_amd import mla
+    from test_convert_oracle_pins import mla_attention_through_the_decode_oracle, rope_hat, std_theta
+    g, h, d, D, n, r_kv, p, M = 4, 8, 16, 64, 400, 40, 56, 1
+    lens = [70, 33, 1]
+    B = len(lens)
+    X, W_K, W_V = synth.calibration(n, D, g, d, seed=21)
+    r = rng(47)
+    W_Q = r.standard_normal((h * d, D)) / np.sqrt(D)
+    ctx = [synth.calibration(L, D, g, d, seed=30 + b)[0] for b, L in enumerate(lens)]
+    theta = std_theta(d)
+    mj = (2 * g - 1) * d
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=4)), g, h, d, M, r_kv, iters=80)
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    # cache rows through mla_cache_append: W_DKVR = [W_DKV^T | W_KR^T]
+    W_DKVR = torch.cat([out["W_DKV"].T, out["W_KR"].T], dim=1).to(torch.float32).contiguous()
+    pages_per_seq = 2
+    pool = torch.full((B * pages_per_seq + 1, 64, r_kv + d), float("nan"), dtype=torch.float32, device="cuda")
+    table = torch.tensor([[5, 2], [1, 6], [4, 3]], dtype=torch.int32, device="cuda")
+    for t in range(max(lens)):
+        x_t = np.stack([ctx[b][t] if t < lens[b] else np.zeros(D) for b in range(B)])
+        pos = torch.tensor([t if t < lens[b] else -1 for b in range(B)], dtype=torch.int32, device="cuda")
+        mla.cache_append(f32(x_t), W_DKVR, pool, table, pos, r_kv)
+    # queries of the newest token of every sequence
+    q = np.stack([(W_Q @ ctx[b][-1]).reshape(h, d) for b in range(B)])
+    W_QR = host(out["W_QR"])
+    q_rope = np.stack([[rope_hat(W_QR[i] @ q[b, i], lens[b] - 1, d, theta) for i in range(h)] for b in range(B)])
+    q_abs = mla.absorb_q(f32(q), out["W_UK"].to(torch.float32).contiguous())
+    o_lat = mla.decode_paged(q_abs, f32(q_rope), pool, table, torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                             1.0 / np.sqrt(d), num_splits=2)
+    got = host(mla.out_proj(o_lat, out["W_UV"].to(torch.float32).contiguous())).astype(np.float64)
+    ref = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    for b in range(B):
+        want = mla_attention_through_the_decode_oracle(ref, ctx[b][-1], ctx[b], W_Q, h, d, lens[b] - 1, theta)
+        assert np.abs(got[b] - want).max() < 5e-5 * max(1.0, np.abs(want).max()), b
