@@ -389,3 +389,51 @@ def test_whole_pipeline_on_the_gpu_conversion_append_decode(cv):
     for b in range(B):
         want = mla_attention_through_the_decode_oracle(ref, ctx[b][-1], ctx[b], W_Q, h, d, lens[b] - 1, theta)
         assert np.abs(got[b] - want).max() < 5e-5 * max(1.0, np.abs(want).max()), b
+
+
+# ------------------------------------------------------------------ error reporting through info (forced from the host)
+
+def test_top_eig_reports_a_start_block_that_lacks_rank(cv):
+    """Two equal columns in the caller's start block: the Cholesky pivot of the second is clamped and
+    counted in info[0]; nothing hangs and nothing is NaN."""
+    m, r, p = 96, 8, 16
+    rs = rng(71)
+    B = rs.standard_normal((m, m))
+    S = B @ B.T / m
+    Q0 = synth.start_block(m, p, seed=9)
+    Q0[:, 5] = Q0[:, 4]
+    evals, R, info = cv.top_eig(dev(S), dev(Q0), r, 10)
+    assert host(info)[0] >= 1
+    assert np.isfinite(host(evals)).all() and np.isfinite(host(R)).all()
+
+
+def test_sym_eig_reports_a_sweep_limit_that_is_too_low(cv):
+    """One sweep does not diagonalise a random matrix: info = -1, the output is still an orthogonal matrix."""
+    for m in (24, 200):                                 # single-workgroup path and chip-wide path
+        A = rng(m).standard_normal((1, m, m))
+        A = A + A.transpose(0, 2, 1)
+        evals, U, info = cv.sym_eig(dev(A), max_sweeps=1)
+        assert host(info)[0] == -1
+        U = host(U)[0]
+        assert np.abs(U.T @ U - np.eye(m)).max() < 1e-12
+        evals_ok, _, info_ok = cv.sym_eig(dev(A), max_sweeps=40)
+        assert host(info_ok)[0] >= 2
+        assert np.abs(host(evals_ok)[0] - co.sym_eig_desc(A[0])[0]).max() < 1e-10 * np.linalg.norm(A[0])
+
+
+def test_convert_layer_with_the_widest_fold(cv):
+    """M g = 128, the limit of the per-group kernels (32 heads folded by 4)."""
+    g, h, d, D, n, M, r_kv, p = 32, 32, 16, 160, 300, 4, 96, 112
+    X, W_K, W_V = synth.calibration(n, D, g, d, seed=8)
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block((2 * g - 1) * d, p, seed=8)),
+                           g, h, d, M, r_kv, iters=60)
+    got = {k: host(v) for k, v in out.items()}
+    want = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    assert (got["info"][:-2] >= 1).all() and got["info"][-2] == 0 and got["info"][-1] >= 1
+    assert rel(got["evals_rope"], want["evals_rope"]) < 1e-10
+    assert abs(got["alpha"][0] - want["alpha"]) < 1e-11 * want["alpha"]
+    assert np.abs(got["evals_joint"][:r_kv] - want["evals_joint"][:r_kv]).max() < 1e-9 * want["evals_joint"][0]
+    for i in (0, 13, 31):
+        assert rel(got["W_UK"][i] @ got["W_DKV"], want["W_UK"][i] @ want["W_DKV"]) < 1e-6
+        assert rel(np.einsum("ab,ac->abc", got["W_QR"][i], got["W_KR"]),
+                   np.einsum("ab,ac->abc", want["W_QR"][i], want["W_KR"])) < 1e-7
