@@ -55,7 +55,7 @@ int mla_conv_rope_moments(const double* K, double* sigma,
  * Batched symmetric eigendecomposition (App. B: the columns of U are the eigenvectors
  * by descending eigenvalue; also the PCA of App. D.2).  Cyclic Jacobi rotations, one
  * workgroup per matrix up to m = 128; a larger matrix is spread over the chip, one launch per
- * rotation step, and the batch is then processed one matrix after the other.
+ * rotation step, the batch is then processed one matrix after the other, and at most 16 sweeps are run.
  *   A      [batch, m, m]  in: symmetric matrices; out: eigenvectors in the COLUMNS, column c
  *                         belonging to evals[c]
  *   evals  [batch, m]     eigenvalues, descending
@@ -110,6 +110,7 @@ int mla_conv_joint_moment(const double* K_nope, int ldk, const double* V, int ld
  *   R      [m, r]   Ritz vectors of the r largest, in columns
  *   info   [2] int  info[0]: 0, or the number of Cholesky pivots that had to be clamped (the block
  *                   lost rank); info[1]: sweeps of the final eigendecomposition, -1 if not converged
+ *                   (within 10 sweeps for p > 128)
  */
 size_t mla_conv_top_eig_workspace_bytes(int m, int p);
 /* One application of the moment matrix to a block, Y = S Q (the product each step of the

@@ -9,6 +9,10 @@ using namespace mla::conv;
 namespace {
 
 constexpr int JACOBI_MAX_SWEEPS = 60;
+// Rayleigh-Ritz matrix of the power iteration (chip-wide solver above order 128): 6-8 sweeps are what it
+// takes; the sweeps enqueued beyond convergence still cost their launches (2.5 us each, 1150 per sweep at
+// order 576), so the cap is kept close.  A matrix that needs more is reported through info (-1).
+constexpr int RITZ_MAX_SWEEPS = 10;
 
 inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 inline int st(hipError_t e) { return e == hipSuccess ? MLA_OK : MLA_ERR_HIP; }
@@ -89,7 +93,7 @@ int top_eig(const double* S, const double* Q0, double* evals, double* R, const T
     if (e != hipSuccess) return MLA_ERR_HIP;
     e = launch_symmetrise(w.T, p, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
-    e = launch_jacobi(w.T, evals, w.Z, info + 1, 1, p, JACOBI_MAX_SWEEPS, s);
+    e = launch_jacobi(w.T, evals, w.Z, info + 1, 1, p, p > 128 ? RITZ_MAX_SWEEPS : JACOBI_MAX_SWEEPS, s);
     if (e != hipSuccess) return MLA_ERR_HIP;
     return st(launch_gemm_f64(gemm_nn(w.Q, p, w.T, p, R, r, m, r, p, 1.0), s));
 }

@@ -646,7 +646,7 @@ static hipError_t launch_jacobi_wide(double* A, double* evals, double* V, void* 
 hipError_t launch_jacobi(double* A, double* evals, double* work, int* info, int batch, int m, int max_sweeps, hipStream_t s) {
     if (m > 128) {                                     // large matrices: the whole chip works on one at a time
         void* extra = work + (size_t)batch * m * m;
-        const int sweeps = std::min(max_sweeps, 16);
+        const int sweeps = std::min(max_sweeps, 16);   // every sweep enqueued costs its launches even after convergence
         for (int b = 0; b < batch; ++b) {
             hipError_t e = launch_jacobi_wide(A + (size_t)b * m * m, evals + (size_t)b * m, work + (size_t)b * m * m,
                                               extra, info + b, m, sweeps, s);
