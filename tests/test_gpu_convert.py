@@ -437,3 +437,18 @@ def test_convert_layer_with_the_widest_fold(cv):
         assert rel(got["W_UK"][i] @ got["W_DKV"], want["W_UK"][i] @ want["W_DKV"]) < 1e-6
         assert rel(np.einsum("ab,ac->abc", got["W_QR"][i], got["W_KR"]),
                    np.einsum("ab,ac->abc", want["W_QR"][i], want["W_KR"])) < 1e-7
+
+
+def test_folding_never_captures_less_than_separate_bases_on_the_gpu(cv):
+    """Proposition of App. C on the GPU's own moments and eigenvalues: the M leading eigenvalues of a folded
+    group's moment sum to at least the leading eigenvalues of its M pairs taken separately."""
+    g, d, n = 8, 32, 500
+    X, W_K, _ = synth.calibration(n, 96, g, d, seed=17)
+    K = cv.project(dev(X), dev(W_K))
+    w1 = host(cv.sym_eig(cv.rope_moments(K, g, d, 1))[0])
+    for M in (2, 4, 8):
+        wM = host(cv.sym_eig(cv.rope_moments(K, g, d, M))[0])
+        for G in range(d // (2 * M)):
+            assert wM[G, :M].sum() >= w1[G * M:(G + 1) * M, 0].sum() * (1 - 1e-12)
+        # folding moves energy between components, not in or out: the traces agree
+        assert abs(wM.sum() - w1.sum()) < 1e-10 * w1.sum()
