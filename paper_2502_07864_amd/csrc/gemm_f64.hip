@@ -2,8 +2,10 @@
 // (activations X W^T, second moments C^T C, block power iteration S Q, the low-rank
 // projections R^T W and W R of App. D.2).
 //
-// Workgroup tile 128 x 128, K step 16, four wavefronts in 2 x 2, each 64 x 64 =
-// 4 x 4 tiles of v_mfma_f64_16x16x4_f64.  Lane l of a wavefront supplies
+// Workgroup tile 128 x 128, K step 16, eight wavefronts in 4 x 2, each 32 x 64 =
+// 2 x 4 tiles of v_mfma_f64_16x16x4_f64 (64 accumulator registers), two workgroups per
+// CU = four wavefronts per SIMD: the matrix pipe of a SIMD always has a wavefront that
+// is not waiting at the barrier or for LDS.  Lane l of a wavefront supplies
 // A[l % 16][l / 16] and B[l / 16][l % 16] and receives D[4 r + l / 16][l % 16] in
 // element r of the result vector.  Both operands are staged k-major in LDS
 // ([k][m] and [k][n]) whichever way they lie in memory, so the inner loop is the
@@ -20,6 +22,8 @@ namespace {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int THREADS = 512;                  // eight wavefronts in 4 x 2, each 32 x 64 = 2 x 4 tiles
+constexpr int EPT = BM * BK / THREADS;        // elements of one operand tile per thread (4)
 constexpr int LD = 132;                       // row pitch of a staged k-row, in doubles: 264 dwords = 8 (mod 64), so
                                               // the 16 k-rows a wavefront writes at once fall on different banks
 constexpr int STAGE = BK * LD;                // one operand, one buffer
@@ -29,27 +33,27 @@ constexpr int STAGE = BK * LD;                // one operand, one buffer
 // otherwise s_mn == 1 and 128 lanes read consecutive elements of one k-row.
 template <bool K_CONTIG>
 __device__ __forceinline__ void fetch(const double* __restrict__ P, long s_mn, long s_k,
-                                      int mn0, int k0, int MN, int K, int tid, double (&r)[8]) {
+                                      int mn0, int k0, int MN, int K, int tid, double (&r)[EPT]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < EPT; ++i) {
         int mn, k;
-        if (K_CONTIG) { k = k0 + (tid & 15); mn = mn0 + (tid >> 4) + 16 * i; }
-        else          { mn = mn0 + (tid & 127); k = k0 + (tid >> 7) + 2 * i; }
+        if (K_CONTIG) { k = k0 + (tid & 15); mn = mn0 + (tid >> 4) + (THREADS / 16) * i; }
+        else          { mn = mn0 + (tid & 127); k = k0 + (tid >> 7) + (THREADS / 128) * i; }
         r[i] = (mn < MN && k < K) ? P[(long)mn * s_mn + (long)k * s_k] : 0.0;
     }
 }
 
 template <bool K_CONTIG>
-__device__ __forceinline__ void stage(double* S, int tid, const double (&r)[8]) {
+__device__ __forceinline__ void stage(double* S, int tid, const double (&r)[EPT]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        if (K_CONTIG) S[(tid & 15) * LD + (tid >> 4) + 16 * i] = r[i];
-        else          S[((tid >> 7) + 2 * i) * LD + (tid & 127)] = r[i];
+    for (int i = 0; i < EPT; ++i) {
+        if (K_CONTIG) S[(tid & 15) * LD + (tid >> 4) + (THREADS / 16) * i] = r[i];
+        else          S[((tid >> 7) + (THREADS / 128) * i) * LD + (tid & 127)] = r[i];
     }
 }
 
 template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n, int tiles, int splits, int kt_per) {
+__global__ __launch_bounds__(THREADS, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n, int tiles, int splits, int kt_per) {
     extern __shared__ double lds[];            // As[2][BK][LD], Bs[2][BK][LD]
     double* As = lds;
     double* Bs = lds + 2 * STAGE;
@@ -65,18 +69,18 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
     const int kt0 = z * kt_per, kt1 = min(nk_all, kt0 + kt_per);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 64;
     const int li = lane & 15, kq = lane >> 4;
     // a wavefront whose 64 x 64 part lies outside the matrix (edge tiles) stages data but multiplies nothing
     const bool inside = m0 + wm < g.M && n0 + wn < g.N;
 
-    f64x4 acc[4][4];
+    f64x4 acc[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-    double ra[8], rb[8];
+    double ra[EPT], rb[EPT];
     fetch<A_KC>(g.A, g.sAm, g.sAk, m0, kt0 * BK, g.M, g.K, tid, ra);
     fetch<B_KC>(g.B, g.sBn, g.sBk, n0, kt0 * BK, g.N, g.K, tid, rb);
     stage<A_KC>(As, tid, ra);
@@ -94,14 +98,14 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
         const double* b_s = Bs + buf * STAGE + wn + li;
 #pragma unroll
         for (int ks = 0; inside && ks < BK / 4; ++ks) {
-            double a[4], b[4];
+            double a[2], b[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                a[t] = a_s[(ks * 4 + kq) * LD + t * 16];
+                if (t < 2) a[t] = a_s[(ks * 4 + kq) * LD + t * 16];
                 b[t] = b_s[(ks * 4 + kq) * LD + t * 16];
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
     if (splits > 1) {                                    // raw slice product; the reduction kernel scales
         double* part = g.partial + (size_t)z * g.M * g.N;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f64_kernel(GemmF64 g, int tiles_n
     if (g.dev_mode == 1) scale *= *g.alpha_dev;
     else if (g.dev_mode == 2) scale /= *g.alpha_dev;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -187,7 +191,7 @@ hipError_t run(const GemmF64& g, hipStream_t s) {
     splits = (nk + kt_per - 1) / kt_per;                 // no empty slice
     const int total = tiles * splits;
     const int grid = ((total + 7) / 8) * 8;
-    gemm_f64_kernel<A_KC, B_KC><<<grid, 256, lds_bytes, s>>>(g, tiles_n, tiles, splits, kt_per);
+    gemm_f64_kernel<A_KC, B_KC><<<grid, THREADS, lds_bytes, s>>>(g, tiles_n, tiles, splits, kt_per);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     const long cells = (long)g.M * g.N;
