@@ -292,7 +292,7 @@ def test_gpu_converted_layer_decodes_like_the_oracles_converted_layer(cv, M):
 
 def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
     """One layer at the shape bench.py times (g = h = 32, d = 128, D = 4096, 4096 tokens, r_kv = 512,
-    block 576, 60 iterations).  The oracle's eigensolver would take minutes here, so the GPU result is
+    block 768, 20 iterations).  The oracle's eigensolver would take minutes here, so the GPU result is
     checked against what must hold at any size, with the moments recomputed in numpy:
     orthogonal bases that diagonalise the per-group moments, Eq. "rorope" on sampled scores,
     alpha, an orthonormal R_KV whose columns are eigenpairs of the numpy moment matrix to the
@@ -300,7 +300,7 @@ def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
     the App. D.2 products."""
     from test_convert_oracle_pins import rope_hat, std_theta
     g = h = 32
-    d, D, n, M, r_kv, p, iters = 128, 4096, 4096, 1, 512, 576, 60
+    d, D, n, M, r_kv, p, iters = 128, 4096, 4096, 1, 512, 768, 20
     mj = (2 * g - 1) * d
     X, W_K, W_V = synth.calibration(n, D, g, d, seed=0)
     out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=0)), g, h, d, M, r_kv, iters)
@@ -334,7 +334,7 @@ def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
     assert np.abs(R.T @ R - np.eye(r_kv)).max() < 1e-11
     assert (np.diff(lam) <= 0).all()
     resid = np.linalg.norm(S @ R - R * lam[:r_kv], axis=0).max() / lam[0]
-    assert resid < 1e-8, resid                       # (lambda_577 / lambda_512)^60 on this spectrum
+    assert resid < 1e-8, resid                       # what 20 iterations of a 768-wide block leave on this spectrum
     assert lam[:r_kv].sum() <= np.trace(S) * (1 + 1e-12)
     Qr, _ = np.linalg.qr(r.standard_normal((mj, 8)))
     assert (np.einsum("ij,ij->j", Qr, S @ Qr) <= lam[0] * (1 + 1e-9)).all()
