@@ -257,9 +257,9 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(double* A_all, double* eva
 }
 
 // ------------------------------------------------------------------ Jacobi eigensolver, one large matrix
-// The same rotations as above, spread over the chip: per step one launch rotates the rows (one
-// workgroup per index pair; it also derives the pair's angle and publishes it) and one launch
-// rotates the columns of A and V.  Launch order on the stream is the only synchronisation.  A sweep
+// The same rotations as above, spread over the chip, one launch per step (one workgroup per index
+// pair: pending column rotations of the previous step on its two rows, then its own angle and row
+// rotation).  Launch order on the stream is the only synchronisation.  A sweep
 // starts with a norm launch that raises `done` once the off-diagonal part is small; later launches
 // then return at once, so the host can enqueue the maximum number of sweeps without reading back.
 struct WideState { double tot; int done, sweeps; };
@@ -293,11 +293,38 @@ __global__ __launch_bounds__(1024) void jw_norm_kernel(const double* __restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void jw_rows_kernel(double* A, int m, int mp, int step, double* __restrict__ cs, const WideState* st) {
+// One step in one launch.  The workgroup of pair (p, q) first applies the column rotations of the
+// PREVIOUS step (all its pairs, angles in cs_prev) to its own two rows of A and V -- every row belongs to
+// exactly one pair of the current step, so every row gets them exactly once -- then derives its own angle,
+// publishes it in cs_next and rotates its two rows of A.  The column rotations of the last step before a
+// norm check are flushed by jw_cols_kernel.
+__global__ __launch_bounds__(256) void jw_step_kernel(double* A, double* V, int m, int mp, int step, int has_prev,
+                                                      const double* __restrict__ cs_prev, double* __restrict__ cs_next,
+                                                      const WideState* st) {
     if (st->done) return;
-    const int k = blockIdx.x;
+    const int k = blockIdx.x, half = mp / 2;
     int p, q;
     round_robin_pair(k, step, mp, p, q);
+    const int nrows = q < m ? 2 : 1;                   // a bye: only row p exists
+    if (has_prev) {
+        const int prev = (step + mp - 2) % (mp - 1);
+        for (int idx = threadIdx.x; idx < nrows * half; idx += 256) {
+            const int i = idx < half ? p : q, kk = idx < half ? idx : idx - half;
+            const double c = cs_prev[2 * kk], s = cs_prev[2 * kk + 1];
+            if (s != 0.0) {
+                int pp, qq;
+                round_robin_pair(kk, prev, mp, pp, qq);
+                const long ip = (long)i * m + pp, iq = (long)i * m + qq;
+                const double ap = A[ip], aq = A[iq];
+                A[ip] = i == qq ? 0.0 : c * ap - s * aq;        // the annihilated pair gets exact zeros
+                A[iq] = i == pp ? 0.0 : s * ap + c * aq;
+                const double vp = V[ip], vq = V[iq];
+                V[ip] = c * vp - s * vq;
+                V[iq] = s * vp + c * vq;
+            }
+        }
+        __syncthreads();
+    }
     double c = 1.0, s = 0.0;
     if (q < m) {
         const double apq = A[(long)p * m + q], app = A[(long)p * m + p], aqq = A[(long)q * m + q];
@@ -309,7 +336,7 @@ __global__ __launch_bounds__(256) void jw_rows_kernel(double* A, int m, int mp, 
         }
     }
     __syncthreads();                                   // every thread holds the angle before a row changes
-    if (threadIdx.x == 0) { cs[2 * k] = c; cs[2 * k + 1] = s; }
+    if (threadIdx.x == 0) { cs_next[2 * k] = c; cs_next[2 * k + 1] = s; }
     if (s == 0.0) return;
     for (int j = threadIdx.x; j < m; j += 256) {
         const long ip = (long)p * m + j, iq = (long)q * m + j;
@@ -616,12 +643,12 @@ hipError_t launch_balance(const double* K, int ldk, const double* V, int ldv, co
 }
 
 // scratch behind the batch of V matrices: angles, ranks, state of the wide solver
-constexpr size_t JACOBI_EXTRA_BYTES = 2 * 1024 * sizeof(double) + EIG_MAX_M * sizeof(int) + 256;
+constexpr size_t JACOBI_EXTRA_BYTES = 2 * (2 * 1024 * sizeof(double)) + EIG_MAX_M * sizeof(int) + 256;
 size_t jacobi_work_bytes(int batch, int m) { return (size_t)batch * m * m * sizeof(double) + JACOBI_EXTRA_BYTES; }
 
 static hipError_t launch_jacobi_wide(double* A, double* evals, double* V, void* extra, int* info, int m, int max_sweeps, hipStream_t s) {
-    double* cs = static_cast<double*>(extra);
-    int* rank = reinterpret_cast<int*>(cs + 2 * 1024);
+    double* cs[2] = {static_cast<double*>(extra), static_cast<double*>(extra) + 2 * 1024};   // angles of step parity
+    int* rank = reinterpret_cast<int*>(cs[1] + 2 * 1024);
     WideState* st = reinterpret_cast<WideState*>(rank + EIG_MAX_M);
     const int mp = m + (m & 1), half = mp / 2;
     hipError_t e;
@@ -632,10 +659,10 @@ static hipError_t launch_jacobi_wide(double* A, double* evals, double* V, void* 
         jw_norm_kernel<<<1, 1024, 0, s>>>(A, m, sweep, st);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (sweep == max_sweeps) break;
-        for (int step = 0; step < mp - 1; ++step) {
-            jw_rows_kernel<<<half, 256, 0, s>>>(A, m, mp, step, cs, st);
-            jw_cols_kernel<<<col_grid, 256, 0, s>>>(A, V, m, mp, step, cs, st);
-        }
+        for (int step = 0; step < mp - 1; ++step)
+            jw_step_kernel<<<half, 256, 0, s>>>(A, V, m, mp, step, step > 0, cs[(step + 1) & 1], cs[step & 1], st);
+        // the column rotations of the sweep's last step, before the norm is taken
+        jw_cols_kernel<<<col_grid, 256, 0, s>>>(A, V, m, mp, mp - 2, cs[(mp - 2) & 1], st);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     jw_rank_kernel<<<1, 1024, 0, s>>>(A, m, evals, rank, st, info);
