@@ -81,6 +81,9 @@ def parse():
     ap.add_argument("--convert-block", type=int, default=768,
                     help="block width p of the power iteration (>= r_kv = 512; 768 with 20 iterations reaches a smaller "
                          "residual than 576 with 60 in 70 %% of the time on the synthetic spectrum)")
+    ap.add_argument("--convert-products-only", action="store_true",
+                    help="with --convert: only the two large fp64 products of the layer shape (moment C^T C and S Q), "
+                         "a few launches each, for counter passes of the profiler")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16, help="sequences in the CPU-oracle sample")
     ap.add_argument("--calib-copy", action="store_true",
@@ -446,6 +449,31 @@ def convert_main(args):
     d, D, n, r_kv, p = 128, 4096, 4096, 512, args.convert_block
     M, iters = args.freqfold, args.convert_iters
     mj = (2 * g - 1) * d
+    if args.convert_products_only:
+        gen = torch.Generator(device="cuda:0").manual_seed(0)
+        C = torch.randn((n, mj), dtype=torch.float64, device="cuda:0", generator=gen)
+        one = torch.ones(1, dtype=torch.float64, device="cuda:0")
+        Q = torch.randn((mj, p), dtype=torch.float64, device="cuda:0", generator=gen)
+        aws = torch.empty(cv.apply_workspace_bytes(mj, p), dtype=torch.uint8, device="cuda:0")
+        times = {}
+        for name, call in (("moment", lambda: cv.joint_moment(C[:, :mj - g * d].contiguous(), C[:, mj - g * d:].contiguous(), one)),
+                           ("S_Q", None)):
+            if name == "moment":
+                S, _ = call()
+                call = None
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                if name == "moment":
+                    cv.joint_moment(C[:, :mj - g * d].contiguous(), C[:, mj - g * d:].contiguous(), one)
+                else:
+                    cv.apply(S, Q, workspace=aws)
+            e1.record()
+            torch.cuda.synchronize()
+            times[name] = e0.elapsed_time(e1) / 3
+        print(json.dumps({"products_ms": times, "moment_TFLOPs": 2.0 * mj * mj * n / times["moment"] / 1e9,
+                          "S_Q_TFLOPs": 2.0 * mj * mj * p / times["S_Q"] / 1e9}))
+        return
     X, W_K, W_V = synth.calibration(n, D, g, d, seed=0)
     Q0 = synth.start_block(mj, p, seed=0)
     dev = lambda a: torch.from_numpy(a).to("cuda:0")
