@@ -452,3 +452,25 @@ def test_folding_never_captures_less_than_separate_bases_on_the_gpu(cv):
             assert wM[G, :M].sum() >= w1[G * M:(G + 1) * M, 0].sum() * (1 - 1e-12)
         # folding moves energy between components, not in or out: the traces agree
         assert abs(wM.sum() - w1.sum()) < 1e-10 * w1.sum()
+
+
+def test_matrix_product_random_shapes(cv):
+    """Ragged sizes through the three transpose cases the chain uses (X W^T, C^T C, S Q with and without K
+    slices): primes, single rows and columns, sizes straddling the 128 x 128 x 16 tile."""
+    import torch
+    r = rng(2024)
+    for case in range(12):
+        n, D, m = (int(v) for v in r.choice([1, 2, 3, 15, 16, 17, 31, 127, 128, 129, 257, 400], size=3))
+        X, W = r.standard_normal((n, D)), r.standard_normal((m, D))
+        assert rel(host(cv.project(dev(X), dev(W))), X @ W.T) < 1e-12, (case, n, D, m)
+        a, b = max(1, m // 2), m - m // 2 if m > 1 else 1
+        Kn, V = r.standard_normal((n, a)), r.standard_normal((n, b))
+        S, _ = cv.joint_moment(dev(Kn), dev(V), dev(np.array([1.0])))
+        C = np.concatenate([Kn, V], axis=1)
+        assert rel(host(S), C.T @ C / n) < 1e-12, (case, n, a, b)
+        mm, p = D, max(1, m // 3)
+        A = r.standard_normal((mm, mm))
+        Q = r.standard_normal((mm, p))
+        ws = torch.empty(max(256, cv.apply_workspace_bytes(mm, p)), dtype=torch.uint8, device="cuda")
+        assert rel(host(cv.apply(dev(A), dev(Q))), A @ Q) < 1e-12, (case, mm, p)
+        assert rel(host(cv.apply(dev(A), dev(Q), workspace=ws)), A @ Q) < 1e-12, (case, mm, p)
