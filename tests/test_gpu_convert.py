@@ -474,3 +474,29 @@ def test_matrix_product_random_shapes(cv):
         ws = torch.empty(max(256, cv.apply_workspace_bytes(mm, p)), dtype=torch.uint8, device="cuda")
         assert rel(host(cv.apply(dev(A), dev(Q))), A @ Q) < 1e-12, (case, mm, p)
         assert rel(host(cv.apply(dev(A), dev(Q), workspace=ws)), A @ Q) < 1e-12, (case, mm, p)
+
+
+def test_largest_orders_the_solvers_take(cv):
+    """Order 2048 for the eigensolver (its limit) and block width 1024 for the power iteration (its limit)."""
+    m = 2048
+    r = rng(77)
+    B = r.standard_normal((m, 300))
+    A = (B @ B.T / 300 + np.diag(np.linspace(0.0, 2.0, m)))[None]
+    evals, U, info = cv.sym_eig(dev(A), max_sweeps=16)
+    evals, U = host(evals)[0], host(U)[0]
+    assert host(info)[0] >= 1
+    w_ref = np.linalg.eigvalsh(A[0])[::-1]
+    assert np.abs(evals - w_ref).max() < 1e-10 * w_ref[0]
+    assert np.abs(U.T @ U - np.eye(m)).max() < 1e-11
+    assert np.abs(A[0] @ U - U * evals).max() < 1e-10 * w_ref[0]
+    m2, r2, p2 = 1300, 600, 1024
+    Qo, _ = np.linalg.qr(r.standard_normal((m2, m2)))
+    lam = (1.0 + np.arange(m2)) ** -1.2
+    S = (Qo * lam) @ Qo.T
+    S = 0.5 * (S + S.T)
+    ev2, R, info2 = cv.top_eig(dev(S), dev(synth.start_block(m2, p2, seed=12)), r2, 40)
+    ev2, R = host(ev2), host(R)
+    assert host(info2)[0] == 0 and host(info2)[1] >= 1
+    assert np.abs(ev2[:r2] - lam[:r2]).max() < 1e-10
+    assert np.abs(R.T @ R - np.eye(r2)).max() < 1e-11
+    assert np.abs(S @ R - R * ev2[:r2]).max() < 1e-9
