@@ -16,7 +16,7 @@ Steps
                                         vectors of a FreqFold group
   rope_moments          App. B          sigma_x + sigma_y per group
   rorope_basis          App. B          U = eigenvectors, eigenvalues descending
-  placement_columns     Sec. 4.2        where component r of a group is stored (first head first)
+  placement_columns     Sec. 4.2        where component r of a group is stored (RoPE key first)
   rotate_rows           Sec. 4.2        W^K and (W^UK)^T rotated by the same U
   kv_balance            Sec. 4.3        alpha
   joint_moment          App. D.2        second-moment matrix of [k_NoPE / alpha ; v]
@@ -33,9 +33,16 @@ Readings taken where the paper leaves a choice (each listed in the design notes)
     g x g matrix must act on the real and on the imaginary vector alike.  Here U of
     a group is (M g) x (M g) and acts identically on the real vector and on the
     imaginary vector of the group (the only reading under which Eq. "rorope" holds).
-  * Component r of a group (eigenvalues descending) is stored in head r // M, pair
-    slot r % M of the group, so that the first head receives the M leading
-    components of every group and the converted model can apply ordinary RoPE to it.
+  * Where the components go.  Of every group the `keep` leading components (eigenvalues
+    descending, 1 <= keep <= M) stay under RoPE; they form the RoPE key, a head of
+    d_rope = 2 * keep * (d / 2M) dimensions in which component r of group G is pair
+    G * keep + r.  With keep = M that is a whole head of d dimensions in which every
+    component sits on one of its group's own M pairs, so ordinary RoPE of width d applies
+    (exactly for M = 1, up to FreqFold's approximation otherwise).  With keep = 1 the
+    RoPE key has one pair per group and ordinary RoPE of width d / M applies: its pair G
+    turns with theta_{G M}, the first frequency of the group (the "effective frequency"
+    of App. C's example).  All other components lose RoPE and form the NoPE key, component
+    r >= keep of group G at NoPE pair (r - keep) * (d / 2M) + G.
   * Eigenvectors are unique up to sign (and up to a rotation inside a repeated
     eigenvalue): callers compare what is unique (eigenvalues, projectors,
     products that do not depend on the sign).
@@ -114,24 +121,35 @@ def rorope_basis(sigma: np.ndarray):
 # Sec. 4.2: rotation of W^K and W^UK
 # --------------------------------------------------------------------------
 
-def placement_columns(g: int, d: int, M: int):
-    """Where component r of group G goes: head r // M, pair G*M + r % M."""
+def rope_width(d: int, M: int, keep=None) -> int:
+    """d_rope: dimensions of the RoPE key when `keep` components per group stay under RoPE."""
+    keep = M if keep is None else keep
+    assert 1 <= keep <= M
+    return 2 * keep * (d // (2 * M))
+
+
+def placement_columns(g: int, d: int, M: int, keep=None):
+    """Rows of the rotated key: the RoPE key first (d_rope rows), then the NoPE key.
+    Component r of group G: r < keep -> RoPE pair G*keep + r; else NoPE pair
+    (r - keep) * n_groups + G, i.e. row d_rope + 2 * that (real), + 1 (imaginary)."""
+    keep = M if keep is None else keep
     n_groups = d // (2 * M)
+    d_rope = rope_width(d, M, keep)
     out_x = np.empty((n_groups, M * g), dtype=np.int64)
     for G in range(n_groups):
         for r in range(M * g):
-            out_x[G, r] = (r // M) * d + 2 * (G * M + r % M)
+            out_x[G, r] = 2 * (G * keep + r) if r < keep else d_rope + 2 * ((r - keep) * n_groups + G)
     return out_x, out_x + 1
 
 
-def rotate_rows(W: np.ndarray, U: np.ndarray, g: int, d: int, M: int = 1) -> np.ndarray:
+def rotate_rows(W: np.ndarray, U: np.ndarray, g: int, d: int, M: int = 1, keep=None) -> np.ndarray:
     """Rows of W ([g*d, anything]) are indexed like the merged key.  The real vector
     and the imaginary vector of every group are replaced by U_G^T times themselves
-    (k' = U^T k) and stored at the placement columns.  W^K is rotated as it stands;
+    (k' = U^T k) and stored at the placement rows.  W^K is rotated as it stands;
     W^UK_i is rotated through its transpose (rows = merged key dimensions)."""
     W = np.asarray(W, dtype=np.float64)
     col_x, col_y = group_columns(g, d, M)
-    out_x, out_y = placement_columns(g, d, M)
+    out_x, out_y = placement_columns(g, d, M, keep)
     out = np.empty_like(W)
     for G in range(col_x.shape[0]):
         out[out_x[G]] = U[G].T @ W[col_x[G]]
@@ -184,27 +202,29 @@ def low_rank_projections(W_DK_nope, W_DV, W_UK_nope, W_UV, alpha: float, R_KV: n
 # the chain
 # --------------------------------------------------------------------------
 
-def convert_layer(X, W_K, W_V, g: int, h: int, d: int, M: int, r_kv: int):
+def convert_layer(X, W_K, W_V, g: int, h: int, d: int, M: int, r_kv: int, keep=None):
     """GQA layer (W_K, W_V: [g*d, D]) -> MLA layer, calibrated on the rows of X [n, D].
+    keep (default M): components per FreqFold group that stay under RoPE; d_rope = keep * d / M.
 
     Returns a dict:
-      W_KR   [d, D]        key projection of the head that keeps RoPE (k_rope = RoPE(W_KR x))
-      W_QR   [h, d, d]     q_rope_i = RoPE(W_QR[i] q_i)          (= (W^UK_RoPE,i)^T)
+      W_KR   [d_rope, D]   key projection of the RoPE key (k_rope = RoPE(W_KR x), RoPE of width d_rope)
+      W_QR   [h, d_rope, d]  q_rope_i = RoPE(W_QR[i] q_i)        (= (W^UK_RoPE,i)^T)
       W_DKV  [r_kv, D]     c_kv = W_DKV x
       W_UK   [h, d, r_kv]  q_abs_i = W_UK[i]^T q_i               (scores against c_kv)
       W_UV   [h, r_kv, d]  o_i = W_UV[i]^T-free form: o_i = o_lat_i @ W_UV[i]
-      alpha, evals_rope [groups, M*g], evals_joint [(2g-1)d], U [groups, Mg, Mg], R_KV."""
+      alpha, evals_rope [groups, M*g], evals_joint [2gd - d_rope], U [groups, Mg, Mg], R_KV."""
     X = np.asarray(X, dtype=np.float64)
     W_K = np.asarray(W_K, dtype=np.float64)
     W_V = np.asarray(W_V, dtype=np.float64)
     W_UK, W_UV = merged_projections(g, h, d)                       # Sec. 4.1
     K = X @ W_K.T                                                  # key activations before RoPE
     evals_rope, U = rorope_basis(rope_moments(K, g, d, M))         # App. B (+ App. C grouping)
-    W_K_rot = rotate_rows(W_K, U, g, d, M)                         # Sec. 4.2
-    W_UK_rot = np.stack([rotate_rows(W_UK[i].T, U, g, d, M).T for i in range(h)])
-    W_KR, W_DK_nope = W_K_rot[:d], W_K_rot[d:]                     # first head keeps RoPE
-    W_QR = np.stack([W_UK_rot[i][:, :d].T for i in range(h)])
-    W_UK_nope = W_UK_rot[:, :, d:]
+    d_rope = rope_width(d, M, keep)
+    W_K_rot = rotate_rows(W_K, U, g, d, M, keep)                   # Sec. 4.2
+    W_UK_rot = np.stack([rotate_rows(W_UK[i].T, U, g, d, M, keep).T for i in range(h)])
+    W_KR, W_DK_nope = W_K_rot[:d_rope], W_K_rot[d_rope:]           # the RoPE key, the NoPE key
+    W_QR = np.stack([W_UK_rot[i][:, :d_rope].T for i in range(h)])
+    W_UK_nope = W_UK_rot[:, :, d_rope:]
     K_nope, V = X @ W_DK_nope.T, X @ W_V.T
     alpha = kv_balance(K_nope, V)                                  # Sec. 4.3
     evals_joint, R_KV = joint_basis(joint_moment(K_nope, V, alpha), r_kv)   # App. D.2

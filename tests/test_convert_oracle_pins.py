@@ -43,6 +43,23 @@ def std_theta(d, base=10000.0):
     return np.array([base ** (-2.0 * l / d) for l in range(d // 2)])
 
 
+def rope_by_component(v, pos, g, d, M, keep, theta_of):
+    """RoPE on a ROTATED merged vector, component by component: the pair stored for component r of
+    group G turns by pos * theta_of(G, r); theta_of returning None leaves the pair alone (NoPE)."""
+    out_x, out_y = co.placement_columns(g, d, M, keep)
+    out = np.array(v, dtype=np.float64)
+    for G in range(out_x.shape[0]):
+        for r in range(M * g):
+            th = theta_of(G, r)
+            if th is None:
+                continue
+            a = pos * th
+            x, y = v[out_x[G, r]], v[out_y[G, r]]
+            out[out_x[G, r]] = x * math.cos(a) - y * math.sin(a)
+            out[out_y[G, r]] = x * math.sin(a) + y * math.cos(a)
+    return out
+
+
 # ------------------------------------------------------------- App. C index example
 
 def test_group_columns_are_the_index_sets_of_the_worked_example():
@@ -65,6 +82,13 @@ def test_group_and_placement_columns_are_permutations_with_head_major_segments()
     for g, d, M in [(2, 8, 1), (2, 8, 2), (4, 16, 4), (3, 12, 3), (8, 64, 2)]:
         col_x, col_y = co.group_columns(g, d, M)
         out_x, out_y = co.placement_columns(g, d, M)
+        for keep in range(1, M + 1):       # any number of kept components: a permutation, RoPE key first
+            kx, ky = co.placement_columns(g, d, M, keep)
+            assert sorted(np.concatenate([kx.ravel(), ky.ravel()]).tolist()) == list(range(g * d))
+            d_rope = co.rope_width(d, M, keep)
+            assert d_rope == keep * d // M
+            assert (kx[:, :keep] < d_rope).all() and (kx[:, keep:] >= d_rope).all()
+            assert (kx[:, :keep] // 2 == np.arange(d // (2 * M))[:, None] * keep + np.arange(keep)[None, :]).all()
         for a, b in [(col_x, col_y), (out_x, out_y)]:
             assert sorted(np.concatenate([a.ravel(), b.ravel()]).tolist()) == list(range(g * d))
             assert (a % 2 == 0).all() and (b == a + 1).all()
@@ -107,19 +131,22 @@ def test_rope_inner_product_is_invariant_under_one_rotation_per_pair(g, d):
 def test_folded_groups_are_invariant_when_their_pairs_share_one_frequency(M):
     """App. C: FreqFold treats the M pairs of a group as one frequency.  With a RoPE whose
     frequency IS constant inside each group the rotation by any (M g) x (M g) orthogonal
-    matrix is exact; with the ordinary frequencies it is not."""
+    matrix is exact when every component keeps that frequency; giving the components the M
+    different frequencies of their group's pairs instead is not."""
     g, d = 3, 8
     r = rng(11 + M)
-    theta_folded = np.repeat(std_theta(d)[::M], M)
+    theta = std_theta(d)
+    theta_folded = np.repeat(theta[::M], M)
     q_hat, k = r.standard_normal(g * d), r.standard_normal(g * d)
     U = np.stack([random_orthogonal(r, M * g) for _ in range(d // (2 * M))])
     q2 = co.rotate_rows(q_hat[:, None], U, g, d, M)[:, 0]
     k2 = co.rotate_rows(k[:, None], U, g, d, M)[:, 0]
     want = rope_hat(q_hat, 31, d, theta_folded) @ rope_hat(k, 6, d, theta_folded)
-    got = rope_hat(q2, 31, d, theta_folded) @ rope_hat(k2, 6, d, theta_folded)
+    folded = lambda G, rr: theta[G * M]
+    got = rope_by_component(q2, 31, g, d, M, M, folded) @ rope_by_component(k2, 6, g, d, M, M, folded)
     assert abs(got - want) < 1e-11 * (1 + abs(want))
-    theta = std_theta(d)
-    assert abs(rope_hat(q2, 31, d, theta) @ rope_hat(k2, 6, d, theta)
+    own = lambda G, rr: theta[G * M + rr % M]
+    assert abs(rope_by_component(q2, 31, g, d, M, M, own) @ rope_by_component(k2, 6, g, d, M, M, own)
                - rope_hat(q_hat, 31, d, theta) @ rope_hat(k, 6, d, theta)) > 1e-4
 
 
@@ -167,28 +194,29 @@ def test_two_by_two_closed_form():
     assert abs(abs(U[:, 0] @ np.array([math.cos(ang), math.sin(ang)])) - 1) < 1e-14
 
 
-@pytest.mark.parametrize("M", [1, 2])
-def test_rotated_key_projection_puts_the_eigenvalues_on_the_placement_slots(M):
-    """After rotating W^K with the basis of its own activations, the energy
-    (real^2 + imaginary^2, averaged over the tokens) of head a, pair G*M+p is
-    eigenvalue a*M+p of group G, and different slots of a group are uncorrelated."""
+@pytest.mark.parametrize("M,keep", [(1, 1), (2, 2), (2, 1), (4, 1), (4, 3)])
+def test_rotated_key_projection_puts_the_eigenvalues_on_the_placement_slots(M, keep):
+    """After rotating W^K with the basis of its own activations, the energy (real^2 + imaginary^2,
+    averaged over the tokens) of the pair that stores component r of group G is eigenvalue r of
+    group G, and different components of a group are uncorrelated.  The RoPE key (the `keep`
+    leading components of every group) therefore holds the largest eigenvalues."""
     g, d, D, n = 4, 8, 10, 64
     r = rng(17)
     X, W_K = r.standard_normal((n, D)), r.standard_normal((g * d, D))
     w, U = co.rorope_basis(co.rope_moments(X @ W_K.T, g, d, M))
-    K2 = X @ co.rotate_rows(W_K, U, g, d, M).T
+    K2 = X @ co.rotate_rows(W_K, U, g, d, M, keep).T
+    out_x, out_y = co.placement_columns(g, d, M, keep)
     for G in range(d // (2 * M)):
-        for a in range(g):
-            for p in range(M):
-                c0 = a * d + 2 * (G * M + p)
-                e = (K2[:, c0] ** 2 + K2[:, c0 + 1] ** 2).mean()
-                assert abs(e - w[G, a * M + p]) < 1e-11
-        c0, c1 = 2 * (G * M), 1 * d + 2 * (G * M)
-        cross = (K2[:, c0] * K2[:, c1] + K2[:, c0 + 1] * K2[:, c1 + 1]).mean()
+        for c in range(M * g):
+            e = (K2[:, out_x[G, c]] ** 2 + K2[:, out_y[G, c]] ** 2).mean()
+            assert abs(e - w[G, c]) < 1e-11
+        cross = (K2[:, out_x[G, 0]] * K2[:, out_x[G, 1]] + K2[:, out_y[G, 0]] * K2[:, out_y[G, 1]]).mean()
         assert abs(cross) < 1e-11
-    # the first head holds at least as much energy as any head had before (M = 1: the most possible)
-    K = X @ W_K.T
-    assert (K2[:, :d] ** 2).sum() >= max((K[:, j * d:(j + 1) * d] ** 2).sum() for j in range(g))
+    d_rope = co.rope_width(d, M, keep)
+    assert abs((K2[:, :d_rope] ** 2).sum() / n - w[:, :keep].sum()) < 1e-10
+    if keep == M:      # a whole head: at least as much energy as any head had before
+        K = X @ W_K.T
+        assert (K2[:, :d] ** 2).sum() >= max((K[:, j * d:(j + 1) * d] ** 2).sum() for j in range(g))
 
 
 def test_folding_captures_at_least_the_separate_leading_eigenvalues():
@@ -274,12 +302,15 @@ def gqa_attention(x_new, X_ctx, W_Q, W_K, W_V, g, h, d, pos_new, theta):
 
 
 def mla_attention_through_the_decode_oracle(cv, x_new, X_ctx, W_Q, h, d, pos_new, theta):
-    """Feed the converted tensors to the absorbed-decode oracle in the layout the decode path consumes."""
+    """Feed the converted tensors to the absorbed-decode oracle in the layout the decode path consumes.
+    theta: the frequencies of the RoPE key, one per pair of its d_rope dimensions."""
     L = len(X_ctx)
     q = (W_Q @ x_new).reshape(h, d)
+    d_r = cv["W_KR"].shape[0]
+    assert len(theta) == d_r // 2
     c_kv = X_ctx @ cv["W_DKV"].T
-    k_rope = np.stack([rope_hat(cv["W_KR"] @ X_ctx[t], t, d, theta) for t in range(L)])
-    q_rope = np.stack([rope_hat(cv["W_QR"][i] @ q[i], pos_new, d, theta) for i in range(h)])
+    k_rope = np.stack([rope_hat(cv["W_KR"] @ X_ctx[t], t, d_r, theta) for t in range(L)])
+    q_rope = np.stack([rope_hat(cv["W_QR"][i] @ q[i], pos_new, d_r, theta) for i in range(h)])
     pool, table, lens = dense_cache([c_kv], [k_rope], page_size=4, seed=1)
     q_abs = oracle.absorb_q(q[None], cv["W_UK"])
     o_lat, _ = oracle.decode_absorbed(q_abs, q_rope[None], pool, None, table, lens, 1.0 / math.sqrt(d))
@@ -295,11 +326,13 @@ def test_conversion_is_exact_at_full_rank_when_rope_is_the_identity():
     X = r.standard_normal((n, D))
     W_Q, W_K, W_V = (r.standard_normal((m, D)) / math.sqrt(D) for m in (h * d, g * d, g * d))
     theta = np.zeros(d // 2)
-    for M in (1, 2):
-        cv = co.convert_layer(X, W_K, W_V, g, h, d, M, (2 * g - 1) * d)
+    for M, keep in ((1, 1), (2, 2), (2, 1), (4, 1), (4, 2)):
+        d_r = co.rope_width(d, M, keep)
+        cv = co.convert_layer(X, W_K, W_V, g, h, d, M, 2 * g * d - d_r, keep)
+        assert cv["W_KR"].shape == (d_r, D) and cv["W_QR"].shape == (h, d_r, d)
         X_ctx = r.standard_normal((L, D))
         want = gqa_attention(X_ctx[-1], X_ctx, W_Q, W_K, W_V, g, h, d, L - 1, theta)
-        got = mla_attention_through_the_decode_oracle(cv, X_ctx[-1], X_ctx, W_Q, h, d, L - 1, theta)
+        got = mla_attention_through_the_decode_oracle(cv, X_ctx[-1], X_ctx, W_Q, h, d, L - 1, theta[:d_r // 2])
         assert np.abs(got - want).max() < 2e-6        # the oracle's pool stores float32
 
 
@@ -327,6 +360,46 @@ def test_rope_head_alone_is_exact_when_keys_are_rank_one_across_heads():
         got = rope_hat(W_QR_i @ q_i, t, d, theta) @ rope_hat(W_K_rot[:d] @ x_k, j, d, theta)
         grp = i // (h // g)
         want = rope_hat(q_i, t, d, theta) @ rope_hat(W_K[grp * d:(grp + 1) * d] @ x_k, j, d, theta)
+        assert abs(got - want) < 1e-11 * (1 + abs(want))
+
+
+@pytest.mark.parametrize("M", [2, 4])
+def test_one_pair_per_group_is_exact_for_rank_one_groups_under_folded_frequencies(M):
+    """keep = 1: the RoPE key has one pair per FreqFold group and takes ordinary RoPE of width d / M,
+    whose pair G turns with theta_{G M}.  If the original layer's RoPE has that frequency on all M pairs
+    of group G (FreqFold's premise) and the group's keys are rank one (all its M g real coordinates
+    multiples of one row, likewise the imaginary ones), every other component vanishes and the RoPE-key
+    score equals the score of the query's own group in the original layer -- at real positions."""
+    g, h, d, D, n = 3, 6, 8, 10, 32
+    n_groups = d // (2 * M)
+    r = rng(53 + M)
+    col_x, col_y = co.group_columns(g, d, M)
+    W_K = np.zeros((g * d, D))
+    for G in range(n_groups):
+        a_row, b_row = r.standard_normal(D), r.standard_normal(D)
+        s = r.uniform(0.5, 2.0, M * g) * r.choice([-1.0, 1.0], M * g)
+        W_K[col_x[G]] = s[:, None] * a_row
+        W_K[col_y[G]] = s[:, None] * b_row
+    X = r.standard_normal((n, D))
+    w, U = co.rorope_basis(co.rope_moments(X @ W_K.T, g, d, M))
+    assert (w[:, 1:] < 1e-12 * w[:, :1]).all()
+    d_r = co.rope_width(d, M, 1)
+    assert d_r == d // M
+    W_K_rot = co.rotate_rows(W_K, U, g, d, M, 1)
+    assert np.abs(X @ W_K_rot[d_r:].T).max() < 1e-12          # the NoPE key is empty
+    W_UK, _ = co.merged_projections(g, h, d)
+    theta = std_theta(d)
+    theta_folded = np.repeat(theta[::M], M)                   # the original layer under FreqFold's premise
+    theta_key = std_theta(d_r)                                # ordinary RoPE of the narrower key
+    assert np.allclose(theta_key, theta[::M], rtol=1e-14)
+    x_q, x_k, t, j = r.standard_normal(D), r.standard_normal(D), 57, 12
+    W_Q = r.standard_normal((h * d, D))
+    for i in range(h):
+        q_i = W_Q[i * d:(i + 1) * d] @ x_q
+        W_QR_i = co.rotate_rows(W_UK[i].T, U, g, d, M, 1)[:d_r]
+        got = rope_hat(W_QR_i @ q_i, t, d_r, theta_key) @ rope_hat(W_K_rot[:d_r] @ x_k, j, d_r, theta_key)
+        grp = i // (h // g)
+        want = rope_hat(q_i, t, d, theta_folded) @ rope_hat(W_K[grp * d:(grp + 1) * d] @ x_k, j, d, theta_folded)
         assert abs(got - want) < 1e-11 * (1 + abs(want))
 
 
