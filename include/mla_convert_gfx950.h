@@ -74,12 +74,19 @@ int mla_conv_sym_eig(double* A, double* evals, double* work, size_t work_bytes, 
  *   for every group G and component r:
  *     W_out[row_x(G, r), :] = sum_c U[G][c, r] W[col_x(G, c), :]        (k' = U^T k)
  *     and the same for the imaginary rows (row + 1),
- *   col_x(G, c = p*g + j) = j*d + 2(GM+p),   row_x(G, r) = (r / M)*d + 2(GM + r % M):
- *   the M leading components of every group go to the first head.
+ *   col_x(G, c = p*g + j) = j*d + 2(GM+p).
+ *   Output rows: first the RoPE key, the `keep` leading components of every group (1 <= keep <= M),
+ *   d_rope = keep * d / M rows:  row_x(G, r) = 2 (G keep + r)  for r < keep;  then the NoPE key:
+ *   row_x(G, r) = d_rope + 2 ((r - keep) d/(2M) + G)  for r >= keep.
+ *   keep = M: the RoPE key is a whole head of d dimensions whose pair G M + r carries a component of
+ *   the group that owns that pair, so ordinary RoPE of width d applies to it.  keep = 1: one pair per
+ *   group, ordinary RoPE of width d / M applies (its pair G turns with the first frequency of group G,
+ *   the effective frequency of App. C's example).  The paper fixes neither; Table 1's most compressed
+ *   LLaMA-2-7B setting keeps 576 = r_kv + d^R values per token, which 512 + 64 (M = 2, keep = 1) meets.
  *   W, W_out [g*d, cols] (distinct buffers), U [d/(2M), M*g, M*g].
  */
 int mla_conv_rotate_rows(const double* W, const double* U, double* W_out,
-                         int g, int d, int M, int cols, void* hip_stream);
+                         int g, int d, int M, int keep, int cols, void* hip_stream);
 
 /*
  * Key/value balancing factor (Sec. 4.3):  alpha = mean_t ||K_nope[t]||_2 / mean_t ||V[t]||_2
@@ -129,24 +136,26 @@ int mla_conv_top_eig(const double* S, const double* Q0, double* evals, double* R
 /*
  * The whole chain for one layer (Sec. 4.1 merged head -> Sec. 4.2 RoRoPE with M-fold FreqFold
  * -> Sec. 4.3 balancing -> App. D.2 joint low-rank projections), on calibration tokens X.
- *   in : X [n, D], W_K [g*d, D], W_V [g*d, D], Q0 [(2g-1)d, p] start block for the joint basis
- *   out: W_KR   [d, D]        k_rope = RoPE(W_KR x)            (the head that keeps RoPE)
- *        W_QR   [h, d, d]     q_rope_i = RoPE(W_QR[i] q_i)
+ *   keep components per group stay under RoPE (see mla_conv_rotate_rows): d_rope = keep * d / M,
+ *   and the joint space of NoPE key and values has m_j = 2 g d - d_rope dimensions.
+ *   in : X [n, D], W_K [g*d, D], W_V [g*d, D], Q0 [m_j, p] start block for the joint basis
+ *   out: W_KR   [d_rope, D]   k_rope = RoPE(W_KR x), RoPE of width d_rope   (the RoPE key)
+ *        W_QR   [h, d_rope, d]  q_rope_i = RoPE(W_QR[i] q_i)
  *        W_DKV  [r_kv, D]     c_kv = W_DKV x                   (App. D.2: R^T [W^DK_NoPE/alpha ; W^DV])
  *        W_UK   [h, d, r_kv]  q_abs_i = q_i . W_UK[i]          (alpha W^UK_NoPE,i R_K)
  *        W_UV   [h, r_kv, d]  o_i = o_lat_i . W_UV[i]          ((W^UV_i R_V)^T)
  *        alpha  [1], evals_rope [d/(2M), M*g], U [d/(2M), M*g, M*g], evals_joint [p],
- *        R_KV [(2g-1)d, r_kv]
+ *        R_KV [m_j, r_kv]
  *        info   [d/(2M) + 2] int: per-group sweeps of the RoRoPE bases, then the two entries of
  *               mla_conv_top_eig
  * The softmax scale of the converted layer stays 1/sqrt(d) (Eq. "qk_rope").
  */
-size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int r_kv, int p);
+size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int keep, int r_kv, int p);
 int mla_convert_layer(const double* X, const double* W_K, const double* W_V, const double* Q0,
                       double* W_KR, double* W_QR, double* W_DKV, double* W_UK, double* W_UV,
                       double* alpha, double* evals_rope, double* U, double* evals_joint, double* R_KV,
                       void* workspace, size_t workspace_bytes, int* info,
-                      int n, int D, int g, int h, int d, int M, int r_kv, int p, int iters,
+                      int n, int D, int g, int h, int d, int M, int keep, int r_kv, int p, int iters,
                       void* hip_stream);
 
 #ifdef __cplusplus

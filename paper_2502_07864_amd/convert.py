@@ -35,7 +35,7 @@ def lib() -> ctypes.CDLL:
         L.mla_conv_sym_eig.restype = i
         L.mla_conv_sym_eig.argtypes = [vp, vp, vp, sz, vp, i, i, i, vp]
         L.mla_conv_rotate_rows.restype = i
-        L.mla_conv_rotate_rows.argtypes = [vp, vp, vp, i, i, i, i, vp]
+        L.mla_conv_rotate_rows.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.mla_conv_kv_balance.restype = i
         L.mla_conv_kv_balance.argtypes = [vp, i, vp, i, vp, vp, i, i, i, vp]
         L.mla_conv_joint_moment.restype = i
@@ -49,9 +49,9 @@ def lib() -> ctypes.CDLL:
         L.mla_conv_apply.restype = i
         L.mla_conv_apply.argtypes = [vp, vp, vp, vp, sz, i, i, vp]
         L.mla_convert_layer_workspace_bytes.restype = sz
-        L.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+        L.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, i]
         L.mla_convert_layer.restype = i
-        L.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 9 + [vp]
+        L.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 10 + [vp]
         _ready = True
     return L
 
@@ -100,10 +100,11 @@ def sym_eig(A: torch.Tensor, max_sweeps: int = 60):
     return evals, U, info
 
 
-def rotate_rows(W: torch.Tensor, U: torch.Tensor, g: int, d: int, M: int = 1) -> torch.Tensor:
+def rotate_rows(W: torch.Tensor, U: torch.Tensor, g: int, d: int, M: int = 1, keep: Optional[int] = None) -> torch.Tensor:
     assert W.shape[0] == g * d
     out = torch.empty_like(W)
-    _check(lib().mla_conv_rotate_rows(_f64(W, "W"), _f64(U, "U"), out.data_ptr(), g, d, M, W.shape[1], _stream(W)),
+    keep = M if keep is None else keep
+    _check(lib().mla_conv_rotate_rows(_f64(W, "W"), _f64(U, "U"), out.data_ptr(), g, d, M, keep, W.shape[1], _stream(W)),
            "mla_conv_rotate_rows")
     return out
 
@@ -157,22 +158,26 @@ def apply(S: torch.Tensor, Q: torch.Tensor, out: Optional[torch.Tensor] = None,
 
 
 def convert_layer(X: torch.Tensor, W_K: torch.Tensor, W_V: torch.Tensor, Q0: torch.Tensor,
-                  g: int, h: int, d: int, M: int, r_kv: int, iters: int, workspace: Optional[torch.Tensor] = None):
-    """The whole chain; returns a dict of the tensors named in the header."""
+                  g: int, h: int, d: int, M: int, r_kv: int, iters: int, workspace: Optional[torch.Tensor] = None,
+                  keep: Optional[int] = None):
+    """The whole chain; returns a dict of the tensors named in the header.  keep (default M): components per
+    FreqFold group that stay under RoPE; the RoPE key is d_rope = keep * d / M wide."""
     n, D = X.shape
     mj, p = Q0.shape
-    assert W_K.shape == (g * d, D) and W_V.shape == (g * d, D) and mj == (2 * g - 1) * d
+    keep = M if keep is None else keep
+    d_rope = keep * (d // M)
+    assert W_K.shape == (g * d, D) and W_V.shape == (g * d, D) and mj == 2 * g * d - d_rope
     groups, Mg = d // (2 * M), M * g
-    out = dict(W_KR=_new(X, d, D), W_QR=_new(X, h, d, d), W_DKV=_new(X, r_kv, D), W_UK=_new(X, h, d, r_kv),
+    out = dict(W_KR=_new(X, d_rope, D), W_QR=_new(X, h, d_rope, d), W_DKV=_new(X, r_kv, D), W_UK=_new(X, h, d, r_kv),
                W_UV=_new(X, h, r_kv, d), alpha=_new(X, 1), evals_rope=_new(X, groups, Mg), U=_new(X, groups, Mg, Mg),
                evals_joint=_new(X, p), R_KV=_new(X, mj, r_kv),
                info=torch.empty(groups + 2, dtype=torch.int32, device=X.device))
-    nbytes = lib().mla_convert_layer_workspace_bytes(n, D, g, h, d, M, r_kv, p)
+    nbytes = lib().mla_convert_layer_workspace_bytes(n, D, g, h, d, M, keep, r_kv, p)
     ws = workspace if workspace is not None else _bytes(X, nbytes)
     _check(lib().mla_convert_layer(
         _f64(X, "X"), _f64(W_K, "W_K"), _f64(W_V, "W_V"), _f64(Q0, "Q0"),
         out["W_KR"].data_ptr(), out["W_QR"].data_ptr(), out["W_DKV"].data_ptr(), out["W_UK"].data_ptr(),
         out["W_UV"].data_ptr(), out["alpha"].data_ptr(), out["evals_rope"].data_ptr(), out["U"].data_ptr(),
         out["evals_joint"].data_ptr(), out["R_KV"].data_ptr(), ws.data_ptr(), ws.numel(), out["info"].data_ptr(),
-        n, D, g, h, d, M, r_kv, p, iters, _stream(X)), "mla_convert_layer")
+        n, D, g, h, d, M, keep, r_kv, p, iters, _stream(X)), "mla_convert_layer")
     return out

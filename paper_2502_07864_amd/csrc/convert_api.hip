@@ -103,12 +103,12 @@ struct LayerWs {
     void* top; size_t top_bytes;
     size_t bytes;
 };
-LayerWs layer_ws(void* base, int n, int D, int g, int h, int d, int M, int p) {
+LayerWs layer_ws(void* base, int n, int D, int g, int h, int d, int M, int keep, int p) {
     LayerWs w{};
     size_t off = 0;
     auto take = [&](size_t count) { double* ptr = base ? reinterpret_cast<double*>(static_cast<char*>(base) + off) : nullptr;
                                     off += align256(count * sizeof(double)); return ptr; };
-    const size_t gd = (size_t)g * d, mj = (size_t)(2 * g - 1) * d, Mg = (size_t)M * g;
+    const size_t gd = (size_t)g * d, mj = 2 * gd - (size_t)keep * (d / M), Mg = (size_t)M * g;
     w.K = take((size_t)n * gd);
     w.sigma_work = take(jacobi_work_bytes(d / (2 * M), (int)Mg) / sizeof(double));
     w.W_K_rot = take(gd * D);
@@ -125,10 +125,10 @@ LayerWs layer_ws(void* base, int n, int D, int g, int h, int d, int M, int p) {
     return w;
 }
 
-bool layer_shape_ok(int n, int D, int g, int h, int d, int M, int r_kv, int p) {
+bool layer_shape_ok(int n, int D, int g, int h, int d, int M, int keep, int r_kv, int p) {
     if (n <= 0 || D <= 0 || g <= 0 || h <= 0 || d <= 0 || M <= 0 || r_kv <= 0 || p <= 0) return false;
-    if (d % 2 || (d / 2) % M || h % g || g < 2) return false;
-    const long mj = (long)(2 * g - 1) * d;
+    if (d % 2 || (d / 2) % M || h % g || g < 2 || keep < 1 || keep > M) return false;
+    const long mj = 2L * g * d - (long)keep * (d / M);
     return r_kv <= p && p <= mj;
 }
 
@@ -163,11 +163,11 @@ int mla_conv_sym_eig(double* A, double* evals, double* work, size_t work_bytes, 
     return st(launch_jacobi(A, evals, work, info, batch, m, max_sweeps, static_cast<hipStream_t>(hip_stream)));
 }
 
-int mla_conv_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int cols, void* hip_stream) {
+int mla_conv_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int keep, int cols, void* hip_stream) {
     if (!W || !U || !W_out) return MLA_ERR_NULL;
-    if (g <= 0 || d <= 0 || M <= 0 || cols <= 0 || d % 2 || (d / 2) % M || W == W_out) return MLA_ERR_SHAPE;
+    if (g <= 0 || d <= 0 || M <= 0 || cols <= 0 || d % 2 || (d / 2) % M || keep < 1 || keep > M || W == W_out) return MLA_ERR_SHAPE;
     if ((long)M * g > MOMENT_MAX_MG || (cols + 31) / 32 > 65535) return MLA_ERR_UNSUPPORTED;
-    return st(launch_rotate_rows(W, U, W_out, g, d, M, cols, static_cast<hipStream_t>(hip_stream)));
+    return st(launch_rotate_rows(W, U, W_out, g, d, M, keep, cols, static_cast<hipStream_t>(hip_stream)));
 }
 
 int mla_conv_kv_balance(const double* K_nope, int ldk, const double* V, int ldv, double* alpha,
@@ -223,26 +223,27 @@ int mla_conv_apply(const double* S, const double* Q, double* Y, void* workspace,
     return st(launch_gemm_f64(g, static_cast<hipStream_t>(hip_stream)));
 }
 
-size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int r_kv, int p) {
-    if (!layer_shape_ok(n, D, g, h, d, M, r_kv, p) || p > TOP_MAX_P || (long)M * g > MOMENT_MAX_MG) return 0;
-    return layer_ws(nullptr, n, D, g, h, d, M, p).bytes;
+size_t mla_convert_layer_workspace_bytes(int n, int D, int g, int h, int d, int M, int keep, int r_kv, int p) {
+    if (!layer_shape_ok(n, D, g, h, d, M, keep, r_kv, p) || p > TOP_MAX_P || (long)M * g > MOMENT_MAX_MG) return 0;
+    return layer_ws(nullptr, n, D, g, h, d, M, keep, p).bytes;
 }
 
 int mla_convert_layer(const double* X, const double* W_K, const double* W_V, const double* Q0,
                       double* W_KR, double* W_QR, double* W_DKV, double* W_UK, double* W_UV,
                       double* alpha, double* evals_rope, double* U, double* evals_joint, double* R_KV,
                       void* workspace, size_t workspace_bytes, int* info,
-                      int n, int D, int g, int h, int d, int M, int r_kv, int p, int iters,
+                      int n, int D, int g, int h, int d, int M, int keep, int r_kv, int p, int iters,
                       void* hip_stream) {
     if (!X || !W_K || !W_V || !Q0 || !W_KR || !W_QR || !W_DKV || !W_UK || !W_UV || !alpha || !evals_rope ||
         !U || !evals_joint || !R_KV || !info) return MLA_ERR_NULL;
-    if (!layer_shape_ok(n, D, g, h, d, M, r_kv, p) || iters < 0 || p < 2) return MLA_ERR_SHAPE;
+    if (!layer_shape_ok(n, D, g, h, d, M, keep, r_kv, p) || iters < 0 || p < 2) return MLA_ERR_SHAPE;
     if (p > TOP_MAX_P || (long)M * g > MOMENT_MAX_MG || (long)M * g < 2) return MLA_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < mla_convert_layer_workspace_bytes(n, D, g, h, d, M, r_kv, p)) return MLA_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < mla_convert_layer_workspace_bytes(n, D, g, h, d, M, keep, r_kv, p)) return MLA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const LayerWs w = layer_ws(workspace, n, D, g, h, d, M, p);
+    const LayerWs w = layer_ws(workspace, n, D, g, h, d, M, keep, p);
     const int gd = g * d, hd = h * d, groups = d / (2 * M), Mg = M * g;
-    const int a = (g - 1) * d, mj = a + gd;
+    const int d_rope = keep * (d / M);        // width of the RoPE key
+    const int a = gd - d_rope, mj = a + gd;   // NoPE key, joint NoPE-key + value space
     hipError_t e;
 #define MLA_TRY(call) do { e = (call); if (e != hipSuccess) return MLA_ERR_HIP; } while (0)
     // Sec. 4.1 / App. B: key activations before RoPE, their per-group moments, the bases U
@@ -250,15 +251,15 @@ int mla_convert_layer(const double* X, const double* W_K, const double* W_V, con
     MLA_TRY(launch_rope_moments(w.K, U, n, g, d, M, s));
     MLA_TRY(launch_jacobi(U, evals_rope, w.sigma_work, info, groups, Mg, JACOBI_MAX_SWEEPS, s));
     // Sec. 4.2: rotate W^K and the selector matrices (W^UK_i)^T, stacked as [g d, h d]
-    MLA_TRY(launch_rotate_rows(W_K, U, w.W_K_rot, g, d, M, D, s));
+    MLA_TRY(launch_rotate_rows(W_K, U, w.W_K_rot, g, d, M, keep, D, s));
     MLA_TRY(launch_selector(w.E, g, h, d, s));
-    MLA_TRY(launch_rotate_rows(w.E, U, w.E_rot, g, d, M, hd, s));
-    // the first head keeps RoPE: W_KR = its rows of W^K; W_QR[i][a][b] = E_rot[a][i d + b]
-    MLA_TRY(launch_copy_scaled(w.W_K_rot, D, W_KR, D, d, D, nullptr, 0, s));
+    MLA_TRY(launch_rotate_rows(w.E, U, w.E_rot, g, d, M, keep, hd, s));
+    // the RoPE key: W_KR = the first d_rope rows of the rotated W^K; W_QR[i][a][b] = E_rot[a][i d + b]
+    MLA_TRY(launch_copy_scaled(w.W_K_rot, D, W_KR, D, d_rope, D, nullptr, 0, s));
     for (int i = 0; i < h; ++i)
-        MLA_TRY(launch_copy_scaled(w.E_rot + (size_t)i * d, hd, W_QR + (size_t)i * d * d, d, d, d, nullptr, 0, s));
-    // Sec. 4.3: activations of the other heads and of the values, alpha
-    MLA_TRY(launch_gemm_f64(gemm_nt(X, D, w.W_K_rot + (size_t)d * D, D, w.C, mj, n, a, D, 1.0), s));
+        MLA_TRY(launch_copy_scaled(w.E_rot + (size_t)i * d, hd, W_QR + (size_t)i * d_rope * d, d, d_rope, d, nullptr, 0, s));
+    // Sec. 4.3: activations of the NoPE key and of the values, alpha
+    MLA_TRY(launch_gemm_f64(gemm_nt(X, D, w.W_K_rot + (size_t)d_rope * D, D, w.C, mj, n, a, D, 1.0), s));
     MLA_TRY(launch_gemm_f64(gemm_nt(X, D, W_V, D, w.C + a, mj, n, gd, D, 1.0), s));
     MLA_TRY(launch_row_norms(w.C, mj, a, w.C + a, mj, gd, w.norms, n, s));
     MLA_TRY(launch_alpha(w.norms, alpha, n, s));
@@ -268,16 +269,16 @@ int mla_convert_layer(const double* X, const double* W_K, const double* W_V, con
     int rc = top_eig(w.S, Q0, evals_joint, R_KV, top_ws(w.top, mj, p), info + groups, mj, r_kv, p, iters, s);
     if (rc != MLA_OK) return rc;
     // W^DKV' = R^T [W^DK_NoPE / alpha ; W^DV]
-    MLA_TRY(launch_copy_scaled(w.W_K_rot + (size_t)d * D, D, w.W_cat, D, a, D, alpha, 2, s));
+    MLA_TRY(launch_copy_scaled(w.W_K_rot + (size_t)d_rope * D, D, w.W_cat, D, a, D, alpha, 2, s));
     MLA_TRY(launch_copy_scaled(W_V, D, w.W_cat + (size_t)a * D, D, gd, D, nullptr, 0, s));
     MLA_TRY(launch_gemm_f64(gemm_tn(R_KV, r_kv, w.W_cat, D, W_DKV, D, r_kv, D, mj, 1.0), s));
-    // W^UK'_i = alpha W^UK_NoPE,i R_K for all heads at once: (E_rot[d:, :])^T R_K -> [h d, r_kv]
-    GemmF64 uk = gemm_tn(w.E_rot + (size_t)d * hd, hd, R_KV, r_kv, W_UK, r_kv, hd, r_kv, a, 1.0);
+    // W^UK'_i = alpha W^UK_NoPE,i R_K for all heads at once: (E_rot[d_rope:, :])^T R_K -> [h d, r_kv]
+    GemmF64 uk = gemm_tn(w.E_rot + (size_t)d_rope * hd, hd, R_KV, r_kv, W_UK, r_kv, hd, r_kv, a, 1.0);
     uk.alpha_dev = alpha;
     uk.dev_mode = 1;
     MLA_TRY(launch_gemm_f64(uk, s));
     // W^UV'_i = W^UV_i R_V: the rows of R_V that belong to the group of head i, transposed
-    MLA_TRY(launch_gather_w_uv(R_KV, W_UV, g, h, d, r_kv, s));
+    MLA_TRY(launch_gather_w_uv(R_KV, W_UV, g, h, d, a, r_kv, s));
 #undef MLA_TRY
     return MLA_OK;
 }

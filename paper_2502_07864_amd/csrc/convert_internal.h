@@ -33,7 +33,7 @@ constexpr int EIG_MAX_M = 2048;      // Jacobi: matrix order
 constexpr int TOP_MAX_P = 1024;      // block power iteration: block width
 
 hipError_t launch_rope_moments(const double* K, double* sigma, int n, int g, int d, int M, hipStream_t s);
-hipError_t launch_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int cols, hipStream_t s);
+hipError_t launch_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int keep, int cols, hipStream_t s);
 hipError_t launch_row_norms(const double* K, int ldk, int a, const double* V, int ldv, int b, double* norms, int n, hipStream_t s);
 hipError_t launch_alpha(const double* norms, double* alpha, int n, hipStream_t s);
 // C[t, 0:a] = K[t, 0:a] / *alpha, C[t, a:a+b] = V[t, 0:b]   (in place allowed)
@@ -52,8 +52,8 @@ hipError_t launch_fill_int(int* dst, int value, int count, hipStream_t s);
 hipError_t launch_copy_scaled(const double* src, long lds_, double* dst, long ldd, int rows, int cols, const double* scale, int mode, hipStream_t s);
 // E [g*d, h*d]: E[j*d + b, i*d + b] = 1 when j is the group of query head i (Sec. 4.1), else 0
 hipError_t launch_selector(double* E, int g, int h, int d, hipStream_t s);
-// W_UV[i, rho, b] = R[(g-1)d + group(i)*d + b, rho]
-hipError_t launch_gather_w_uv(const double* R, double* W_UV, int g, int h, int d, int r, hipStream_t s);
+// W_UV[i, rho, b] = R[nope + group(i)*d + b, rho]   (nope: rows of the NoPE key in front of the values)
+hipError_t launch_gather_w_uv(const double* R, double* W_UV, int g, int h, int d, int nope, int r, hipStream_t s);
 
 }  // namespace conv
 }  // namespace mla

@@ -80,8 +80,10 @@ __global__ __launch_bounds__(256) void rope_moments_kernel(const double* __restr
 
 // ------------------------------------------------------------------ Sec. 4.2: rotation of rows
 // grid (2 * groups, column tiles of 32): part 0 rotates the real rows, part 1 the imaginary rows.
+// Output rows: the RoPE key first (component r < keep of group G at pair G * keep + r), then the NoPE
+// key (component r >= keep at pair (r - keep) * groups + G).
 __global__ __launch_bounds__(256) void rotate_rows_kernel(const double* __restrict__ W, const double* __restrict__ U,
-                                                          double* __restrict__ W_out, int g, int d, int M, int cols) {
+                                                          double* __restrict__ W_out, int g, int d, int M, int keep, int cols) {
     __shared__ double ws[MOMENT_MAX_MG][33];
     const int part = blockIdx.x & 1, G = blockIdx.x >> 1, Mg = M * g, tid = threadIdx.x;
     const int col0 = blockIdx.y * 32;
@@ -96,7 +98,8 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const double* __restri
     for (int r = tid >> 5; r < Mg; r += 8) {
         double a = 0.0;
         for (int c = 0; c < Mg; ++c) a += Ug[c * Mg + r] * ws[c][cc];
-        const long row = (long)(r / M) * d + 2 * (G * M + r % M) + part;
+        const int groups = d / (2 * M);
+        const long row = (r < keep ? 2L * (G * keep + r) : 2L * keep * groups + 2L * ((long)(r - keep) * groups + G)) + part;
         if (col0 + cc < cols) W_out[row * cols + col0 + cc] = a;
     }
 }
@@ -587,12 +590,12 @@ __global__ __launch_bounds__(256) void selector_kernel(double* __restrict__ E, i
 }
 
 __global__ __launch_bounds__(256) void gather_w_uv_kernel(const double* __restrict__ R, double* __restrict__ W_UV,
-                                                          int g, int h, int d, int r) {
+                                                          int g, int h, int d, int nope, int r) {
     const long total = (long)h * r * d;
     const int per = h / g;
     for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
         const int b = (int)(idx % d), rho = (int)((idx / d) % r), i = (int)(idx / ((long)d * r));
-        W_UV[idx] = R[((long)(g - 1) * d + (long)(i / per) * d + b) * r + rho];
+        W_UV[idx] = R[((long)nope + (long)(i / per) * d + b) * r + rho];
     }
 }
 
@@ -621,9 +624,9 @@ hipError_t launch_rope_moments(const double* K, double* sigma, int n, int g, int
     return hipGetLastError();
 }
 
-hipError_t launch_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int cols, hipStream_t s) {
+hipError_t launch_rotate_rows(const double* W, const double* U, double* W_out, int g, int d, int M, int keep, int cols, hipStream_t s) {
     dim3 grid(2 * (d / (2 * M)), (cols + 31) / 32);
-    rotate_rows_kernel<<<grid, 256, 0, s>>>(W, U, W_out, g, d, M, cols);
+    rotate_rows_kernel<<<grid, 256, 0, s>>>(W, U, W_out, g, d, M, keep, cols);
     return hipGetLastError();
 }
 
@@ -750,8 +753,8 @@ hipError_t launch_selector(double* E, int g, int h, int d, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_gather_w_uv(const double* R, double* W_UV, int g, int h, int d, int r, hipStream_t s) {
-    gather_w_uv_kernel<<<grid_for((long)h * r * d), 256, 0, s>>>(R, W_UV, g, h, d, r);
+hipError_t launch_gather_w_uv(const double* R, double* W_UV, int g, int h, int d, int nope, int r, hipStream_t s) {
+    gather_w_uv_kernel<<<grid_for((long)h * r * d), 256, 0, s>>>(R, W_UV, g, h, d, nope, r);
     return hipGetLastError();
 }
 

@@ -246,7 +246,7 @@ def conv_lib(lib):
     lib.mla_conv_sym_eig_workspace_bytes.restype = sz
     lib.mla_conv_sym_eig_workspace_bytes.argtypes = [i, i]
     lib.mla_conv_sym_eig.argtypes = [vp, vp, vp, sz, vp, i, i, i, vp]
-    lib.mla_conv_rotate_rows.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.mla_conv_rotate_rows.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     lib.mla_conv_kv_balance.argtypes = [vp, i, vp, i, vp, vp, i, i, i, vp]
     lib.mla_conv_joint_moment.argtypes = [vp, i, vp, i, vp, vp, vp, i, i, i, vp]
     lib.mla_conv_top_eig_workspace_bytes.restype = sz
@@ -256,8 +256,8 @@ def conv_lib(lib):
     lib.mla_conv_apply_workspace_bytes.argtypes = [i, i]
     lib.mla_conv_apply.argtypes = [vp, vp, vp, vp, sz, i, i, vp]
     lib.mla_convert_layer_workspace_bytes.restype = sz
-    lib.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
-    lib.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 9 + [vp]
+    lib.mla_convert_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, i]
+    lib.mla_convert_layer.argtypes = [vp] * 14 + [vp, sz, vp] + [i] * 10 + [vp]
     return lib
 
 
@@ -277,8 +277,10 @@ def test_conversion_step_validation(lib):
     assert L.mla_conv_rope_moments(P, P, 8, 2, 7, 1, None) == E_SHAPE        # odd head dimension
     assert L.mla_conv_rope_moments(P, P, 8, 2, 8, 3, None) == E_SHAPE        # 4 pairs do not fold by 3
     assert L.mla_conv_rope_moments(P, P, 8, 32, 128, 8, None) == E_UNSUP     # M g = 256 > 128
-    assert L.mla_conv_rotate_rows(P, P, P, 2, 8, 1, 16, None) == E_SHAPE     # in place is not allowed
-    assert L.mla_conv_rotate_rows(P, P, P + 64, 2, 8, 1, 0, None) == E_SHAPE
+    assert L.mla_conv_rotate_rows(P, P, P, 2, 8, 1, 1, 16, None) == E_SHAPE     # in place is not allowed
+    assert L.mla_conv_rotate_rows(P, P, P + 64, 2, 8, 1, 1, 0, None) == E_SHAPE
+    assert L.mla_conv_rotate_rows(P, P, P + 64, 2, 8, 2, 3, 16, None) == E_SHAPE  # keep > M
+    assert L.mla_conv_rotate_rows(P, P, P + 64, 2, 8, 2, 0, 16, None) == E_SHAPE  # keep < 1
     assert L.mla_conv_kv_balance(P, 4, P, 4, None, P, 8, 4, 4, None) == E_NULL
     assert L.mla_conv_kv_balance(P, 3, P, 4, P, P, 8, 4, 4, None) == E_SHAPE  # ldk < a
     assert L.mla_conv_joint_moment(P, 4, P, 4, P, P, None, 8, 4, 4, None) == E_NULL
@@ -311,25 +313,28 @@ def test_conversion_eigensolver_validation(lib):
 
 def test_conversion_chain_validation(lib):
     L = conv_lib(lib)
-    ok = dict(n=256, D=64, g=4, h=8, d=16, M=1, r_kv=24, p=32, iters=10)
+    ok = dict(n=256, D=64, g=4, h=8, d=16, M=1, keep=1, r_kv=24, p=32, iters=10)
 
     def call(ws_bytes=1 << 40, null_at=None, **kw):
         a = dict(ok, **kw)
         ptrs = [P] * 14
         if null_at is not None:
             ptrs[null_at] = None
-        return L.mla_convert_layer(*ptrs, P, ws_bytes, P, a["n"], a["D"], a["g"], a["h"], a["d"], a["M"],
+        return L.mla_convert_layer(*ptrs, P, ws_bytes, P, a["n"], a["D"], a["g"], a["h"], a["d"], a["M"], a["keep"],
                                    a["r_kv"], a["p"], a["iters"], None)
 
-    need = L.mla_convert_layer_workspace_bytes(256, 64, 4, 8, 16, 1, 24, 32)
+    need = L.mla_convert_layer_workspace_bytes(256, 64, 4, 8, 16, 1, 1, 24, 32)
     assert need > 256 * (7 * 16) * 8 and need % 256 == 0
     assert call(null_at=0) == E_NULL and call(null_at=13) == E_NULL
     assert call(h=6) == E_SHAPE            # h not a multiple of g
     assert call(d=15) == E_SHAPE
-    assert call(M=3) == E_SHAPE            # 8 pairs do not fold by 3
+    assert call(M=3, keep=3) == E_SHAPE    # 8 pairs do not fold by 3
+    assert call(M=2, keep=3) == E_SHAPE    # more kept components than the group has pairs
+    assert call(M=2, keep=1, p=121) == E_SHAPE   # p > 2 g d - d_rope = 120
+    assert call(M=2, keep=1, p=120, ws_bytes=16) == E_WS   # a valid shape: only the workspace is wrong
     assert call(r_kv=40) == E_SHAPE        # r_kv > p
     assert call(p=200) == E_SHAPE          # p > (2g-1)d = 112
     assert call(g=1, h=8) == E_SHAPE       # nothing to merge
-    assert call(g=32, h=32, d=128, M=8, D=4096, r_kv=512, p=576) == E_UNSUP   # M g > 128
+    assert call(g=32, h=32, d=128, M=8, keep=8, D=4096, r_kv=512, p=576) == E_UNSUP   # M g > 128
     assert call(ws_bytes=need - 1) == E_WS
-    assert L.mla_convert_layer_workspace_bytes(256, 64, 4, 6, 16, 1, 24, 32) == 0
+    assert L.mla_convert_layer_workspace_bytes(256, 64, 4, 6, 16, 1, 1, 24, 32) == 0

@@ -120,13 +120,14 @@ def test_sym_eig_rorope_bases_have_the_oracles_projectors(cv):
 
 # ------------------------------------------------------------------ Sec. 4.2 / 4.3 / D.2 steps
 
-@pytest.mark.parametrize("g,d,M,cols", [(4, 16, 1, 50), (4, 16, 2, 33), (3, 12, 3, 7), (8, 64, 4, 100), (32, 128, 1, 40)])
-def test_rotate_rows(cv, g, d, M, cols):
+@pytest.mark.parametrize("g,d,M,keep,cols", [(4, 16, 1, 1, 50), (4, 16, 2, 2, 33), (4, 16, 2, 1, 33), (3, 12, 3, 2, 7),
+                                             (8, 64, 4, 4, 100), (8, 64, 4, 1, 100), (32, 128, 1, 1, 40), (32, 128, 2, 1, 40)])
+def test_rotate_rows(cv, g, d, M, keep, cols):
     r = rng(g + d + M)
     W = r.standard_normal((g * d, cols))
     U = r.standard_normal((d // (2 * M), M * g, M * g))
-    got = host(cv.rotate_rows(dev(W), dev(U), g, d, M))
-    assert rel(got, co.rotate_rows(W, U, g, d, M)) < 1e-12
+    got = host(cv.rotate_rows(dev(W), dev(U), g, d, M, keep))
+    assert rel(got, co.rotate_rows(W, U, g, d, M, keep)) < 1e-12
 
 
 @pytest.mark.parametrize("n,a,b", [(100, 48, 64), (1, 3, 5), (333, 130, 7)])
@@ -181,20 +182,24 @@ def test_apply_with_k_slices_matches_the_plain_product(cv):
 
 # ------------------------------------------------------------------ the chain
 
-def chain_case(g, h, d, D, n, M, r_kv, p, seed):
+def chain_case(g, h, d, D, n, M, keep, r_kv, p, seed):
     X, W_K, W_V = synth.calibration(n, D, g, d, seed=seed)
-    Q0 = synth.start_block((2 * g - 1) * d, p, seed=seed)
+    Q0 = synth.start_block(2 * g * d - co.rope_width(d, M, keep), p, seed=seed)
     return X, W_K, W_V, Q0
 
 
-@pytest.mark.parametrize("g,h,d,D,n,M,r_kv,p", [(4, 8, 16, 96, 512, 1, 40, 56), (4, 8, 16, 96, 512, 2, 40, 56),
-                                                (2, 6, 8, 40, 200, 4, 12, 20), (8, 8, 32, 128, 300, 1, 64, 96)])
-def test_convert_layer_against_the_oracle_chain(cv, g, h, d, D, n, M, r_kv, p):
-    X, W_K, W_V, Q0 = chain_case(g, h, d, D, n, M, r_kv, p, seed=g + M)
-    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(Q0), g, h, d, M, r_kv, iters=80)
+@pytest.mark.parametrize("g,h,d,D,n,M,keep,r_kv,p", [(4, 8, 16, 96, 512, 1, 1, 40, 56), (4, 8, 16, 96, 512, 2, 2, 40, 56),
+                                                     (4, 8, 16, 96, 512, 2, 1, 40, 56), (2, 6, 8, 40, 200, 4, 4, 12, 20),
+                                                     (2, 6, 8, 40, 200, 4, 1, 12, 20), (8, 8, 32, 128, 300, 1, 1, 64, 96),
+                                                     (8, 8, 32, 128, 300, 4, 2, 64, 96)])
+def test_convert_layer_against_the_oracle_chain(cv, g, h, d, D, n, M, keep, r_kv, p):
+    X, W_K, W_V, Q0 = chain_case(g, h, d, D, n, M, keep, r_kv, p, seed=g + M)
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(Q0), g, h, d, M, r_kv, iters=80, keep=keep)
     got = {k: host(v) for k, v in out.items()}
-    want = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    want = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv, keep)
     groups = d // (2 * M)
+    d_rope = co.rope_width(d, M, keep)
+    assert got["W_KR"].shape == (d_rope, D) and got["W_QR"].shape == (h, d_rope, d)
     assert (got["info"][:groups] >= 1).all() and got["info"][groups] == 0 and got["info"][groups + 1] >= 1
     assert abs(got["alpha"][0] - want["alpha"]) < 1e-11 * want["alpha"]
     assert rel(got["evals_rope"], want["evals_rope"]) < 1e-10
@@ -202,13 +207,13 @@ def test_convert_layer_against_the_oracle_chain(cv, g, h, d, D, n, M, r_kv, p):
     # A sign flip of a RoRoPE basis vector flips one coordinate of the rotated key, hence one row of
     # R_KV: undo those flips (read off the two sets of bases) before comparing the projectors.
     sign = np.sign(np.einsum("gcr,gcr->gr", got["U"], want["U"]))
-    out_x, out_y = co.placement_columns(g, d, M)
-    flip = np.ones((2 * g - 1) * d)
+    out_x, out_y = co.placement_columns(g, d, M, keep)
+    flip = np.ones(2 * g * d - d_rope)
     for G in range(groups):
         for r in range(M * g):
             for row in (out_x[G, r], out_y[G, r]):
-                if row >= d:
-                    flip[row - d] = sign[G, r]
+                if row >= d_rope:
+                    flip[row - d_rope] = sign[G, r]
     assert projector_gap(got["R_KV"] * flip[:, None], want["R_KV"]) < 1e-7
     # sign-free products.  Rope head: row a of W_QR[i] and row a of W_KR flip together.
     for i in range(h):
@@ -236,12 +241,14 @@ def decode_converted_layer_on_gpu(out, X_ctx, q, d, pos_new, theta, page_size=64
     W = {k: host(v) for k, v in out.items()}
     h = q.shape[0]
     L = len(X_ctx)
+    d_r = W["W_KR"].shape[0]                                    # width of the RoPE key; theta: its d_r / 2 frequencies
+    assert len(theta) == d_r // 2
     c_kv = X_ctx @ W["W_DKV"].T
-    k_rope = np.stack([rope_hat(W["W_KR"] @ X_ctx[t], t, d, theta) for t in range(L)])
-    q_rope = np.stack([rope_hat(W["W_QR"][i] @ q[i], pos_new, d, theta) for i in range(h)])
+    k_rope = np.stack([rope_hat(W["W_KR"] @ X_ctx[t], t, d_r, theta) for t in range(L)])
+    q_rope = np.stack([rope_hat(W["W_QR"][i] @ q[i], pos_new, d_r, theta) for i in range(h)])
     d_c = c_kv.shape[1]
     pages = (L + page_size - 1) // page_size
-    pool = np.zeros((pages + 1, page_size, d_c + d), dtype=np.float32)
+    pool = np.zeros((pages + 1, page_size, d_c + d_r), dtype=np.float32)
     order = np.arange(pages)[::-1] + 1                          # pages stored in reverse, page 0 unused
     for t in range(L):
         pool[order[t // page_size], t % page_size] = np.concatenate([c_kv[t], k_rope[t]])
@@ -269,20 +276,23 @@ def test_gpu_conversion_then_gpu_decode_reproduces_gqa_when_nothing_is_lost(cv):
     assert np.abs(got - want).max() < 2e-5 * max(1.0, np.abs(want).max())
 
 
-@pytest.mark.parametrize("M", [1, 2])
-def test_gpu_converted_layer_decodes_like_the_oracles_converted_layer(cv, M):
+@pytest.mark.parametrize("M,keep", [(1, 1), (2, 2), (2, 1)])
+def test_gpu_converted_layer_decodes_like_the_oracles_converted_layer(cv, M, keep):
     """Truncated rank and real positions: the attention output of the converted layer does not depend on
-    the signs of the bases, so GPU conversion + GPU decode must match numpy conversion + the decode oracle."""
+    the signs of the bases, so GPU conversion + GPU decode must match numpy conversion + the decode oracle.
+    The RoPE key takes ordinary RoPE of its own width (d for keep = M, d / M for keep = 1)."""
     from test_convert_oracle_pins import mla_attention_through_the_decode_oracle, std_theta
     g, h, d, D, n, L, r_kv, p = 4, 8, 16, 64, 400, 150, 40, 56
     X, W_K, W_V = synth.calibration(n, D, g, d, seed=11 + M)
     r = rng(43)
     W_Q = r.standard_normal((h * d, D)) / np.sqrt(D)
     X_ctx = synth.calibration(L, D, g, d, seed=13)[0]
-    theta = std_theta(d)
-    mj = (2 * g - 1) * d
-    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=3)), g, h, d, M, r_kv, iters=80)
-    ref = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv)
+    d_rope = co.rope_width(d, M, keep)
+    theta = std_theta(d_rope)
+    mj = 2 * g * d - d_rope
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=3)), g, h, d, M, r_kv, iters=80,
+                           keep=keep)
+    ref = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv, keep)
     want = mla_attention_through_the_decode_oracle(ref, X_ctx[-1], X_ctx, W_Q, h, d, L - 1, theta)
     got = decode_converted_layer_on_gpu(out, X_ctx, (W_Q @ X_ctx[-1]).reshape(h, d), d, L - 1, theta)
     assert np.abs(got - want).max() < 2e-5 * max(1.0, np.abs(want).max())
