@@ -301,11 +301,13 @@ def gqa_attention(x_new, X_ctx, W_Q, W_K, W_V, g, h, d, pos_new, theta):
     return np.stack(outs)
 
 
-def mla_attention_through_the_decode_oracle(cv, x_new, X_ctx, W_Q, h, d, pos_new, theta):
+def mla_attention_through_the_decode_oracle(cv, x_new, X_ctx, W_Q, h, d, pos_new, theta, q=None):
     """Feed the converted tensors to the absorbed-decode oracle in the layout the decode path consumes.
-    theta: the frequencies of the RoPE key, one per pair of its d_rope dimensions."""
+    theta: the frequencies of the RoPE key, one per pair of its d_rope dimensions.  q: the query heads
+    [h, d] if the caller has them already (else W_Q x_new)."""
     L = len(X_ctx)
-    q = (W_Q @ x_new).reshape(h, d)
+    if q is None:
+        q = (W_Q @ x_new).reshape(h, d)
     d_r = cv["W_KR"].shape[0]
     assert len(theta) == d_r // 2
     c_kv = X_ctx @ cv["W_DKV"].T

@@ -510,3 +510,55 @@ def test_largest_orders_the_solvers_take(cv):
     assert np.abs(ev2[:r2] - lam[:r2]).max() < 1e-10
     assert np.abs(R.T @ R - np.eye(r2)).max() < 1e-11
     assert np.abs(S @ R - R * ev2[:r2]).max() < 1e-9
+
+
+def test_converted_gqa_layer_runs_on_the_matrix_core_decode_path(cv):
+    """A GQA layer with 128-dimensional heads (g = 8 key/value heads, h = 32 query heads, as LLaMA-3-8B has
+    them) converted with 2-fold FreqFold and one RoPE pair per group lands exactly on the decode path's
+    headline shape: latent 512 + RoPE key 64, 32 heads of 128.  Conversion in fp64 on the GPU, weights
+    rounded to bf16, cache rows written by mla_cache_append into a bf16 paged cache, decode on the
+    matrix-core kernels -- against the numpy conversion fed to the decode oracle (the attention output
+    does not depend on the signs of the bases).  bf16 bar of the decode path: 2e-2."""
+    import torch
+    from helpers import max_abs_rel, to_torch, widen_gpu
+    from paper_2502_07864_amd import mla
+    from test_convert_oracle_pins import mla_attention_through_the_decode_oracle, rope_hat, std_theta
+    g, h, d, D, n, M, keep, r_kv, p = 8, 32, 128, 1024, 2048, 2, 1, 512, 640
+    d_rope = co.rope_width(d, M, keep)
+    assert d_rope == 64
+    mj = 2 * g * d - d_rope
+    lens = [300, 129, 64]
+    B = len(lens)
+    bf16 = lambda a: synth.bf16_bits_to_f32(synth.to_bf16_bits(np.asarray(a, dtype=np.float32))).astype(np.float64)
+    X, W_K, W_V = synth.calibration(n, D, g, d, seed=23)
+    r = rng(59)
+    W_Q = r.standard_normal((h * d, D)) / np.sqrt(D)
+    ctx = [bf16(synth.calibration(L, D, g, d, seed=40 + b)[0]) for b, L in enumerate(lens)]   # hidden states as stored
+    theta = std_theta(d_rope)
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=6)), g, h, d, M, r_kv, iters=40,
+                           keep=keep)
+    info = host(out["info"])
+    assert (info[:-2] >= 1).all() and info[-2] == 0 and info[-1] >= 1
+    tb = lambda t: t.to(torch.bfloat16).contiguous()
+    W_DKVR = tb(torch.cat([out["W_DKV"].T, out["W_KR"].T], dim=1))              # [D, 512 + 64]
+    pages_per_seq = 5
+    pool = torch.full((B * pages_per_seq + 1, 64, r_kv + d_rope), float("nan"), dtype=torch.bfloat16, device="cuda")
+    table = torch.from_numpy(rng(5).permutation(B * pages_per_seq).reshape(B, pages_per_seq).astype(np.int32) + 1).cuda()
+    for t in range(max(lens)):
+        x_t = np.stack([ctx[b][t] if t < lens[b] else np.zeros(D) for b in range(B)])
+        pos = torch.tensor([t if t < lens[b] else -1 for b in range(B)], dtype=torch.int32, device="cuda")
+        mla.cache_append(to_torch(synth.to_bf16_bits(x_t.astype(np.float32)), "bf16"), W_DKVR, pool, table, pos, r_kv)
+    q = np.stack([bf16((W_Q @ ctx[b][-1]).reshape(h, d)) for b in range(B)])     # queries as stored
+    W_QR = host(out["W_QR"])
+    q_rope = np.stack([[rope_hat(W_QR[i] @ q[b, i], lens[b] - 1, d_rope, theta) for i in range(h)] for b in range(B)])
+    as_bf16 = lambda a: to_torch(synth.to_bf16_bits(np.asarray(a, dtype=np.float32)), "bf16")
+    q_abs = mla.absorb_q(as_bf16(q), tb(out["W_UK"]))
+    ws = mla.decode_paged(q_abs, as_bf16(q_rope), pool, table, torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                          1.0 / np.sqrt(d), num_splits=4, flags=mla.FLAG_SKIP_MERGE)
+    _, got = mla.merge_out_proj(ws, tb(out["W_UV"]), B, 4)
+    got = widen_gpu(got)
+    ref = co.convert_layer(X, W_K, W_V, g, h, d, M, r_kv, keep)
+    want = np.stack([mla_attention_through_the_decode_oracle(ref, None, ctx[b], None, h, d, lens[b] - 1, theta, q=q[b])
+                     for b in range(B)])
+    assert np.isfinite(got).all()
+    assert max_abs_rel(got, want) <= 2e-2, max_abs_rel(got, want)
