@@ -77,7 +77,10 @@ def parse():
                     help="secondary row: the offline GQA->MLA conversion of one LLaMA-2-7B-shaped layer (fp64) "
                          "instead of the decode step")
     ap.add_argument("--convert-iters", type=int, default=20, help="block power iterations of the joint basis")
-    ap.add_argument("--freqfold", type=int, default=1, help="FreqFold group size M of the conversion")
+    ap.add_argument("--freqfold", type=int, default=2, help="FreqFold group size M of the conversion")
+    ap.add_argument("--convert-keep", type=int, default=1,
+                    help="components per FreqFold group that stay under RoPE: the RoPE key is keep * 128 / M wide "
+                         "(default M = 2, keep = 1: 64, the decode path's 512 + 64 row)")
     ap.add_argument("--convert-block", type=int, default=768,
                     help="block width p of the power iteration (>= r_kv = 512; 768 with 20 iterations reaches a smaller "
                          "residual than 576 with 60 in 70 %% of the time on the synthetic spectrum)")
@@ -447,8 +450,9 @@ def convert_main(args):
 
     g = h = 32
     d, D, n, r_kv, p = 128, 4096, 4096, 512, args.convert_block
-    M, iters = args.freqfold, args.convert_iters
-    mj = (2 * g - 1) * d
+    M, keep, iters = args.freqfold, args.convert_keep, args.convert_iters
+    d_rope = keep * (d // M)
+    mj = 2 * g * d - d_rope
     if args.convert_products_only:
         gen = torch.Generator(device="cuda:0").manual_seed(0)
         C = torch.randn((n, mj), dtype=torch.float64, device="cuda:0", generator=gen)
@@ -478,10 +482,10 @@ def convert_main(args):
     Q0 = synth.start_block(mj, p, seed=0)
     dev = lambda a: torch.from_numpy(a).to("cuda:0")
     Xd, Kd, Vd, Qd = dev(X), dev(W_K), dev(W_V), dev(Q0)
-    ws = torch.empty(cv.lib().mla_convert_layer_workspace_bytes(n, D, g, h, d, M, r_kv, p), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(cv.lib().mla_convert_layer_workspace_bytes(n, D, g, h, d, M, keep, r_kv, p), dtype=torch.uint8, device="cuda:0")
 
     def step():
-        return cv.convert_layer(Xd, Kd, Vd, Qd, g, h, d, M, r_kv, iters, workspace=ws)
+        return cv.convert_layer(Xd, Kd, Vd, Qd, g, h, d, M, r_kv, iters, workspace=ws, keep=keep)
     steps, warmup = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
     for _ in range(warmup):
         out = step()
@@ -497,8 +501,8 @@ def convert_main(args):
     # what was computed: orthonormal basis, and how far the r_kv Ritz pairs are from eigenpairs of the
     # moment matrix rebuilt here from the library's own step calls (S R - R diag(evals), column norms)
     U = out["U"]
-    W_rot = cv.rotate_rows(Kd, U, g, d, M)
-    K_nope, V = cv.project(Xd, W_rot[d:].contiguous()), cv.project(Xd, Vd)
+    W_rot = cv.rotate_rows(Kd, U, g, d, M, keep)
+    K_nope, V = cv.project(Xd, W_rot[d_rope:].contiguous()), cv.project(Xd, Vd)
     S, _ = cv.joint_moment(K_nope, V, out["alpha"])
     R, ev = out["R_KV"], out["evals_joint"][:r_kv]
     Rp = torch.zeros((mj, p), dtype=torch.float64, device="cuda:0")
@@ -525,21 +529,23 @@ def convert_main(args):
     tflops = flop / (launch_ms * 1e-3) / 1e12
     # algorithmic flop of the chain: activations, moments, iterations (S Q, Gram, Q = Y L^-T), projections
     gd = g * d
-    chain_flop = (2.0 * n * D * gd + 2.0 * n * D * (gd - d) + 2.0 * n * D * gd + 2.0 * mj * mj * n
+    chain_flop = (2.0 * n * D * gd + 2.0 * n * D * (gd - d_rope) + 2.0 * n * D * gd + 2.0 * mj * mj * n
                   + (iters + 1) * flop + (iters + 4) * 2 * (2.0 * mj * p * p)
-                  + 2.0 * r_kv * D * mj + 2.0 * h * d * r_kv * (gd - d))
+                  + 2.0 * r_kv * D * mj + 2.0 * h * d * r_kv * (gd - d_rope))
     rec = {"metric": "GQA->MLA conversion of one LLaMA-2-7B-shaped layer, ms (fp64), 1 GPU",
            "value": round(ms, 2), "unit": "ms/layer", "n_gpus": 1, "steps": steps, "warmup": warmup,
            "ms_per_step": round(ms, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
            "dtype": "f64", "data": "synthetic",
-           "config": {"workload": f"one layer g=h={g} d={d} D={D}, {n} synthetic calibration tokens, FreqFold M={M}, "
-                                  f"r_kv={r_kv}, block width {p}, {iters} block power iterations",
-                      "g": g, "h": h, "d": d, "D": D, "n": n, "M": M, "r_kv": r_kv, "p": p, "iters": iters},
+           "config": {"workload": f"one layer g=h={g} d={d} D={D}, {n} synthetic calibration tokens, FreqFold M={M} with "
+                                  f"{keep} RoPE pair(s) per group (RoPE key {d_rope} wide), r_kv={r_kv}, block width {p}, "
+                                  f"{iters} block power iterations",
+                      "g": g, "h": h, "d": d, "D": D, "n": n, "M": M, "keep": keep, "d_rope": d_rope, "r_kv": r_kv,
+                      "p": p, "iters": iters},
            "chain_TFLOPs": round(chain_flop / (ms * 1e-3) / 1e12, 2),
            "checks": {"ritz_residual_over_lambda1": resid, "orthonormality": orth,
                       "captured_second_moment": round(captured, 6), "alpha": out["alpha"].item(),
                       "rope_basis_sweeps_max": int(info[:-2].max()), "ritz_sweeps": int(info[-1])},
-           "roofline": {"bound": "mfma", "kernel": f"gemm_f64_kernel<true, false> (S Q, 8064 x 8064 x {p}, K range in slices) "
+           "roofline": {"bound": "mfma", "kernel": f"gemm_f64_kernel<true, false> (S Q, {mj} x {mj} x {p}, K range in slices) "
                                                    "+ gemm_f64_reduce_kernel",
                         "achieved": round(tflops, 2), "peak": 78.6, "unit": "TFLOP/s", "frac": round(tflops / 78.6, 4),
                         "traffic": None, "algorithmic_flop_per_launch": flop, "launch_us": round(launch_ms * 1e3, 1),
@@ -553,14 +559,14 @@ def convert_main(args):
         D2, n2, r2, p2 = 2048, 4096, 256, 384
         X2, K2, V2 = synth.calibration(n2, D2, g2, d, seed=1)
         t0 = time.perf_counter()
-        ref = co.convert_layer(X2, K2, V2, g2, h2, d, M, r2)
+        ref = co.convert_layer(X2, K2, V2, g2, h2, d, M, r2, keep)
         cpu_s = time.perf_counter() - t0
-        Q2 = dev(synth.start_block((2 * g2 - 1) * d, p2, seed=1))
+        Q2 = dev(synth.start_block(2 * g2 * d - d_rope, p2, seed=1))
         a2 = [dev(a) for a in (X2, K2, V2)]
-        cv.convert_layer(*a2, Q2, g2, h2, d, M, r2, iters)
+        cv.convert_layer(*a2, Q2, g2, h2, d, M, r2, iters, keep=keep)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        got = cv.convert_layer(*a2, Q2, g2, h2, d, M, r2, iters)
+        got = cv.convert_layer(*a2, Q2, g2, h2, d, M, r2, iters, keep=keep)
         torch.cuda.synchronize()
         gpu_s = time.perf_counter() - t0
         ev_err = float(np.abs(got["evals_joint"][:r2].cpu().numpy() - ref["evals_joint"][:r2]).max() / ref["evals_joint"][0])

@@ -301,46 +301,55 @@ def test_gpu_converted_layer_decodes_like_the_oracles_converted_layer(cv, M, kee
 # ------------------------------------------------------------------ the benchmark shape, by properties
 
 def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
-    """One layer at the shape bench.py times (g = h = 32, d = 128, D = 4096, 4096 tokens, r_kv = 512,
-    block 768, 20 iterations).  The oracle's eigensolver would take minutes here, so the GPU result is
+    """One layer at the shape bench.py times (g = h = 32, d = 128, D = 4096, 4096 tokens, 2-fold FreqFold
+    with one RoPE pair per group, r_kv = 512 -- the 512 + 64 row of the decode path --, block 768,
+    20 iterations).  The oracle's eigensolver would take minutes here, so the GPU result is
     checked against what must hold at any size, with the moments recomputed in numpy:
-    orthogonal bases that diagonalise the per-group moments, Eq. "rorope" on sampled scores,
-    alpha, an orthonormal R_KV whose columns are eigenpairs of the numpy moment matrix to the
-    iteration's accuracy, Ritz values above every Rayleigh quotient of random directions, and
-    the App. D.2 products."""
-    from test_convert_oracle_pins import rope_hat, std_theta
+    orthogonal bases that diagonalise the per-group moments, Eq. "rorope" on sampled scores (with the
+    group's frequency on all its components, FreqFold's premise), alpha, an orthonormal R_KV whose
+    columns are eigenpairs of the numpy moment matrix to the iteration's accuracy, Ritz values above
+    every Rayleigh quotient of random directions, and the App. D.2 products."""
+    from test_convert_oracle_pins import rope_by_component, rope_hat, std_theta
     g = h = 32
-    d, D, n, M, r_kv, p, iters = 128, 4096, 4096, 1, 512, 768, 20
-    mj = (2 * g - 1) * d
+    d, D, n, M, keep, r_kv, p, iters = 128, 4096, 4096, 2, 1, 512, 768, 20
+    d_rope = co.rope_width(d, M, keep)
+    a_nope = g * d - d_rope
+    mj = a_nope + g * d
     X, W_K, W_V = synth.calibration(n, D, g, d, seed=0)
-    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=0)), g, h, d, M, r_kv, iters)
+    out = cv.convert_layer(dev(X), dev(W_K), dev(W_V), dev(synth.start_block(mj, p, seed=0)), g, h, d, M, r_kv, iters,
+                           keep=keep)
     got = {k: host(v) for k, v in out.items()}
+    assert got["W_KR"].shape == (64, D) and got["W_DKV"].shape == (512, D)
     assert (got["info"][:-2] >= 1).all() and got["info"][-2] == 0 and got["info"][-1] >= 1
     U, ev = got["U"], got["evals_rope"]
     # App. B: orthogonal, descending, and diagonalising the moments of the numpy activations
     K = X @ W_K.T
-    for G in (0, 17, 63):
-        assert np.abs(U[G].T @ U[G] - np.eye(g)).max() < 1e-12
+    sigma = co.rope_moments(K, g, d, M)
+    for G in (0, 17, 31):
+        assert np.abs(U[G].T @ U[G] - np.eye(M * g)).max() < 1e-12
         assert (np.diff(ev[G]) <= 0).all()
-        sig = co.rope_moments(K[:, [j * d + 2 * G + c for j in range(g) for c in (0, 1)]], g, 2, 1)[0]
-        assert np.abs(U[G].T @ sig @ U[G] - np.diag(ev[G])).max() < 1e-10 * ev[G][0]
-    # Eq. "rorope": sampled scores of the rotated merged query / key equal the unrotated ones
+        assert np.abs(U[G].T @ sigma[G] @ U[G] - np.diag(ev[G])).max() < 1e-10 * ev[G][0]
+    # Eq. "rorope" under FreqFold's premise: sampled scores of the rotated merged query / key equal the unrotated ones
     r = rng(3)
     theta = std_theta(d)
-    W_K_rot = co.rotate_rows(W_K, U, g, d, M)
-    assert rel(got["W_KR"], W_K_rot[:d]) < 1e-12
+    theta_folded = np.repeat(theta[::M], M)
+    folded = lambda G, rr: theta[G * M]
+    W_K_rot = co.rotate_rows(W_K, U, g, d, M, keep)
+    assert rel(got["W_KR"], W_K_rot[:d_rope]) < 1e-12
     for trial in range(3):
         x_k, q_hat = X[r.integers(n)], r.standard_normal(g * d)
-        q_rot = co.rotate_rows(q_hat[:, None], U, g, d, M)[:, 0]
+        q_rot = co.rotate_rows(q_hat[:, None], U, g, d, M, keep)[:, 0]
         t, j = int(r.integers(4096)), int(r.integers(4096))
-        want = rope_hat(q_hat, t, d, theta) @ rope_hat(W_K @ x_k, j, d, theta)
-        assert abs(rope_hat(q_rot, t, d, theta) @ rope_hat(W_K_rot @ x_k, j, d, theta) - want) < 1e-9 * (1 + abs(want))
+        want = rope_hat(q_hat, t, d, theta_folded) @ rope_hat(W_K @ x_k, j, d, theta_folded)
+        have = rope_by_component(q_rot, t, g, d, M, keep, folded) @ rope_by_component(W_K_rot @ x_k, j, g, d, M, keep, folded)
+        assert abs(have - want) < 1e-9 * (1 + abs(want))
     # Sec. 4.3 and App. D.2 against numpy moments
-    K_nope, V = X @ W_K_rot[d:].T, X @ W_V.T
+    K_nope, V = X @ W_K_rot[d_rope:].T, X @ W_V.T
     alpha = co.kv_balance(K_nope, V)
     assert abs(got["alpha"][0] - alpha) < 1e-11 * alpha
     S = co.joint_moment(K_nope, V, alpha)
     R, lam = got["R_KV"], got["evals_joint"]
+    assert R.shape == (mj, r_kv)
     assert np.abs(R.T @ R - np.eye(r_kv)).max() < 1e-11
     assert (np.diff(lam) <= 0).all()
     resid = np.linalg.norm(S @ R - R * lam[:r_kv], axis=0).max() / lam[0]
@@ -349,15 +358,15 @@ def test_convert_layer_at_the_llama2_7b_layer_shape_by_properties(cv):
     Qr, _ = np.linalg.qr(r.standard_normal((mj, 8)))
     assert (np.einsum("ij,ij->j", Qr, S @ Qr) <= lam[0] * (1 + 1e-9)).all()
     # the products of App. D.2 from the GPU's own R_KV (exact identities, whatever the basis)
-    W_cat = np.concatenate([W_K_rot[d:] / alpha, W_V])
+    W_cat = np.concatenate([W_K_rot[d_rope:] / alpha, W_V])
     assert rel(got["W_DKV"], R.T @ W_cat) < 1e-11
     i = 5
     E_i = np.zeros((g * d, d))
     E_i[i * d:(i + 1) * d] = np.eye(d)                # (W^UK_i)^T for h = g
-    E_rot = co.rotate_rows(E_i, U, g, d, M)
-    assert rel(got["W_UK"][i], alpha * E_rot[d:].T @ R[:(g - 1) * d]) < 1e-11
-    assert rel(got["W_QR"][i], E_rot[:d]) < 1e-12
-    assert rel(got["W_UV"][i], R[(g - 1) * d + i * d:(g - 1) * d + (i + 1) * d].T) == 0.0
+    E_rot = co.rotate_rows(E_i, U, g, d, M, keep)
+    assert rel(got["W_UK"][i], alpha * E_rot[d_rope:].T @ R[:a_nope]) < 1e-11
+    assert rel(got["W_QR"][i], E_rot[:d_rope]) < 1e-12
+    assert rel(got["W_UV"][i], R[a_nope + i * d:a_nope + (i + 1) * d].T) == 0.0
 
 
 def test_whole_pipeline_on_the_gpu_conversion_append_decode(cv):
