@@ -2,10 +2,11 @@
 //   absorb   : q_abs[b,h,:] = q_nope[b,h,:] . W_UK[h]     (K = d_head, N = d_c)
 //   out-proj : out[b,h,:]   = o_lat[b,h,:]  . W_UV[h]     (K = d_c,    N = d_head)
 // Both are Y[b,h,n] = sum_k X[b,h,k] W[h,k,n]: H independent skinny GEMMs whose
-// cost is reading W once.  A workgroup owns 64 output columns of one head for
-// up to 16 batch rows; its four wavefronts split k, each lane streaming one
-// column of W (coalesced along n) against the batch rows held in LDS, and the
-// four partial sums are reduced through LDS.
+// cost is reading W once.  A workgroup owns NT (64, 32 or 16) output columns of one head
+// for up to 16 batch rows; its four wavefronts split k, and inside a wavefront 64 / NT lane
+// groups split it further, each lane streaming one column of W (coalesced along n) against
+// the batch rows held in LDS; the partial sums are reduced through LDS.  The narrower tiles
+// give a small problem (one batch row, 128 output columns) a workgroup per CU.
 #include "mla_internal.h"
 
 namespace mla {
@@ -13,7 +14,7 @@ namespace {
 
 constexpr int HG_THREADS = 256;
 constexpr int HG_BT = 16;     // batch rows per workgroup
-constexpr int HG_NT = 64;     // output columns per workgroup
+constexpr int HG_NT = 64;     // widest tile of output columns per workgroup
 constexpr int HG_KC = 512;    // k staged in LDS per pass
 
 template <bool BF16>
@@ -23,18 +24,21 @@ __device__ __forceinline__ float ld(const void* p, size_t i)
     return static_cast<const float*>(p)[i];
 }
 
-template <bool BF16, bool Y_F32>
+template <bool BF16, bool Y_F32, int NT>
 __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, const void* W, void* Y,
                                                                 int B, int H, int K, int N)
 {
+    constexpr int KS = 64 / NT;          // k slices inside a wavefront
+    constexpr int NSL = 4 * KS;          // k slices in all
     // batch rows of one k adjacent: a 128-bit LDS read fetches four of them (an LDS instruction
     // costs the wavefront ~17 cycles of issue whatever its width), and groups of four rows past
     // the batch are not read at all
     __shared__ __attribute__((aligned(16))) float x_t[HG_KC][HG_BT];
-    __shared__ float red_s[4][HG_BT][HG_NT];
+    __shared__ float red_s[NSL][HG_BT][NT];
 
-    const int tid = threadIdx.x, lane = tid & 63, kg = tid >> 6;
-    const int n = blockIdx.x * HG_NT + lane;
+    const int tid = threadIdx.x, lane = tid & 63, col = lane % NT;
+    const int kg = (tid >> 6) * KS + lane / NT;      // this lane's k slice
+    const int n = blockIdx.x * NT + col;
     const int h = blockIdx.y;
     const int b0 = blockIdx.z * HG_BT;
     const int nb = min(HG_BT, B - b0);
@@ -53,7 +57,7 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
         }
         __syncthreads();
         if (n < N) {
-            const int per = (kc + 3) / 4;
+            const int per = (kc + NSL - 1) / NSL;
             const int kb = kg * per, ke = min(kc, kb + per);
             auto step = [&](int k, float w) {
 #pragma unroll
@@ -81,14 +85,17 @@ __global__ __launch_bounds__(HG_THREADS) void head_gemm_kernel(const void* X, co
         }
     }
 #pragma unroll
-    for (int i = 0; i < HG_BT; ++i) red_s[kg][i][lane] = acc[i];
+    for (int i = 0; i < HG_BT; ++i) red_s[kg][i][col] = acc[i];
     __syncthreads();
-    for (int idx = tid; idx < HG_BT * HG_NT; idx += HG_THREADS) {
-        int bb = idx / HG_NT, nn = idx % HG_NT;
-        int col = blockIdx.x * HG_NT + nn;
-        if (bb < nb && col < N) {
-            float v = (red_s[0][bb][nn] + red_s[1][bb][nn]) + (red_s[2][bb][nn] + red_s[3][bb][nn]);
-            size_t o = ((size_t)(b0 + bb) * H + h) * N + col;
+    for (int idx = tid; idx < HG_BT * NT; idx += HG_THREADS) {
+        int bb = idx / NT, nn = idx % NT;
+        int oc = blockIdx.x * NT + nn;
+        if (bb < nb && oc < N) {
+            float v = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < NSL; sl += 4)      // slices of one wavefront group first, as the 64-column tile always did
+                v += (red_s[sl][bb][nn] + red_s[sl + 1][bb][nn]) + (red_s[sl + 2][bb][nn] + red_s[sl + 3][bb][nn]);
+            size_t o = ((size_t)(b0 + bb) * H + h) * N + oc;
             if (BF16 && !Y_F32) static_cast<uint16_t*>(Y)[o] = (uint16_t)f32_to_bf16_bits(v);
             else                static_cast<float*>(Y)[o] = v;
         }
@@ -212,10 +219,21 @@ hipError_t launch_head_gemm(const void* X, const void* W, void* Y, int B, int H,
         if (try_launch_mfma<32>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
         if (try_launch_mfma<64>(X, W, Y, B, H, K, N, y_f32, s, &err)) return err;
     }
-    dim3 grid((N + HG_NT - 1) / HG_NT, H, (B + HG_BT - 1) / HG_BT), block(HG_THREADS);
-    if (io == MLA_BF16 && y_f32) head_gemm_kernel<true, true><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
-    else if (io == MLA_BF16)     head_gemm_kernel<true, false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
-    else                         head_gemm_kernel<false, false><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N);
+    // widest column tile that still gives the chip a workgroup per CU
+    const long per_col_tile = (long)H * ((B + HG_BT - 1) / HG_BT);
+    int nt = HG_NT;
+    while (nt > 16 && (long)((N + nt - 1) / nt) * per_col_tile < 256) nt /= 2;
+    dim3 grid((N + nt - 1) / nt, H, (B + HG_BT - 1) / HG_BT), block(HG_THREADS);
+#define MLA_HEAD_GEMM(NT_)                                                                                          \
+    do {                                                                                                            \
+        if (io == MLA_BF16 && y_f32) head_gemm_kernel<true, true, NT_><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N); \
+        else if (io == MLA_BF16)     head_gemm_kernel<true, false, NT_><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N); \
+        else                         head_gemm_kernel<false, false, NT_><<<grid, block, 0, s>>>(X, W, Y, B, H, K, N); \
+    } while (0)
+    if (nt == 64) MLA_HEAD_GEMM(64);
+    else if (nt == 32) MLA_HEAD_GEMM(32);
+    else MLA_HEAD_GEMM(16);
+#undef MLA_HEAD_GEMM
     return hipGetLastError();
 }
 
