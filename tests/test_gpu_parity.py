@@ -85,7 +85,8 @@ def test_gather_bit_exact(mla, name, shrink):
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,H,d_head,d_c", [(1, 32, 128, 512), (16, 32, 128, 512), (37, 28, 128, 256),
-                                            (3, 5, 24, 40), (130, 4, 128, 512)])
+                                            (3, 5, 24, 40), (130, 4, 128, 512), (128, 28, 128, 256),
+                                            (64, 32, 128, 512)])
 def test_absorb_and_out_proj(mla, io, B, H, d_head, d_c):
     import torch
     r = synth.stream(7, B * 1000 + H)
@@ -478,22 +479,94 @@ def test_step_C2_full_three_calls(mla):
     assert max_abs_rel(widen_gpu(out2), chain["out"]) <= 2e-2
 
 
-def test_decode_C4_full_sampled(mla):
+def check_bench_step(mla, w, num_splits, flags=0):
+    """The call sequence the benchmark times -- mla_absorb_q, mla_decode_paged with the partials left
+    in the workspace (plus `flags`), mla_merge_out_proj -- at full size, every sequence and head
+    against the oracle: q_abs, o_lat and lse from the stored q_abs, out from the stored o_lat, and
+    out against the un-rounded fp64 chain.  Also the plain mla_decode_paged call (decode + merge)."""
+    import torch
+    d = DeviceWorkload(w)
+    q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+    ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                          num_splits=num_splits, kv_scale=d.kv_scale, flags=mla.FLAG_SKIP_MERGE | flags)
+    o_lat, out, lse = mla.merge_out_proj(ws, d.W_UV, w.B, num_splits, return_lse=True, flags=flags)
+    o_call, lse_call = run_decode(mla, d, q_abs, num_splits, flags)
+    torch.cuda.synchronize()
+    assert max_abs_rel(widen_gpu(q_abs), oracle.absorb_q(w.q_nope, w.W_UK)) <= 2e-2
+    ref_o, ref_lse = oracle_decode(w, q_abs_storage(q_abs))
+    for o_x, lse_x in ((o_lat, lse), (o_call, lse_call)):
+        got = widen_gpu(o_x)
+        assert np.isfinite(got).all()
+        assert max_abs_rel(got, ref_o) <= 2e-2
+        # per sequence as well: a short sequence must not hide behind the batch's largest value
+        for b in range(w.B):
+            assert max_abs_rel(got[b], ref_o[b]) <= 2e-2, f"sequence {b} (length {int(w.seq_lens[b])})"
+        assert lse_err(widen_gpu(lse_x), ref_lse) <= 2e-2
+    assert storage_bits(o_call).tobytes() == storage_bits(o_lat).tobytes()
+    ref_out = oracle.out_proj(storage_bits(o_lat), w.W_UV)
+    assert max_abs_rel(widen_gpu(out), ref_out) <= 2e-2
+    chain = oracle.mla_step(w.q_nope, w.q_rope, w.W_UK, w.W_UV, w.pool, w.kv_scale, w.page_table,
+                            w.seq_lens, w.softmax_scale)
+    got_out = widen_gpu(out)
+    assert np.isfinite(got_out).all()
+    assert max_abs_rel(got_out, chain["out"]) <= 2e-2
+    for b in range(w.B):
+        assert max_abs_rel(got_out[b], chain["out"][b]) <= 2e-2, f"sequence {b} (length {int(w.seq_lens[b])})"
+
+
+def test_step_C4_full_bench_sequence(mla):
+    """Batch 128 x 4096 tokens, 28 heads, d_c 256, 2 chunks: all 128 sequences."""
     w = synth.config("C4")
-    check_decode(mla, w, w.num_splits, b_sel=[0, 1, 63, 64, 127])
+    check_bench_step(mla, w, w.num_splits)
 
 
-def test_decode_C3_full_sampled(mla):
+def test_step_C3_full_bench_sequence(mla):
+    """64 sequences of 1024 .. 32768 tokens, balanced partition with 4 workgroups per sequence (the
+    benchmark's launch) and the uniform partition with the configuration's 16 chunks: all sequences."""
     w = synth.config("C3")
-    order = np.argsort(w.seq_lens)
-    b_sel = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, w.B - 1})
-    check_decode(mla, w, w.num_splits, b_sel=b_sel)
+    check_bench_step(mla, w, 4, flags=BAL)
+    check_bench_step(mla, w, w.num_splits)
 
 
-def test_decode_C5_full_sampled(mla):
-    """fp8 cache, 131072-token context, 32 chunks; one of the four sequences checked."""
+def test_step_C5_full_bench_sequence(mla):
+    """fp8 cache, 4 sequences of 131072 tokens, 32 chunks: all four sequences."""
     w = synth.config("C5")
-    check_decode(mla, w, w.num_splits, b_sel=[2])
+    check_bench_step(mla, w, w.num_splits)
+
+
+@pytest.mark.parametrize("B,H,d_c,S,flags", [(128, 28, 256, 2, 0),      # the wide-batch shape: 16 batch rows per workgroup
+                                             (137, 28, 256, 3, 0),      # last row group partly filled
+                                             (130, 32, 512, 2, 0),      # 8 batch rows per workgroup, last group of 2
+                                             (64, 32, 512, 4, 4),       # balanced partition, 64 sequences
+                                             (70, 32, 512, 2, 4)])      # balanced, two scan blocks
+def test_fused_tail_wide_batches(mla, B, H, d_c, S, flags):
+    """mla_merge_out_proj on batches wide enough that a workgroup takes 8 or 16 batch rows (several
+    tasks per wavefront): o_lat / lse bit for bit those of mla_merge_partials, out against the
+    oracle's projection of the stored o_lat and against mla_out_proj."""
+    import torch
+    lens = [int(x) for x in (np.arange(B) * 37 % 190 + 1)]
+    lens[3], lens[B - 1] = 0, 64
+    w = synth.make_workload("wide-tail", B=B, H=H, d_head=128, d_c=d_c, d_rope=64, seq_lens=lens,
+                            io_dtype="bf16", cache_dtype="bf16", placement="random", free_frac=0.1, seed=B + d_c)
+    d = DeviceWorkload(w)
+    q_abs = mla.absorb_q(d.q_nope, d.W_UK)
+    ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                          num_splits=S, flags=mla.FLAG_SKIP_MERGE | flags)
+    o1, l1 = mla.merge_partials(ws, B, H, d_c, S, q_abs.dtype, return_lse=True, flags=flags)
+    out1 = mla.out_proj(o1, d.W_UV)
+    o2, out2, l2 = mla.merge_out_proj(ws, d.W_UV, B, S, return_lse=True, flags=flags)
+    torch.cuda.synchronize()
+    assert storage_bits(o1).tobytes() == storage_bits(o2).tobytes()
+    assert storage_bits(l1).tobytes() == storage_bits(l2).tobytes()
+    ref_o, ref_lse = oracle_decode(w, q_abs_storage(q_abs))
+    assert max_abs_rel(widen_gpu(o2), ref_o) <= 2e-2
+    assert lse_err(widen_gpu(l2), ref_lse) <= 2e-2
+    ref = oracle.out_proj(storage_bits(o2), w.W_UV)
+    got = widen_gpu(out2)
+    assert max_abs_rel(got, ref) <= 2e-2
+    for b in range(B):
+        assert max_abs_rel(got[b], ref[b]) <= 2e-2, f"batch row {b}"
+    assert max_abs_rel(got, widen_gpu(out1)) <= 1e-2
 
 
 # ------------------------------------------------------------ cache append
