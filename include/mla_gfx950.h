@@ -20,7 +20,11 @@
  * General conventions
  *  - Every pointer is a DEVICE pointer unless the comment says "host".
  *    The caller owns every buffer, including the workspace; the library
- *    allocates no device memory and keeps no state between calls.
+ *    allocates no device memory.  It keeps no state between calls that a
+ *    result depends on; what it does keep per process is bookkeeping: which
+ *    kernels have had their dynamic-LDS limit raised (conversion kernels),
+ *    and, per device, the address of the static scratch array of
+ *    mla_decode_paged_static.
  *  - Tensors are dense, row-major, innermost index last, and 16-byte aligned.
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *    All work is enqueued on it and the call returns without waiting.
@@ -52,7 +56,9 @@ typedef enum {
     MLA_ERR_SHAPE       = -2,  /* a size is <= 0 or inconsistent               */
     MLA_ERR_UNSUPPORTED = -3,  /* shape / dtype combination not implemented    */
     MLA_ERR_WORKSPACE   = -4,  /* workspace missing or too small               */
-    MLA_ERR_HIP         = -6   /* a HIP runtime call (launch) failed           */
+    MLA_ERR_HIP         = -6,  /* a HIP runtime call (launch) failed           */
+    MLA_ERR_SCRATCH_LIMIT = -7 /* mla_decode_paged_static: the sizes need more
+                                  scratch than the library's static array holds */
 } mla_status;
 
 /* Flags for mla_decode_paged. */
@@ -173,6 +179,41 @@ int mla_decode_paged(const void* q_abs, const void* q_rope,
                      int num_pages, int max_pages_per_seq, int num_splits,
                      float softmax_scale, mla_dtype io_dtype,
                      mla_dtype cache_dtype, unsigned flags, void* hip_stream);
+
+/*
+ * mla_decode_paged for callers that cannot allocate and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels as mla_decode_paged,
+ * without `workspace` / `workspace_bytes`: the split-KV partial results live
+ * in a device array that is part of the library's code object
+ * (mla_static_scratch_bytes() = 32 MiB; every GPU the library runs on holds its
+ * own copy until the process ends).  The call allocates and frees nothing.
+ *
+ *  - Sizes for which mla_decode_workspace_bytes(B, H, d_c, num_splits) exceeds
+ *    mla_static_scratch_bytes() are rejected with MLA_ERR_SCRATCH_LIMIT before
+ *    anything is launched (the headline shape B 16, H 32, d_c 512, 16 chunks
+ *    needs 17.9 MB).
+ *  - MLA_FLAG_SKIP_MERGE is rejected (MLA_ERR_UNSUPPORTED): the partials would
+ *    stay in an array the caller cannot name.  The other flags work as usual.
+ *  - The device that owns the buffers and the stream must be the current
+ *    device of the calling thread.  On its first call on a device the library
+ *    looks up that device's address of the array (hipGetSymbolAddress; no
+ *    allocation) and keeps it.
+ *  - All calls on one GPU share that GPU's array, which keeps the previous
+ *    call's contents; nothing in it needs clearing (every partial that is read
+ *    has been written by the same call, or is discarded by a select).  Calls
+ *    that overlap on one GPU (different streams, or several host threads) race
+ *    on it: serialise them, or use mla_decode_paged with separate workspaces.
+ */
+size_t mla_static_scratch_bytes(void);
+int mla_decode_paged_static(const void* q_abs, const void* q_rope,
+                            const void* kv_cache, const float* kv_scale,
+                            const int32_t* page_table, const int32_t* seq_lens,
+                            void* o_lat, float* lse,
+                            int B, int H, int d_c, int d_rope, int page_size,
+                            int num_pages, int max_pages_per_seq, int num_splits,
+                            float softmax_scale, mla_dtype io_dtype,
+                            mla_dtype cache_dtype, unsigned flags, void* hip_stream);
 
 /*
  * mla_decode_paged for q_len query tokens per sequence in one pass over the

@@ -3,6 +3,8 @@
 // exercised on a machine without a GPU.
 #include "mla_internal.h"
 
+#include <mutex>
+
 using namespace mla;
 
 namespace {
@@ -49,7 +51,118 @@ void fill_merge_params(MergeParams& m, const void* workspace, int B, int H, int 
     m.B = B; m.H = H; m.d_c = d_c; m.num_splits = eff_splits;
 }
 
+// Arguments of one decode call (mla_decode_paged_multi's, without the workspace).
+struct DecodeCall {
+    const void* q_abs; const void* q_rope; const void* kv_cache; const float* kv_scale;
+    const int32_t* page_table; const int32_t* seq_lens; void* o_lat; float* lse;
+    int B, q_len, heads, d_c, d_rope, page_size, num_pages, max_pages_per_seq, num_splits;
+    float softmax_scale;
+    mla_dtype io_dtype, cache_dtype;
+    unsigned flags;
+    void* hip_stream;
+};
+
+// whether the call runs on the matrix-core kernels
+bool uses_mfma(const DecodeCall& c)
+{
+    DecodeParams p = {};
+    p.B = c.B; p.H = c.q_len * c.heads; p.d_c = c.d_c; p.d_rope = c.d_rope; p.page_size = c.page_size;
+    p.num_splits = effective_splits(c.B, c.num_splits);
+    return !(c.flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, c.io_dtype, c.cache_dtype);
+}
+
+// host-side validation of everything but the workspace; touches no HIP call
+int decode_validate(const DecodeCall& c)
+{
+    const bool skip_merge = (c.flags & MLA_FLAG_SKIP_MERGE) != 0;
+    if (!c.q_abs || !c.kv_cache || !c.page_table || !c.seq_lens || (!c.o_lat && !skip_merge)) return MLA_ERR_NULL;
+    if (c.d_rope > 0 && !c.q_rope) return MLA_ERR_NULL;
+    if (c.B <= 0 || c.q_len <= 0 || c.heads <= 0 || c.d_c <= 0 || c.d_rope < 0 || c.page_size <= 0 ||
+        c.num_pages <= 0 || c.max_pages_per_seq <= 0 || c.num_splits <= 0)
+        return MLA_ERR_SHAPE;
+    if ((long long)c.max_pages_per_seq * c.page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
+    if (!(c.softmax_scale == c.softmax_scale)) return MLA_ERR_SHAPE;
+    if ((long long)c.q_len * c.heads > 1024) return MLA_ERR_UNSUPPORTED;
+    if (!io_ok(c.io_dtype)) return MLA_ERR_UNSUPPORTED;
+    if (c.cache_dtype != MLA_F32 && c.cache_dtype != MLA_BF16 && c.cache_dtype != MLA_FP8_E4M3)
+        return MLA_ERR_UNSUPPORTED;
+    if (c.cache_dtype == MLA_F32 && c.io_dtype != MLA_F32) return MLA_ERR_UNSUPPORTED;
+    if (c.cache_dtype == MLA_FP8_E4M3 && !c.kv_scale) return MLA_ERR_NULL;
+    if (c.cache_dtype != MLA_FP8_E4M3 && c.kv_scale) return MLA_ERR_SHAPE;
+    if (c.d_c > 512 || c.d_c % 8 || c.d_rope > 64 || c.d_rope % 8) return MLA_ERR_UNSUPPORTED;
+    if (c.B > 65535 || c.num_splits > 16383) return MLA_ERR_UNSUPPORTED;
+    if (c.flags & MLA_FLAG_BALANCED) {
+        // only the matrix-core kernel has this partition; grid size; page counts are summed in 32 bits
+        if (!uses_mfma(c)) return MLA_ERR_UNSUPPORTED;
+        const int S = effective_splits(c.B, c.num_splits);
+        if ((long long)c.B * S > 0x3FFFFF || (long long)c.B * c.max_pages_per_seq > 0x7FFFFFFFLL)
+            return MLA_ERR_UNSUPPORTED;
+    }
+    return MLA_OK;
+}
+
+// launches of a validated call; `workspace` is large enough and 256-byte aligned
+int decode_launch(const DecodeCall& c, void* workspace)
+{
+    const bool skip_merge = (c.flags & MLA_FLAG_SKIP_MERGE) != 0;
+    const int B = c.B, H = c.q_len * c.heads;   // query rows per sequence
+    hipStream_t stream = static_cast<hipStream_t>(c.hip_stream);
+    DecodeParams p;
+    p.q_abs = c.q_abs; p.q_rope = c.q_rope; p.kv = c.kv_cache; p.kv_scale = c.kv_scale;
+    p.page_table = c.page_table; p.seq_lens = c.seq_lens;
+    p.o_part = static_cast<float*>(workspace);
+    const int S = effective_splits(B, c.num_splits);
+    const WsLayout wl = ws_layout(B, H, c.d_c, S);
+    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.lse_off);
+    p.plan = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + wl.plan_off);
+    p.B = B; p.H = H; p.d_c = c.d_c; p.d_rope = c.d_rope; p.page_size = c.page_size;
+    p.num_pages = c.num_pages; p.max_pages = c.max_pages_per_seq; p.num_splits = S;
+    p.chunk_pages = (c.max_pages_per_seq + S - 1) / S;
+    p.q_len = c.q_len; p.heads = c.heads;
+    p.q_inner = 1; p.o_final = nullptr; p.lse_final = nullptr;
+    p.scale = c.softmax_scale;
+
+    const bool balanced = (c.flags & MLA_FLAG_BALANCED) != 0;
+    const bool mfma = uses_mfma(c);
+    hipError_t e;
+    if (mfma && !balanced && decode_mfma_wide_supported(p, c.io_dtype, c.cache_dtype))
+        e = launch_decode_mfma_wide(p, stream);
+    else if (mfma) e = launch_decode_mfma(p, c.cache_dtype, stream, balanced);
+    else      e = launch_decode_portable(p, c.io_dtype, c.cache_dtype, stream);
+    if (e != hipSuccess) return MLA_ERR_HIP;
+    if (skip_merge) return MLA_OK;
+
+    MergeParams m;
+    fill_merge_params(m, workspace, B, H, c.d_c, S, balanced);
+    m.o_lat = c.o_lat; m.lse = c.lse;
+    e = launch_merge(m, c.io_dtype, stream);
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
 }  // namespace
+
+// ---- scratch of mla_decode_paged_static: split-KV partials in a device array of the library's own.
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address that
+// goes into kernel arguments is looked up once per device, with that device current.
+static constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+static constexpr int MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static std::mutex scratch_mutex;
+static void* scratch_ptr[MAX_DEVICES];   // device address of `scratch` on device i (nullptr: not looked up yet)
+
+static void* static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
 
 extern "C" {
 
@@ -62,6 +175,9 @@ const char* mla_status_string(int status)
         case MLA_ERR_UNSUPPORTED: return "MLA_ERR_UNSUPPORTED: shape or dtype combination not implemented";
         case MLA_ERR_WORKSPACE:   return "MLA_ERR_WORKSPACE: workspace missing, misaligned or too small";
         case MLA_ERR_HIP:         return "MLA_ERR_HIP: a HIP runtime call failed";
+        case MLA_ERR_SCRATCH_LIMIT:
+            return "MLA_ERR_SCRATCH_LIMIT: the call needs more scratch than the library's static array holds "
+                   "(mla_static_scratch_bytes)";
         default:                  return "unknown mla status";
     }
 }
@@ -119,62 +235,35 @@ int mla_decode_paged_multi(const void* q_abs, const void* q_rope, const void* kv
                            int max_pages_per_seq, int num_splits, float softmax_scale,
                            mla_dtype io_dtype, mla_dtype cache_dtype, unsigned flags, void* hip_stream)
 {
-    const bool skip_merge = (flags & MLA_FLAG_SKIP_MERGE) != 0;
-    if (!q_abs || !kv_cache || !page_table || !seq_lens || (!o_lat && !skip_merge)) return MLA_ERR_NULL;
-    if (d_rope > 0 && !q_rope) return MLA_ERR_NULL;
-    if (B <= 0 || q_len <= 0 || heads <= 0 || d_c <= 0 || d_rope < 0 || page_size <= 0 || num_pages <= 0 ||
-        max_pages_per_seq <= 0 || num_splits <= 0)
-        return MLA_ERR_SHAPE;
-    if ((long long)max_pages_per_seq * page_size > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
-    if (!(softmax_scale == softmax_scale)) return MLA_ERR_SHAPE;
-    if ((long long)q_len * heads > 1024) return MLA_ERR_UNSUPPORTED;
-    const int H = q_len * heads;   // query rows per sequence
-    if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
-    if (cache_dtype != MLA_F32 && cache_dtype != MLA_BF16 && cache_dtype != MLA_FP8_E4M3)
-        return MLA_ERR_UNSUPPORTED;
-    if (cache_dtype == MLA_F32 && io_dtype != MLA_F32) return MLA_ERR_UNSUPPORTED;
-    if (cache_dtype == MLA_FP8_E4M3 && !kv_scale) return MLA_ERR_NULL;
-    if (cache_dtype != MLA_FP8_E4M3 && kv_scale) return MLA_ERR_SHAPE;
-    if (d_c > 512 || d_c % 8 || d_rope > 64 || d_rope % 8) return MLA_ERR_UNSUPPORTED;
-    if (B > 65535 || num_splits > 16383) return MLA_ERR_UNSUPPORTED;
-    const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
+    const DecodeCall c = {q_abs, q_rope, kv_cache, kv_scale, page_table, seq_lens, o_lat, lse, B, q_len, heads,
+                          d_c, d_rope, page_size, num_pages, max_pages_per_seq, num_splits, softmax_scale,
+                          io_dtype, cache_dtype, flags, hip_stream};
+    const int st = decode_validate(c);
+    if (st != MLA_OK) return st;
+    const size_t need = mla_decode_workspace_bytes(B, q_len * heads, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
+    return decode_launch(c, workspace);
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    DecodeParams p;
-    p.q_abs = q_abs; p.q_rope = q_rope; p.kv = kv_cache; p.kv_scale = kv_scale;
-    p.page_table = page_table; p.seq_lens = seq_lens;
-    p.o_part = static_cast<float*>(workspace);
-    const int S = effective_splits(B, num_splits);
-    const WsLayout wl = ws_layout(B, H, d_c, S);
-    p.lse_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.lse_off);
-    p.plan = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + wl.plan_off);
-    p.B = B; p.H = H; p.d_c = d_c; p.d_rope = d_rope; p.page_size = page_size;
-    p.num_pages = num_pages; p.max_pages = max_pages_per_seq; p.num_splits = S;
-    p.chunk_pages = (max_pages_per_seq + S - 1) / S;
-    p.q_len = q_len; p.heads = heads;
-    p.q_inner = 1; p.o_final = nullptr; p.lse_final = nullptr;
-    p.scale = softmax_scale;
+size_t mla_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
 
-    const bool balanced = (flags & MLA_FLAG_BALANCED) != 0;
-    const bool mfma = !(flags & MLA_FLAG_PORTABLE_KERNEL) && decode_mfma_supported(p, io_dtype, cache_dtype);
-    if (balanced && !mfma) return MLA_ERR_UNSUPPORTED;   // only the matrix-core kernel has this partition
-    if (balanced && ((long long)B * S > 0x3FFFFF || (long long)B * max_pages_per_seq > 0x7FFFFFFFLL))
-        return MLA_ERR_UNSUPPORTED;   // grid size; page counts are summed in 32 bits
-    hipError_t e;
-    if (mfma && !balanced && decode_mfma_wide_supported(p, io_dtype, cache_dtype))
-        e = launch_decode_mfma_wide(p, stream);
-    else if (mfma) e = launch_decode_mfma(p, cache_dtype, stream, balanced);
-    else      e = launch_decode_portable(p, io_dtype, cache_dtype, stream);
-    if (e != hipSuccess) return MLA_ERR_HIP;
-    if (skip_merge) return MLA_OK;
-
-    MergeParams m;
-    fill_merge_params(m, workspace, B, H, d_c, S, balanced);
-    m.o_lat = o_lat; m.lse = lse;
-    e = launch_merge(m, io_dtype, stream);
-    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+int mla_decode_paged_static(const void* q_abs, const void* q_rope, const void* kv_cache,
+                            const float* kv_scale, const int32_t* page_table, const int32_t* seq_lens,
+                            void* o_lat, float* lse, int B, int H, int d_c, int d_rope, int page_size,
+                            int num_pages, int max_pages_per_seq, int num_splits, float softmax_scale,
+                            mla_dtype io_dtype, mla_dtype cache_dtype, unsigned flags, void* hip_stream)
+{
+    if (flags & MLA_FLAG_SKIP_MERGE) return MLA_ERR_UNSUPPORTED;   // the partials would stay in the library's own array
+    const DecodeCall c = {q_abs, q_rope, kv_cache, kv_scale, page_table, seq_lens, o_lat, lse, B, 1, H,
+                          d_c, d_rope, page_size, num_pages, max_pages_per_seq, num_splits, softmax_scale,
+                          io_dtype, cache_dtype, flags, hip_stream};
+    const int st = decode_validate(c);
+    if (st != MLA_OK) return st;
+    if (mla_decode_workspace_bytes(B, H, d_c, num_splits) > STATIC_SCRATCH_BYTES) return MLA_ERR_SCRATCH_LIMIT;
+    void* ptr = static_scratch_of_current_device();
+    if (!ptr) return MLA_ERR_HIP;
+    return decode_launch(c, ptr);
 }
 
 int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_lat, float* lse,

@@ -23,7 +23,8 @@ FLAG_DEFAULT, FLAG_PORTABLE_KERNEL, FLAG_SKIP_MERGE, FLAG_BALANCED = 0, 1, 2, 4
 EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
            "mla_merge_out_proj", "mla_gather_paged", "mla_append_workspace_bytes", "mla_cache_append",
-           "mla_decode_paged_multi", "mla_merge_out_proj_multi", "mla_prefill_workspace_bytes", "mla_prefill_mha")
+           "mla_decode_paged_multi", "mla_merge_out_proj_multi", "mla_prefill_workspace_bytes", "mla_prefill_mha",
+           "mla_static_scratch_bytes", "mla_decode_paged_static")
 
 
 class MlaError(RuntimeError):
@@ -54,6 +55,11 @@ def lib() -> ctypes.CDLL:
         L.mla_decode_paged.restype = i
         L.mla_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        i, i, i, i, i, i, i, i, f, i, i, u, vp]
+        L.mla_static_scratch_bytes.restype = ctypes.c_size_t
+        L.mla_static_scratch_bytes.argtypes = []
+        L.mla_decode_paged_static.restype = i
+        L.mla_decode_paged_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
+                                              i, i, i, i, i, i, i, i, f, i, i, u, vp]
         L.mla_decode_paged_multi.restype = i
         L.mla_decode_paged_multi.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                              i, i, i, i, i, i, i, i, i, f, i, i, u, vp]
@@ -192,6 +198,43 @@ def decode_paged(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: 
     if skip_merge:
         return workspace
     return (out, lse) if lse is not None else out
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().mla_static_scratch_bytes())
+
+
+def decode_paged_static(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: torch.Tensor,
+                        page_table: torch.Tensor, seq_lens: torch.Tensor, softmax_scale: float,
+                        out: torch.Tensor, num_splits: int = 1, kv_scale: Optional[torch.Tensor] = None,
+                        lse: Optional[torch.Tensor] = None, flags: int = 0):
+    """decode_paged without a workspace (the partials live in the library's static device array) and
+    without any allocation: the caller passes `out` [B,H,d_c] (and `lse` [B,H] fp32 if wanted).
+    The tensors' device must be the current device."""
+    B, H, d_c = q_abs.shape
+    num_pages, page_size, row = kv_cache.shape
+    d_rope = row - d_c
+    if d_rope < 0:
+        raise ValueError("cache rows are shorter than d_c")
+    if d_rope and (q_rope is None or tuple(q_rope.shape) != (B, H, d_rope) or q_rope.dtype != q_abs.dtype):
+        raise ValueError("q_rope must be [B, H, d_rope] of q_abs's dtype")
+    if page_table.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise TypeError("page_table and seq_lens must be int32")
+    if page_table.dim() != 2 or page_table.shape[0] != B or seq_lens.shape != (B,):
+        raise ValueError("page_table must be [B, max_pages_per_seq], seq_lens [B]")
+    if tuple(out.shape) != (B, H, d_c) or out.dtype != q_abs.dtype:
+        raise ValueError("out must be [B, H, d_c] of q_abs's dtype")
+    if lse is not None and (tuple(lse.shape) != (B, H) or lse.dtype != torch.float32):
+        raise ValueError("lse must be float32 [B, H]")
+    if q_abs.device.index != torch.cuda.current_device():
+        raise ValueError("the tensors' device must be the current device")
+    _check(lib().mla_decode_paged_static(
+        _dev(q_abs, "q_abs"), _dev(q_rope, "q_rope"), _dev(kv_cache, "kv_cache"),
+        _dev(kv_scale, "kv_scale"), _dev(page_table, "page_table"), _dev(seq_lens, "seq_lens"),
+        _dev(out, "out"), _dev(lse, "lse"), B, H, d_c, d_rope, page_size, num_pages,
+        page_table.shape[1], num_splits, float(softmax_scale), _io_code(q_abs),
+        _cache_code(kv_cache), int(flags), _stream(q_abs)), "mla_decode_paged_static")
+    return out
 
 
 def decode_paged_multi(q_abs: torch.Tensor, q_rope: Optional[torch.Tensor], kv_cache: torch.Tensor,

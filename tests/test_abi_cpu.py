@@ -11,7 +11,7 @@ ROOT = Path(__file__).resolve().parents[1]
 HEADERS = sorted((ROOT / "include").glob("*.h"))
 LIBPATH = ROOT / "paper_2502_07864_amd" / "libmla_gfx950.so"
 
-OK, E_NULL, E_SHAPE, E_UNSUP, E_WS, E_HIP = 0, -1, -2, -3, -4, -6
+OK, E_NULL, E_SHAPE, E_UNSUP, E_WS, E_HIP, E_SCRATCH = 0, -1, -2, -3, -4, -6, -7
 F32, BF16, FP8 = 0, 1, 2
 
 
@@ -29,6 +29,9 @@ def lib():
     L.mla_decode_workspace_bytes.restype = ctypes.c_size_t
     L.mla_decode_workspace_bytes.argtypes = [i, i, i, i]
     L.mla_decode_paged.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 8 + [f, i, i, u, vp]
+    L.mla_static_scratch_bytes.restype = ctypes.c_size_t
+    L.mla_static_scratch_bytes.argtypes = []
+    L.mla_decode_paged_static.argtypes = [vp] * 8 + [i] * 8 + [f, i, i, u, vp]
     L.mla_decode_paged_multi.argtypes = [vp] * 9 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, u, vp]
     L.mla_merge_out_proj_multi.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp] + [i] * 7 + [u, vp]
     L.mla_prefill_workspace_bytes.restype = ctypes.c_size_t
@@ -121,6 +124,32 @@ def decode_args(**kw):
 ])
 def test_decode_validation(lib, kw, want):
     assert lib.mla_decode_paged(*decode_args(**kw)) == want
+
+
+def static_args(**kw):
+    a = decode_args(**kw)
+    del a[8:10]                  # no workspace, no workspace_bytes
+    return a
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q_abs=None), E_NULL), (dict(o=None), E_NULL), (dict(cache=FP8), E_NULL),
+    (dict(B=0), E_SHAPE), (dict(splits=0), E_SHAPE), (dict(io=FP8), E_UNSUP), (dict(d_c=520), E_UNSUP),
+    (dict(flags=2), E_UNSUP),                                   # MLA_FLAG_SKIP_MERGE
+    (dict(flags=4, io=F32, cache=F32), E_UNSUP),                # balanced partition without the matrix-core kernel
+    (dict(B=64, splits=16), E_SCRATCH),                         # 64 x 17 x 32 x 513 x 4 B = 71 MB
+    (dict(B=16, H=64, splits=16), E_SCRATCH),
+])
+def test_static_scratch_decode_validation(lib, kw, want):
+    """Everything, the scratch limit included, is rejected before the first HIP call."""
+    assert lib.mla_decode_paged_static(*static_args(**kw)) == want
+
+
+def test_static_scratch_limit(lib):
+    n = lib.mla_static_scratch_bytes()
+    assert n == 32 << 20
+    assert lib.mla_decode_workspace_bytes(16, 32, 512, 16) <= n     # the headline shape fits
+    assert b"SCRATCH" in lib.mla_status_string(E_SCRATCH)
 
 
 @pytest.mark.parametrize("kw,q_len,want", [
