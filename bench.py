@@ -28,7 +28,6 @@ from pathlib import Path
 
 ROOT = Path(__file__).resolve().parent
 sys.path.insert(0, str(ROOT))
-sys.path.insert(0, str(ROOT / "tests"))
 
 HBM_PEAK_GBPS = 8000.0
 
@@ -106,8 +105,9 @@ def main():
 
     import numpy as np
     import torch
-    from helpers import DeviceWorkload
-    from paper_2502_07864_amd import mla, synth
+    from workloads.device import DeviceWorkload
+    from paper_2502_07864_amd import mla
+    from workloads import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -159,7 +159,7 @@ def main():
     else:
         # the q_len newest tokens of every sequence query the cache at once; their own rows are
         # the last q_len rows the cache already holds
-        from helpers import to_torch
+        from workloads.device import to_torch
         qn, qr = synth.multi_queries(w, T)
         q_nope, q_rope = to_torch(qn, w.io_dtype, "cuda:0"), to_torch(qr, w.io_dtype, "cuda:0")
         q_abs = torch.empty((B, T, H, d_c), dtype=io_t, device="cuda:0")
@@ -391,8 +391,9 @@ def prefill_main(args):
     """Secondary row: the MHA-paradigm prefill call on the workload's cache."""
     import numpy as np
     import torch
-    from helpers import DeviceWorkload, to_torch
-    from paper_2502_07864_amd import mla, synth
+    from workloads.device import DeviceWorkload, to_torch
+    from paper_2502_07864_amd import mla
+    from workloads import synth
 
     w = synth.config(args.workload)
     assert w.io_dtype == "bf16" and w.cache_dtype == "bf16", "prefill runs on bf16 caches"
@@ -446,7 +447,8 @@ def convert_main(args):
     """Secondary row: offline conversion of one GQA layer to MLA (Sec. 4, App. B-D) in fp64."""
     import numpy as np
     import torch
-    from paper_2502_07864_amd import convert as cv, synth
+    from paper_2502_07864_amd import convert as cv
+    from workloads import synth
 
     g = h = 32
     d, D, n, r_kv, p = 128, 4096, 4096, 512, args.convert_block

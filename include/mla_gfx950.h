@@ -356,7 +356,7 @@ size_t mla_append_workspace_bytes(int B, int D, int d_c, int d_rope, mla_dtype i
 
 /*
  * Cache append: produces and stores the cache row of one new token per
- * sequence (Sec. 3.2, MLA equations: c^{KV}_t = W^{DKV} x_t,
+ * sequence (Sec. 3.3, MLA equations: c^{KV}_t = W^{DKV} x_t,
  * k^R_t = RoPE(W^{KR} x_t, t); App. D.2: the latent is what the cache keeps;
  * RoPE as in Sec. 3.1 Eq. 1, consecutive (real, imaginary) pairs, pair i
  * turned by t * rope_base^(-2i/d_rope)):

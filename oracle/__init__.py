@@ -348,7 +348,7 @@ def mla_step(q_nope, q_rope, W_UK, W_UV, pool, kv_scale, page_table, seq_lens,
 
 
 # --------------------------------------------------------------------------
-# cache append (Sec. 3.2 MLA equations: c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t))
+# cache append (Sec. 3.3 MLA equations: c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t))
 # --------------------------------------------------------------------------
 
 def rope(v, pos: float, base: float = 10000.0) -> np.ndarray:

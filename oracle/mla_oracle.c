@@ -501,7 +501,7 @@ int oracle_decode_split(const double* q_abs, const double* q_rope,
 
 /* ======================================================================
  * Cache append: the step that produces the row the decode reads.
- * Sec. 3.2 (MLA equations, left column):
+ * Sec. 3.3 (MLA equations, left column):
  *     c_t^{KV} = W^{DKV} x_t          k_t^R = RoPE(W^{KR} x_t, t)
  * and the row kept per token is their concatenation [c^{KV} ; k^R]
  * (App. D.2: the r_kv-dimensional latent is what the cache stores).

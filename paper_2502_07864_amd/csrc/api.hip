@@ -51,6 +51,13 @@ void fill_merge_params(MergeParams& m, const void* workspace, int B, int H, int 
     m.B = B; m.H = H; m.d_c = d_c; m.num_splits = eff_splits;
 }
 
+// The merge kernels index their wavefronts (one per output row and block of 256 columns) with 32-bit
+// integers: sizes whose row count would not fit are refused rather than wrapped.
+bool merge_rows_overflow(long long B, long long H, int d_c)
+{
+    return B * H * ((d_c + 255) / 256) > 0x7FFFFFFFLL;
+}
+
 // Arguments of one decode call (mla_decode_paged_multi's, without the workspace).
 struct DecodeCall {
     const void* q_abs; const void* q_rope; const void* kv_cache; const float* kv_scale;
@@ -274,6 +281,7 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes, void* o_la
     if (B <= 0 || H <= 0 || d_c <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
     if (H > 65535 || B > 65535 || d_c % 4 || d_c > 2048) return MLA_ERR_UNSUPPORTED;
+    if (merge_rows_overflow(B, H, d_c)) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, H, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;
@@ -301,6 +309,7 @@ int mla_merge_out_proj_multi(const void* workspace, size_t workspace_bytes, cons
     if (!io_ok(io_dtype)) return MLA_ERR_UNSUPPORTED;
     if ((long long)q_len * heads > 65535 || (long long)B * q_len > 65535 || d_c % 4 || d_c > 2048)
         return MLA_ERR_UNSUPPORTED;
+    if (merge_rows_overflow(B, q_len * heads, d_c)) return MLA_ERR_UNSUPPORTED;
     const size_t need = mla_decode_workspace_bytes(B, q_len * heads, d_c, num_splits);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return MLA_ERR_WORKSPACE;

@@ -1,5 +1,5 @@
 // Cache append: the row the decode reads, produced for one new token per sequence
-// (Sec. 3.2, MLA equations, left column):
+// (Sec. 3.3, MLA equations, left column):
 //     c^{KV}_t = W^{DKV} x_t        k^R_t = RoPE(W^{KR} x_t, t)        row = [c^{KV}_t ; k^R_t]
 // with RoPE as in Sec. 3.1, Eq. 1 (consecutive pairs (real, imaginary), pair i turned by
 // t * base^(-2i/d^R)).  The two projections are one skinny GEMM x . [W^{DKV} ; W^{KR}]^T whose cost

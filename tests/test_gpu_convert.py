@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from oracle import convert_oracle as co
-from paper_2502_07864_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2502_07864_amd import synth
+from workloads import synth
 
 GOLDEN = Path(__file__).parent / "golden"
 RNG = np.random.default_rng(1234)
@@ -665,7 +665,7 @@ def test_stored_cache_values_are_widened_exactly():
 
 
 # ------------------------------------------------------------ cache append
-# Sec. 3.2 (MLA equations): c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t); Sec. 3.1 Eq. 1 for RoPE.
+# Sec. 3.3 (MLA equations): c^{KV} = W^{DKV} x, k^R = RoPE(W^{KR} x, t); Sec. 3.1 Eq. 1 for RoPE.
 
 def test_A1_rope_closed_forms():
     """Eq. 1: position 0 is the identity; the first pair (theta = 1) of (1, 0) at position

@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 from helpers import DeviceWorkload, lse_err, max_abs_rel, storage_bits, widen_gpu
-from paper_2502_07864_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 
