@@ -101,6 +101,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         if (wg_lin >= p.B * p.num_splits) return;   // padding of the last group of 8
     }
     const int hb = zi * 32;
+    const bool stream_once = Z == 1;   // no other workgroup reads this one's cached rows
     auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
                            const size_t out_slot) {
     // Balanced partition: the body runs in a loop.  Everything derived from the thread index is
@@ -214,12 +215,25 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         if (rows_valid(t) <= 0) return 0;   // a page outside the pool is never dereferenced
         const unsigned char* src = kv + (size_t)ptab[t >> 1] * PAGE_B + (size_t)(t & 1) * TILE_B;
         const uint32_t dst = lds_base + (uint32_t)(((t - t0) % NBUF) * TILE_B + wave * 1024);
+        if (stream_once) {
+            // this workgroup is the only reader of these rows: non-temporal loads (measured on a
+            // bare ring of the same loads: 6.7 instead of 6.0 TB/s over the chip)
 #pragma unroll
-        for (int k = 0; k < NLOAD; ++k) {
-            const unsigned char* gp = src + goff[k];
-            const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(m0v), "v"(gp) : "memory");
+            for (int k = 0; k < NLOAD; ++k) {
+                const unsigned char* gp = src + goff[k];
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            }
+        } else {
+            // further groups of query rows read the same rows from this XCD's L2: ordinary loads
+#pragma unroll
+            for (int k = 0; k < NLOAD; ++k) {
+                const unsigned char* gp = src + goff[k];
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            }
         }
         return NLOAD;
     };
