@@ -77,6 +77,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
     __shared__ float scale_lds[2][TILE_ROWS];        // fp8: row scales of the two widened tiles
     __shared__ int seg_lds[BAL ? 64 : 1][3];         // balanced partition: (sequence, first row, end row) per segment
+    __shared__ int jump_flag;                        // raised by a wavefront whose fast pass met a score far above its reference
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
     const int tid = threadIdx.x;
@@ -115,9 +116,13 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int hg = wave & 1, tg = wave >> 1;
     const int n = lane & 15, g = lane >> 4;
     const int HL = min(32, p.H - hb);          // query rows of this workgroup
+    // cleared here, read after the tile loop: at least one workgroup barrier lies between (every
+    // chunk that reaches the loop stages a tile), and between one segment's read and the next
+    // segment's clear (the barrier after run_segment)
+    if (tid == 0) jump_flag = 0;
     // where query row h's (h counted over the whole sequence) partial row and log-sum-exp go
-    auto o_row = [&](int h) -> float* {
-        return p.o_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
+    auto o_row = [&](int h) -> uint16_t* {    // partial rows are bf16 (the io dtype of this kernel)
+        return static_cast<uint16_t*>(p.o_part) + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
     };
     auto lse_at = [&](int h) -> float* {
         return p.lse_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits));
@@ -132,32 +137,26 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int warm = ptab[min(BAL ? seg_row0 / 64 : split * p.chunk_pages, p.max_pages - 1)];
     int L = seq_lens_c[b];
 
-    // ---- this wave's 16 query rows as B operands, resident for the whole chunk.
-    // fp8 path: plain global loads.  bf16 path: the rows [q_abs | q_rope] of all heads are laid
-    // out exactly like a cache tile (one row per head, same chunk swizzle; rows of absent heads
-    // zero-filled) and travel through the last ring slot, which is free until the first tile
-    // has been consumed, as direct-to-LDS loads.  They are requested here, while the two scalar
-    // loads above are still on their way, and ahead of the first tiles, so that waiting for
-    // them does not mean waiting for the tiles.
+    // ---- this wave's 16 query rows as B operands, resident for the whole chunk: lane (g, n) holds
+    // elements 8g .. 8g+7 of every 32-element k-step of head 16 hg + n.  They are requested here,
+    // while the two scalar loads above are still on their way and ahead of the first tiles.
+    // bf16 path: the loads are inline assembly like the tile loads, because the compiler, which
+    // cannot see those, would otherwise wait for "everything in flight" (the whole ring) at the
+    // first use of a query register; their arrival is awaited by count below, where the registers
+    // are handed to the compiler.  (An earlier version sent the query rows through the last ring
+    // slot: that slot could then not be requested before the rows had been copied to registers,
+    // which left the memory system without requests for about 1.5 us at the start.)
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-    LDS_AS unsigned char* qslot = lds + (NBUF - 1) * TILE_B;
+    const int head = hg * 16 + n;
+    u32x4 qraw[FP8 ? 1 : NKS];
     if constexpr (!FP8) {
-        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
-        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
-        const uint32_t dst = lds_base + (uint32_t)((NBUF - 1) * TILE_B + wave * 1024);
+        const int hq = min(head, HL - 1);     // absent heads read a present one; their registers are cleared below
+        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + hb + hq) * D_C + g * 8;
+        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + hb + hq) * 64 + g * 8;
 #pragma unroll
-        for (int k = 0; k < NLOAD; ++k) {
-            const int P = (k * 4 + wave) * 64 + lane;
-            const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
-            if (r < HL) {
-                const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
-                                                      : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
-                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                             :: "s"(m0v), "v"(gp) : "memory");
-            } else {
-                *(LDS_AS u32x4*)(qslot + P * 16) = (u32x4){0u, 0u, 0u, 0u};
-            }
+        for (int ks = 0; ks < NKS; ++ks) {
+            const uint16_t* src = ks < D_C / 32 ? qa + ks * 32 : qr + (ks - D_C / 32) * 32;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qraw[ks]) : "v"(src) : "memory");
         }
     }
 
@@ -173,7 +172,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
     const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
 
-    const int head = hg * 16 + n;
     bf16x8 qreg[NKS];
     if constexpr (FP8) {
         const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + hb + head) * D_C;
@@ -329,7 +327,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 
     bool ring_full = false;   // tile t0 + NBUF - 1 has been requested ahead of the first stage step
     // request tile t0 + NBUF - 1 into the last ring slot before the first stage step (which
-    // then must not request it again); only once nobody reads the query rows there any more
+    // then must not request it again)
     auto fill_last_slot = [&]() {
         ahead[NBUF - 2] = t0 + NBUF - 1 < t1 ? fetch_tile(t0 + NBUF - 1) : 0;
         ring_full = true;
@@ -502,27 +500,26 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
     } else {
-        start_ring(false);
+        start_ring(true);
         // wait for the query rows only: the tile loads requested after them stay in flight
+        // (vector memory loads complete in the order they were issued)
         {
             int later = first_issued;   // tile t0
 #pragma unroll
-            for (int i = 0; i < NBUF - 2; ++i) later += ahead[i];
-            if (NBUF > 3 && later >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
-            else if (NBUF > 2 && later >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
+            for (int i = 0; i < NBUF - 1; ++i) later += ahead[i];
+            if (NBUF > 3 && later >= 4 * NLOAD)      wait_vmcnt<4 * NLOAD>();
+            else if (NBUF > 2 && later >= 3 * NLOAD) wait_vmcnt<3 * NLOAD>();
+            else if (later >= 2 * NLOAD)             wait_vmcnt<2 * NLOAD>();
             else if (later >= NLOAD)                 wait_vmcnt<NLOAD>();
             else                                     wait_vmcnt<0>();
         }
-        __syncthreads();
-        const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
-        const uint32_t q_key = (uint32_t)swz_key(n);
+        // from here on the registers hold the rows: this is where the compiler learns of them
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks)
-            qreg[ks] = *(LDS_AS bf16x8*)(qslot + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
-        // once every wave has its query rows in registers the slot joins the ring: its first
-        // tile is requested right away instead of after the first tile has arrived
-        __syncthreads();
-        fill_last_slot();
+        for (int ks = 0; ks < NKS; ++ks) {
+            asm volatile("" : "+v"(qraw[ks]));
+            if (head >= HL) qraw[ks] = (u32x4){0u, 0u, 0u, 0u};
+            qreg[ks] = __builtin_bit_cast(bf16x8, qraw[ks]);
+        }
     }
 
     bool jumped = false;
@@ -542,7 +539,11 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         finish_tile(t, page_t2);
     }
 
-    if (__builtin_expect(__syncthreads_or(jumped), 0)) {
+    // a plain flag and one barrier: the library's workgroup-wide OR costs about 1400 cycles here,
+    // at a point where no cached row is in flight any more
+    if (jumped) jump_flag = 1;
+    __syncthreads();
+    if (__builtin_expect(jump_flag != 0, 0)) {
         // ---- careful pass (rare): the same chunk again with a moving reference.  The tile
         // loop is nested in an outer loop whose body rescales the accumulators; the inner loop
         // is left, before the offending tile is accumulated, whenever a tile maximum exceeds
@@ -589,33 +590,37 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         __syncthreads();  // every wave is done with the tiles of the second pass too
     }
 
-    // ---- merge the two row halves of each head group, normalise, write the partial.
+    // ---- merge the two row halves of each head group, normalise, write the partial (bf16).
     // Both wavefronts of a head group hold all D_C columns for their 16 tile rows.  Each hands the
-    // column half it does not finish to its partner through LDS and finishes the other half:
-    // combine, transpose (a lane holds 4 consecutive columns of head n per column tile, which
-    // written straight out would give 64-byte runs) and store whole 1 KB runs.
+    // column half it does not finish to its partner through LDS, rounded to bf16 (the partial is
+    // stored in bf16 anyway; this halves the LDS traffic of the epilogue, during which no
+    // cached row is in flight), and finishes the other half: combine, transpose (a lane holds 4
+    // consecutive columns of head n per column tile, which written straight out would give
+    // 32-byte runs) and store whole 1 KB runs.
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
     // Every wave has passed a barrier after its last tile read and nothing is in flight: the
     // tile ring is free and serves as exchange space.
     constexpr int HCT = NCT / 2;             // column tiles each wavefront finishes
-    constexpr int RSO = HCT * 64 + 16;       // row stride of the transposed half (padded: conflict-free both ways)
-    constexpr int XCH = (HCT * 1024 + 512) > 16 * RSO ? (HCT * 1024 + 512) : 16 * RSO;  // per wavefront
+    constexpr int RSO = HCT * 32 + 32;       // row stride of the transposed half in bytes (padded: conflict-free both ways)
+    constexpr int XCH = (HCT * 512 + 512) > 16 * RSO ? (HCT * 512 + 512) : 16 * RSO;  // per wavefront
     static_assert(4 * XCH <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* mine = lds + (hg * 2 + tg) * XCH;          // written by the partner
     LDS_AS unsigned char* theirs = lds + (hg * 2 + (tg ^ 1)) * XCH;  // written by this wavefront
     auto hand_over = [&](auto first) {
         constexpr int C0 = decltype(first)::value;
 #pragma unroll
-        for (int i = 0; i < HCT; ++i) *(LDS_AS f32x4*)(theirs + (i * 64 + lane) * 16) = oacc[C0 + i];
+        for (int i = 0; i < HCT; ++i)
+            *(LDS_AS u32x2*)(theirs + (i * 64 + lane) * 8) =
+                (u32x2){pack_bf16x2(oacc[C0 + i][0], oacc[C0 + i][1]), pack_bf16x2(oacc[C0 + i][2], oacc[C0 + i][3])};
     };
     if (tg == 0) hand_over(std::integral_constant<int, HCT>{});
     else         hand_over(std::integral_constant<int, 0>{});
-    *(LDS_AS float*)(theirs + HCT * 1024 + lane * 4) = m_run;
-    *(LDS_AS float*)(theirs + HCT * 1024 + 256 + lane * 4) = l_w;
+    *(LDS_AS float*)(theirs + HCT * 512 + lane * 4) = m_run;
+    *(LDS_AS float*)(theirs + HCT * 512 + 256 + lane * 4) = l_w;
     __syncthreads();
-    const float m1 = *(LDS_AS float*)(mine + HCT * 1024 + lane * 4);
-    const float l1 = *(LDS_AS float*)(mine + HCT * 1024 + 256 + lane * 4);
+    const float m1 = *(LDS_AS float*)(mine + HCT * 512 + lane * 4);
+    const float l1 = *(LDS_AS float*)(mine + HCT * 512 + 256 + lane * 4);
     const float m_all = fmaxf(m_run, m1);
     const float m_use = m_all == -INFINITY ? 0.f : m_all;
     const float w0 = fast_exp2(m_run - m_use), w1 = fast_exp2(m1 - m_use);
@@ -629,26 +634,29 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         constexpr int C0 = decltype(first)::value;
 #pragma unroll
         for (int i = 0; i < HCT; ++i) {
-            f32x4 o1 = *(LDS_AS f32x4*)(mine + (i * 64 + lane) * 16);
+            const u32x2 b1 = *(LDS_AS u32x2*)(mine + (i * 64 + lane) * 8);
+            const f32x4 o1 = (f32x4){bf16_bits_to_f32(b1[0] & 0xFFFFu), __uint_as_float(b1[0] & 0xFFFF0000u),
+                                     bf16_bits_to_f32(b1[1] & 0xFFFFu), __uint_as_float(b1[1] & 0xFFFF0000u)};
             oacc[C0 + i] = oacc[C0 + i] * s0 + o1 * s1;
         }
 #pragma unroll
         for (int i = 0; i < HCT; ++i)
-            *(LDS_AS f32x4*)(mine + n * RSO + (i * 16 + g * 4) * 4) = oacc[C0 + i];
+            *(LDS_AS u32x2*)(mine + n * RSO + (i * 16 + g * 4) * 2) =
+                (u32x2){pack_bf16x2(oacc[C0 + i][0], oacc[C0 + i][1]), pack_bf16x2(oacc[C0 + i][2], oacc[C0 + i][3])};
     };
     if (tg == 0) finish_half(std::integral_constant<int, 0>{});
     else         finish_half(std::integral_constant<int, HCT>{});
     const int nrow = min(16, HL - hg * 16);
-    constexpr int LPR = HCT * 4;             // lanes (of 16 bytes) covering one row of the half
-    constexpr int RPI = 64 / LPR;            // rows one store instruction covers (1 or 2)
-    static_assert(LPR == 64 || LPR == 32, "half a latent row is 1 KB or 512 B");
-#pragma unroll 4
+    constexpr int LPR = HCT * 2;             // lanes (of 16 bytes = 8 bf16) covering one row of the half
+    constexpr int RPI = 64 / LPR;            // rows one store instruction covers (2 or 4)
+    static_assert(LPR == 32 || LPR == 16, "half a latent row is 512 B or 256 B");
+#pragma unroll
     for (int r0 = 0; r0 < 16; r0 += RPI) {
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
-            f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = o_row(hb + hg * 16 + r) + tg * (HCT * 16) + c * 4;
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+            const u32x4 v = *(LDS_AS u32x4*)(mine + r * RSO + c * 16);
+            uint16_t* dst = o_row(hb + hg * 16 + r) + tg * (HCT * 16) + c * 8;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
         }
     }
     if (tg == 0 && head < HL && g == 0)
@@ -753,27 +761,48 @@ static unsigned grid_1d(const DecodeParams& p)
     return (unsigned)(Z > 1 ? (n + 7) / 8 * 8 * Z : n);
 }
 
+// Ring depth of the bf16 kernels.  The wavefronts that consume a tile are the ones that request the
+// next: while they stand in the memory pipe's queue the rows they asked for earlier land, so at
+// the end of a chunk NBUF - 1 tiles are still waiting to be consumed after the last request has
+// gone out.  A short chunk (C2: 16 tiles) pays for every tile of that backlog and runs best with
+// three slots (measured 30.2 -> 29.2 us; two slots leave the memory system without a request between
+// tiles: 31.5 us); on long chunks the deeper ring is the faster one (C3: 202.7 against 206 us).
+static int ring_depth(const DecodeParams& p, bool balanced)
+{
+    const long long tiles = balanced ? 2LL * p.max_pages / (p.num_splits > 0 ? p.num_splits : 1) : 2LL * p.chunk_pages;
+    return tiles <= 64 ? 3 : 4;
+}
+
+template <int D_C, bool FP8, bool BAL>
+static void launch_one(const DecodeParams& p, dim3 grid, dim3 block, hipStream_t s, int depth)
+{
+    if constexpr (FP8) decode_mfma_kernel<D_C, true, 2, 1, BAL><<<grid, block, 0, s>>>(p);
+    else if (depth == 3) decode_mfma_kernel<D_C, false, 3, 1, BAL><<<grid, block, 0, s>>>(p);
+    else                 decode_mfma_kernel<D_C, false, 4, 1, BAL><<<grid, block, 0, s>>>(p);
+}
+
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced)
 {
     const bool fp8 = cache == MLA_FP8_E4M3;
     dim3 block(MF_THREADS);
+    const int depth = ring_depth(p, balanced);
     if (balanced) {
         if (!p.plan) return hipErrorInvalidValue;
         // workgroups = sequences x chunks per sequence (x groups of 32 query rows)
         dim3 grid(grid_1d(p));
-        if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, true><<<grid, block, 0, s>>>(p);
-        else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, true><<<grid, block, 0, s>>>(p);
-        else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, true><<<grid, block, 0, s>>>(p);
-        else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1, true><<<grid, block, 0, s>>>(p);
+        if (p.d_c == 512 && !fp8)      launch_one<512, false, true>(p, grid, block, s, depth);
+        else if (p.d_c == 256 && !fp8) launch_one<256, false, true>(p, grid, block, s, depth);
+        else if (p.d_c == 512 && fp8)  launch_one<512, true, true>(p, grid, block, s, depth);
+        else if (p.d_c == 256 && fp8)  launch_one<256, true, true>(p, grid, block, s, depth);
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
     dim3 grid(p.B, p.num_splits);
     if (p.H > 32) grid = dim3(grid_1d(p));
-    if (p.d_c == 512 && !fp8)      decode_mfma_kernel<512, false, 4, 1, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && !fp8) decode_mfma_kernel<256, false, 4, 1, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 512 && fp8)  decode_mfma_kernel<512, true, 4, 1, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256 && fp8)  decode_mfma_kernel<256, true, 4, 1, false><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512 && !fp8)      launch_one<512, false, false>(p, grid, block, s, depth);
+    else if (p.d_c == 256 && !fp8) launch_one<256, false, false>(p, grid, block, s, depth);
+    else if (p.d_c == 512 && fp8)  launch_one<512, true, false>(p, grid, block, s, depth);
+    else if (p.d_c == 256 && fp8)  launch_one<256, true, false>(p, grid, block, s, depth);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

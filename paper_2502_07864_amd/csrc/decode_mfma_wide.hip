@@ -82,7 +82,9 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     const int hb = zi * WD_ROWS;
     const int HL = min(WD_ROWS, p.H - hb);     // query rows of this workgroup
 
-    auto o_row = [&](int h) -> float* { return p.o_part + part_index(b, h, split, p.H, p.num_splits) * D_C; };
+    auto o_row = [&](int h) -> uint16_t* {    // partial rows are bf16 (the io dtype of this kernel)
+        return static_cast<uint16_t*>(p.o_part) + part_index(b, h, split, p.H, p.num_splits) * D_C;
+    };
     auto lse_at = [&](int h) -> float* { return p.lse_part + part_index(b, h, split, p.H, p.num_splits); };
 
     // read-only tables through the scalar cache (no vector-memory counter involved)
@@ -435,26 +437,30 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
         inv[hi] = lt[hi] > 0.f ? 1.f / lt[hi] : 0.f;
     }
     // transpose through LDS (a lane holds 4 consecutive columns of query row n per column tile,
-    // which written straight out would give 16-byte pieces) and store whole runs
+    // which written straight out would give 8-byte pieces), rounded to bf16, and store whole runs
     constexpr int CW = D_C / 2;                 // columns per wavefront
-    constexpr int RSO = CW * 4 + 16;            // row stride of the transposed block (padded)
+    constexpr int RSO = CW * 2 + 32;            // row stride of the transposed block in bytes (padded)
     static_assert(4 * 32 * RSO <= NBUF * TILE_B, "exchange space must fit in the tile ring");
     LDS_AS unsigned char* mine = lds + wave * (32 * RSO);
 #pragma unroll
     for (int hi = 0; hi < 2; ++hi)
 #pragma unroll
         for (int ct = 0; ct < CTW; ++ct)
-            *(LDS_AS f32x4*)(mine + (hi * 16 + n) * RSO + (ct * 16 + g * 4) * 4) = oacc[hi][ct] * inv[hi];
-    constexpr int LPR = CW / 4;                 // lanes (of 16 bytes) covering one row of the half (64 / 32)
-    constexpr int RPI = 64 / LPR;               // rows one store instruction covers (1 or 2)
+        {
+            const f32x4 o = oacc[hi][ct] * inv[hi];
+            *(LDS_AS u32x2*)(mine + (hi * 16 + n) * RSO + (ct * 16 + g * 4) * 2) =
+                (u32x2){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        }
+    constexpr int LPR = CW / 8;                 // lanes (of 16 bytes = 8 bf16) covering one row of the half (32 / 16)
+    constexpr int RPI = 64 / LPR;               // rows one store instruction covers (2 or 4)
     const int nrow = min(32, HL - hp * 32);
 #pragma unroll 4
     for (int r0 = 0; r0 < 32; r0 += RPI) {
         const int r = r0 + lane / LPR, c = lane % LPR;
         if (r < nrow) {
-            f32x4 v = *(LDS_AS f32x4*)(mine + r * RSO + c * 16);
-            float* dst = o_row(hb + hp * 32 + r) + a * CW + c * 4;
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+            const u32x4 v = *(LDS_AS u32x4*)(mine + r * RSO + c * 16);
+            uint16_t* dst = o_row(hb + hp * 32 + r) + a * CW + c * 8;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
         }
     }
     if (a == 0 && g == 0) {

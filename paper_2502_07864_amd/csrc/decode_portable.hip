@@ -8,6 +8,7 @@
 // folded into a running softmax (second line of the absorbed attention
 // equation, Sec. 3.3 of the paper) and accumulated into the latent output.
 #include "mla_internal.h"
+#include <type_traits>
 
 namespace mla {
 namespace {
@@ -257,7 +258,10 @@ __global__ __launch_bounds__(PT_THREADS) void decode_portable_kernel(DecodeParam
         if (c < p.d_c) {
             for (int h = 0; h < nh; ++h) {
                 float l = l_s[h];
-                p.o_part[part_index(b, h0 + h, split, p.H, p.num_splits) * p.d_c + c] = l > 0.f ? acc[i][h] / l : 0.f;
+                const float val = l > 0.f ? acc[i][h] / l : 0.f;
+                const size_t at = part_index(b, h0 + h, split, p.H, p.num_splits) * p.d_c + c;
+                if constexpr (std::is_same<QT, bf16_tag>::value) static_cast<uint16_t*>(p.o_part)[at] = (uint16_t)f32_to_bf16_bits(val);
+                else                                             static_cast<float*>(p.o_part)[at] = val;
             }
         }
     }
@@ -330,12 +334,12 @@ __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
         for (int i = 0; i < 4; ++i) {             // columns tid*4 + i*512 (d_c <= 2048 per pass)
             const int c = tid * 4 + i * 512;
             if (c >= p.d_c) break;
-            const float* src = p.o_part + (first + (size_t)s0 * step) * p.d_c + c;
+            const size_t src = (first + (size_t)s0 * step) * p.d_c + c;   // element index into the partial rows
             for (int s = 0; s < ns; s += 8) {
                 float4 v[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    v[j] = *reinterpret_cast<const float4*>(src + (size_t)min(s + j, ns - 1) * step * p.d_c);
+                    v[j] = load_part4<OUT_BF16>(p.o_part, src + (size_t)min(s + j, ns - 1) * step * p.d_c);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     // weight 0 for empty chunks (their rows were never written: discarded by the
@@ -386,12 +390,12 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
     // multiplied by zero.
     constexpr int BATCH = 16;
     const size_t stride = (size_t)p.d_c;
-    const float* base = p.o_part + part_index(b, h, 0, p.H, S) * p.d_c + cb * 256 + lane * 4;
+    const size_t base = part_index(b, h, 0, p.H, S) * p.d_c + cb * 256 + lane * 4;   // element index
     const float ls = lane < S ? p.lse_part[part_index(b, h, lane, p.H, S)] : -INFINITY;
     float4 v[BATCH];
 #pragma unroll
     for (int i = 0; i < BATCH; ++i)   // rows past the last chunk re-read it (weight zero)
-        v[i] = *reinterpret_cast<const float4*>(base + (size_t)min(i, S - 1) * stride);
+        v[i] = load_part4<OUT_BF16>(p.o_part, base + (size_t)min(i, S - 1) * stride);
 
     const ChunkWeights cw = chunk_weights(ls, S);
 
@@ -400,7 +404,7 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
         if (s0 > 0) {
 #pragma unroll
             for (int i = 0; i < BATCH; ++i)
-                v[i] = *reinterpret_cast<const float4*>(base + (size_t)min(s0 + i, S - 1) * stride);
+                v[i] = load_part4<OUT_BF16>(p.o_part, base + (size_t)min(s0 + i, S - 1) * stride);
         }
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {

@@ -59,14 +59,16 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
     // wave task = (batch row, block of 256 columns); partial rows [s0, s0 + BATCH) of a task
     auto task_base = [&](int task) {
         const int bl = task / CB, cb = task % CB;
-        return p.o_part + part_index(b0 + bl, h, 0, p.H, S) * D_C + cb * 256 + lane * 4;
+        return part_index(b0 + bl, h, 0, p.H, S) * D_C + cb * 256 + lane * 4;   // element index into the partial rows
     };
     // rows past the last chunk re-read the last one (their weight is zero): no branches, the
     // kernel's code stays short and straight, which matters for a kernel this brief
-    auto load_rows = [&](const float* base, int s0, f32x4 (&v)[BATCH]) {
+    auto load_rows = [&](size_t base, int s0, f32x4 (&v)[BATCH]) {
 #pragma unroll
-        for (int i = 0; i < BATCH; ++i)
-            v[i] = *reinterpret_cast<const f32x4*>(base + (size_t)min(s0 + i, S - 1) * D_C);
+        for (int i = 0; i < BATCH; ++i) {
+            const float4 r = load_part4<true>(p.o_part, base + (size_t)min(s0 + i, S - 1) * D_C);
+            v[i] = (f32x4){r.x, r.y, r.z, r.w};
+        }
     };
 
     // ---- (1) the first task's chunk weights and partial rows are requested ahead of everything
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(256) void merge_out_proj_kernel(MergeParams p, cons
     // next one's rows requested before the current one is reduced
     auto reduce = [&](int task, f32x4 (&v)[BATCH], float ls) {
         const int bl = task / CB, cb = task % CB, b = b0 + bl;
-        const float* base = task_base(task);
+        const size_t base = task_base(task);
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
         const ChunkWeights cw = chunk_weights(ls, S);
         for (int s0 = 0; s0 < S; s0 += BATCH) {

@@ -20,7 +20,8 @@ struct DecodeParams {
     const float* kv_scale;      // [num_pages, page_size] (fp8 cache) or nullptr
     const int32_t* page_table;  // [B, max_pages]
     const int32_t* seq_lens;    // [B]
-    float* o_part;              // [B, H, S, d_c]  chunk-normalised partial outputs
+    void* o_part;               // [B, H, S, d_c]  chunk-normalised partial outputs, stored in the io dtype
+                                // (fp32 io: fp32; bf16 io: bf16 -- half the bytes to write and to merge)
     float* lse_part;            // [B, H, S]       natural-log LSE per chunk (-inf = empty)
     int32_t* plan;              // balanced partition only: [B, 2] first partial slot and count per
                                 // sequence (the partials are then [slot, H, d_c] / [slot, H])
@@ -39,7 +40,7 @@ __host__ __device__ __forceinline__ int visible_rows(const DecodeParams& p, int 
 }
 
 struct MergeParams {
-    const float* o_part;
+    const void* o_part;    // partial outputs in the io dtype (see DecodeParams)
     const float* lse_part;
     const int32_t* plan;   // nullptr, or (balanced partition) [B, 2] first slot and count per sequence
     void* o_lat;   // [B,H,d_c] io dtype
@@ -99,6 +100,19 @@ __device__ __forceinline__ float chunk_weight_at(const ChunkWeights& cw, float l
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16)
 {
     return __uint_as_float(bits16 << 16);
+}
+
+// Four consecutive values of a partial output row (element index a multiple of 4); the rows are
+// stored in the io dtype: BF16 = true reads 8 bytes, false 16.
+template <bool BF16> __device__ __forceinline__ float4 load_part4(const void* base, size_t elem)
+{
+    if constexpr (BF16) {
+        const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + elem);
+        return make_float4(bf16_bits_to_f32(v.x & 0xFFFFu), __uint_as_float(v.x & 0xFFFF0000u),
+                           bf16_bits_to_f32(v.y & 0xFFFFu), __uint_as_float(v.y & 0xFFFF0000u));
+    } else {
+        return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+    }
 }
 
 // fp32 -> bf16 bits, round to nearest even, NaN kept quiet.
