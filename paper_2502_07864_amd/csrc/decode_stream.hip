@@ -1,0 +1,450 @@
+// Matrix-core paged decode for a bf16 latent cache, with the wavefronts that request cached rows
+// kept apart from the wavefronts that consume them (gfx950 / CDNA4).
+//
+// Second line of the absorbed attention equation (Sec. 3.3 of the paper): all H heads score
+// against the ONE shared row k_hat_j = [c_j ; k^R_j] and weight the same latent rows c_j:
+//     S^T [tok x heads]   = K [tok x (d_c+64)] . Q^T [(d_c+64) x heads]
+//     O^T [d_c x heads]  += V^T [d_c x tok] . P^T [tok x heads]
+// with V = the first d_c columns of the very same LDS tile as K (see decode_mfma.hip for the
+// operand layouts, the transposed formulation, the chunk swizzle and the fixed-reference fast
+// pass with its careful second pass; this kernel shares all of them).
+//
+// What is different here is who does what.  A direct-to-LDS load leaves the wavefront that issues
+// it standing in the memory pipe's queue until the request is accepted, and with the memory system
+// saturated that is most of a tile period.  When the consuming wavefronts issue the requests
+// themselves (decode_mfma.hip) they fall behind the rows that land meanwhile, and that backlog
+// (ring depth - 1 tiles) is still to be consumed when the last request has gone out; their
+// accumulators (all d_c columns for half the tile rows) also need a hand-over between the two row
+// halves at the end, at one wavefront per SIMD.  Here a workgroup has eight wavefronts, two per
+// SIMD:
+//   wavefronts 4..7 (producers) do nothing but request tiles (nine 128-bit direct-to-LDS loads per
+//     tile each) and wait for them by count;
+//   wavefronts 0..3 (consumers) never touch the vector-memory counter.  Consumer (hg, ch) owns
+//     heads 16 hg .. 16 hg + 15 and latent columns [ch d_c/2, (ch+1) d_c/2) for ALL 32 rows of a
+//     tile: it scores both 16-row blocks (the score contraction is done twice per head group,
+//     once per column half: the kernel has matrix-core time to spare, it is bound by the
+//     memory stream) and accumulates its column half with K = 32 (one v_mfma_f32_16x16x32_bf16 per
+//     column tile, fed by two transposing LDS reads).  Its 64 accumulator registers hold complete
+//     sums, so the epilogue is normalise, transpose, store: no hand-over, no combine.
+// Both kinds meet at one workgroup barrier per tile (tile t has landed, everybody is done with
+// tile t - 1, whose slot the producers then fill again).
+#include "mla_internal.h"
+#include "mfma_tile.h"
+#include <type_traits>
+
+namespace mla {
+namespace {
+
+constexpr int ST_THREADS = 512;   // 4 consumer + 4 producer wavefronts
+
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+template <int D_C>
+__global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
+{
+    constexpr int NBUF = 3;                     // ring slots: one being consumed, two requested (this kernel is for short chunks)
+    constexpr bool BAL = false;                 // uniform chunks only; the balanced partition runs decode_mfma.hip's kernel
+    constexpr int ROW = D_C + 64;               // elements per cache row
+    constexpr int ROWB = ROW * 2;               // bytes per row
+    constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
+    constexpr int PAGE_B = 64 * ROWB;           // bytes per page
+    constexpr int TILE_B = TILE_ROWS * ROWB;    // bytes per tile
+    constexpr int NLOAD = TILE_B / (256 * 16);  // 16-byte loads per producer thread per tile (9 / 5)
+    constexpr int NKS = ROW / 32;               // k-steps of the score contraction (18 / 10)
+    constexpr int WCT = D_C / 32;               // column tiles of the value contraction per consumer (16 / 8)
+    constexpr int SG = NKS % 3 == 0 ? 3 : 2;    // k-steps per read-ahead group (score)
+    constexpr int VG = 4;                       // column tiles per read-ahead group (value)
+    constexpr int RSO = WCT * 32 + 32;          // epilogue: row stride of the transposed block in bytes (padded)
+    static_assert(TILE_B % (256 * 16) == 0, "tile must split evenly over the producers' loads");
+    static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
+    static_assert(NLOAD * NBUF < 64, "vmcnt is a 6-bit counter");
+    static_assert(4 * 16 * RSO <= NBUF * TILE_B, "the epilogue's transposition space must fit in the tile ring");
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
+    // the query rows [q_abs | q_rope] of the 32 heads, laid out exactly like a cache tile (one row per
+    // head, same chunk swizzle): requested by the producers as direct-to-LDS loads right after the
+    // first tile, read into registers by the consumers after the first barrier
+    __shared__ __attribute__((aligned(1024))) unsigned char qmem[TILE_B];
+    __shared__ int jump_flag;                        // raised by a consumer whose fast pass met a score far above its reference
+    LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    // Workgroup -> query-row group and (sequence, chunk): as in decode_mfma.hip (groups of 32 query
+    // rows beyond the first go to further workgroups, 8 linear ids apart: same XCD, shared L2).
+    const int Z = (p.H + 31) / 32;
+    int wg_lin = blockIdx.x, zi = 0;
+    if (Z > 1) {
+        const int id = blockIdx.x, r = id >> 3;
+        zi = r % Z;
+        wg_lin = (r / Z) * 8 + (id & 7);
+        if (wg_lin >= p.B * p.num_splits) return;   // padding of the last group of 8
+    }
+    const int hb = zi * 32;
+    const bool stream_once = Z == 1;   // no other workgroup reads this one's cached rows
+
+    auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
+                           const size_t out_slot) {
+    // (balanced partition: everything derived from the thread index is derived again per segment
+    // from a value the compiler cannot see through, so that it is not kept in registers across
+    // segments)
+    int opaque_zero = 0;
+    if constexpr (BAL) asm volatile("" : "+v"(opaque_zero));
+    const int tid = (int)threadIdx.x + opaque_zero;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = wave >= 4;
+    const int w4 = wave & 3;
+    const int hg = w4 & 1, ch = w4 >> 1;       // consumers: head group, column half
+    const int n = lane & 15, g = lane >> 4;
+    const int HL = min(32, p.H - hb);          // query rows of this workgroup
+    if (tid == 0) jump_flag = 0;               // read after the tile loop, behind at least one barrier
+    auto o_row = [&](int h) -> uint16_t* {     // partial rows are bf16 (the io dtype of this kernel)
+        return static_cast<uint16_t*>(p.o_part) + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
+    };
+    auto lse_at = [&](int h) -> float* {
+        return p.lse_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits));
+    };
+
+    // read-only tables go through the scalar cache
+    const CONST_AS int32_t* seq_lens_c = (const CONST_AS int32_t*)p.seq_lens;
+    const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
+    const int warm = ptab[min(BAL ? seg_row0 / 64 : split * p.chunk_pages, p.max_pages - 1)];
+    int L = seq_lens_c[b];
+
+    const int head = hg * 16 + n;
+    bf16x8 qreg[NKS];   // consumers: this wave's 16 query rows as B operands, resident for the whole chunk:
+                        // lane (g, n) holds elements 8g .. 8g+7 of every 32-element k-step of head 16 hg + n
+
+    asm volatile("" :: "s"(warm));
+    L = max(0, min(L, p.max_pages * 64));
+    const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;             // first cached row of this segment
+    const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);  // one past its last row
+    if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
+        if (tid < HL) *lse_at(hb + tid) = -INFINITY;
+        return;
+    }
+    const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
+    const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
+
+    // rows of tile t that belong to this chunk (0 if its page id is outside the pool)
+    auto rows_valid = [&](int t) {
+        int page = ptab[t >> 1];
+        return (page >= 0 && page < p.num_pages) ? min(TILE_ROWS, row1 - t * TILE_ROWS) : 0;
+    };
+
+    // ---- producers: tile staging, HBM -> LDS with direct-to-LDS 128-bit loads (inline assembly:
+    // the compiler keeps no record of them).  Load k of producer w fills LDS chunks [(4k+w)*64, +64)
+    // of the tile; LDS chunk P = row r, position pc holds the row's chunk pc ^ key(r).
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    uint32_t goff[NLOAD];   // byte offset of this thread's chunk inside a tile's rows
+#pragma unroll
+    for (int k = 0; k < NLOAD; ++k) {
+        int P = (k * 4 + w4) * 64 + lane;
+        int r = P / CPR, pc = P % CPR;
+        goff[k] = (uint32_t)(r * ROWB + ((pc ^ swz_key(r)) << 4));
+    }
+    const unsigned char* kv = static_cast<const unsigned char*>(p.kv);
+    // returns the number of loads this thread issued (0 or NLOAD; uniform)
+    auto fetch_tile = [&](int t) -> int {
+        if (rows_valid(t) <= 0) return 0;   // a page outside the pool is never dereferenced
+        const unsigned char* src = kv + (size_t)ptab[t >> 1] * PAGE_B + (size_t)(t & 1) * TILE_B;
+        const uint32_t dst = lds_base + (uint32_t)(((t - t0) % NBUF) * TILE_B + w4 * 1024);
+        if (stream_once) {
+            // this workgroup is the only reader of these rows: non-temporal loads
+#pragma unroll
+            for (int k = 0; k < NLOAD; ++k) {
+                const unsigned char* gp = src + goff[k];
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            }
+        } else {
+            // further groups of query rows read the same rows from this XCD's L2: ordinary loads
+#pragma unroll
+            for (int k = 0; k < NLOAD; ++k) {
+                const unsigned char* gp = src + goff[k];
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            }
+        }
+        return NLOAD;
+    };
+
+    // producers: the query rows into their LDS area, chunk by chunk like a tile (rows of absent
+    // heads zero-filled); requested once per segment, right after the first tile's loads
+    LDS_AS unsigned char* qlds = (LDS_AS unsigned char*)qmem;
+    auto fetch_query_rows = [&]() {
+        const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
+        const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
+        const uint32_t dst = (uint32_t)(uintptr_t)qlds + (uint32_t)(w4 * 1024);
+#pragma unroll
+        for (int k = 0; k < NLOAD; ++k) {
+            const int P = (k * 4 + w4) * 64 + lane;
+            const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
+            if (r < HL) {
+                const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
+                                                      : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst + k * 4096);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(m0v), "v"(gp) : "memory");
+            } else {
+                *(LDS_AS u32x4*)(qlds + P * 16) = (u32x4){0u, 0u, 0u, 0u};
+            }
+        }
+    };
+
+    // ---- consumers: running softmax state; this lane's head = column n of the D tiles, its rows
+    // 4g .. 4g+3 of each of the tile's two 16-row blocks
+    float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
+    float l_run = 0.f;         // this lane's share of the running sum (its 8 rows per tile)
+    f32x4 oacc[WCT];
+#pragma unroll
+    for (int i = 0; i < WCT; ++i) oacc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const float sc = p.scale * LOG2E;
+    // score A operand: row 16 rb + n, chunk 4 ks + g
+    const uint32_t a_row = (uint32_t)(n * ROWB);
+    const uint32_t a_key = (uint32_t)swz_key(n);
+    uint32_t a_base[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) a_base[e] = a_row + ((((uint32_t)(4 * e + g)) ^ a_key) << 4);
+    // value A operand (transposing reads): the lane supplies row 16 rb + 4g + (n>>2), 8 bytes at
+    // element column 16 ct + 4 (n&3), i.e. chunk 2 ct + ((n&3)>>1), half (n&1)
+    const uint32_t v_row = (uint32_t)((g * 4 + (n >> 2)) * ROWB);
+    const uint32_t v_key = (uint32_t)swz_key(g * 4 + (n >> 2));
+    uint32_t v_base[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8);
+    // first cached row (of the sequence) that some query row of the sequence must not see
+    const int causal_from = L - (p.q_len - 1);
+    // maximum over the four lane groups (a block's 16 rows), on every lane
+    auto over_groups = [&](float v) {
+        v = fmaxf(v, __shfl_xor(v, 16));
+        return fmaxf(v, __shfl_xor(v, 32));
+    };
+
+    // S^T = K . Q^T for one 16-row block x 16 heads, scaled to log2 units, rows outside the chunk
+    // or beyond the query row's own position at -inf
+    auto score_block = [&](LDS_AS unsigned char* blk, int t, int rb, int n_valid, float (&x)[4]) {
+        f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        bf16x8 a0[NKS];
+#pragma unroll
+        for (int ks = 0; ks < SG; ++ks)
+            a0[ks] = *(LDS_AS bf16x8*)(blk + a_base[ks & 1] + (ks >> 1) * 128);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s0 = 0; s0 < NKS; s0 += SG) {
+#pragma unroll
+            for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks)
+                a0[ks] = *(LDS_AS bf16x8*)(blk + a_base[ks & 1] + (ks >> 1) * 128);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
+        if (n_valid < TILE_ROWS || (t + 1) * TILE_ROWS > causal_from) {
+            const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TILE_ROWS);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (rb * 16 + g * 4 + i >= seen) x[i] = -INFINITY;
+        }
+    };
+
+    // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded weights),
+    // then O^T += V^T . P^T over the tile's 32 rows: k slot 8g + j of the second contraction is
+    // tile row 4g + j (j < 4) or 16 + 4g + j - 4, which is how the weights lie in the registers
+    // after scoring and what two transposing reads (one per 16-row block) deliver
+    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x0)[4], const float (&x1)[4]) {
+        const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
+        const uint32_t p01 = pack_bf16x2(fast_exp2(x0[0] - m_use), fast_exp2(x0[1] - m_use));
+        const uint32_t p23 = pack_bf16x2(fast_exp2(x0[2] - m_use), fast_exp2(x0[3] - m_use));
+        const uint32_t p45 = pack_bf16x2(fast_exp2(x1[0] - m_use), fast_exp2(x1[1] - m_use));
+        const uint32_t p67 = pack_bf16x2(fast_exp2(x1[2] - m_use), fast_exp2(x1[3] - m_use));
+        l_run += ((bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                  (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16))) +
+                 ((bf16_bits_to_f32(p45 & 0xFFFFu) + bf16_bits_to_f32(p45 >> 16)) +
+                  (bf16_bits_to_f32(p67 & 0xFFFFu) + bf16_bits_to_f32(p67 >> 16)));
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){p01, p23, p45, p67});
+        s16x4 lo[WCT], hi[WCT];
+        auto rd = [&](int i) {
+            const int ct = ch * WCT + i;
+            LDS_AS unsigned char* a = tile + v_base[ct & 3] + (ct >> 2) * 128;
+            lo[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)a);
+            hi[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 16 * ROWB));
+        };
+#pragma unroll
+        for (int i = 0; i < VG; ++i) rd(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c0 = 0; c0 < WCT; c0 += VG) {
+#pragma unroll
+            for (int i = c0 + VG; i < c0 + 2 * VG && i < WCT; ++i) rd(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = c0; i < c0 + VG && i < WCT; ++i) {
+                const s16x8 va = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+                oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), pb, oacc[i], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- one pass over the chunk's tiles.  CAREFUL = false: the fast pass, every head keeps the
+    // maximum of its first tile with a visible row as the reference of all its exponentials and
+    // only records whether a later score exceeded it by more than FAST_GAP.  CAREFUL = true: the
+    // reference moves (and the accumulators are rescaled) whenever a tile maximum exceeds it by
+    // more than RESCALE_GAP.  Producers and consumers execute the same barriers.
+    auto sweep = [&](auto careful_tag) -> bool {
+        constexpr bool CAREFUL = decltype(careful_tag)::value;
+        int ahead[NBUF - 1];   // producers: loads issued for the tiles after the one being consumed, oldest first
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
+        if (producer) {
+            fetch_tile(t0);    // its loads are the oldest: every wait below covers them
+            if constexpr (!CAREFUL) fetch_query_rows();   // older than every later tile's loads as well
+#pragma unroll
+            for (int i = 0; i < NBUF - 2; ++i)
+                if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+        }
+        bool jumped = false;
+        for (int t = t0; t < t1; ++t) {
+            LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
+            const int n_valid = rows_valid(t);
+            if (producer) {
+                // wait until my loads of tile t have landed (younger tiles may stay in flight)
+                int younger = 0;
+#pragma unroll
+                for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];
+                if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+                else if (younger >= 2 * NLOAD)             wait_vmcnt<2 * NLOAD>();
+                else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
+                else                                       wait_vmcnt<0>();
+            }
+            // tile t has landed (every producer's part), and every consumer is done with tile t - 1
+            __syncthreads();
+            if (producer) {
+                const int tn = t + NBUF - 1;             // goes into the slot tile t - 1 has left
+                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
+#pragma unroll
+                for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];   // tile t + 1 becomes the oldest in flight
+                ahead[NBUF - 2] = 0;
+            }
+            if (n_valid < TILE_ROWS) {
+                // ragged last tile (or a page id outside the pool): rows that are not part of the
+                // sequence become zeros so that whatever they hold stays out
+                for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += ST_THREADS)
+                    *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+                __syncthreads();
+            }
+            if (!producer) {
+                if (!CAREFUL && t == t0) {
+                    // the query rows have landed with the first tile (they were requested before
+                    // the second): into registers, where they stay
+                    const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
+                    const uint32_t q_key = (uint32_t)swz_key(n);
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+                        qreg[ks] = *(LDS_AS bf16x8*)(qlds + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
+                }
+                float x0[4], x1[4];
+                score_block(tile, t, 0, n_valid, x0);
+                score_block(tile + 16 * ROWB, t, 1, n_valid, x1);
+                const float lmax = fmaxf(fmaxf(fmaxf(x0[0], x0[1]), fmaxf(x0[2], x0[3])),
+                                         fmaxf(fmaxf(x1[0], x1[1]), fmaxf(x1[2], x1[3])));
+                if constexpr (!CAREFUL) {
+                    if (__any(m_run == -INFINITY)) {       // first tile with a visible row (as a rule: the first tile)
+                        const float tmax = over_groups(lmax);
+                        if (m_run == -INFINITY) m_run = tmax;
+                    }
+                    jumped |= lmax > m_run + FAST_GAP;
+                } else {
+                    const float tmax = over_groups(lmax);
+                    if (m_run == -INFINITY) m_run = tmax;  // nothing accumulated yet: nothing to rescale
+                    if (__any(tmax > m_run + RESCALE_GAP)) {
+                        const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
+                        const float alpha = fast_exp2(m_run - m_new);   // 1 for the lanes that keep their reference
+                        l_run *= alpha;
+#pragma unroll
+                        for (int i = 0; i < WCT; ++i) oacc[i] *= alpha;
+                        m_run = m_new;
+                    }
+                }
+                accumulate_tile(tile, x0, x1);
+            }
+        }
+        return jumped;
+    };
+
+    const bool jumped = sweep(std::false_type{});
+    if (jumped) jump_flag = 1;
+    __syncthreads();   // every consumer is done with the last tile; nothing is in flight (the producers waited for it)
+    if (__builtin_expect(jump_flag != 0, 0)) {
+        // ---- careful pass (rare): the same chunk again with a moving reference
+        m_run = -INFINITY;
+        l_run = 0.f;
+#pragma unroll
+        for (int i = 0; i < WCT; ++i) oacc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        sweep(std::true_type{});
+        __syncthreads();
+    }
+
+    // ---- consumers: normalise and write the partial (bf16).  A consumer holds its column half of
+    // its 16 heads complete; a lane holds 4 consecutive columns of head n per column tile, which
+    // written straight out would give 8-byte pieces, so the block is transposed through LDS (the
+    // tile ring is free: every wave has passed a barrier after its last tile) and stored in
+    // whole runs of half a latent row.
+    if (!producer) {
+        float lt = l_run + __shfl_xor(l_run, 16);
+        lt += __shfl_xor(lt, 32);
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        LDS_AS unsigned char* mine = lds + w4 * (16 * RSO);
+#pragma unroll
+        for (int i = 0; i < WCT; ++i) {
+            const f32x4 o = oacc[i] * inv;
+            *(LDS_AS u32x2*)(mine + n * RSO + (i * 16 + g * 4) * 2) =
+                (u32x2){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        }
+        const int nrow = min(16, HL - hg * 16);
+        constexpr int LPR = WCT * 2;             // lanes (of 16 bytes = 8 bf16) covering one row of the half (32 / 16)
+        constexpr int RPI = 64 / LPR;            // rows one store instruction covers (2 / 4)
+        // all reads first, then all stores, from one base address and a row stride (computing the
+        // address of every row anew, with a wait for its LDS read in between, tripled the time
+        // of this loop)
+        const size_t row_stride = (size_t)(BAL ? 1 : p.num_splits) * D_C;   // elements between the partial rows of consecutive heads
+        const int rl = lane / LPR, c = lane % LPR;
+        uint16_t* dst0 = o_row(hb + hg * 16) + (size_t)rl * row_stride + ch * (WCT * 16) + c * 8;
+        u32x4 v[16 / RPI];
+#pragma unroll
+        for (int j = 0; j < 16 / RPI; ++j) v[j] = *(LDS_AS u32x4*)(mine + (j * RPI + rl) * RSO + c * 16);
+#pragma unroll
+        for (int j = 0; j < 16 / RPI; ++j)
+            if (j * RPI + rl < nrow)
+                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4*>(dst0 + (size_t)(j * RPI) * row_stride));
+        if (ch == 0 && head < HL && g == 0)
+            *lse_at(hb + head) = lt > 0.f ? (m_run + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+    }
+    };  // run_segment
+
+    // Workgroup -> (sequence, chunk): linear ids run over the sequences first, chunk by chunk, with
+    // the sequence rotated by the chunk index (see decode_mfma.hip).
+    const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, cy = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
+    run_segment((cx + cy) % p.B, cy, 0, 0, 0);
+}
+
+}  // namespace
+
+hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
+{
+    dim3 block(ST_THREADS);
+    if (p.d_c == 512)      decode_stream_kernel<512><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256><<<grid, block, 0, s>>>(p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace mla
