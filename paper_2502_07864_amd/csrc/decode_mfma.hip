@@ -650,14 +650,19 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     constexpr int LPR = HCT * 2;             // lanes (of 16 bytes = 8 bf16) covering one row of the half
     constexpr int RPI = 64 / LPR;            // rows one store instruction covers (2 or 4)
     static_assert(LPR == 32 || LPR == 16, "half a latent row is 512 B or 256 B");
+    // all reads first, then all stores, from one base address and a row stride (an address
+    // computed anew for every row, with a wait for its LDS read in between, tripled this loop)
+    {
+        const size_t row_stride = (size_t)(BAL ? 1 : p.num_splits) * D_C;   // elements between the partial rows of consecutive heads
+        const int rl = lane / LPR, c = lane % LPR;
+        uint16_t* dst0 = o_row(hb + hg * 16) + (size_t)rl * row_stride + tg * (HCT * 16) + c * 8;
+        u32x4 v[16 / RPI];
 #pragma unroll
-    for (int r0 = 0; r0 < 16; r0 += RPI) {
-        const int r = r0 + lane / LPR, c = lane % LPR;
-        if (r < nrow) {
-            const u32x4 v = *(LDS_AS u32x4*)(mine + r * RSO + c * 16);
-            uint16_t* dst = o_row(hb + hg * 16 + r) + tg * (HCT * 16) + c * 8;
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-        }
+        for (int j = 0; j < 16 / RPI; ++j) v[j] = *(LDS_AS u32x4*)(mine + (j * RPI + rl) * RSO + c * 16);
+#pragma unroll
+        for (int j = 0; j < 16 / RPI; ++j)
+            if (j * RPI + rl < nrow)
+                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4*>(dst0 + (size_t)(j * RPI) * row_stride));
     }
     if (tg == 0 && head < HL && g == 0)
         *lse_at(hb + head) = lt > 0.f ? (m_all + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;

@@ -454,13 +454,21 @@ __global__ __launch_bounds__(MF_THREADS, 1) void decode_mfma_wide_kernel(DecodeP
     constexpr int LPR = CW / 8;                 // lanes (of 16 bytes = 8 bf16) covering one row of the half (32 / 16)
     constexpr int RPI = 64 / LPR;               // rows one store instruction covers (2 or 4)
     const int nrow = min(32, HL - hp * 32);
-#pragma unroll 4
-    for (int r0 = 0; r0 < 32; r0 += RPI) {
-        const int r = r0 + lane / LPR, c = lane % LPR;
-        if (r < nrow) {
-            const u32x4 v = *(LDS_AS u32x4*)(mine + r * RSO + c * 16);
-            uint16_t* dst = o_row(hb + hp * 32 + r) + a * CW + c * 8;
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
+    // reads in batches of eight, then their stores, from one base address and a row stride
+    {
+        const size_t row_stride = (size_t)p.num_splits * D_C;   // elements between the partial rows of consecutive query rows
+        const int rl = lane / LPR, c = lane % LPR;
+        uint16_t* dst0 = o_row(hb + hp * 32) + (size_t)rl * row_stride + a * CW + c * 8;
+        constexpr int NI = 32 / RPI;               // store instructions (16 / 8)
+#pragma unroll
+        for (int j0 = 0; j0 < NI; j0 += 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = *(LDS_AS u32x4*)(mine + ((j0 + j) * RPI + rl) * RSO + c * 16);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if ((j0 + j) * RPI + rl < nrow)
+                    __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4*>(dst0 + (size_t)((j0 + j) * RPI) * row_stride));
         }
     }
     if (a == 0 && g == 0) {
