@@ -28,6 +28,17 @@
 //     sums, so the epilogue is normalise, transpose, store: no hand-over, no combine.
 // Both kinds meet at one workgroup barrier per tile (tile t has landed, everybody is done with
 // tile t - 1, whose slot the producers then fill again).
+//
+// FP8 = true: OCP e4m3 cache with one fp32 scale per row.  A tile is a whole page of codes (64 rows,
+// the same 36 KB as 32 bf16 rows) and travels raw, by the same direct-to-LDS loads; the codes are
+// widened exactly to bf16 where the consumers read their operands (8 codes per lane and MFMA:
+// four v_cvt_scalef32_pk_bf16_fp8 with scale 1), so both contractions are the bf16 ones and LDS
+// holds and delivers half the bytes.  The value operand comes from the 8-bit transposing read
+// (ds_read_b64_tr_b8: lane 16g + n supplies 8 bytes of row 8g + n/2 and receives rows 8g .. 8g+7
+// of column n: checked on the device), whose k order (k slot 8g + j = row 8g + j) the score
+// contraction is made to match by which LDS row each of its operand lanes reads: block bk of a
+// 32-row half scores rows 8i + 4bk .. 8i + 4bk + 3 (i = 0 .. 3), so that a lane's eight weights
+// are those of rows 8g .. 8g+7.  A row's scale multiplies its score and rides on its weight.
 #include "mla_internal.h"
 #include "mfma_tile.h"
 #include <type_traits>
@@ -38,17 +49,23 @@ namespace {
 constexpr int ST_THREADS = 512;   // 4 consumer + 4 producer wavefronts
 
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 
-template <int D_C>
+template <int D_C, bool FP8>
 __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
 {
     constexpr int NBUF = 3;                     // ring slots: one being consumed, two requested (this kernel is for short chunks)
     constexpr bool BAL = false;                 // uniform chunks only; the balanced partition runs decode_mfma.hip's kernel
     constexpr int ROW = D_C + 64;               // elements per cache row
-    constexpr int ROWB = ROW * 2;               // bytes per row
-    constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
+    constexpr int ROWB = ROW * (FP8 ? 1 : 2);   // bytes per cached row
+    constexpr int CPR = ROWB / 16;              // 16-byte chunks per cached row (72 / 40; fp8: 36 / 20)
     constexpr int PAGE_B = 64 * ROWB;           // bytes per page
-    constexpr int TILE_B = TILE_ROWS * ROWB;    // bytes per tile
+    constexpr int TR = FP8 ? 64 : 32;           // cached rows per tile (fp8: a whole page, bf16: half a page)
+    constexpr int NH = TR / 32;                 // 32-row halves of a tile, consumed one after the other
+    constexpr int TILE_B = TR * ROWB;           // bytes per tile (36864 / 20480 for either format)
+    constexpr int QROWB = ROW * 2;              // bytes per query row (bf16)
+    constexpr int QCPR = QROWB / 16;            // 16-byte chunks per query row
+    static_assert(32 * QROWB == TILE_B, "the 32 query rows are loaded like one tile");
     constexpr int NLOAD = TILE_B / (256 * 16);  // 16-byte loads per producer thread per tile (9 / 5)
     constexpr int NKS = ROW / 32;               // k-steps of the score contraction (18 / 10)
     constexpr int WCT = D_C / 32;               // column tiles of the value contraction per consumer (16 / 8)
@@ -56,7 +73,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     constexpr int VG = 4;                       // column tiles per read-ahead group (value)
     constexpr int RSO = WCT * 32 + 32;          // epilogue: row stride of the transposed block in bytes (padded)
     static_assert(TILE_B % (256 * 16) == 0, "tile must split evenly over the producers' loads");
-    static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
+    static_assert(QCPR % 8 == 0 && CPR % (FP8 ? 4 : 8) == 0, "the chunk swizzles need rows of whole groups of chunks");
     static_assert(NLOAD * NBUF < 64, "vmcnt is a 6-bit counter");
     static_assert(4 * 16 * RSO <= NBUF * TILE_B, "the epilogue's transposition space must fit in the tile ring");
 
@@ -65,6 +82,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     // head, same chunk swizzle): requested by the producers as direct-to-LDS loads right after the
     // first tile, read into registers by the consumers after the first barrier
     __shared__ __attribute__((aligned(1024))) unsigned char qmem[TILE_B];
+    __shared__ float sc_lds[FP8 ? NBUF : 1][64];     // fp8: the row scales of the tiles in the ring
     __shared__ int jump_flag;                        // raised by a consumer whose fast pass met a score far above its reference
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
@@ -124,13 +142,20 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         if (tid < HL) *lse_at(hb + tid) = -INFINITY;
         return;
     }
-    const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
-    const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
+    const int t0 = row0 / TR;                                       // tiles [t0, t1) of the sequence
+    const int t1 = (row1 + TR - 1) / TR;
+    // Chunk swizzle of a cached row in LDS (applied on the global-address side of the loads: LDS
+    // chunk position pc of row r holds the row's chunk pc ^ key(r)).  bf16: mfma_tile.h's key.
+    // fp8: rows are 64 bytes mod 256 long, so rows 4 apart share a quarter of the 256-byte bank window;
+    // the score reads touch rows {8i + 4bk + j} and the transposing reads rows 8g .. 8g+7 at one chunk
+    // index each, and with this 2-bit key (it stays inside aligned groups of 4 chunks, which also the
+    // 36- and 20-chunk rows consist of) the rows that share a quarter land on different positions.
+    auto row_key = [](int r) { return FP8 ? (((r >> 3) + (r >> 2)) & 3) : swz_key(r); };
 
     // rows of tile t that belong to this chunk (0 if its page id is outside the pool)
     auto rows_valid = [&](int t) {
-        int page = ptab[t >> 1];
-        return (page >= 0 && page < p.num_pages) ? min(TILE_ROWS, row1 - t * TILE_ROWS) : 0;
+        int page = ptab[FP8 ? t : t >> 1];
+        return (page >= 0 && page < p.num_pages) ? min(TR, row1 - t * TR) : 0;
     };
 
     // ---- producers: tile staging, HBM -> LDS with direct-to-LDS 128-bit loads (inline assembly:
@@ -142,14 +167,23 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     for (int k = 0; k < NLOAD; ++k) {
         int P = (k * 4 + w4) * 64 + lane;
         int r = P / CPR, pc = P % CPR;
-        goff[k] = (uint32_t)(r * ROWB + ((pc ^ swz_key(r)) << 4));
+        goff[k] = (uint32_t)(r * ROWB + ((pc ^ row_key(r)) << 4));
     }
     const unsigned char* kv = static_cast<const unsigned char*>(p.kv);
     // returns the number of loads this thread issued (0 or NLOAD; uniform)
     auto fetch_tile = [&](int t) -> int {
         if (rows_valid(t) <= 0) return 0;   // a page outside the pool is never dereferenced
-        const unsigned char* src = kv + (size_t)ptab[t >> 1] * PAGE_B + (size_t)(t & 1) * TILE_B;
+        const int page = ptab[FP8 ? t : t >> 1];
+        const unsigned char* src = kv + (size_t)page * PAGE_B + (FP8 ? (size_t)0 : (size_t)(t & 1) * TILE_B);
         const uint32_t dst = lds_base + (uint32_t)(((t - t0) % NBUF) * TILE_B + w4 * 1024);
+        if constexpr (FP8) {
+            if (w4 == 0) {   // the page's 64 row scales: one 4-byte direct-to-LDS load per lane
+                const float* sp = p.kv_scale + (size_t)page * 64 + lane;
+                const uint32_t m0s = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(LDS_AS float*)&sc_lds[(t - t0) % NBUF][0]);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                             :: "s"(m0s), "v"(sp) : "memory");
+            }
+        }
         if (stream_once) {
             // this workgroup is the only reader of these rows: non-temporal loads
 #pragma unroll
@@ -169,7 +203,16 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                              :: "s"(m0v), "v"(gp) : "memory");
             }
         }
-        return NLOAD;
+        return NLOAD + ((FP8 && w4 == 0) ? 1 : 0);
+    };
+    // wait until at most `younger` of this wave's loads are outstanding (the largest count on the
+    // list that does not exceed it; a tile is NLOAD loads, one more for the wave that fetches the scales)
+    auto wait_younger = [&](int younger) {
+        if (FP8 && younger >= 2 * NLOAD + 2) wait_vmcnt<2 * NLOAD + 2>();
+        else if (younger >= 2 * NLOAD)       wait_vmcnt<2 * NLOAD>();
+        else if (FP8 && younger >= NLOAD + 1) wait_vmcnt<NLOAD + 1>();
+        else if (younger >= NLOAD)           wait_vmcnt<NLOAD>();
+        else                                 wait_vmcnt<0>();
     };
 
     // producers: the query rows into their LDS area, chunk by chunk like a tile (rows of absent
@@ -182,7 +225,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 #pragma unroll
         for (int k = 0; k < NLOAD; ++k) {
             const int P = (k * 4 + w4) * 64 + lane;
-            const int r = P / CPR, c = (P % CPR) ^ swz_key(r);
+            const int r = P / QCPR, c = (P % QCPR) ^ swz_key(r);
             if (r < HL) {
                 const unsigned char* gp = c < D_C / 8 ? qa + ((size_t)r * D_C + c * 8) * 2
                                                       : qr + ((size_t)r * 64 + (c - D_C / 8) * 8) * 2;
@@ -195,87 +238,152 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         }
     };
 
-    // ---- consumers: running softmax state; this lane's head = column n of the D tiles, its rows
-    // 4g .. 4g+3 of each of the tile's two 16-row blocks
+    // ---- consumers: running softmax state; this lane's head = column n of the D tiles; of every
+    // 32-row half of a tile it owns 4 rows of each of the two 16-row score blocks (bf16: rows 4g + i
+    // and 16 + 4g + i; fp8: rows 8g + i and 8g + 4 + i)
     float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
-    float l_run = 0.f;         // this lane's share of the running sum (its 8 rows per tile)
+    float l_run = 0.f;         // this lane's share of the running sum (its 8 rows per half)
     f32x4 oacc[WCT];
 #pragma unroll
     for (int i = 0; i < WCT; ++i) oacc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const float sc = p.scale * LOG2E;
-    // score A operand: row 16 rb + n, chunk 4 ks + g
-    const uint32_t a_row = (uint32_t)(n * ROWB);
-    const uint32_t a_key = (uint32_t)swz_key(n);
-    uint32_t a_base[2];
+    // Score A operand of block bk, lane (g, n): one row of the half, elements 8 (4 ks + g) .. + 7.
+    //   bf16: row 16 bk + n, 16-byte chunk 4 ks + g;
+    //   fp8 : row 8 (n / 4) + n % 4 + 4 bk, 8 bytes: chunk 2 ks + g / 2, half g % 2.
+    // The swizzled chunk index splits into a per-lane part (low bits, xor-ed with the row's key; the
+    // key is the same in both halves of a tile, and for bf16 in both blocks) and a compile-time part.
+    uint32_t a_base[2][2];   // [block][k-step parity]
 #pragma unroll
-    for (int e = 0; e < 2; ++e) a_base[e] = a_row + ((((uint32_t)(4 * e + g)) ^ a_key) << 4);
-    // value A operand (transposing reads): the lane supplies row 16 rb + 4g + (n>>2), 8 bytes at
-    // element column 16 ct + 4 (n&3), i.e. chunk 2 ct + ((n&3)>>1), half (n&1)
-    const uint32_t v_row = (uint32_t)((g * 4 + (n >> 2)) * ROWB);
-    const uint32_t v_key = (uint32_t)swz_key(g * 4 + (n >> 2));
+    for (int bk = 0; bk < 2; ++bk) {
+        const int a_r = FP8 ? 8 * (n >> 2) + (n & 3) + 4 * bk : 16 * bk + n;   // the lane's row of the half
+        const uint32_t a_key = (uint32_t)row_key(a_r);
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            a_base[bk][e] = (uint32_t)(a_r * ROWB) +
+                            (FP8 ? ((((uint32_t)(2 * e + (g >> 1))) ^ a_key) << 4) + (uint32_t)((g & 1) * 8)
+                                 : ((((uint32_t)(4 * e + g)) ^ a_key) << 4));
+    }
+    constexpr int A_STEP = FP8 ? 64 : 128;                         // bytes from k-step ks to ks + 2
+    // Value A operand (transposing reads), lane (g, n) supplies 8 bytes:
+    //   bf16: row 4g + n / 4 of a 16-row block, element columns 16 ct + 4 (n % 4) ..: chunk 2 ct + (n % 4) / 2, half n % 2;
+    //   fp8 : row 8g + n / 2 of the half, columns 16 ct + 8 (n % 2) ..: chunk ct, half n % 2.
+    const int v_r = FP8 ? 8 * g + (n >> 1) : g * 4 + (n >> 2);
+    const uint32_t v_key = (uint32_t)row_key(v_r);
     uint32_t v_base[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-        v_base[e] = v_row + ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4) + (uint32_t)((n & 1) * 8);
+        v_base[e] = (uint32_t)(v_r * ROWB) + (uint32_t)((n & 1) * 8) +
+                    (FP8 ? ((((uint32_t)e) ^ v_key) << 4)
+                         : ((((uint32_t)(2 * e) + (uint32_t)((n & 3) >> 1)) ^ v_key) << 4));
+    constexpr int V_STEP = FP8 ? 64 : 128;                         // bytes from column tile ct to ct + 4
     // first cached row (of the sequence) that some query row of the sequence must not see
     const int causal_from = L - (p.q_len - 1);
-    // maximum over the four lane groups (a block's 16 rows), on every lane
+    // maximum over the four lane groups, on every lane
     auto over_groups = [&](float v) {
         v = fmaxf(v, __shfl_xor(v, 16));
         return fmaxf(v, __shfl_xor(v, 32));
     };
+    // eight e4m3 codes -> eight bf16, exactly (scale 1; e4m3 has 3 mantissa bits)
+    auto widen8 = [](u32x2 c) -> bf16x8 {
+        const u32x4 w = (u32x4){
+            __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[0], 1.0f, false)),
+            __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[0], 1.0f, true)),
+            __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[1], 1.0f, false)),
+            __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[1], 1.0f, true))};
+        return __builtin_bit_cast(bf16x8, w);
+    };
 
-    // S^T = K . Q^T for one 16-row block x 16 heads, scaled to log2 units, rows outside the chunk
-    // or beyond the query row's own position at -inf
-    auto score_block = [&](LDS_AS unsigned char* blk, int t, int rb, int n_valid, float (&x)[4]) {
-        f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-        bf16x8 a0[NKS];
+    // S^T = K . Q^T for the two 16-row blocks x 16 heads of the half at `half`, scaled to log2 units
+    // (fp8: times the rows' scales, returned in rs), rows outside the chunk or beyond the query
+    // row's own position at -inf.  The two blocks' contractions are interleaved: each is a chain of
+    // MFMAs into one accumulator, and a chain on its own runs at the instruction's latency, not at
+    // its issue rate.
+    auto score_half = [&](LDS_AS unsigned char* half, LDS_AS const float* scales, int t, int h, int n_valid,
+                          float (&x0)[4], float (&x1)[4], float (&rs0)[4], float (&rs1)[4]) {
+        f32x4 sacc0 = (f32x4){0.f, 0.f, 0.f, 0.f}, sacc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
+        typedef typename std::conditional<FP8, u32x2, bf16x8>::type raw_t;
+        raw_t a0[NKS], a1[NKS];
+        auto rd = [&](int ks) {
+            a0[ks] = *(LDS_AS raw_t*)(half + a_base[0][ks & 1] + (ks >> 1) * A_STEP);
+            a1[ks] = *(LDS_AS raw_t*)(half + a_base[1][ks & 1] + (ks >> 1) * A_STEP);
+        };
+        auto operand = [&](raw_t v) -> bf16x8 {
+            if constexpr (FP8) return widen8(v); else return v;
+        };
 #pragma unroll
-        for (int ks = 0; ks < SG; ++ks)
-            a0[ks] = *(LDS_AS bf16x8*)(blk + a_base[ks & 1] + (ks >> 1) * 128);
+        for (int ks = 0; ks < SG; ++ks) rd(ks);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s0 = 0; s0 < NKS; s0 += SG) {
 #pragma unroll
-            for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks)
-                a0[ks] = *(LDS_AS bf16x8*)(blk + a_base[ks & 1] + (ks >> 1) * 128);
+            for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks) rd(ks);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc, 0, 0, 0);
+            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks) {
+                sacc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(operand(a0[ks]), qreg[ks], sacc0, 0, 0, 0);
+                sacc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(operand(a1[ks]), qreg[ks], sacc1, 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+        // tile row behind D row 4g of block 0 / block 1
+        const int r0 = h * 32 + (FP8 ? 8 * g : 4 * g), r1 = r0 + (FP8 ? 4 : 16);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
-        if (n_valid < TILE_ROWS || (t + 1) * TILE_ROWS > causal_from) {
-            const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TILE_ROWS);
+        for (int i = 0; i < 4; ++i) {
+            rs0[i] = FP8 ? scales[r0 + i] : 1.f;
+            rs1[i] = FP8 ? scales[r1 + i] : 1.f;
+            x0[i] = sacc0[i] * (FP8 ? sc * rs0[i] : sc);
+            x1[i] = sacc1[i] * (FP8 ? sc * rs1[i] : sc);
+        }
+        if (n_valid < TR || (t + 1) * TR > causal_from) {
+            const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TR);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (rb * 16 + g * 4 + i >= seen) x[i] = -INFINITY;
+            for (int i = 0; i < 4; ++i) {
+                if (r0 + i >= seen) x0[i] = -INFINITY;
+                if (r1 + i >= seen) x1[i] = -INFINITY;
+            }
         }
     };
 
-    // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded weights),
-    // then O^T += V^T . P^T over the tile's 32 rows: k slot 8g + j of the second contraction is
-    // tile row 4g + j (j < 4) or 16 + 4g + j - 4, which is how the weights lie in the registers
-    // after scoring and what two transposing reads (one per 16-row block) deliver
-    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x0)[4], const float (&x1)[4]) {
+    // weights p = 2^(x - m_run) rounded to bf16, then O^T += V^T . P^T over the half's 32 rows with
+    // K = 32: the lane's eight weights are the B operand as they stand, k slot 8g + j being
+    //   bf16: half row 4g + j (j < 4) or 16 + 4g + j - 4, which two 16-bit transposing reads (one per
+    //         16-row block) deliver; the normaliser sums exactly the rounded weights;
+    //   fp8 : half row 8g + j, which one 8-bit transposing read delivers (codes, widened here); a
+    //         row's scale rides on its weight, the normaliser sums the plain weights.
+    auto accumulate_half = [&](LDS_AS unsigned char* half, const float (&x0)[4], const float (&x1)[4],
+                               const float (&rs0)[4], const float (&rs1)[4]) {
         const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
-        const uint32_t p01 = pack_bf16x2(fast_exp2(x0[0] - m_use), fast_exp2(x0[1] - m_use));
-        const uint32_t p23 = pack_bf16x2(fast_exp2(x0[2] - m_use), fast_exp2(x0[3] - m_use));
-        const uint32_t p45 = pack_bf16x2(fast_exp2(x1[0] - m_use), fast_exp2(x1[1] - m_use));
-        const uint32_t p67 = pack_bf16x2(fast_exp2(x1[2] - m_use), fast_exp2(x1[3] - m_use));
-        l_run += ((bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
-                  (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16))) +
-                 ((bf16_bits_to_f32(p45 & 0xFFFFu) + bf16_bits_to_f32(p45 >> 16)) +
-                  (bf16_bits_to_f32(p67 & 0xFFFFu) + bf16_bits_to_f32(p67 >> 16)));
+        float e0[4], e1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { e0[i] = fast_exp2(x0[i] - m_use); e1[i] = fast_exp2(x1[i] - m_use); }
+        uint32_t p01, p23, p45, p67;
+        if constexpr (FP8) {
+            l_run += ((e0[0] + e0[1]) + (e0[2] + e0[3])) + ((e1[0] + e1[1]) + (e1[2] + e1[3]));
+            p01 = pack_bf16x2(e0[0] * rs0[0], e0[1] * rs0[1]); p23 = pack_bf16x2(e0[2] * rs0[2], e0[3] * rs0[3]);
+            p45 = pack_bf16x2(e1[0] * rs1[0], e1[1] * rs1[1]); p67 = pack_bf16x2(e1[2] * rs1[2], e1[3] * rs1[3]);
+        } else {
+            p01 = pack_bf16x2(e0[0], e0[1]); p23 = pack_bf16x2(e0[2], e0[3]);
+            p45 = pack_bf16x2(e1[0], e1[1]); p67 = pack_bf16x2(e1[2], e1[3]);
+            l_run += ((bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                      (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16))) +
+                     ((bf16_bits_to_f32(p45 & 0xFFFFu) + bf16_bits_to_f32(p45 >> 16)) +
+                      (bf16_bits_to_f32(p67 & 0xFFFFu) + bf16_bits_to_f32(p67 >> 16)));
+        }
         const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){p01, p23, p45, p67});
-        s16x4 lo[WCT], hi[WCT];
+        u32x2 lo[WCT], hi[FP8 ? 1 : WCT];
         auto rd = [&](int i) {
             const int ct = ch * WCT + i;
-            LDS_AS unsigned char* a = tile + v_base[ct & 3] + (ct >> 2) * 128;
-            lo[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)a);
-            hi[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 16 * ROWB));
+            LDS_AS unsigned char* a = half + v_base[ct & 3] + (ct >> 2) * V_STEP;
+            if constexpr (FP8) {
+                lo[i] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)a));
+            } else {
+                lo[i] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)a));
+                hi[i] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 16 * ROWB)));
+            }
+        };
+        auto operand = [&](int i) -> bf16x8 {
+            if constexpr (FP8) return widen8(lo[i]);
+            else return __builtin_bit_cast(bf16x8, (u32x4){lo[i][0], lo[i][1], hi[i][0], hi[i][1]});
         };
 #pragma unroll
         for (int i = 0; i < VG; ++i) rd(i);
@@ -286,10 +394,8 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
             for (int i = c0 + VG; i < c0 + 2 * VG && i < WCT; ++i) rd(i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = c0; i < c0 + VG && i < WCT; ++i) {
-                const s16x8 va = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), pb, oacc[i], 0, 0, 0);
-            }
+            for (int i = c0; i < c0 + VG && i < WCT; ++i)
+                oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(operand(i), pb, oacc[i], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -320,10 +426,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                 int younger = 0;
 #pragma unroll
                 for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];
-                if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
-                else if (younger >= 2 * NLOAD)             wait_vmcnt<2 * NLOAD>();
-                else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
-                else                                       wait_vmcnt<0>();
+                wait_younger(younger);
             }
             // tile t has landed (every producer's part), and every consumer is done with tile t - 1
             __syncthreads();
@@ -334,26 +437,32 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                 for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];   // tile t + 1 becomes the oldest in flight
                 ahead[NBUF - 2] = 0;
             }
-            if (n_valid < TILE_ROWS) {
+            if (n_valid < TR) {
                 // ragged last tile (or a page id outside the pool): rows that are not part of the
-                // sequence become zeros so that whatever they hold stays out
-                for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += ST_THREADS)
+                // sequence become zeros (fp8: and so do their scales) so that whatever they hold stays out
+                for (int i = tid; i < (TR - n_valid) * CPR; i += ST_THREADS)
                     *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+                if constexpr (FP8) {
+                    if (tid >= n_valid && tid < TR) sc_lds[(t - t0) % NBUF][tid] = 0.f;
+                }
                 __syncthreads();
             }
             if (!producer) {
                 if (!CAREFUL && t == t0) {
                     // the query rows have landed with the first tile (they were requested before
                     // the second): into registers, where they stay
-                    const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
+                    const uint32_t q_row = (uint32_t)((hg * 16 + n) * QROWB);
                     const uint32_t q_key = (uint32_t)swz_key(n);
 #pragma unroll
                     for (int ks = 0; ks < NKS; ++ks)
                         qreg[ks] = *(LDS_AS bf16x8*)(qlds + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
                 }
-                float x0[4], x1[4];
-                score_block(tile, t, 0, n_valid, x0);
-                score_block(tile + 16 * ROWB, t, 1, n_valid, x1);
+                LDS_AS const float* scales = (LDS_AS const float*)&sc_lds[FP8 ? (t - t0) % NBUF : 0][0];
+#pragma unroll
+                for (int h = 0; h < NH; ++h) {
+                LDS_AS unsigned char* half = tile + h * 32 * ROWB;
+                float x0[4], x1[4], rs0[4], rs1[4];
+                score_half(half, scales, t, h, n_valid, x0, x1, rs0, rs1);
                 const float lmax = fmaxf(fmaxf(fmaxf(x0[0], x0[1]), fmaxf(x0[2], x0[3])),
                                          fmaxf(fmaxf(x1[0], x1[1]), fmaxf(x1[2], x1[3])));
                 if constexpr (!CAREFUL) {
@@ -374,7 +483,8 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                         m_run = m_new;
                     }
                 }
-                accumulate_tile(tile, x0, x1);
+                accumulate_half(half, x0, x1, rs0, rs1);
+                }
             }
         }
         return jumped;
@@ -438,11 +548,13 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 
 }  // namespace
 
-hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
+hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s, bool fp8)
 {
     dim3 block(ST_THREADS);
-    if (p.d_c == 512)      decode_stream_kernel<512><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_stream_kernel<256><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512 && !fp8)      decode_stream_kernel<512, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && !fp8) decode_stream_kernel<256, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 512 && fp8)  decode_stream_kernel<512, true><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256 && fp8)  decode_stream_kernel<256, true><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

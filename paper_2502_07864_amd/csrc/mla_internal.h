@@ -141,9 +141,9 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code)
 hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
 bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
-// bf16 caches, uniform chunks of at most 32 tiles: the kernel with separate requesting and consuming
-// wavefronts (same grid as launch_decode_mfma's)
-hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s);
+// uniform chunks, bf16 caches (chunks of at most 32 tiles) and fp8 caches: the kernel with separate
+// requesting and consuming wavefronts (same grid as launch_decode_mfma's)
+hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s, bool fp8);
 bool       decode_mfma_wide_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s);   // 64 query rows per workgroup
 hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s);  // causal attention over materialised keys / values
