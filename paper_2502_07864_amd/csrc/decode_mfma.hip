@@ -809,7 +809,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s, false);
     // fp8 caches of any chunk length: raw codes through the ring, widened where the operands are read
     // (C5: 92.4 -> 86.3 us against the kernel below, which widens a tile into LDS before it is consumed)
-    if (fp8) return launch_decode_stream(p, grid, s, true);
+    if (fp8) return launch_decode_stream_fp8(p, grid, s);
     if (p.d_c == 512 && !fp8)      launch_one<512, false, false>(p, grid, block, s, depth);
     else if (p.d_c == 256 && !fp8) launch_one<256, false, false>(p, grid, block, s, depth);
     else if (p.d_c == 512 && fp8)  launch_one<512, true, false>(p, grid, block, s, depth);
