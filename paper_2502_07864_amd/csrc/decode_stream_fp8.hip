@@ -51,6 +51,14 @@ constexpr int SF_THREADS = 512;   // 4 V + 4 S wavefronts
 typedef __attribute__((ext_vector_type(2))) int i32x2;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
+// s_waitcnt vmcnt(min(younger, N))
+template <int N>
+__device__ __forceinline__ void wait_at_most(int younger)
+{
+    if (younger >= N) wait_vmcnt<N>();
+    else if constexpr (N > 0) wait_at_most<N - 1>(younger);
+}
+
 template <int D_C>
 __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(DecodeParams p)
 {
@@ -215,19 +223,8 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
         return (k_last - k_first) + ((swave && w4 == 0) ? 1 : 0);
     };
     // wait until at most `younger` of this wave's loads are outstanding (the count is an immediate of
-    // the instruction: the largest on the list that does not exceed it; a tile is NLV loads of a V
-    // wavefront, NLOAD - NLV of an S wavefront, one more for the one that fetches the scales)
-    auto wait_younger = [&](int younger) {
-        constexpr int NLS = NLOAD - NLV;
-        if (younger >= 2 * NLV)            wait_vmcnt<2 * NLV>();
-        else if (younger >= 2 * NLS + 2)   wait_vmcnt<2 * NLS + 2>();
-        else if (younger >= 2 * NLS)       wait_vmcnt<2 * NLS>();
-        else if (younger >= NLV)           wait_vmcnt<NLV>();
-        else if (younger >= NLS + 1)       wait_vmcnt<NLS + 1>();
-        else if (younger >= NLS)           wait_vmcnt<NLS>();
-        else                               wait_vmcnt<0>();
-    };
-    static_assert(2 * NLV >= 2 * (NLOAD - NLV) + 2 && NLV >= NLOAD - NLV + 1, "the list above is in descending order");
+    // the instruction, hence the chain of cases)
+    auto wait_younger = [&](int younger) { wait_at_most<2 * NLOAD + 2>(younger); };
     // the query rows [q_abs | q_rope] of the 32 heads into slot 3, laid out like 32 rows of a bf16
     // tile (one row per head, mfma_tile.h's chunk swizzle; rows of absent heads zero-filled)
     LDS_AS unsigned char* qlds = lds + 3 * TILE_B;
@@ -306,7 +303,7 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
     // block 1), rope: block 0, block 1; a latent operand feeds two instructions (the query rows' two
     // terms), a rope operand one (both terms at once).  An LDS read of this width takes about 200
     // cycles to come back (measured): the reads run three operands ahead.
-    auto score_half = [&](LDS_AS unsigned char* half, f32x4 (&sacc)[2]) {
+    auto score_half = [&](LDS_AS unsigned char* half, LDS_AS const float* scales, int h, f32x4 (&sacc)[2], f32x4 (&rs)[2]) {
         constexpr int NO = 2 * NJ + 2;                       // operands of the half
         constexpr int D = 3;                                 // operands requested ahead
         u32x4 op[NO][2];
@@ -319,6 +316,9 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
         sacc[0] = sacc[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int m = 0; m < D && m < NO; ++m) ord(m);
+        // the rows' scales (lane (g, n): rows 8g .. 8g+7 of the half), needed right behind the last instruction
+#pragma unroll
+        for (int bk = 0; bk < 2; ++bk) rs[bk] = *(LDS_AS const f32x4*)(scales + h * 32 + 8 * g + 4 * bk);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < NO; ++m) {
@@ -333,19 +333,16 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // the sums of half h of tile t -> scores in log2 units (times the rows' scales, returned in rs, and
+    // the sums of half h of tile t -> scores in log2 units (times the rows' scales rs and
     // the power of two taken out of the query rows), rows outside the chunk or beyond the query row's
     // own position at -inf
-    auto finish_half = [&](const f32x4 (&sacc)[2], LDS_AS const float* scales, int t, int h, int n_valid,
-                           float (&x)[2][4], f32x4 (&rs)[2]) {
+    auto finish_half = [&](const f32x4 (&sacc)[2], const f32x4 (&rs)[2], int t, int h, int n_valid, float (&x)[2][4]) {
         const float unit = sc * q_unit;
         const int r0 = h * 32 + 8 * g;   // tile row behind D row 4g of block 0; block 1: 4 rows further
 #pragma unroll
-        for (int bk = 0; bk < 2; ++bk) {
-            rs[bk] = *(LDS_AS const f32x4*)(scales + r0 + 4 * bk);
+        for (int bk = 0; bk < 2; ++bk)
 #pragma unroll
             for (int i = 0; i < 4; ++i) x[bk][i] = sacc[bk][i] * (unit * rs[bk][i]);
-        }
         if (n_valid < TR || (t + 1) * TR > causal_from) {
             const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TR);
 #pragma unroll
@@ -433,8 +430,8 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
             f32x4 rso[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                score_half(tile + h * 32 * ROWB, sacc);
-                finish_half(sacc, scales, t, h, n_valid, x, rs);
+                score_half(tile + h * 32 * ROWB, scales, h, sacc, rs);
+                finish_half(sacc, rs, t, h, n_valid, x);
                 reference_step(careful_tag, x, jumped, factor);
                 if (h == hh) {
 #pragma unroll
@@ -447,8 +444,8 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
             }
             weigh_half(xo, rso, par);
         } else {
-            score_half(tile + hh * 32 * ROWB, sacc);
-            finish_half(sacc, scales, t, hh, n_valid, x, rs);
+            score_half(tile + hh * 32 * ROWB, scales, hh, sacc, rs);
+            finish_half(sacc, rs, t, hh, n_valid, x);
             reference_step(careful_tag, x, jumped, factor);
             weigh_half(x, rs, par);
         }
@@ -469,7 +466,7 @@ __global__ __launch_bounds__(SF_THREADS, 1) void decode_stream_fp8_kernel(Decode
         for (int e = 0; e < 4; ++e) vb[e] = base + ((((uint32_t)e) ^ key) << 4);
     }
     auto v_tile = [&](auto careful_tag, LDS_AS unsigned char* vtile, int par) {
-        constexpr int VP = 4;                  // column tiles whose reads are in flight
+        constexpr int VP = 4;                   // column tiles whose reads are in flight
         u32x2 vv[WCT][2];
         auto value_read = [&](int i) {
             const int ct = ch * WCT + i;
