@@ -806,9 +806,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     if (p.H > 32) grid = dim3(grid_1d(p));
     // short chunks: the kernel whose consumers do not issue the requests themselves (C2: 29.0 -> 27.5 us);
     // on long chunks its doubled score contraction makes it the slower one (C4, 64 tiles: 55.2 against 53.1 us)
-    if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s, false);
-    // fp8 caches of any chunk length: raw codes through the ring, widened where the operands are read
-    // (C5: 92.4 -> 86.3 us against the kernel below, which widens a tile into LDS before it is consumed)
+    if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s);
+    // fp8 caches of any chunk length: the kernel that contracts the codes as they are (C5: 92.4 -> 62 us
+    // against the kernel below, which widens a tile to bf16 in LDS before it is consumed)
     if (fp8) return launch_decode_stream_fp8(p, grid, s);
     if (p.d_c == 512 && !fp8)      launch_one<512, false, false>(p, grid, block, s, depth);
     else if (p.d_c == 256 && !fp8) launch_one<256, false, false>(p, grid, block, s, depth);

@@ -141,9 +141,9 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code)
 hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype cache, hipStream_t s);
 bool       decode_mfma_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced = false);
-// uniform chunks, bf16 caches (chunks of at most 32 tiles) and fp8 caches: the kernel with separate
-// requesting and consuming wavefronts (same grid as launch_decode_mfma's)
-hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s, bool fp8);
+// uniform chunks of at most 32 tiles, bf16 caches: the kernel with separate requesting and consuming
+// wavefronts (same grid as launch_decode_mfma's)
+hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s);
 // uniform chunks, fp8 caches: wavefronts that turn tiles into softmax weights beside wavefronts that
 // contract the tile before with them (same grid as launch_decode_mfma's)
 hipError_t launch_decode_stream_fp8(const DecodeParams& p, dim3 grid, hipStream_t s);
