@@ -91,8 +91,8 @@ def parse():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch the page-gather kernel (a plain copy of the whole cache, "
                          "known size) so hardware byte counters can be scaled against it")
-    ap.add_argument("--traffic-json", default=str(ROOT / "profiles" / "decode_mfma_C2_traffic.json"),
-                    help="HBM traffic per launch from rocprofv3 counters, if recorded")
+    ap.add_argument("--traffic-json", default=str(ROOT / "profiles" / "decode_traffic.json"),
+                    help="HBM traffic per launch of the decode kernels from rocprofv3 counters, per workload, if recorded")
     return ap.parse_args()
 
 
@@ -288,19 +288,43 @@ def main():
     cache_bytes = w.cache_bytes_per_step                      # C2: 1152 B x 131072 tokens
     dec_avg_us = float(dec_b2b_us)
     achieved = cache_bytes / (dec_avg_us * 1e-6) / 1e9
-    # HBM bytes per launch from the committed rocprofv3 counter summary; only valid while the
-    # kernel source is the one the counters were taken on
-    traffic = None
+    # which kernel mla_decode_paged launches for this call (the library's dispatch rule, restated)
+    fp8 = w.cache_dtype == "fp8_e4m3"
+    if w.io_dtype != "bf16":
+        kernel_name = "decode_portable_kernel<float, float>"
+    elif T > 1:
+        kernel_name = f"decode_mfma_wide_kernel<{d_c}>"
+    elif args.balanced:
+        tiles = 2 * d.page_table.shape[1] // max(1, S)
+        kernel_name = f"decode_mfma_kernel<{d_c}, {'true, 2' if fp8 else 'false, ' + ('3' if tiles <= 64 else '4')}, 1, true>"
+    elif fp8:
+        kernel_name = f"decode_stream_fp8_kernel<{d_c}>"
+    else:
+        tiles = 2 * (-(-d.page_table.shape[1] // S))
+        kernel_name = (f"decode_stream_kernel<{d_c}>" if tiles <= 32 else
+                       f"decode_mfma_kernel<{d_c}, false, {'3' if tiles <= 64 else '4'}, 1, false>")
+    # HBM bytes per launch from the committed rocprofv3 counter summary; only valid for the default
+    # launch configuration of the workload and while the kernel sources are the ones the counters
+    # were taken on
+    traffic, traffic_source = None, None
     tp = Path(args.traffic_json)
-    if tp.exists() and args.workload == "C2":
+    default_config = args.partition == "auto" and T == 1 and not args.unfused_tail and S == (4 if args.workload == "C3" else w.num_splits)
+    if tp.exists() and default_config:
         try:
             import hashlib
-            tj = json.loads(tp.read_text())
-            src = ROOT / "paper_2502_07864_amd" / "csrc" / "decode_mfma.hip"
-            if hashlib.sha256(src.read_bytes()).hexdigest()[:16] == tj.get("kernel_source_sha256_16"):
-                traffic = tj.get("hbm_bytes_per_launch")
+            tj = json.loads(tp.read_text()).get(args.workload)
+            if tj and tj.get("kernel") == kernel_name:
+                csrc = ROOT / "paper_2502_07864_amd" / "csrc"
+                same = all(hashlib.sha256((csrc / f).read_bytes()).hexdigest()[:16] == h
+                           for f, h in tj.get("source_sha256_16", {}).items())
+                if same:
+                    traffic = tj.get("hbm_bytes_per_launch")
+                    traffic_source = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (one pass each), scaled by the page-gather "
+                                      f"copy of the same run; {tj.get('summary')}")
+                else:
+                    traffic_source = "null: the kernel source has changed since the counters in profiles/decode_traffic.json were taken"
         except Exception:
-            traffic = None
+            traffic, traffic_source = None, None
 
     rec = {
         "metric": METRICS[args.workload] + (f", {T} query tokens per sequence" if T > 1 else ""),
@@ -330,11 +354,9 @@ def main():
                                            "p90": round(float(np.percentile(dec_us, 90)), 2)},
                        ("merge+out_proj" if args.unfused_tail else "merge_out_proj_fused"):
                            {"avg": round(float(mrg_us.mean()), 2)}},
-        "roofline": {"bound": "hbm", "kernel": {"C2": "decode_mfma_kernel<512, false, 4, 1, BAL>", "C3": "decode_mfma_kernel<512, false, 4, 1, BAL>",
-                                "C4": "decode_mfma_kernel<256, false, 4, 1, BAL>", "C5": "decode_mfma_kernel<512, true, 4, 1, BAL>",
-                                "C1": "decode_portable_kernel<float, float>"}[args.workload].replace("BAL", "true" if args.balanced else "false"),
+        "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": cache_bytes,
                      "launch_us": round(dec_avg_us, 2),
                      "timing": f"mean of {args.steps} back-to-back launches between two HIP events on the launch stream"},

@@ -121,6 +121,28 @@ def test_offline_fold_of_W_UK_into_the_query_projection(mla):
     assert max_abs_rel(q_folded, q_two_step) <= TOL["bf16"]
 
 
+def test_offline_fold_of_W_UV_into_the_output_projection(mla):
+    """App. A.2.2 (the second rewrite): y = W^O [W^{UV}_h o_h]_h = sum_h W'^O_h o^_h with
+    W'^O_h = W^{UV}_h W^O_h, built offline with the library's own per-head product by passing the d_c
+    rows of every W^{UV}_h as the batch:  fold[c, h, :] = W_UV[h][c, :] . W^O[h].  The folded route
+    sum_h o^_h . fold[:, h, :] then equals W^O applied to out_proj's result."""
+    import torch
+    D, H, d_head, d_c, B = 384, 8, 128, 512, 5
+    r = synth.stream(12, 3)
+    Wv = synth.store(synth.normal(r, (H, d_c, d_head), 1 / math.sqrt(d_c)), "bf16")      # [H, d_c, d_head]
+    WO = synth.store(synth.normal(r, (H, d_head, D), 1 / math.sqrt(H * d_head)), "bf16") # [H, d_head, D]
+    o_lat = synth.normal(r, (B, H, d_c)).astype(np.float64)
+    rows = np.ascontiguousarray(np.transpose(Wv, (1, 0, 2)))                              # [d_c, H, d_head]: the batch
+    fold = mla.absorb_q(to_torch(rows, "bf16"), to_torch(WO, "bf16"))                     # [d_c, H, D] on the GPU
+    torch.cuda.synchronize()
+    want_fold = oracle.absorb_q(rows, WO)                                                  # fp64, from the stored values
+    assert max_abs_rel(widen_gpu(fold), want_fold) <= TOL["bf16"]
+    y_folded = np.einsum("bhc,chD->bD", o_lat, widen_gpu(fold).astype(np.float64))
+    o_head = np.einsum("bhc,hck->bhk", o_lat, oracle.widen(Wv).astype(np.float64))
+    y_two_step = np.einsum("bhk,hkD->bD", o_head, oracle.widen(WO).astype(np.float64))
+    assert max_abs_rel(y_folded, y_two_step) <= TOL["bf16"]
+
+
 # ------------------------------------------------------------ decode, fp32
 
 @pytest.mark.parametrize("num_splits", [1, 4, 16])
