@@ -108,9 +108,11 @@ int mla_out_proj(const void* o_lat, const void* W_UV, void* out,
 
 /*
  * Bytes of device workspace mla_decode_paged needs for these sizes (split-KV
- * partial results: fp32 partial outputs and log-sum-exps for B * (S + 1)
- * chunks, S as described under num_splits, plus a [B, 2] int32 table the
- * balanced partition uses).  The same size serves both partitions.
+ * partial results for B * (S + 1) chunks, S as described under num_splits:
+ * partial outputs in the io dtype, sized here as if they were fp32, and fp32
+ * log-sum-exps; plus a [B, 2] int32 table the balanced partition uses).  The
+ * same size serves both partitions and both io dtypes.  What the workspace
+ * holds after MLA_FLAG_SKIP_MERGE is for the merge calls of this library only.
  * Pure host function; returns 0 if an argument is <= 0.
  */
 size_t mla_decode_workspace_bytes(int B, int H, int d_c, int num_splits);
