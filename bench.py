@@ -243,6 +243,24 @@ def main():
     torch.cuda.synchronize()
     dec_call_us = e0.elapsed_time(e1) * 1e3 / args.steps
 
+    # the bf16 stream kernel's launch shape with everything but the tile traffic taken out (same
+    # grid, ring, requests, waits and barriers; no query rows, arithmetic or output): what reading
+    # the cached rows once costs in this shape, the floor the decode kernel's time is read against
+    stream_only_us = None
+    if (w.io_dtype == "bf16" and w.cache_dtype == "bf16" and T == 1 and not args.balanced
+            and 2 * (-(-d.page_table.shape[1] // S)) <= 32):
+        def probe(i):
+            k = i % len(pools)
+            mla.diag_stream_tiles(pools[k], tables[k], d.seq_lens, S)
+        for i in range(min(args.warmup, 10)):
+            probe(i)
+        e0.record()
+        for i in range(args.steps):
+            probe(i)
+        e1.record()
+        torch.cuda.synchronize()
+        stream_only_us = e0.elapsed_time(e1) * 1e3 / args.steps
+
     # last pass (after everything above, it overwrites B cache rows): the cache-append call that
     # produces the next token's row, model dimension 4096, back to back
     append = None
@@ -301,7 +319,7 @@ def main():
         kernel_name = f"decode_stream_fp8_kernel<{d_c}>"
     else:
         tiles = 2 * (-(-d.page_table.shape[1] // S))
-        kernel_name = (f"decode_stream_kernel<{d_c}>" if tiles <= 32 else
+        kernel_name = (f"decode_stream_kernel<{d_c}, false>" if tiles <= 32 else
                        f"decode_mfma_kernel<{d_c}, false, {'3' if tiles <= 64 else '4'}, 1, false>")
     # HBM bytes per launch from the committed rocprofv3 counter summary; only valid for the default
     # launch configuration of the workload and while the kernel sources are the ones the counters
@@ -362,6 +380,12 @@ def main():
                      "timing": f"mean of {args.steps} back-to-back launches between two HIP events on the launch stream"},
     }
 
+    if stream_only_us is not None:
+        rec["roofline"]["stream_only"] = {
+            "kernel": f"decode_stream_kernel<{d_c}, true>", "launch_us": round(float(stream_only_us), 2),
+            "frac": round(cache_bytes / (stream_only_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+            "note": "mla_diag_stream_tiles: the decode kernel's grid, tile ring, loads, waits and barriers with no "
+                    "arithmetic and no output, back to back like launch_us"}
     if append is not None:
         rec["cache_append"] = append
 

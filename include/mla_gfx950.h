@@ -408,6 +408,27 @@ int mla_gather_paged(const void* kv_cache, const int32_t* page_table,
                      int B, int max_len, int row_bytes, int page_size,
                      int num_pages, int max_pages_per_seq, void* hip_stream);
 
+/*
+ * Diagnostic: how fast one launch of the bf16 decode kernel's shape can stream
+ * a cache at all.  Runs the tile requests, counted waits and per-tile barriers
+ * of the kernel mla_decode_paged uses for short uniform chunks (grid B x
+ * num_splits, ring of three 36 KB tiles per workgroup, non-temporal
+ * direct-to-LDS loads) with no query rows, no arithmetic and no output: the
+ * time of a launch is what Sec. 3.3's second line costs on this part when
+ * everything but reading the cached rows once is free.  bench.py reports it
+ * beside the decode kernel's time.
+ *
+ *   kv_cache   [num_pages, 64, d_c + 64] bf16 (device), d_c 256 or 512
+ *   page_table [B, max_pages_per_seq] int32, seq_lens [B] int32 (device)
+ *   num_splits chunks per sequence, as for mla_decode_paged
+ *
+ * Reads only; page ids outside [0, num_pages) are skipped.  Returns MLA_OK or
+ * an error code as the other calls do; allocates nothing.
+ */
+int mla_diag_stream_tiles(const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens,
+                          int B, int d_c, int num_pages, int max_pages_per_seq, int num_splits,
+                          void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -455,4 +455,22 @@ int mla_gather_paged(const void* kv_cache, const int32_t* page_table, const int3
     return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
 }
 
+int mla_diag_stream_tiles(const void* kv_cache, const int32_t* page_table, const int32_t* seq_lens,
+                          int B, int d_c, int num_pages, int max_pages_per_seq, int num_splits,
+                          void* hip_stream)
+{
+    if (!kv_cache || !page_table || !seq_lens) return MLA_ERR_NULL;
+    if (B <= 0 || num_pages <= 0 || max_pages_per_seq <= 0 || num_splits <= 0) return MLA_ERR_SHAPE;
+    if ((long long)max_pages_per_seq * 64 > 0x7FFFFFFFLL) return MLA_ERR_SHAPE;
+    if ((d_c != 256 && d_c != 512) || B > 65535 || num_splits > 65535) return MLA_ERR_UNSUPPORTED;
+    DecodeParams p = {};
+    p.kv = kv_cache; p.page_table = page_table; p.seq_lens = seq_lens;
+    p.B = B; p.H = 32; p.heads = 32; p.q_len = 1; p.q_inner = 1;
+    p.d_c = d_c; p.d_rope = 64; p.page_size = 64; p.num_pages = num_pages; p.max_pages = max_pages_per_seq;
+    p.num_splits = min(num_splits, max_pages_per_seq);
+    p.chunk_pages = (max_pages_per_seq + p.num_splits - 1) / p.num_splits;
+    hipError_t e = launch_decode_stream_probe(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MLA_OK : MLA_ERR_HIP;
+}
+
 }  // extern "C"

@@ -39,7 +39,9 @@ constexpr int ST_THREADS = 512;   // 4 consumer + 4 producer wavefronts
 
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-template <int D_C>
+// PROBE = true: the diagnostic variant behind mla_diag_stream_tiles: the same tile requests, waits and
+// barriers, no query rows, no arithmetic, no output (how fast this launch shape can stream at all).
+template <int D_C, bool PROBE>
 __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
 {
     constexpr int NBUF = 3;                     // ring slots: one being consumed, two requested (this kernel is for short chunks)
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;             // first cached row of this segment
     const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);  // one past its last row
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
-        if (tid < HL) *lse_at(hb + tid) = -INFINITY;
+        if (!PROBE && tid < HL) *lse_at(hb + tid) = -INFINITY;
         return;
     }
     const int t0 = row0 / TILE_ROWS;                                // tiles [t0, t1) of the sequence
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
         if (producer) {
             fetch_tile(t0);    // its loads are the oldest: every wait below covers them
-            if constexpr (!CAREFUL) fetch_query_rows();   // older than every later tile's loads as well
+            if constexpr (!CAREFUL && !PROBE) fetch_query_rows();   // older than every later tile's loads as well
 #pragma unroll
             for (int i = 0; i < NBUF - 2; ++i)
                 if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
@@ -349,7 +351,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                     *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
                 __syncthreads();
             }
-            if (!producer) {
+            if (!producer && !PROBE) {
                 if (!CAREFUL && t == t0) {
                     // the query rows have landed with the first tile (they were requested before
                     // the second): into registers, where they stay
@@ -390,6 +392,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const bool jumped = sweep(std::false_type{});
     if (jumped) jump_flag = 1;
     __syncthreads();   // every consumer is done with the last tile; nothing is in flight (the producers waited for it)
+    if constexpr (PROBE) return;
     if (__builtin_expect(jump_flag != 0, 0)) {
         // ---- careful pass (rare): the same chunk again with a moving reference
         m_run = -INFINITY;
@@ -448,8 +451,17 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
 {
     dim3 block(ST_THREADS);
-    if (p.d_c == 512)      decode_stream_kernel<512><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_stream_kernel<256><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_stream_kernel<512, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256, false><<<grid, block, 0, s>>>(p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_stream_probe(const DecodeParams& p, hipStream_t s)
+{
+    dim3 grid(p.B, p.num_splits), block(ST_THREADS);
+    if (p.d_c == 512)      decode_stream_kernel<512, true><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256, true><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

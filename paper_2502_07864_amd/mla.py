@@ -24,7 +24,7 @@ EXPORTS = ("mla_status_string", "mla_version", "mla_absorb_q", "mla_out_proj",
            "mla_decode_workspace_bytes", "mla_decode_paged", "mla_merge_partials",
            "mla_merge_out_proj", "mla_gather_paged", "mla_append_workspace_bytes", "mla_cache_append",
            "mla_decode_paged_multi", "mla_merge_out_proj_multi", "mla_prefill_workspace_bytes", "mla_prefill_mha",
-           "mla_static_scratch_bytes", "mla_decode_paged_static")
+           "mla_static_scratch_bytes", "mla_decode_paged_static", "mla_diag_stream_tiles")
 
 
 class MlaError(RuntimeError):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.mla_merge_out_proj.argtypes = [vp, ctypes.c_size_t, vp, vp, vp, vp, i, i, i, i, i, i, u, vp]
         L.mla_gather_paged.restype = i
         L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        L.mla_diag_stream_tiles.restype = i
+        L.mla_diag_stream_tiles.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.mla_append_workspace_bytes.restype = ctypes.c_size_t
         L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
         L.mla_cache_append.restype = i
@@ -388,6 +390,19 @@ def gather_paged(kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: tor
                                   row_bytes, page_size, num_pages, page_table.shape[1],
                                   _stream(kv_cache)), "mla_gather_paged")
     return dense
+
+
+def diag_stream_tiles(kv_cache: torch.Tensor, page_table: torch.Tensor, seq_lens: torch.Tensor,
+                      num_splits: int) -> None:
+    """Diagnostic: the bf16 decode kernel's tile requests, waits and barriers over the cached rows,
+    with no arithmetic and no output (what streaming the cache once costs in that launch shape)."""
+    num_pages, page_size, row = kv_cache.shape
+    if kv_cache.dtype != torch.bfloat16 or page_size != 64:
+        raise ValueError("diag_stream_tiles takes a bf16 cache with pages of 64 rows")
+    _check(lib().mla_diag_stream_tiles(_dev(kv_cache, "kv_cache"), _dev(page_table, "page_table"),
+                                       _dev(seq_lens, "seq_lens"), seq_lens.shape[0], row - 64, num_pages,
+                                       page_table.shape[1], num_splits, _stream(kv_cache)),
+           "mla_diag_stream_tiles")
 
 
 def append_workspace_bytes(B: int, D: int, d_c: int, d_rope: int, io_dtype: torch.dtype = torch.bfloat16) -> int:

@@ -38,6 +38,7 @@ def lib():
     L.mla_prefill_workspace_bytes.argtypes = [i, i, i, i]
     L.mla_prefill_mha.argtypes = [vp] * 10 + [ctypes.c_size_t] + [i] * 9 + [f, i, i, vp]
     L.mla_gather_paged.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.mla_diag_stream_tiles.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     L.mla_append_workspace_bytes.restype = ctypes.c_size_t
     L.mla_append_workspace_bytes.argtypes = [i, i, i, i, i]
     L.mla_cache_append.argtypes = [vp] * 7 + [ctypes.c_size_t] + [i] * 7 + [f, i, i, vp]
@@ -229,6 +230,19 @@ def test_gather_validation(lib):
     assert g(P, P, P, P, 1, 0, 64, 4, 2, 1, None) == E_SHAPE
     assert g(P, P, P, P, 1, 4, 0, 4, 2, 1, None) == E_SHAPE
     assert g(P, P, P, P, 1, 4, 6, 4, 2, 1, None) == E_UNSUP
+
+
+def test_stream_probe_validation(lib):
+    g = lib.mla_diag_stream_tiles
+    assert g(None, P, P, 1, 512, 8, 4, 2, None) == E_NULL
+    assert g(P, None, P, 1, 512, 8, 4, 2, None) == E_NULL
+    assert g(P, P, None, 1, 512, 8, 4, 2, None) == E_NULL
+    assert g(P, P, P, 0, 512, 8, 4, 2, None) == E_SHAPE
+    assert g(P, P, P, 1, 512, 0, 4, 2, None) == E_SHAPE
+    assert g(P, P, P, 1, 512, 8, 0, 2, None) == E_SHAPE
+    assert g(P, P, P, 1, 512, 8, 4, 0, None) == E_SHAPE
+    assert g(P, P, P, 1, 128, 8, 4, 2, None) == E_UNSUP
+    assert g(P, P, P, 70000, 512, 8, 4, 2, None) == E_UNSUP
 
 
 def append_args(**kw):

@@ -81,6 +81,24 @@ def test_gather_bit_exact(mla, name, shrink):
     assert dense.cpu().numpy().tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("d_c,H,num_splits", [(512, 32, 1), (512, 32, 7), (256, 28, 2)])
+def test_stream_probe_reads_only(mla, d_c, H, num_splits):
+    """The diagnostic stream kernel (tile traffic of the bf16 decode kernel, nothing else) over
+    ragged lengths, an empty sequence, NaN-poisoned free pages and a page id outside the pool:
+    it completes, and the cache, the tables and a decode call afterwards are what they were."""
+    import torch
+    w = ragged_workload(d_c=d_c, H=H, lens=[300, 0, 64, 1000, 65, 1], seed=61)
+    d = DeviceWorkload(w)
+    table = d.page_table.clone()
+    table[3, 2] = w.num_pages + 5          # skipped by the kernel, never dereferenced
+    before = d.pool.clone()
+    mla.diag_stream_tiles(d.pool, table, d.seq_lens, num_splits)
+    mla.diag_stream_tiles(d.pool, d.page_table, d.seq_lens, num_splits)
+    torch.cuda.synchronize()
+    assert d.pool.view(torch.int16).equal(before.view(torch.int16))
+    check_decode(mla, w, num_splits)
+
+
 # ------------------------------------------------------- the two projections
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
