@@ -369,10 +369,12 @@ __global__ __launch_bounds__(128) void merge_kernel(MergeParams p)
     if (p.lse && tid == 0) p.lse[(size_t)b * p.H + h] = z > 0.f ? m + logf(z) : -INFINITY;
 }
 
-// Streaming variant for d_c a multiple of 256 and at most 64 chunks: one wavefront per
-// (sequence, head, block of 256 columns).  Lane s owns the log-sum-exp of chunk s; every lane
-// streams one float4 per chunk with the loads of up to 16 chunks in flight.
-template <bool OUT_BF16>
+// Streaming variant for d_c a multiple of 256: one wavefront per (sequence, head, block of 256
+// columns).  Lane s owns the log-sum-exp of chunk s; every lane streams one float4 per chunk with
+// the loads of up to 16 chunks in flight.  PLAN = false: uniform partition, at most 64 chunks.
+// PLAN = true: the chunks the balanced partition's plan names for the sequence, any number of
+// them, 64 at a time.
+template <bool OUT_BF16, bool PLAN>
 __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -383,35 +385,40 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(MergeParams p)
     const int cb = wid % blocks_per_row;
     const int bh = wid / blocks_per_row;
     const int b = bh / p.H, h = bh % p.H;
-    const int S = p.num_splits;
+    const ChunkSpan c = PLAN ? planned_span(p.plan[2 * b], p.plan[2 * b + 1], p, h)
+                             : ChunkSpan{part_index(b, h, 0, p.H, p.num_splits), 1, p.num_splits};
+    const int S = c.S;
 
     // Start streaming the first chunks' partial rows before their weights are known.  Rows of
     // empty chunks were never written: whatever is read there is discarded by a select, not
     // multiplied by zero.
     constexpr int BATCH = 16;
-    const size_t stride = (size_t)p.d_c;
-    const size_t base = part_index(b, h, 0, p.H, S) * p.d_c + cb * 256 + lane * 4;   // element index
-    const float ls = lane < S ? p.lse_part[part_index(b, h, lane, p.H, S)] : -INFINITY;
+    const size_t stride = c.step * (size_t)p.d_c;
+    const size_t base = c.first * p.d_c + cb * 256 + lane * 4;   // element index
+    const float ls0 = span_lse(p.lse_part, c, 0, lane);
     float4 v[BATCH];
+    // rows past the last chunk re-read it (weight zero); a sequence without chunks reads its first slot's row
+    auto row = [&](int s) { return base + (size_t)max(0, min(s, S - 1)) * stride; };
 #pragma unroll
-    for (int i = 0; i < BATCH; ++i)   // rows past the last chunk re-read it (weight zero)
-        v[i] = load_part4<OUT_BF16>(p.o_part, base + (size_t)min(i, S - 1) * stride);
+    for (int i = 0; i < BATCH; ++i) v[i] = load_part4<OUT_BF16>(p.o_part, row(i));
 
-    const ChunkWeights cw = chunk_weights(ls, S);
+    const ChunkWeights cw = PLAN ? span_weights(p.lse_part, c, ls0, lane) : chunk_weights(ls0, S);
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < S; s0 += BATCH) {
-        if (s0 > 0) {
+    for (int blk = 0; blk < S; blk += 64) {
+        const float ls = blk ? span_lse(p.lse_part, c, blk, lane) : ls0;
+        for (int s0 = 0; s0 < min(64, S - blk); s0 += BATCH) {
+            if (blk + s0 > 0) {
 #pragma unroll
-            for (int i = 0; i < BATCH; ++i)
-                v[i] = load_part4<OUT_BF16>(p.o_part, base + (size_t)min(s0 + i, S - 1) * stride);
-        }
+                for (int i = 0; i < BATCH; ++i) v[i] = load_part4<OUT_BF16>(p.o_part, row(blk + s0 + i));
+            }
 #pragma unroll
-        for (int i = 0; i < BATCH; ++i) {
-            const float ws = chunk_weight_at(cw, ls, s0 + i);   // 0 at and past S
-            const bool live = ws != 0.f;
-            acc.x = fmaf(ws, live ? v[i].x : 0.f, acc.x); acc.y = fmaf(ws, live ? v[i].y : 0.f, acc.y);
-            acc.z = fmaf(ws, live ? v[i].z : 0.f, acc.z); acc.w = fmaf(ws, live ? v[i].w : 0.f, acc.w);
+            for (int i = 0; i < BATCH; ++i) {
+                const float ws = chunk_weight_at(cw, ls, s0 + i);   // 0 at and past S
+                const bool live = ws != 0.f;
+                acc.x = fmaf(ws, live ? v[i].x : 0.f, acc.x); acc.y = fmaf(ws, live ? v[i].y : 0.f, acc.y);
+                acc.z = fmaf(ws, live ? v[i].z : 0.f, acc.z); acc.w = fmaf(ws, live ? v[i].w : 0.f, acc.w);
+            }
         }
     }
     const size_t o = (size_t)bh * p.d_c + cb * 256 + lane * 4;
@@ -469,11 +476,16 @@ hipError_t launch_decode_portable(const DecodeParams& p, mla_dtype io, mla_dtype
 
 hipError_t launch_merge(const MergeParams& p, mla_dtype io, hipStream_t s)
 {
-    if (!p.plan && p.d_c % 256 == 0 && p.num_splits <= 64) {
+    if (p.d_c % 256 == 0 && (p.plan || p.num_splits <= 64)) {
         const int waves = p.B * p.H * (p.d_c / 256);
         dim3 grid((waves + 3) / 4), block(256);
-        if (io == MLA_BF16) merge_wave_kernel<true><<<grid, block, 0, s>>>(p);
-        else                merge_wave_kernel<false><<<grid, block, 0, s>>>(p);
+        if (io == MLA_BF16) {
+            if (p.plan) merge_wave_kernel<true, true><<<grid, block, 0, s>>>(p);
+            else        merge_wave_kernel<true, false><<<grid, block, 0, s>>>(p);
+        } else {
+            if (p.plan) merge_wave_kernel<false, true><<<grid, block, 0, s>>>(p);
+            else        merge_wave_kernel<false, false><<<grid, block, 0, s>>>(p);
+        }
         return hipGetLastError();
     }
     dim3 grid(p.H, p.B), block(128);

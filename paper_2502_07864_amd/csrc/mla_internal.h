@@ -97,6 +97,57 @@ __device__ __forceinline__ float chunk_weight_at(const ChunkWeights& cw, float l
     return __expf(lane_value(ls, s) - cw.ref) * cw.inv;
 }
 
+// Where the S partials of one (sequence, query row) lie: chunk s has its log-sum-exp at
+// lse_part[first + s * step] and its row at element (first + s * step) * d_c of o_part.  Uniform
+// partition: S adjacent entries; balanced partition: the slots the plan names, one every H entries
+// ([slot, H] / [slot, H, d_c]), S of them (0 for an empty sequence; any number otherwise).
+struct ChunkSpan {
+    size_t first, step;
+    int S;
+};
+
+// (a plan entry that does not fit the workspace's slots -- a workspace no balanced decode call has
+// written -- reads as an empty sequence)
+__device__ __forceinline__ ChunkSpan planned_span(int first_slot, int count, const MergeParams& p, int h)
+{
+    const long long slots = (long long)p.B * (p.num_splits + 1);
+    if (first_slot < 0 || count < 0 || (long long)first_slot + count > slots) { first_slot = 0; count = 0; }
+    return ChunkSpan{(size_t)first_slot * p.H + h, (size_t)p.H, count};
+}
+
+// log-sum-exp of chunk blk + lane of a span (-inf at and past S), blk a multiple of 64
+__device__ __forceinline__ float span_lse(const float* lse_part, const ChunkSpan& c, int blk, int lane)
+{
+    const int s = blk + lane;
+    return s < c.S ? lse_part[c.first + (size_t)s * c.step] : -INFINITY;
+}
+
+// chunk_weights for a span of any length: the same operations in the same order over blocks of 64
+// chunks (ls0 = span_lse of block 0), so that up to 64 chunks the result is chunk_weights' bit for bit
+__device__ __forceinline__ ChunkWeights span_weights(const float* lse_part, const ChunkSpan& c, float ls0, int lane)
+{
+    ChunkWeights cw;
+    cw.m = -INFINITY;
+    for (int blk = 0; blk < c.S; blk += 64) {
+        const float ls = blk ? span_lse(lse_part, c, blk, lane) : ls0;
+        for (int s0 = 0; s0 < min(64, c.S - blk); s0 += 16) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cw.m = fmaxf(cw.m, lane_value(ls, s0 + i));
+        }
+    }
+    cw.ref = cw.m == -INFINITY ? 0.f : cw.m;
+    cw.z = 0.f;
+    for (int blk = 0; blk < c.S; blk += 64) {
+        const float ls = blk ? span_lse(lse_part, c, blk, lane) : ls0;
+        for (int s0 = 0; s0 < min(64, c.S - blk); s0 += 16) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cw.z += __expf(lane_value(ls, s0 + i) - cw.ref);
+        }
+    }
+    cw.inv = cw.z > 0.f ? 1.f / cw.z : 0.f;
+    return cw;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16)
 {
     return __uint_as_float(bits16 << 16);

@@ -341,6 +341,29 @@ def test_balanced_matches_uniform_and_fused_tail_call(mla):
     assert max_abs_rel(widen_gpu(out_t), ref) <= TOL["bf16"]
 
 
+def test_balanced_more_than_64_chunks_of_one_sequence(mla):
+    """One long sequence among short ones with many workgroups: the plan gives it well over 64
+    chunks (the merge walks them 64 at a time).  Decode + merge against the oracle, and the fused
+    tail bit for bit the separate merge."""
+    import torch
+    w = ragged_workload(lens=[6000, 1, 130, 0], seed=79)
+    check_decode(mla, w, 40, flags=BAL)          # 4 x 40 = 160 workgroups over 98 pages; sequence 0 holds 94 of them
+    check_decode(mla, w, 25, flags=BAL)          # 4 x 25 x 4 (cut again to fill the chip) = 400 workgroups
+    d = DeviceWorkload(w)
+    q_abs = gpu_q_abs(mla, d)
+    ws = mla.decode_paged(q_abs, d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                          num_splits=40, flags=mla.FLAG_SKIP_MERGE | BAL)
+    o_m, lse_m = mla.merge_partials(ws, w.B, w.H, w.d_c, 40, q_abs.dtype, return_lse=True, flags=BAL)
+    o_t, out_t, lse_t = mla.merge_out_proj(ws, d.W_UV, w.B, 40, return_lse=True, flags=BAL)
+    torch.cuda.synchronize()
+    plan_off = mla.decode_workspace_bytes(w.B, w.H, w.d_c, 40) - 256
+    counts = ws[plan_off:plan_off + 8 * w.B].view(torch.int32).cpu().numpy().reshape(w.B, 2)[:, 1]
+    assert counts[0] > 64 and counts[3] == 0, counts
+    assert storage_bits(o_t).tobytes() == storage_bits(o_m).tobytes()
+    assert storage_bits(lse_t).tobytes() == storage_bits(lse_m).tobytes()
+    assert max_abs_rel(widen_gpu(out_t), oracle.out_proj(q_abs_storage(o_t), w.W_UV)) <= TOL["bf16"]
+
+
 def test_balanced_needs_the_matrix_core_kernel(mla):
     w = synth.config("C1", shrink=4)          # fp32: portable kernel only
     d = DeviceWorkload(w)
