@@ -233,6 +233,32 @@ def test_decode_fp8_cache(mla):
     check_decode(mla, w2, 2, tol=1e-5)
 
 
+def test_decode_fp8_chunks_longer_than_the_page_registers(mla):
+    """256 sequences with one chunk each (nothing is cut again): the two long ones run 141 and 129
+    tiles in one workgroup, past the 64 + 64 page ids a wavefront holds at a time.  Then the same with
+    queries dominated by a key near the end of the long sequences: the second pass walks the page
+    blocks again from the start."""
+    import torch
+    lens = [9000, 8200] + [1] * 254
+    w = ragged_workload(cache="fp8_e4m3", lens=lens, seed=23)
+    sel = [0, 1, 2, 255]
+    check_decode(mla, w, 1, b_sel=sel)
+    d = DeviceWorkload(w)
+    q = oracle.widen(q_abs_storage(gpu_q_abs(mla, d))).astype(np.float32)
+    for b, j in ((0, 8990), (1, 8150)):
+        page, slot = int(w.page_table[b, j // 64]), j % 64
+        row = np.array([oracle.widen_e4m3_code(c) for c in w.pool[page, slot, :512]]) * float(w.kv_scale[page, slot])
+        q[b] = 30.0 * row[None, :] / max(1e-6, float(np.abs(row).max()))
+    q_bits = synth.to_bf16_bits(q)
+    o, lse = mla.decode_paged(to_torch(q_bits, "bf16"), d.q_rope, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                              num_splits=1, kv_scale=d.kv_scale, return_lse=True)
+    torch.cuda.synchronize()
+    ref_o, ref_lse = oracle.decode_absorbed(q_bits[sel], w.q_rope[sel], w.pool, w.kv_scale, w.page_table[sel],
+                                            w.seq_lens[sel], w.softmax_scale)
+    assert max_abs_rel(widen_gpu(o)[sel], ref_o) <= 2e-2
+    assert lse_err(widen_gpu(lse)[sel], ref_lse) <= 2e-2
+
+
 def test_decode_f32_io_bf16_cache(mla):
     w = ragged_workload(cache="bf16", io="f32", lens=[130, 64, 7], seed=10)
     check_decode(mla, w, 2, tol=1e-5)
