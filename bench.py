@@ -51,8 +51,11 @@ WORKLOADS = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # defaults long enough for the clocks to settle: a step is tens of microseconds, and with 200 steps
+    # behind 20 the timed region (8 ms at C2) still sat on the ramp (C2 41.0 against 39.2 us/step, C5
+    # 86.6 against 75.2 with these counts on the same box)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--copies", type=int, default=0,
                     help="distinct cache copies cycled through (0 = enough to exceed 900 MB)")
     ap.add_argument("--unfused-tail", action="store_true",
