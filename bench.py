@@ -315,15 +315,15 @@ def main():
         kernel_name = "decode_portable_kernel<float, float>"
     elif T > 1:
         kernel_name = f"decode_mfma_wide_kernel<{d_c}>"
+    elif fp8:
+        kernel_name = f"decode_stream_fp8_kernel<{d_c}, {'true' if args.balanced else 'false'}>"
     elif args.balanced:
         tiles = 2 * d.page_table.shape[1] // max(1, S)
-        kernel_name = f"decode_mfma_kernel<{d_c}, {'true, 2' if fp8 else 'false, ' + ('3' if tiles <= 64 else '4')}, 1, true>"
-    elif fp8:
-        kernel_name = f"decode_stream_fp8_kernel<{d_c}>"
+        kernel_name = f"decode_mfma_kernel<{d_c}, {'3' if tiles <= 64 else '4'}, 1, true>"
     else:
         tiles = 2 * (-(-d.page_table.shape[1] // S))
         kernel_name = (f"decode_stream_kernel<{d_c}, false>" if tiles <= 32 else
-                       f"decode_mfma_kernel<{d_c}, false, {'3' if tiles <= 64 else '4'}, 1, false>")
+                       f"decode_mfma_kernel<{d_c}, {'3' if tiles <= 64 else '4'}, 1, false>")
     # HBM bytes per launch from the committed rocprofv3 counter summary; only valid for the default
     # launch configuration of the workload and while the kernel sources are the ones the counters
     # were taken on

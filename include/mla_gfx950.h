@@ -272,7 +272,8 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes,
 /*
  * Fused tail: mla_merge_partials followed by mla_out_proj in one call (one
  * kernel where the shapes allow: bf16 io, d_head 128, d_c 256 or 512, at most
- * 64 chunks; otherwise the two kernels back to back).  Same results as the two
+ * 64 chunks of the uniform partition or any balanced one; otherwise the two
+ * kernels back to back).  Same results as the two
  * calls: o_lat is the merged latent output rounded to the io dtype, and out is
  * computed from that rounded o_lat.
  *   workspace  [in]  as written by mla_decode_paged(..., MLA_FLAG_SKIP_MERGE)
@@ -280,8 +281,7 @@ int mla_merge_partials(const void* workspace, size_t workspace_bytes,
  *   o_lat      [B, H, d_c] io dtype (output, required)
  *   lse        [B, H] fp32 (output, may be NULL)
  *   out        [B, H, d_head] io dtype (output)
- *   flags      MLA_FLAG_BALANCED iff the decode call had it (the two kernels
- *              then run back to back); other bits ignored
+ *   flags      MLA_FLAG_BALANCED iff the decode call had it; other bits ignored
  */
 int mla_merge_out_proj(const void* workspace, size_t workspace_bytes,
                        const void* W_UV, void* o_lat, float* lse, void* out,

@@ -55,8 +55,23 @@ def build_library(verbose: bool = False, extra_flags=()) -> Path:
             print(out)
         return obj
 
+    def check_pending_registers() -> None:
+        # decode_mfma.hip's query rows: loads with register outputs awaited later by count (asm_checks.py)
+        from .asm_checks import check_listing
+        src = CSRC / "decode_mfma.hip"
+        asm = OBJDIR / "decode_mfma.s"
+        cmd = [cc, *HIPCC_FLAGS, *extra_flags, "-S", "--cuda-device-only", str(src), "-o", str(asm)]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {src.name}:\n{r.stdout}{r.stderr}")
+        seen = check_listing(asm.read_text(), "decode_mfma_kernel")
+        if not seen or not all(seen.values()):
+            raise RuntimeError(f"asm check found no query-row loads to look at in {sorted(seen)}")
+
     with ThreadPoolExecutor(max_workers=min(4, os.cpu_count() or 1)) as ex:
+        check = ex.submit(check_pending_registers)
         objs = list(ex.map(compile_one, sources()))
+        check.result()
     tmp = LIB.with_suffix(".so.tmp")
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,4 +1,5 @@
-// Matrix-core paged decode for a bf16 or fp8 (e4m3 + per-row scale) latent cache (gfx950 / CDNA4).
+// Matrix-core paged decode for a bf16 latent cache (gfx950 / CDNA4), and the dispatch of the other
+// matrix-core decode kernels (decode_stream.hip, decode_stream_fp8.hip).
 //
 // Second line of the absorbed attention equation (Sec. 3.3 of the paper): all
 // H heads score against the ONE shared row k_hat_j = [c_j ; k^R_j] and weight
@@ -46,17 +47,15 @@
 namespace mla {
 namespace {
 
-// FP8 = false: bf16 cache, tiles go HBM -> LDS directly (ring of four).
-// FP8 = true : OCP e4m3 cache with one fp32 scale per row.  Codes are widened exactly to bf16 on
-//              their way HBM -> registers -> LDS (two tiles), so the arithmetic below is the same;
-//              the row's scale multiplies its score and its weight instead of its 576 values.
-// NBUF = tiles in the LDS ring (bf16 path): 4 fills LDS with one workgroup per CU; 2 leaves room
+// bf16 caches (tiles go HBM -> LDS directly); fp8 caches have a kernel of their own
+// (decode_stream_fp8.hip).
+// NBUF = tiles in the LDS ring: 4 fills LDS with one workgroup per CU; 2 leaves room
 //        for two workgroups per CU (WPE = waves per SIMD the register budget is sized for).
 // BAL  = false: one workgroup per (sequence, chunk), chunks of the same number of pages.
 //        true : the page lists of all sequences, laid end to end, are cut into as many equal
 //               ranges as there are workgroups; a workgroup walks its range sequence by sequence
 //               (one segment each) and writes one partial result per segment.
-template <int D_C, bool FP8, int NBUF, int WPE, bool BAL>
+template <int D_C, int NBUF, int WPE, bool BAL>
 __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int ROW = D_C + 64;               // elements per cache row
@@ -75,7 +74,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     static_assert(NBUF >= 2 && NBUF <= 4, "ring depth");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
-    __shared__ float scale_lds[2][TILE_ROWS];        // fp8: row scales of the two widened tiles
     __shared__ int seg_lds[BAL ? 64 : 1][3];         // balanced partition: (sequence, first row, end row) per segment
     __shared__ int jump_flag;                        // raised by a wavefront whose fast pass met a score far above its reference
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
@@ -148,8 +146,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // which left the memory system without requests for about 1.5 us at the start.)
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     const int head = hg * 16 + n;
-    u32x4 qraw[FP8 ? 1 : NKS];
-    if constexpr (!FP8) {
+    u32x4 qraw[NKS];
+    {
         const int hq = min(head, HL - 1);     // absent heads read a present one; their registers are cleared below
         const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + hb + hq) * D_C + g * 8;
         const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + hb + hq) * 64 + g * 8;
@@ -173,19 +171,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     const int t1 = (row1 + TILE_ROWS - 1) / TILE_ROWS;
 
     bf16x8 qreg[NKS];
-    if constexpr (FP8) {
-        const uint16_t* qa = static_cast<const uint16_t*>(p.q_abs) + ((size_t)b * p.H + hb + head) * D_C;
-        const uint16_t* qr = static_cast<const uint16_t*>(p.q_rope) + ((size_t)b * p.H + hb + head) * 64;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (head < HL) {
-                const uint16_t* src = ks < D_C / 32 ? qa + ks * 32 + g * 8 : qr + (ks - D_C / 32) * 32 + g * 8;
-                v = *reinterpret_cast<const uint4*>(src);
-            }
-            qreg[ks] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
 
     // ---- tile staging: HBM -> LDS with direct-to-LDS 128-bit loads.
     // Load k of wave w fills LDS chunks [(4k+w)*64, +64) of the tile (the hardware writes lane
@@ -236,62 +221,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         return NLOAD;
     };
 
-    // ---- fp8 staging: 16-byte loads (16 codes) one tile ahead in registers, widened to bf16 and
-    // stored with the same swizzled layout the direct-to-LDS path produces.  The address unit
-    // takes as long over a narrow load as over a wide one, so the tile is fetched in as few
-    // instructions as its size allows.
-    constexpr int CPR8 = ROW / 8;                    // 8-code chunks per row (= 16-byte bf16 chunks)
-    constexpr int RAW_B = TILE_ROWS * ROW;           // bytes of a tile of codes (18432 / 10240)
-    constexpr int N16 = RAW_B / 16;                  // 16-byte pieces per tile (1152 / 640)
-    constexpr int NLOAD8 = (N16 + MF_THREADS - 1) / MF_THREADS;   // loads per thread per tile (5 / 3; the last is half used)
-    static_assert(CPR8 % 2 == 0, "a 16-byte piece must not straddle two rows");
-    u32x4 stg[FP8 ? NLOAD8 : 1];
-    float stg_scale = 0.f;
-    // piece c16 = k * 256 + tid sits at byte c16 * 16 of the tile's rows in HBM (rows are
-    // contiguous); its two 8-code halves go to LDS row r = 2 c16 / CPR8, swizzled 16-byte positions
-    // col and col + 1 (col even, so the second is the first with address bit 4 flipped)
-    uint32_t loff8[FP8 ? NLOAD8 : 1];
-    if constexpr (FP8) {
-#pragma unroll
-        for (int k = 0; k < NLOAD8; ++k) {
-            const int c8 = 2 * (k * MF_THREADS + tid);
-            const int r = c8 / CPR8, col = c8 % CPR8;
-            loff8[k] = (uint32_t)(r * ROWB + ((col ^ swz_key(r)) << 4));
-        }
-    }
-    // `page` is the page id of tile t, looked up by the caller well ahead of this call (a scalar
-    // load that would otherwise be waited for right here, once per tile)
-    auto fetch_regs = [&](int t, int page) {
-        const int nv = (page >= 0 && page < p.num_pages) ? min(TILE_ROWS, row1 - t * TILE_ROWS) : 0;
-        if (nv <= 0) page = 0;
-        const unsigned char* src = kv + (size_t)page * (64 * ROW) + (size_t)(t & 1) * RAW_B + tid * 16;
-        const int limit = nv * (CPR8 / 2);   // pieces that belong to valid rows
-#pragma unroll
-        for (int k = 0; k < NLOAD8; ++k) {
-            u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-            if (k * MF_THREADS + tid < limit) v = *reinterpret_cast<const u32x4*>(src + k * (MF_THREADS * 16));
-            stg[k] = v;
-        }
-        if (tid < TILE_ROWS)
-            stg_scale = tid < nv ? p.kv_scale[(size_t)page * 64 + (t & 1) * TILE_ROWS + tid] : 0.f;
-    };
-    auto store_regs = [&](int slot) {
-#pragma unroll
-        for (int k = 0; k < NLOAD8; ++k) {
-            if (k * MF_THREADS + tid < N16) {
-                u32x4 w[2];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    // two codes -> two bf16 in one instruction (scale 1: exact, e4m3 has 3 mantissa bits)
-                    w[j >> 1][2 * (j & 1)]     = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(stg[k][j], 1.0f, false));
-                    w[j >> 1][2 * (j & 1) + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(stg[k][j], 1.0f, true));
-                }
-                *(LDS_AS u32x4*)(lds + slot * TILE_B + loff8[k]) = w[0];
-                *(LDS_AS u32x4*)(lds + slot * TILE_B + (loff8[k] ^ 16u)) = w[1];
-            }
-        }
-        if (tid < TILE_ROWS) scale_lds[slot][tid] = stg_scale;
-    };
 
     // ---- running softmax state: this lane's head = column n of the D tiles
     float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
@@ -323,7 +252,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     int ahead[NBUF - 1];
 
     int first_issued = 0;   // loads issued for tile t0 by the last start_ring()
-    auto slot_of = [&](int t) { return FP8 ? ((t - t0) & 1) : ((t - t0) % NBUF); };
+    auto slot_of = [&](int t) { return (t - t0) % NBUF; };
 
     bool ring_full = false;   // tile t0 + NBUF - 1 has been requested ahead of the first stage step
     // request tile t0 + NBUF - 1 into the last ring slot before the first stage step (which
@@ -333,72 +262,49 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         ring_full = true;
     };
     auto start_ring = [&](bool whole_ring) {
-        if constexpr (FP8) {
-            fetch_regs(t0, ptab[t0 >> 1]);
-            store_regs(0);
-            if (t0 + 1 < t1) fetch_regs(t0 + 1, ptab[(t0 + 1) >> 1]);
-        } else {
 #pragma unroll
-            for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
-            first_issued = fetch_tile(t0);   // every chunk that gets here has at least one tile
+        for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
+        first_issued = fetch_tile(t0);   // every chunk that gets here has at least one tile
 #pragma unroll
-            for (int i = 0; i < NBUF - 2; ++i)
-                if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
-            ring_full = false;
-            if (whole_ring) fill_last_slot();
-        }
+        for (int i = 0; i < NBUF - 2; ++i)
+            if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+        ring_full = false;
+        if (whole_ring) fill_last_slot();
     };
 
     // publish tile t (and keep the stream going); returns its number of valid rows
     auto stage_tile = [&](int t, LDS_AS unsigned char* tile) -> int {
         const int n_valid = rows_valid(t);
-        if constexpr (FP8) {
-            // tile t was stored by every wave before this barrier; the other slot is free
-            __syncthreads();
-            return n_valid;
-        } else {
-            // wait until my loads of tile t have landed (younger tiles may stay in flight);
-            // after the barrier everybody's have, and every wave is done with tile t-1, whose
-            // ring slot now receives tile t + NBUF - 1
-            int younger = 0;
+        // wait until my loads of tile t have landed (younger tiles may stay in flight);
+        // after the barrier everybody's have, and every wave is done with tile t-1, whose
+        // ring slot now receives tile t + NBUF - 1
+        int younger = 0;
 #pragma unroll
-            for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];   // the last entry is 0 unless ring_full
-            if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
-            else if (NBUF > 2 && younger >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
-            else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
-            else                                       wait_vmcnt<0>();
-            __syncthreads();
-            if (!ring_full) {
-                const int tn = t + NBUF - 1;
-                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
-            }
-            ring_full = false;
-            if (n_valid < TILE_ROWS) {
-                // ragged last tile (or a page id outside the pool): rows that are not part of
-                // the sequence become zeros so that whatever they hold stays out
-                for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
-                    *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
-                __syncthreads();
-            }
-            // tile t+1 becomes the oldest one in flight
-#pragma unroll
-            for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
-            ahead[NBUF - 2] = 0;
-            return n_valid;
+        for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];   // the last entry is 0 unless ring_full
+        if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
+        else if (NBUF > 2 && younger >= 2 * NLOAD) wait_vmcnt<2 * NLOAD>();
+        else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
+        else                                       wait_vmcnt<0>();
+        __syncthreads();
+        if (!ring_full) {
+            const int tn = t + NBUF - 1;
+            ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
         }
+        ring_full = false;
+        if (n_valid < TILE_ROWS) {
+            // ragged last tile (or a page id outside the pool): rows that are not part of
+            // the sequence become zeros so that whatever they hold stays out
+            for (int i = tid; i < (TILE_ROWS - n_valid) * CPR; i += MF_THREADS)
+                *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+            __syncthreads();
+        }
+        // tile t+1 becomes the oldest one in flight
+#pragma unroll
+        for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];
+        ahead[NBUF - 2] = 0;
+        return n_valid;
     };
 
-    // after tile t has been accumulated (fp8): hand tile t+1 over to LDS, request tile t+2
-    auto finish_tile = [&](int t, int page_t2) {
-        if constexpr (FP8) {
-            if (t + 1 < t1) {
-                store_regs(slot_of(t + 1));
-                if (t + 2 < t1) fetch_regs(t + 2, page_t2);
-            }
-        }
-    };
-    // page id of tile t + 2, requested at the top of tile t's iteration (fp8 path)
-    auto page_ahead = [&](int t) { return FP8 ? ptab[min((t + 2) >> 1, p.max_pages - 1)] : 0; };
 
     // S^T = K . Q^T for this wave's 16 rows x 16 heads, scaled to log2 units, invalid rows at
     // -inf; returns the maximum over this lane's 4 rows of its head.  Operand reads run
@@ -406,7 +312,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // sinking the reads back next to their uses.
     // first cached row (of the sequence) that some query row of the sequence must not see
     const int causal_from = L - (p.q_len - 1);
-    auto score_tile = [&](LDS_AS unsigned char* tile, int slot, int t, int n_valid, float (&x)[4], float (&rs)[4]) -> float {
+    auto score_tile = [&](LDS_AS unsigned char* tile, int t, int n_valid, float (&x)[4]) -> float {
         f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
         bf16x8 a0[NKS];
 #pragma unroll
@@ -425,10 +331,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            rs[i] = FP8 ? scale_lds[slot][tg * 16 + g * 4 + i] : 1.f;   // per-row dequantisation scale
-            x[i] = sacc[i] * (FP8 ? sc * rs[i] : sc);
-        }
+        for (int i = 0; i < 4; ++i) x[i] = sacc[i] * sc;
         if (n_valid < TILE_ROWS || (t + 1) * TILE_ROWS > causal_from) {
             // ragged last tile, and the upper limit of this lane's query row (Eq. "mqa": the sum
             // runs up to the query token's own position)
@@ -448,24 +351,13 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
 
     // weights p = 2^(x - m_run) rounded to bf16 (the normaliser sums exactly the rounded
     // weights), then O^T += V^T . P^T with transposing reads one group of VG tiles ahead
-    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x)[4], const float (&rs)[4]) {
+    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x)[4]) {
         const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
-        uint32_t p01, p23;
-        if constexpr (FP8) {
-            // the value rows are scale * codes: the scale rides on the weight; the normaliser
-            // sums the plain weights
-            const float e0 = fast_exp2(x[0] - m_use), e1 = fast_exp2(x[1] - m_use);
-            const float e2 = fast_exp2(x[2] - m_use), e3 = fast_exp2(x[3] - m_use);
-            l_run += (e0 + e1) + (e2 + e3);
-            p01 = pack_bf16x2(e0 * rs[0], e1 * rs[1]);
-            p23 = pack_bf16x2(e2 * rs[2], e3 * rs[3]);
-        } else {
-            p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
-            p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
-            // the normaliser sums exactly the rounded weights that get multiplied
-            l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
-                     (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
-        }
+        const uint32_t p01 = pack_bf16x2(fast_exp2(x[0] - m_use), fast_exp2(x[1] - m_use));
+        const uint32_t p23 = pack_bf16x2(fast_exp2(x[2] - m_use), fast_exp2(x[3] - m_use));
+        // the normaliser sums exactly the rounded weights that get multiplied
+        l_run += (bf16_bits_to_f32(p01 & 0xFFFFu) + bf16_bits_to_f32(p01 >> 16)) +
+                 (bf16_bits_to_f32(p23 & 0xFFFFu) + bf16_bits_to_f32(p23 >> 16));
         const s16x4 pb = __builtin_bit_cast(s16x4, (u32x2){p01, p23});
         s16x4 va[NCT];
 #pragma unroll
@@ -493,13 +385,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     // long as no later score exceeds the reference by more than FAST_GAP (log2 units): then
     // p <= 2^FAST_GAP and neither p, the normaliser nor the accumulators can overflow.  A
     // larger jump is only recorded here; the chunk is then recomputed by the careful pass.
-    if constexpr (FP8) {
-        start_ring(false);
-        // Pin the completion of the query loads here, outside the tile loop: left to itself the
-        // compiler would wait for them at their first use inside the loop, on every iteration.
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(qreg[ks]));
-    } else {
+    {
         start_ring(true);
         // wait for the query rows only: the tile loads requested after them stay in flight
         // (vector memory loads complete in the order they were issued)
@@ -526,17 +412,15 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
     for (int t = t0; t < t1; ++t) {
         const int slot = slot_of(t);
         LDS_AS unsigned char* tile = lds + slot * TILE_B;
-        const int page_t2 = page_ahead(t);
         const int n_valid = stage_tile(t, tile);
-        float x[4], rs[4];
-        const float lmax = score_tile(tile, slot, t, n_valid, x, rs);
+        float x[4];
+        const float lmax = score_tile(tile, t, n_valid, x);
         if (__any(m_run == -INFINITY)) {       // first tile with a visible row (as a rule: the first tile)
             const float tmax = over_groups(lmax);
             if (m_run == -INFINITY) m_run = tmax;
         }
         jumped |= lmax > m_run + FAST_GAP;
-        accumulate_tile(tile, x, rs);
-        finish_tile(t, page_t2);
+        accumulate_tile(tile, x);
     }
 
     // a plain flag and one barrier: the library's workgroup-wide OR costs about 1400 cycles here,
@@ -552,7 +436,6 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
         l_run = 0.f;
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) oacc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if constexpr (FP8) __syncthreads();   // every wave is done reading both slots
         start_ring(true);
         int t = t0;
         bool staged = false;       // tile t has already been through its stage step
@@ -571,8 +454,8 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
                 LDS_AS unsigned char* tile = lds + slot * TILE_B;
                 if (!staged) n_valid = stage_tile(t, tile);
                 staged = false;
-                float x[4], rs[4];
-                const float tmax = over_groups(score_tile(tile, slot, t, n_valid, x, rs));
+                float x[4];
+                const float tmax = over_groups(score_tile(tile, t, n_valid, x));
                 if (m_run == -INFINITY) m_run = tmax;     // nothing accumulated yet: nothing to rescale
                 if (__any(tmax > m_run + RESCALE_GAP)) {
                     const float m_new = tmax > m_run + RESCALE_GAP ? tmax : m_run;
@@ -582,8 +465,7 @@ __global__ __launch_bounds__(MF_THREADS, WPE) void decode_mfma_kernel(DecodePara
                     rescale = true;
                     break;
                 }
-                accumulate_tile(tile, x, rs);
-                finish_tile(t, page_ahead(t));
+                accumulate_tile(tile, x);
             }
             if (!rescale) break;
         }
@@ -778,12 +660,11 @@ static int ring_depth(const DecodeParams& p, bool balanced)
     return tiles <= 64 ? 3 : 4;
 }
 
-template <int D_C, bool FP8, bool BAL>
+template <int D_C, bool BAL>
 static void launch_one(const DecodeParams& p, dim3 grid, dim3 block, hipStream_t s, int depth)
 {
-    if constexpr (FP8) decode_mfma_kernel<D_C, true, 2, 1, BAL><<<grid, block, 0, s>>>(p);
-    else if (depth == 3) decode_mfma_kernel<D_C, false, 3, 1, BAL><<<grid, block, 0, s>>>(p);
-    else                 decode_mfma_kernel<D_C, false, 4, 1, BAL><<<grid, block, 0, s>>>(p);
+    if (depth == 3) decode_mfma_kernel<D_C, 3, 1, BAL><<<grid, block, 0, s>>>(p);
+    else            decode_mfma_kernel<D_C, 4, 1, BAL><<<grid, block, 0, s>>>(p);
 }
 
 hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_t s, bool balanced)
@@ -795,10 +676,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
         if (!p.plan) return hipErrorInvalidValue;
         // workgroups = sequences x chunks per sequence (x groups of 32 query rows)
         dim3 grid(grid_1d(p));
-        if (p.d_c == 512 && !fp8)      launch_one<512, false, true>(p, grid, block, s, depth);
-        else if (p.d_c == 256 && !fp8) launch_one<256, false, true>(p, grid, block, s, depth);
-        else if (p.d_c == 512 && fp8)  launch_one<512, true, true>(p, grid, block, s, depth);
-        else if (p.d_c == 256 && fp8)  launch_one<256, true, true>(p, grid, block, s, depth);
+        if (fp8) return launch_decode_stream_fp8(p, grid, s, true);
+        if (p.d_c == 512)      launch_one<512, true>(p, grid, block, s, depth);
+        else if (p.d_c == 256) launch_one<256, true>(p, grid, block, s, depth);
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
@@ -807,13 +687,12 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     // short chunks: the kernel whose consumers do not issue the requests themselves (C2: 29.0 -> 27.5 us);
     // on long chunks its doubled score contraction makes it the slower one (C4, 64 tiles: 55.2 against 53.1 us)
     if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s);
-    // fp8 caches of any chunk length: the kernel that contracts the codes as they are (C5: 92.4 -> 62 us
-    // against the kernel below, which widens a tile to bf16 in LDS before it is consumed)
-    if (fp8) return launch_decode_stream_fp8(p, grid, s);
-    if (p.d_c == 512 && !fp8)      launch_one<512, false, false>(p, grid, block, s, depth);
-    else if (p.d_c == 256 && !fp8) launch_one<256, false, false>(p, grid, block, s, depth);
-    else if (p.d_c == 512 && fp8)  launch_one<512, true, false>(p, grid, block, s, depth);
-    else if (p.d_c == 256 && fp8)  launch_one<256, true, false>(p, grid, block, s, depth);
+    // fp8 caches, either partition, any chunk length: the kernel that contracts the codes as they are
+    // (C5: 92.4 -> 62 us against an fp8 variant of the kernel above that widened every tile to bf16 in
+    // LDS before it was consumed; that variant is gone)
+    if (fp8) return launch_decode_stream_fp8(p, grid, s, false);
+    if (p.d_c == 512)      launch_one<512, false>(p, grid, block, s, depth);
+    else if (p.d_c == 256) launch_one<256, false>(p, grid, block, s, depth);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

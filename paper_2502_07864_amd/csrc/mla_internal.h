@@ -199,7 +199,7 @@ hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
 hipError_t launch_decode_stream_probe(const DecodeParams& p, hipStream_t s);
 // uniform chunks, fp8 caches: wavefronts that turn tiles into softmax weights beside wavefronts that
 // contract the tile before with them (same grid as launch_decode_mfma's)
-hipError_t launch_decode_stream_fp8(const DecodeParams& p, dim3 grid, hipStream_t s);
+hipError_t launch_decode_stream_fp8(const DecodeParams& p, dim3 grid, hipStream_t s, bool balanced);
 bool       decode_mfma_wide_supported(const DecodeParams& p, mla_dtype io, mla_dtype cache);
 hipError_t launch_decode_mfma_wide(const DecodeParams& p, hipStream_t s);   // 64 query rows per workgroup
 hipError_t launch_prefill_attention(const DecodeParams& p, hipStream_t s);  // causal attention over materialised keys / values

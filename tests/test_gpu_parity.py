@@ -335,6 +335,26 @@ def test_decode_balanced_shapes_and_caches(mla):
     check_decode(mla, w, 2, flags=BAL, b_sel=[0, 1, 63, 64, 65, 69])
 
 
+@pytest.mark.parametrize("num_splits", [1, 2, 7, 32])
+def test_decode_fp8_balanced_ragged(mla, num_splits):
+    """fp8 cache under the balanced partition (the kernel that contracts the codes as they are, run
+    segment by segment): ranges that cross sequence boundaries, short sequences sharing a workgroup,
+    NaN-poisoned free pages, tail slots and scales."""
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", seed=81), num_splits, flags=BAL)
+
+
+def test_decode_fp8_balanced_shapes(mla):
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", d_c=256, H=28, lens=[300, 1, 64, 0, 999, 4096], seed=82), 3, flags=BAL)
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", lens=[5000], seed=83), 16, flags=BAL)        # one sequence, many workgroups
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", lens=[3, 2, 1], seed=84), 64, flags=BAL)     # more workgroups than pages
+    check_decode(mla, ragged_workload(cache="fp8_e4m3", lens=[0, 1, 0, 64, 5, 0], seed=85), 3, flags=BAL)
+    w = ragged_workload(cache="fp8_e4m3", lens=[700] * 70, seed=86)                                  # two scan blocks
+    check_decode(mla, w, 2, flags=BAL, b_sel=[0, 1, 63, 64, 65, 69])
+    w = ragged_workload(cache="fp8_e4m3", lens=[9000, 1, 130, 0] + [70] * 60, seed=87)               # many segments in one workgroup
+    check_decode(mla, w, 1, flags=BAL, b_sel=[0, 1, 2, 3, 4, 63])
+    check_bench_step(mla, synth.config("C5", shrink=16), 8, flags=BAL)                               # with the fused tail
+
+
 def test_decode_balanced_all_sequences_empty(mla):
     import torch
     w = ragged_workload(lens=[0, 0, 0], seed=77)
