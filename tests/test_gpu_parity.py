@@ -960,6 +960,9 @@ def test_multi_token_fewer_rows_than_tokens_and_empty(mla):
 def test_multi_token_fp8_cache_and_fused_tail(mla):
     check_multi(mla, synth.config("C5", shrink=64), 2, 8)
     check_multi(mla, synth.config("C5", shrink=64), 2, 8, flags=1)
+    # fp8 under the balanced partition, several groups of 32 query rows per segment
+    check_multi(mla, synth.config("C5", shrink=64), 2, 8, flags=BAL)
+    check_multi(mla, ragged_workload(cache="fp8_e4m3", lens=[300, 2, 64, 0, 999, 65], seed=38), 3, 3, flags=BAL, fused_tail=True)
     w = synth.config("C2", shrink=8)
     check_multi(mla, w, 2, 4, fused_tail=True)                 # one kernel for merge + W_UV
     check_multi(mla, w, 3, 4, flags=BAL, fused_tail=True)      # balanced: merge, then the projection
