@@ -355,9 +355,10 @@ def test_decode_fp8_balanced_shapes(mla):
     check_bench_step(mla, synth.config("C5", shrink=16), 8, flags=BAL)                               # with the fused tail
 
 
-def test_decode_balanced_all_sequences_empty(mla):
+@pytest.mark.parametrize("cache", ["bf16", "fp8_e4m3"])
+def test_decode_balanced_all_sequences_empty(mla, cache):
     import torch
-    w = ragged_workload(lens=[0, 0, 0], seed=77)
+    w = ragged_workload(lens=[0, 0, 0], seed=77, cache=cache)
     d = DeviceWorkload(w)
     o, lse = run_decode(mla, d, gpu_q_abs(mla, d), 2, BAL)
     torch.cuda.synchronize()
