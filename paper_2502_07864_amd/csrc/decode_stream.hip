@@ -45,7 +45,6 @@ template <int D_C, bool PROBE>
 __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
 {
     constexpr int NBUF = 3;                     // ring slots: one being consumed, two requested (this kernel is for short chunks)
-    constexpr bool BAL = false;                 // uniform chunks only; the balanced partition runs decode_mfma.hip's kernel
     constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
@@ -85,16 +84,12 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int hb = zi * 32;
     const bool stream_once = Z == 1;   // no other workgroup reads this one's cached rows
 
-    auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
-                           const size_t out_slot) {
-    // (balanced partition: everything derived from the thread index is derived again per segment
-    // from a value the compiler cannot see through, so that it is not kept in registers across
-    // segments)
-    int opaque_zero = 0;
-    if constexpr (BAL) asm volatile("" : "+v"(opaque_zero));
-    const int tid = (int)threadIdx.x + opaque_zero;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Workgroup -> (sequence, chunk): linear ids run over the sequences first, chunk by chunk, with
+    // the sequence rotated by the chunk index (see decode_mfma.hip).  Uniform chunks only: the
+    // balanced partition runs decode_mfma.hip's kernel.
+    const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, split = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
+    const int b = (cx + split) % p.B;
+    const int tid = (int)threadIdx.x;
     const bool producer = wave >= 4;
     const int w4 = wave & 3;
     const int hg = w4 & 1, ch = w4 >> 1;       // consumers: head group, column half
@@ -102,16 +97,16 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int HL = min(32, p.H - hb);          // query rows of this workgroup
     if (tid == 0) jump_flag = 0;               // read after the tile loop, behind at least one barrier
     auto o_row = [&](int h) -> uint16_t* {     // partial rows are bf16 (the io dtype of this kernel)
-        return static_cast<uint16_t*>(p.o_part) + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
+        return static_cast<uint16_t*>(p.o_part) + part_index(b, h, split, p.H, p.num_splits) * D_C;
     };
     auto lse_at = [&](int h) -> float* {
-        return p.lse_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits));
+        return p.lse_part + part_index(b, h, split, p.H, p.num_splits);
     };
 
     // read-only tables go through the scalar cache
     const CONST_AS int32_t* seq_lens_c = (const CONST_AS int32_t*)p.seq_lens;
     const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
-    const int warm = ptab[min(BAL ? seg_row0 / 64 : split * p.chunk_pages, p.max_pages - 1)];
+    const int warm = ptab[min(split * p.chunk_pages, p.max_pages - 1)];
     int L = seq_lens_c[b];
 
     const int head = hg * 16 + n;
@@ -120,8 +115,8 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 
     asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
-    const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;             // first cached row of this segment
-    const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);  // one past its last row
+    const int row0 = split * p.chunk_pages * 64;                  // first cached row of this chunk
+    const int row1 = min(row0 + p.chunk_pages * 64, L);           // one past its last row
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
         if (!PROBE && tid < HL) *lse_at(hb + tid) = -INFINITY;
         return;
@@ -425,7 +420,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         // all reads first, then all stores, from one base address and a row stride (computing the
         // address of every row anew, with a wait for its LDS read in between, tripled the time
         // of this loop)
-        const size_t row_stride = (size_t)(BAL ? 1 : p.num_splits) * D_C;   // elements between the partial rows of consecutive heads
+        const size_t row_stride = (size_t)p.num_splits * D_C;   // elements between the partial rows of consecutive heads
         const int rl = lane / LPR, c = lane % LPR;
         uint16_t* dst0 = o_row(hb + hg * 16) + (size_t)rl * row_stride + ch * (WCT * 16) + c * 8;
         u32x4 v[16 / RPI];
@@ -438,12 +433,6 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         if (ch == 0 && head < HL && g == 0)
             *lse_at(hb + head) = lt > 0.f ? (m_run + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
     }
-    };  // run_segment
-
-    // Workgroup -> (sequence, chunk): linear ids run over the sequences first, chunk by chunk, with
-    // the sequence rotated by the chunk index (see decode_mfma.hip).
-    const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, cy = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
-    run_segment((cx + cy) % p.B, cy, 0, 0, 0);
 }
 
 }  // namespace
