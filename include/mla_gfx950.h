@@ -412,7 +412,7 @@ int mla_gather_paged(const void* kv_cache, const int32_t* page_table,
  * Diagnostic: how fast one launch of the bf16 decode kernel's shape can stream
  * a cache at all.  Runs the tile requests, counted waits and per-tile barriers
  * of the kernel mla_decode_paged uses for short uniform chunks (grid B x
- * num_splits, ring of three 36 KB tiles per workgroup, non-temporal
+ * num_splits, ring of four 36 KB tiles per workgroup, non-temporal
  * direct-to-LDS loads) with no query rows, no arithmetic and no output: the
  * time of a launch is what Sec. 3.3's second line costs on this part when
  * everything but reading the cached rows once is free.  bench.py reports it

@@ -684,8 +684,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
     }
     dim3 grid(p.B, p.num_splits);
     if (p.H > 32) grid = dim3(grid_1d(p));
-    // short chunks: the kernel whose consumers do not issue the requests themselves (C2: 29.0 -> 27.5 us);
-    // on long chunks its doubled score contraction makes it the slower one (C4, 64 tiles: 55.2 against 53.1 us)
+    // short chunks: the kernel with requesting-and-scoring wavefronts apart from the accumulating ones
+    // (C2: 29.0 -> 27.5 us); on long chunks the two are level (C4, 64 tiles: 52.7 against 53.9 us per
+    // launch, 67.3 against 66.5 us per step) and this file's kernel keeps them
     if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s);
     // fp8 caches, either partition, any chunk length: the kernel that contracts the codes as they are
     // (C5: 92.4 -> 62 us against an fp8 variant of the kernel above that widened every tile to bf16 in

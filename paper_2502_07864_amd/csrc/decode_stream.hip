@@ -16,18 +16,24 @@
 // (ring depth - 1 tiles) is still to be consumed when the last request has gone out; their
 // accumulators (all d_c columns for half the tile rows) also need a hand-over between the two row
 // halves at the end, at one wavefront per SIMD.  Here a workgroup has eight wavefronts, two per
-// SIMD:
-//   wavefronts 4..7 (producers) do nothing but request tiles (nine 128-bit direct-to-LDS loads per
-//     tile each) and wait for them by count;
+// SIMD, and the work of a tile is cut in two stages that run one tile apart:
+//   wavefronts 4..7 (producers) request the tiles (nine 128-bit direct-to-LDS loads per tile
+//     each), wait for them by count, and SCORE: producer (hg, rb) holds the query rows of heads
+//     16 hg .. 16 hg + 15 in registers and contracts 16-row block rb of tile t + 1 against them
+//     while the consumers work on tile t; the scaled scores (one 128-bit value per lane) go
+//     through a small double-buffered LDS array;
 //   wavefronts 0..3 (consumers) never touch the vector-memory counter.  Consumer (hg, ch) owns
 //     heads 16 hg .. 16 hg + 15 and latent columns [ch d_c/2, (ch+1) d_c/2) for ALL 32 rows of a
-//     tile: it scores both 16-row blocks (the score contraction is done twice per head group,
-//     once per column half: the kernel has matrix-core time to spare, it is bound by the
-//     memory stream) and accumulates its column half with K = 32 (one v_mfma_f32_16x16x32_bf16 per
-//     column tile, fed by two transposing LDS reads).  Its 64 accumulator registers hold complete
-//     sums, so the epilogue is normalise, transpose, store: no hand-over, no combine.
-// Both kinds meet at one workgroup barrier per tile (tile t has landed, everybody is done with
-// tile t - 1, whose slot the producers then fill again).
+//     tile: it picks up both blocks' scores, forms the weights and accumulates its column half
+//     with K = 32 (one v_mfma_f32_16x16x32_bf16 per column tile, fed by two transposing LDS
+//     reads).  Its 64 accumulator registers hold complete sums, so the epilogue is normalise,
+//     transpose, store: no hand-over, no combine.
+// Neither kind needs a whole tile period for its share (about 0.7 and 0.55 of it at d_c = 512), so
+// the sweep follows the memory stream also where the shader clock is at the low end of its range;
+// with the scores on the consumers as well, those needed 0.8 to 0.85 of the period and set the
+// pace there.  Both kinds meet at one workgroup barrier per tile (tile t's scores are written,
+// tile t + 1 has landed, everybody is done with tile t - 1, whose slot the producers then fill
+// again).
 #include "mla_internal.h"
 #include "mfma_tile.h"
 #include <type_traits>
@@ -35,7 +41,7 @@
 namespace mla {
 namespace {
 
-constexpr int ST_THREADS = 512;   // 4 consumer + 4 producer wavefronts
+constexpr int ST_THREADS = 512;   // 4 consumer (weights, values) + 4 producer (requests, scores) wavefronts
 
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
@@ -44,7 +50,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 template <int D_C, bool PROBE>
 __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
 {
-    constexpr int NBUF = 3;                     // ring slots: one being consumed, two requested (this kernel is for short chunks)
+    constexpr int NBUF = 4;                     // ring slots: tile t (values), tile t + 1 (scores), two on their way
     constexpr int ROW = D_C + 64;               // elements per cache row
     constexpr int ROWB = ROW * 2;               // bytes per row
     constexpr int CPR = ROWB / 16;              // 16-byte chunks per row (72 / 40)
@@ -58,14 +64,17 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     constexpr int RSO = WCT * 32 + 32;          // epilogue: row stride of the transposed block in bytes (padded)
     static_assert(TILE_B % (256 * 16) == 0, "tile must split evenly over the producers' loads");
     static_assert(CPR % 8 == 0, "chunk swizzle needs rows of whole 128-byte groups");
-    static_assert(NLOAD * NBUF < 64, "vmcnt is a 6-bit counter");
+    static_assert(NLOAD * (NBUF + 1) < 64, "vmcnt is a 6-bit counter");
     static_assert(4 * 16 * RSO <= NBUF * TILE_B, "the epilogue's transposition space must fit in the tile ring");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * TILE_B];
-    // the query rows [q_abs | q_rope] of the 32 heads, laid out exactly like a cache tile (one row per
-    // head, same chunk swizzle): requested by the producers as direct-to-LDS loads right after the
-    // first tile, read into registers by the consumers after the first barrier
-    __shared__ __attribute__((aligned(1024))) unsigned char qmem[TILE_B];
+    // (the query rows [q_abs | q_rope] of the 32 heads travel like a cache tile, one row per head with
+    // the same chunk swizzle: requested as direct-to-LDS loads into the ring's last slot right after
+    // the first tile, read into the producers' registers after the first barrier; then the slot
+    // joins the ring)
+    // scaled scores of a tile's two 16-row blocks, from the wavefronts that score to those that
+    // accumulate: [tile parity][head group][block][lane]
+    __shared__ f32x4 xbuf[2][2][2][64];
     __shared__ int jump_flag;                        // raised by a consumer whose fast pass met a score far above its reference
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int tid = (int)threadIdx.x;
     const bool producer = wave >= 4;
     const int w4 = wave & 3;
-    const int hg = w4 & 1, ch = w4 >> 1;       // consumers: head group, column half
+    const int hg = w4 & 1, ch = w4 >> 1;       // head group; consumers: column half, producers: 16-row block
     const int n = lane & 15, g = lane >> 4;
     const int HL = min(32, p.H - hb);          // query rows of this workgroup
     if (tid == 0) jump_flag = 0;               // read after the tile loop, behind at least one barrier
@@ -110,8 +119,12 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     int L = seq_lens_c[b];
 
     const int head = hg * 16 + n;
-    bf16x8 qreg[NKS];   // consumers: this wave's 16 query rows as B operands, resident for the whole chunk:
-                        // lane (g, n) holds elements 8g .. 8g+7 of every 32-element k-step of head 16 hg + n
+    // A wavefront scores or accumulates for life, and one register allocation serves both kinds: the
+    // query rows of the scoring wavefronts (B operands, resident for the whole chunk: lane (g, n) holds
+    // elements 8g .. 8g+7 of every 32-element k-step of head 16 hg + n; 72 / 40 registers) and the
+    // accumulators of the others (64 / 32) are therefore the SAME registers, st[]
+    constexpr int NST = NKS > WCT ? NKS : WCT;
+    f32x4 st[NST];
 
     asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
@@ -171,7 +184,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 
     // producers: the query rows into their LDS area, chunk by chunk like a tile (rows of absent
     // heads zero-filled); requested once per segment, right after the first tile's loads
-    LDS_AS unsigned char* qlds = (LDS_AS unsigned char*)qmem;
+    LDS_AS unsigned char* qlds = lds + 3 * TILE_B;
     auto fetch_query_rows = [&]() {
         const unsigned char* qa = static_cast<const unsigned char*>(p.q_abs) + ((size_t)b * p.H + hb) * D_C * 2;
         const unsigned char* qr = static_cast<const unsigned char*>(p.q_rope) + ((size_t)b * p.H + hb) * 128;
@@ -192,13 +205,12 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         }
     };
 
-    // ---- consumers: running softmax state; this lane's head = column n of the D tiles, its rows
+    // ---- running softmax state (consumers); this lane's head = column n of the D tiles, its rows
     // 4g .. 4g+3 of each of the tile's two 16-row blocks
     float m_run = -INFINITY;   // reference of the exponentials, scaled scores in log2 units
     float l_run = 0.f;         // this lane's share of the running sum (its 8 rows per tile)
-    f32x4 oacc[WCT];
 #pragma unroll
-    for (int i = 0; i < WCT; ++i) oacc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NST; ++i) st[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const float sc = p.scale * LOG2E;
     // score A operand: row 16 rb + n, chunk 4 ks + g
     const uint32_t a_row = (uint32_t)(n * ROWB);
@@ -222,17 +234,13 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         return fmaxf(v, __shfl_xor(v, 32));
     };
 
-    // S^T = K . Q^T for the tile's two 16-row blocks x 16 heads, scaled to log2 units, rows outside the
-    // chunk or beyond the query row's own position at -inf.  The two blocks' contractions are
-    // interleaved: each is a chain of MFMAs into one accumulator, and a chain of this instruction
-    // on its own runs at its latency, not at its issue rate.
-    auto score_tile = [&](LDS_AS unsigned char* tile, int t, int n_valid, float (&x0)[4], float (&x1)[4]) {
-        f32x4 sacc0 = (f32x4){0.f, 0.f, 0.f, 0.f}, sacc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
-        bf16x8 a0[NKS], a1[NKS];
-        auto rd = [&](int ks) {
-            a0[ks] = *(LDS_AS bf16x8*)(tile + a_base[ks & 1] + (ks >> 1) * 128);
-            a1[ks] = *(LDS_AS bf16x8*)(tile + 16 * ROWB + a_base[ks & 1] + (ks >> 1) * 128);
-        };
+    // S^T = K . Q^T for 16-row block rb of a tile x 16 heads, scaled to log2 units, rows outside the
+    // chunk or beyond the query row's own position at -inf
+    auto score_block = [&](LDS_AS unsigned char* tile, int rb, int t, int n_valid, f32x4& x) {
+        f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        bf16x8 a0[NKS];
+        LDS_AS unsigned char* rows = tile + rb * 16 * ROWB;
+        auto rd = [&](int ks) { a0[ks] = *(LDS_AS bf16x8*)(rows + a_base[ks & 1] + (ks >> 1) * 128); };
 #pragma unroll
         for (int ks = 0; ks < SG; ++ks) rd(ks);
         __builtin_amdgcn_sched_barrier(0);
@@ -242,21 +250,16 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
             for (int ks = s0 + SG; ks < s0 + 2 * SG && ks < NKS; ++ks) rd(ks);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks) {
-                sacc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], qreg[ks], sacc0, 0, 0, 0);
-                sacc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[ks], qreg[ks], sacc1, 0, 0, 0);
-            }
+            for (int ks = s0; ks < s0 + SG && ks < NKS; ++ks)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], __builtin_bit_cast(bf16x8, st[ks]), sacc, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { x0[i] = sacc0[i] * sc; x1[i] = sacc1[i] * sc; }
+        x = sacc * sc;
         if (n_valid < TILE_ROWS || (t + 1) * TILE_ROWS > causal_from) {
             const int seen = min(n_valid, visible_rows(p, L, hb + head) - t * TILE_ROWS);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (g * 4 + i >= seen) x0[i] = -INFINITY;
-                if (16 + g * 4 + i >= seen) x1[i] = -INFINITY;
-            }
+            for (int i = 0; i < 4; ++i)
+                if (rb * 16 + g * 4 + i >= seen) x[i] = -INFINITY;
         }
     };
 
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     // then O^T += V^T . P^T over the tile's 32 rows: k slot 8g + j of the second contraction is
     // tile row 4g + j (j < 4) or 16 + 4g + j - 4, which is how the weights lie in the registers
     // after scoring and what two transposing reads (one per 16-row block) deliver
-    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const float (&x0)[4], const float (&x1)[4]) {
+    auto accumulate_tile = [&](LDS_AS unsigned char* tile, const f32x4 x0, const f32x4 x1) {
         const float m_use = m_run == -INFINITY ? 0.f : m_run;  // only while every row so far is masked
         const uint32_t p01 = pack_bf16x2(fast_exp2(x0[0] - m_use), fast_exp2(x0[1] - m_use));
         const uint32_t p23 = pack_bf16x2(fast_exp2(x0[2] - m_use), fast_exp2(x0[3] - m_use));
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 #pragma unroll
             for (int i = c0; i < c0 + VG && i < WCT; ++i) {
                 const s16x8 va = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), pb, oacc[i], 0, 0, 0);
+                st[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), pb, st[i], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -306,39 +309,58 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     // more than RESCALE_GAP.  Producers and consumers execute the same barriers.
     auto sweep = [&](auto careful_tag) -> bool {
         constexpr bool CAREFUL = decltype(careful_tag)::value;
-        int ahead[NBUF - 1];   // producers: loads issued for the tiles after the one being consumed, oldest first
+        // the query rows travel in slot 3, which joins the ring when the scoring wavefronts have read them
+        constexpr bool Q_IN_RING = !CAREFUL && !PROBE;
+        const int rb = ch;   // producers: the 16-row block of every tile this wavefront scores (for head group hg)
+        auto await_all_but = [&](int younger) {
+            if (younger >= 2 * NLOAD)  wait_vmcnt<2 * NLOAD>();
+            else if (younger >= NLOAD) wait_vmcnt<NLOAD>();
+            else                       wait_vmcnt<0>();
+        };
+        int c3 = 0;   // producers: loads issued for tile t0 + 3
+        {
+            int c1 = 0, c2 = 0;
+            if (producer) {
+                fetch_tile(t0);    // its loads are the oldest: every wait below covers them
+                if constexpr (Q_IN_RING) fetch_query_rows();
+                if (t0 + 1 < t1) c1 = fetch_tile(t0 + 1);
+                if (t0 + 2 < t1) c2 = fetch_tile(t0 + 2);
+                await_all_but(c1 + c2);
+            }
+            __syncthreads();   // the first tile and the query rows are there (every producer's part)
+            if (producer) {
+                if constexpr (Q_IN_RING) {
+                    const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
+                    const uint32_t q_key = (uint32_t)swz_key(n);
 #pragma unroll
-        for (int i = 0; i < NBUF - 1; ++i) ahead[i] = 0;
-        if (producer) {
-            fetch_tile(t0);    // its loads are the oldest: every wait below covers them
-            if constexpr (!CAREFUL && !PROBE) fetch_query_rows();   // older than every later tile's loads as well
+                    for (int ks = 0; ks < NKS; ++ks)
+                        st[ks] = *(LDS_AS f32x4*)(qlds + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
+                    // (the reads have to be back before the barrier that releases the slot)
 #pragma unroll
-            for (int i = 0; i < NBUF - 2; ++i)
-                if (t0 + 1 + i < t1) ahead[i] = fetch_tile(t0 + 1 + i);
+                    for (int ks = 0; ks < NKS; ++ks) asm volatile("" :: "v"(st[ks]));
+                }
+            }
+            __syncthreads();   // the query rows are in registers: their slot joins the ring
+            if (producer) {
+                // (scores first: with two tiles in flight the new requests would wait for a free
+                // place in the memory pipeline and hold the scores back)
+                if constexpr (!PROBE) {
+                    f32x4 xs;
+                    score_block(lds, rb, t0, rows_valid(t0), xs);
+                    xbuf[0][hg][rb][lane] = xs;
+                    asm volatile("" ::: "memory");
+                }
+                if (t0 + 3 < t1) c3 = fetch_tile(t0 + 3);
+                await_all_but(c2 + c3);   // the second tile is there
+            }
         }
         bool jumped = false;
         for (int t = t0; t < t1; ++t) {
+            const int par = (t - t0) & 1;
             LDS_AS unsigned char* tile = lds + ((t - t0) % NBUF) * TILE_B;
             const int n_valid = rows_valid(t);
-            if (producer) {
-                // wait until my loads of tile t have landed (younger tiles may stay in flight)
-                int younger = 0;
-#pragma unroll
-                for (int i = 0; i < NBUF - 1; ++i) younger += ahead[i];
-                if (NBUF > 3 && younger >= 3 * NLOAD)      wait_vmcnt<3 * NLOAD>();
-                else if (younger >= 2 * NLOAD)             wait_vmcnt<2 * NLOAD>();
-                else if (younger >= NLOAD)                 wait_vmcnt<NLOAD>();
-                else                                       wait_vmcnt<0>();
-            }
-            // tile t has landed (every producer's part), and every consumer is done with tile t - 1
+            // tile t's scores are in LDS, tile t + 1 has landed, and everybody is done with tile t - 1
             __syncthreads();
-            if (producer) {
-                const int tn = t + NBUF - 1;             // goes into the slot tile t - 1 has left
-                ahead[NBUF - 2] = tn < t1 ? fetch_tile(tn) : 0;
-#pragma unroll
-                for (int i = 0; i < NBUF - 2; ++i) ahead[i] = ahead[i + 1];   // tile t + 1 becomes the oldest in flight
-                ahead[NBUF - 2] = 0;
-            }
             if (n_valid < TILE_ROWS) {
                 // ragged last tile (or a page id outside the pool): rows that are not part of the
                 // sequence become zeros so that whatever they hold stays out
@@ -346,18 +368,19 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                     *(LDS_AS u32x4*)(tile + n_valid * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
                 __syncthreads();
             }
-            if (!producer && !PROBE) {
-                if (!CAREFUL && t == t0) {
-                    // the query rows have landed with the first tile (they were requested before
-                    // the second): into registers, where they stay
-                    const uint32_t q_row = (uint32_t)((hg * 16 + n) * ROWB);
-                    const uint32_t q_key = (uint32_t)swz_key(n);
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks)
-                        qreg[ks] = *(LDS_AS bf16x8*)(qlds + q_row + ((((uint32_t)(4 * ks + g)) ^ q_key) << 4));
+            if (producer) {
+                // tile t + 3 into the slot tile t - 1 has left (the first time round it is on its way already)
+                const int cn = t == t0 ? c3 : (t + 3 < t1 ? fetch_tile(t + 3) : 0);
+                if constexpr (!PROBE) {
+                    if (t + 1 < t1) {
+                        f32x4 xs;
+                        score_block(lds + ((t + 1 - t0) % NBUF) * TILE_B, rb, t + 1, rows_valid(t + 1), xs);
+                        xbuf[par ^ 1][hg][rb][lane] = xs;
+                    }
                 }
-                float x0[4], x1[4];
-                score_tile(tile, t, n_valid, x0, x1);
+                await_all_but(cn);   // tile t + 2 is there before the next barrier
+            } else if constexpr (!PROBE) {
+                const f32x4 x0 = xbuf[par][hg][0][lane], x1 = xbuf[par][hg][1][lane];
                 const float lmax = fmaxf(fmaxf(fmaxf(x0[0], x0[1]), fmaxf(x0[2], x0[3])),
                                          fmaxf(fmaxf(x1[0], x1[1]), fmaxf(x1[2], x1[3])));
                 if constexpr (!CAREFUL) {
@@ -374,7 +397,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
                         const float alpha = fast_exp2(m_run - m_new);   // 1 for the lanes that keep their reference
                         l_run *= alpha;
 #pragma unroll
-                        for (int i = 0; i < WCT; ++i) oacc[i] *= alpha;
+                        for (int i = 0; i < WCT; ++i) st[i] *= alpha;
                         m_run = m_new;
                     }
                 }
@@ -393,7 +416,8 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         m_run = -INFINITY;
         l_run = 0.f;
 #pragma unroll
-        for (int i = 0; i < WCT; ++i) oacc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < WCT; ++i)
+            if (!producer) st[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
         sweep(std::true_type{});
         __syncthreads();
     }
@@ -410,7 +434,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         LDS_AS unsigned char* mine = lds + w4 * (16 * RSO);
 #pragma unroll
         for (int i = 0; i < WCT; ++i) {
-            const f32x4 o = oacc[i] * inv;
+            const f32x4 o = st[i] * inv;
             *(LDS_AS u32x2*)(mine + n * RSO + (i * 16 + g * 4) * 2) =
                 (u32x2){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
         }
