@@ -322,10 +322,11 @@ def main():
         kernel_name = f"decode_stream_fp8_kernel<{d_c}, {'true' if args.balanced else 'false'}>"
     elif args.balanced:
         tiles = 2 * d.page_table.shape[1] // max(1, S)
-        kernel_name = f"decode_mfma_kernel<{d_c}, {'3' if tiles <= 64 else '4'}, 1, true>"
+        kernel_name = (f"decode_stream_kernel<{d_c}, false, true>" if d_c == 512 else
+                       f"decode_mfma_kernel<{d_c}, {'3' if tiles <= 64 else '4'}, 1, true>")
     else:
         tiles = 2 * (-(-d.page_table.shape[1] // S))
-        kernel_name = (f"decode_stream_kernel<{d_c}, false>" if tiles <= 32 else
+        kernel_name = (f"decode_stream_kernel<{d_c}, false, false>" if (d_c == 512 or tiles <= 32) else
                        f"decode_mfma_kernel<{d_c}, {'3' if tiles <= 64 else '4'}, 1, false>")
     # HBM bytes per launch from the committed rocprofv3 counter summary; only valid for the default
     # launch configuration of the workload and while the kernel sources are the ones the counters
@@ -389,7 +390,7 @@ def main():
 
     if stream_only_us is not None:
         rec["roofline"]["stream_only"] = {
-            "kernel": f"decode_stream_kernel<{d_c}, true>", "launch_us": round(float(stream_only_us), 2),
+            "kernel": f"decode_stream_kernel<{d_c}, true, false>", "launch_us": round(float(stream_only_us), 2),
             "frac": round(cache_bytes / (stream_only_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
             "note": "mla_diag_stream_tiles: the decode kernel's grid, tile ring, loads, waits and barriers with no "
                     "arithmetic and no output, back to back like launch_us"}

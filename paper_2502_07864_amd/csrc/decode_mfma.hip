@@ -1,5 +1,8 @@
 // Matrix-core paged decode for a bf16 latent cache (gfx950 / CDNA4), and the dispatch of the other
-// matrix-core decode kernels (decode_stream.hip, decode_stream_fp8.hip).
+// matrix-core decode kernels (decode_stream.hip, decode_stream_fp8.hip).  The kernel of this file
+// serves d_c = 256 on long chunks and under the balanced partition (everything else at bf16 goes to
+// decode_stream.hip's); the tile layout, the swizzle, the transposed formulation, the two passes
+// and the balanced plan described here are shared by all of them.
 //
 // Second line of the absorbed attention equation (Sec. 3.3 of the paper): all
 // H heads score against the ONE shared row k_hat_j = [c_j ; k^R_j] and weight
@@ -677,23 +680,24 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
         // workgroups = sequences x chunks per sequence (x groups of 32 query rows)
         dim3 grid(grid_1d(p));
         if (fp8) return launch_decode_stream_fp8(p, grid, s, true);
-        if (p.d_c == 512)      launch_one<512, true>(p, grid, block, s, depth);
-        else if (p.d_c == 256) launch_one<256, true>(p, grid, block, s, depth);
+        // d_c = 512: the two-stage kernel (C3: 202.3 against 204.7 us per launch)
+        if (p.d_c == 512) return launch_decode_stream_balanced(p, grid, s);
+        if (p.d_c == 256) launch_one<256, true>(p, grid, block, s, depth);
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
     dim3 grid(p.B, p.num_splits);
     if (p.H > 32) grid = dim3(grid_1d(p));
-    // short chunks: the kernel with requesting-and-scoring wavefronts apart from the accumulating ones
-    // (C2: 29.0 -> 27.5 us); on long chunks the two are level (C4, 64 tiles: 52.7 against 53.9 us per
-    // launch, 67.3 against 66.5 us per step) and this file's kernel keeps them
-    if (!fp8 && 2LL * p.chunk_pages <= 32) return launch_decode_stream(p, grid, s);
+    // d_c = 512, and short chunks at d_c = 256: the kernel with requesting-and-scoring wavefronts apart
+    // from the accumulating ones (C2: 29.0 -> 27.5 us; the C3 cache in 4 uniform chunks of up to 256
+    // tiles: 280 -> 230 us).  On long chunks at d_c = 256 the two are level per launch and this
+    // file's kernel is ahead per step (C4, 64 tiles: 52.9 against 53.0 us, 66.4 against 67.4 us)
+    if (!fp8 && (p.d_c == 512 || 2LL * p.chunk_pages <= 32)) return launch_decode_stream(p, grid, s);
     // fp8 caches, either partition, any chunk length: the kernel that contracts the codes as they are
     // (C5: 92.4 -> 62 us against an fp8 variant of the kernel above that widened every tile to bf16 in
     // LDS before it was consumed; that variant is gone)
     if (fp8) return launch_decode_stream_fp8(p, grid, s, false);
-    if (p.d_c == 512)      launch_one<512, false>(p, grid, block, s, depth);
-    else if (p.d_c == 256) launch_one<256, false>(p, grid, block, s, depth);
+    if (p.d_c == 256) launch_one<256, false>(p, grid, block, s, depth);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

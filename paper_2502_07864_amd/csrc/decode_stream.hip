@@ -47,7 +47,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 // PROBE = true: the diagnostic variant behind mla_diag_stream_tiles: the same tile requests, waits and
 // barriers, no query rows, no arithmetic, no output (how fast this launch shape can stream at all).
-template <int D_C, bool PROBE>
+// BAL = true: the balanced partition (one-dimensional grid; a workgroup owns an equal share of the
+// pages of all sequences and works through the segments of sequences inside it, exactly as in
+// decode_mfma.hip, whose plan and slot numbering this is).
+template <int D_C, bool PROBE, bool BAL>
 __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodeParams p)
 {
     constexpr int NBUF = 4;                     // ring slots: tile t (values), tile t + 1 (scores), two on their way
@@ -76,6 +79,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     // accumulate: [tile parity][head group][block][lane]
     __shared__ f32x4 xbuf[2][2][2][64];
     __shared__ int jump_flag;                        // raised by a consumer whose fast pass met a score far above its reference
+    __shared__ int seg_lds[BAL ? 64 : 1][3];         // balanced partition: this workgroup's segments within a block of 64 sequences
     LDS_AS unsigned char* lds = (LDS_AS unsigned char*)smem;
 
     const int lane = threadIdx.x & 63;
@@ -93,12 +97,18 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int hb = zi * 32;
     const bool stream_once = Z == 1;   // no other workgroup reads this one's cached rows
 
-    // Workgroup -> (sequence, chunk): linear ids run over the sequences first, chunk by chunk, with
-    // the sequence rotated by the chunk index (see decode_mfma.hip).  Uniform chunks only: the
-    // balanced partition runs decode_mfma.hip's kernel.
-    const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, split = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
-    const int b = (cx + split) % p.B;
-    const int tid = (int)threadIdx.x;
+    // one chunk (uniform partition) or one segment (balanced: rows [seg_row0, seg_row1) of sequence b,
+    // partials into slot out_slot)
+    auto run_segment = [&](const int b, const int split, const int seg_row0, const int seg_row1,
+                           const size_t out_slot) {
+    // (balanced partition: everything derived from the thread index is derived again per segment
+    // from a value the compiler cannot see through, so that it is not kept in registers across
+    // segments)
+    int opaque_zero = 0;
+    if constexpr (BAL) asm volatile("" : "+v"(opaque_zero));
+    const int tid = BAL ? (int)threadIdx.x + opaque_zero : (int)threadIdx.x;
+    const int lane = BAL ? (tid & 63) : (int)(threadIdx.x & 63);
+    const int wave = __builtin_amdgcn_readfirstlane(BAL ? tid >> 6 : (int)threadIdx.x >> 6);
     const bool producer = wave >= 4;
     const int w4 = wave & 3;
     const int hg = w4 & 1, ch = w4 >> 1;       // head group; consumers: column half, producers: 16-row block
@@ -106,16 +116,16 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
     const int HL = min(32, p.H - hb);          // query rows of this workgroup
     if (tid == 0) jump_flag = 0;               // read after the tile loop, behind at least one barrier
     auto o_row = [&](int h) -> uint16_t* {     // partial rows are bf16 (the io dtype of this kernel)
-        return static_cast<uint16_t*>(p.o_part) + part_index(b, h, split, p.H, p.num_splits) * D_C;
+        return static_cast<uint16_t*>(p.o_part) + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits)) * D_C;
     };
     auto lse_at = [&](int h) -> float* {
-        return p.lse_part + part_index(b, h, split, p.H, p.num_splits);
+        return p.lse_part + (BAL ? (out_slot * p.H + h) : part_index(b, h, split, p.H, p.num_splits));
     };
 
     // read-only tables go through the scalar cache
     const CONST_AS int32_t* seq_lens_c = (const CONST_AS int32_t*)p.seq_lens;
     const CONST_AS int32_t* ptab = (const CONST_AS int32_t*)(p.page_table + (size_t)b * p.max_pages);
-    const int warm = ptab[min(split * p.chunk_pages, p.max_pages - 1)];
+    const int warm = ptab[min(BAL ? seg_row0 / 64 : split * p.chunk_pages, p.max_pages - 1)];
     int L = seq_lens_c[b];
 
     const int head = hg * 16 + n;
@@ -128,8 +138,8 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 
     asm volatile("" :: "s"(warm));
     L = max(0, min(L, p.max_pages * 64));
-    const int row0 = split * p.chunk_pages * 64;                  // first cached row of this chunk
-    const int row1 = min(row0 + p.chunk_pages * 64, L);           // one past its last row
+    const int row0 = BAL ? seg_row0 : split * p.chunk_pages * 64;                  // first cached row of this chunk
+    const int row1 = BAL ? min(seg_row1, L) : min(row0 + p.chunk_pages * 64, L);   // one past its last row
     if (row0 >= row1) {  // empty chunk: weight zero in the merge, partial output never read
         if (!PROBE && tid < HL) *lse_at(hb + tid) = -INFINITY;
         return;
@@ -444,7 +454,7 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         // all reads first, then all stores, from one base address and a row stride (computing the
         // address of every row anew, with a wait for its LDS read in between, tripled the time
         // of this loop)
-        const size_t row_stride = (size_t)p.num_splits * D_C;   // elements between the partial rows of consecutive heads
+        const size_t row_stride = (size_t)(BAL ? 1 : p.num_splits) * D_C;   // elements between the partial rows of consecutive heads
         const int rl = lane / LPR, c = lane % LPR;
         uint16_t* dst0 = o_row(hb + hg * 16) + (size_t)rl * row_stride + ch * (WCT * 16) + c * 8;
         u32x4 v[16 / RPI];
@@ -457,6 +467,78 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
         if (ch == 0 && head < HL && g == 0)
             *lse_at(hb + head) = lt > 0.f ? (m_run + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
     }
+    };  // run_segment
+
+    if constexpr (!BAL) {
+        // linear ids run over the sequences first, chunk by chunk, with the sequence rotated by the
+        // chunk index (see decode_mfma.hip)
+        const int cx = Z > 1 ? wg_lin % p.B : (int)blockIdx.x, cy = Z > 1 ? wg_lin / p.B : (int)blockIdx.y;
+        run_segment((cx + cy) % p.B, cy, 0, 0, 0);
+    } else {
+        // ---- balanced partition, exactly as in decode_mfma.hip: pages of sequence b: P_b =
+        // ceil(len_b / 64); workgroup w of G owns the global pages [P w / G, P (w+1) / G) of the
+        // concatenation, P = sum_b P_b.  Every wavefront derives the same plan by itself (lanes stand
+        // for sequences, 64 at a time, a wave scan gives each sequence's first and last global page);
+        // workgroup 0 writes the plan for the merge, a workgroup with an empty range inside a
+        // sequence's span marks its slot empty.
+        const int wg = wg_lin, G = p.B * p.num_splits;
+        auto seq_len_of = [&](int bb) { return bb < p.B ? max(0, min(p.seq_lens[bb], p.max_pages * 64)) : 0; };
+        auto wave_scan = [&](int v) {                // inclusive prefix sum over the 64 lanes
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int u = __shfl_up(v, o);
+                if (lane >= o) v += u;
+            }
+            return v;
+        };
+        int total = 0;
+        for (int blk = 0; blk < p.B; blk += 64)
+            total += __shfl(wave_scan((seq_len_of(blk + lane) + 63) >> 6), 63);
+        total = __builtin_amdgcn_readfirstlane(total);
+        const int ps = __builtin_amdgcn_readfirstlane((int)((long long)total * wg / G));
+        const int pe = __builtin_amdgcn_readfirstlane((int)((long long)total * (wg + 1) / G));
+        int carry = 0;
+        for (int blk = 0; blk < p.B; blk += 64) {
+            int nseg = 0;
+            {
+                const int bb = blk + lane;
+                const int len = seq_len_of(bb);
+                const int pg = (len + 63) >> 6;
+                const int incl = carry + wave_scan(pg), excl = incl - pg;
+                // workgroup of global page x: the largest w with P w / G <= x
+                const int w0 = pg > 0 ? (int)((((long long)excl + 1) * G - 1) / total) : 0;
+                const int w1 = pg > 0 ? (int)(((long long)incl * G - 1) / total) : -1;
+                if (wg == 0 && wave == 0 && bb < p.B) {
+                    // sequence bb's partials are the slots first .. first + cnt - 1 (slot of a segment
+                    // = workgroup + sequence index: strictly increasing along the concatenation)
+                    p.plan[2 * bb] = pg > 0 ? w0 + bb : 0;
+                    p.plan[2 * bb + 1] = w1 - w0 + 1;
+                }
+                if (ps == pe && pg > 0 && wave == 0 && w0 <= wg && wg <= w1) {
+                    for (int h = hb; h < min(p.H, hb + 32); ++h) p.lse_part[((size_t)wg + bb) * p.H + h] = -INFINITY;
+                }
+                const int lo = max(ps, excl), hi = min(pe, incl);
+                const bool mine = pg > 0 && lo < hi;
+                const unsigned long long mask = __ballot(mine);
+                nseg = __builtin_popcountll(mask);
+                if (mine && wave == 0) {
+                    const int k = __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+                    seg_lds[k][0] = bb;
+                    seg_lds[k][1] = (lo - excl) * 64;
+                    seg_lds[k][2] = (hi - excl) * 64;     // clipped to the length inside the segment
+                }
+                carry = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+            }
+            __syncthreads();
+            for (int k = 0; k < nseg; ++k) {
+                const int sb = seg_lds[k][0], r0 = seg_lds[k][1], r1 = seg_lds[k][2];
+                run_segment(sb, 0, r0, r1, (size_t)wg + (size_t)sb);
+                __syncthreads();   // the next segment reuses the LDS the epilogue just read
+            }
+            if (carry >= pe && wg != 0) break;   // nothing further overlaps (workgroup 0 goes on: it writes the plan)
+            __syncthreads();                     // the list is rewritten for the next block
+        }
+    }
 }
 
 }  // namespace
@@ -464,8 +546,18 @@ __global__ __launch_bounds__(ST_THREADS, 1) void decode_stream_kernel(DecodePara
 hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
 {
     dim3 block(ST_THREADS);
-    if (p.d_c == 512)      decode_stream_kernel<512, false><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_stream_kernel<256, false><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_stream_kernel<512, false, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256, false, false><<<grid, block, 0, s>>>(p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_stream_balanced(const DecodeParams& p, dim3 grid, hipStream_t s)
+{
+    dim3 block(ST_THREADS);
+    if (!p.plan) return hipErrorInvalidValue;
+    if (p.d_c == 512)      decode_stream_kernel<512, false, true><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256, false, true><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -473,8 +565,8 @@ hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s)
 hipError_t launch_decode_stream_probe(const DecodeParams& p, hipStream_t s)
 {
     dim3 grid(p.B, p.num_splits), block(ST_THREADS);
-    if (p.d_c == 512)      decode_stream_kernel<512, true><<<grid, block, 0, s>>>(p);
-    else if (p.d_c == 256) decode_stream_kernel<256, true><<<grid, block, 0, s>>>(p);
+    if (p.d_c == 512)      decode_stream_kernel<512, true, false><<<grid, block, 0, s>>>(p);
+    else if (p.d_c == 256) decode_stream_kernel<256, true, false><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

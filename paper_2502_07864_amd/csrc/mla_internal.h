@@ -195,6 +195,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, mla_dtype cache, hipStream_
 // uniform chunks of at most 32 tiles, bf16 caches: the kernel with separate requesting and consuming
 // wavefronts (same grid as launch_decode_mfma's)
 hipError_t launch_decode_stream(const DecodeParams& p, dim3 grid, hipStream_t s);
+// the same kernel under the balanced partition (needs p.plan; launch_decode_mfma's balanced grid)
+hipError_t launch_decode_stream_balanced(const DecodeParams& p, dim3 grid, hipStream_t s);
 // the same kernel's tile requests, waits and barriers alone (diagnostic: no query rows, arithmetic or output)
 hipError_t launch_decode_stream_probe(const DecodeParams& p, hipStream_t s);
 // uniform chunks, fp8 caches: wavefronts that turn tiles into softmax weights beside wavefronts that

@@ -205,6 +205,14 @@ def test_decode_bf16_ragged(mla, num_splits, flags):
     check_decode(mla, ragged_workload(), num_splits, flags)
 
 
+@pytest.mark.parametrize("num_splits", [1, 3])
+def test_decode_bf16_long_uniform_chunks(mla, num_splits):
+    """Chunks of several hundred tiles in the two-stage kernel (d_c = 512 takes it at every chunk
+    length), beside a short and a one-tile sequence."""
+    w = ragged_workload(lens=[20000, 5000, 33], seed=11)
+    check_decode(mla, w, num_splits)
+
+
 @pytest.mark.parametrize("flags", [0, 1])
 def test_decode_bf16_C4_shape(mla, flags):
     """28 heads (padded to the 32-row tile), d_c = 256."""
