@@ -341,6 +341,10 @@ def test_decode_balanced_shapes_and_caches(mla):
     check_decode(mla, ragged_workload(lens=[0, 1, 0, 64, 5, 0], seed=75), 3, flags=BAL)
     w = ragged_workload(lens=[700] * 70, seed=76)                            # more than 64 sequences: two scan blocks
     check_decode(mla, w, 2, flags=BAL, b_sel=[0, 1, 63, 64, 65, 69])
+    w = ragged_workload(lens=[9000, 1, 130, 0] + [70] * 60, seed=78)         # many segments in one workgroup
+    check_decode(mla, w, 1, flags=BAL, b_sel=[0, 1, 2, 3, 4, 63])
+    w = ragged_workload(d_c=256, H=28, lens=[9000, 1, 130, 0] + [70] * 60, seed=79)
+    check_decode(mla, w, 1, flags=BAL, b_sel=[0, 1, 2, 3, 4, 63])
 
 
 @pytest.mark.parametrize("num_splits", [1, 2, 7, 32])
