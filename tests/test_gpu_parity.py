@@ -531,6 +531,31 @@ def test_dominant_score_and_uniform_weights(mla):
         assert np.abs(widen_gpu(o) - target[:, None, :]).max() <= 2e-2 * np.abs(target).max()
 
 
+@pytest.mark.parametrize("flags", [0, BAL])
+@pytest.mark.parametrize("d_c", [512, 256])
+def test_dominant_late_score_takes_the_careful_pass(mla, flags, d_c):
+    """One chunk per sequence, and the one score that dominates sits in its seventh tile: the fixed
+    reference of the fast pass (the first tile's maximum) is exceeded by far more than it
+    tolerates, so the chunk is redone with a moving reference.  Both partitions, both latent widths;
+    the result is the dominant row itself and the whole output matches the oracle."""
+    import torch
+    w = ragged_workload(d_c=d_c, lens=[300, 2000, 217], seed=16)
+    d = DeviceWorkload(w)
+    rows = oracle.widen(oracle.gather_paged(w.pool, w.page_table, w.seq_lens, 2000).view(np.uint16))
+    target = np.stack([rows[0, 217, :d_c], rows[1, 1900, :d_c], rows[2, 216, :d_c]])
+    q1 = to_torch(synth.to_bf16_bits((40.0 * target[:, None, :].repeat(32, 1)).astype(np.float32)), "bf16")
+    r0 = torch.zeros((3, 32, 64), dtype=torch.bfloat16, device="cuda")
+    o, lse = mla.decode_paged(q1, r0, d.pool, d.page_table, d.seq_lens, w.softmax_scale,
+                              num_splits=1, return_lse=True, flags=flags)
+    torch.cuda.synchronize()
+    assert np.isfinite(widen_gpu(o)).all() and np.isfinite(widen_gpu(lse)).all()
+    assert np.abs(widen_gpu(o) - target[:, None, :]).max() <= 2e-2 * np.abs(target).max()
+    ref_o, ref_lse = oracle.decode_absorbed(q_abs_storage(q1), q_abs_storage(r0), w.pool, w.kv_scale,
+                                            w.page_table, w.seq_lens, w.softmax_scale)
+    assert max_abs_rel(widen_gpu(o), ref_o) <= TOL["bf16"]
+    assert lse_err(widen_gpu(lse), ref_lse) <= 2e-2
+
+
 def test_GQA_reduction_on_gpu(mla):
     """Sec. 4.1 at GPU size: H = 32 heads in g = 2 groups, d_head = 128, latent
     = [k_1 k_2 v_1 v_2] (d_c = 512), selector-identity W_UK / W_UV: the three
